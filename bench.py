@@ -1,0 +1,109 @@
+"""Throughput of the ensemble hot path on one MI355X.
+
+A step is one pass of the whole hot path (input staging, every member's forward pass on its
+worker streams, fused softmax-and-mean) over one request of n synthetic images resident in HBM.
+Prints one JSON line: images per second, the roofline figures of the dominant kernel (measured
+with HIP events on the worker streams) and the CPU oracle's rate on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--images", type=int, default=1024)
+    ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--cpu-sample", type=int, default=16, help="images the CPU oracle is timed on (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: the path uses no second device (run with --gpus 1)")
+
+    import numpy as np
+    import torch
+    import paper_2208_14049_amd as ens
+    import synth
+    from synth import nets as N, weights as W
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    ens.lib()
+
+    nets = N.config_members(2)                                  # 3 x ResNet-18-shaped, bf16
+    blobs = [W.quantise_weights_bf16(n, W.make_blob(n, synth.BASE_SEED, i)) for i, n in enumerate(nets)]
+    E = ens.Ensemble(nets, blobs)
+    E.ens_set_alloc([[args.batch] * len(nets)])
+    n = args.images
+    g = torch.Generator(device="cuda").manual_seed(synth.BASE_SEED + 1000)
+    images = torch.randn((n, 224, 224, 3), generator=g, device="cuda", dtype=torch.float32)
+    out = torch.empty((n, E.classes), device="cuda", dtype=torch.float32)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        E.ens_predict(images, out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        E.ens_predict(images, out)                              # synchronous: returns when Y is complete
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    value = n * args.steps / dt
+
+    # per-kernel durations: same launches, each bracketed by HIP events on its worker stream
+    E.ens_set_profiling(1)
+    prof = {}
+    psteps = max(1, min(3, args.steps))
+    for _ in range(psteps):
+        E.ens_predict(images, out)
+        for c in E.ens_profile():
+            p = prof.setdefault(c["name"], dict(ms=0.0, launches=0, flop=0.0, bytes=0.0))
+            for k in ("ms", "launches", "flop", "bytes"):
+                p[k] += c[k]
+    E.ens_set_profiling(0)
+    dom_name, dom = max(prof.items(), key=lambda kv: kv[1]["ms"])
+    achieved = dom["flop"] / (dom["ms"] * 1e-3) / 1e12 if dom["ms"] > 0 else 0.0
+    roofline = dict(bound="mfma", kernel=dom_name, achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS,
+                    unit="TFLOP/s", frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=None,
+                    avg_launch_us=round(dom["ms"] * 1e3 / max(1, dom["launches"]), 2),
+                    launches_per_step=dom["launches"] // psteps,
+                    kernels={k: dict(ms_per_step=round(v["ms"] / psteps, 4), launches=v["launches"] // psteps,
+                                     tflops=round(v["flop"] / max(v["ms"], 1e-9) / 1e9, 2),
+                                     gbs=round(v["bytes"] / max(v["ms"], 1e-9) / 1e6, 1)) for k, v in prof.items()})
+
+    cpu = None
+    if args.cpu_sample > 0:
+        import oracle
+        ns = args.cpu_sample
+        x = images[:ns].cpu().numpy()
+        oracle.forward_logits(nets[0], blobs[0], x[:1])          # loads the oracle library
+        t0 = time.perf_counter()
+        oracle.ensemble_predict(nets, blobs, x, real="f32")
+        cdt = time.perf_counter() - t0
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        cpu = dict(value=round(ns / cdt, 3), unit="images/s", cores=cores, kind="oracle",
+                   sample="%d of the %d request images through all %d members" % (ns, n, len(nets)))
+    E.close()
+
+    print(json.dumps({
+        "metric": "ensemble images/sec on 1 MI355X", "value": round(value, 1), "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "3 x ResNet-18-shaped ensemble, 1000 classes, 224x224x3 N(0,1) images, "
+                               "batch %d per member, mean of softmax" % args.batch,
+                   "request_images": n, "allocation": [[args.batch] * len(nets)], "input": "fp32 NHWC resident in HBM"},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }))
+
+
+if __name__ == "__main__":
+    main()

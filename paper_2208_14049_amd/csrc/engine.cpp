@@ -1,0 +1,761 @@
+// The inference-system core (section "The inference system") on one GPU and its C interface.
+//
+// The paper's processes become: the segment broadcaster -> a host loop that hands every segment
+// once to every member; a worker (batcher, predictor, prediction sender) -> a HIP stream plus an
+// activation arena whose kernels write logits straight into the member's row block, so there
+// is nothing to reassemble; the prediction accumulator -> one fused softmax-and-mean kernel
+// after an event join of all worker streams (fixed member order, no atomics).
+#include "engine.h"
+
+#include <algorithm>
+#include <chrono>
+#include <cstdio>
+#include <cstring>
+
+#include "planner.h"
+#include "seedgen.h"
+
+using namespace ens;
+
+#define HIP_TRY(expr)                                                                       \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess) {                                                             \
+            fprintf(stderr, "ens: %s failed: %s (%s:%d)\n", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return e_ == hipErrorOutOfMemory ? ENS_E_NOMEM : ENS_E_HIP;                     \
+        }                                                                                   \
+    } while (0)
+
+namespace ens {
+
+const char* conv_bf16_variant_name(const ConvArgs& a);
+
+static int prof_class(ens_handle* h, const std::string& name) {
+    for (size_t i = 0; i < h->prof.size(); i++)
+        if (h->prof[i].name == name) return (int)i;
+    h->prof.push_back(ProfClass{name});
+    return (int)h->prof.size() - 1;
+}
+
+static View view_of(const Worker& w, const Member& m, int t, int c0) {
+    View v;
+    v.p = w.arena + w.layout.offset[t];
+    v.stride = m.tensors[t].cs;
+    v.c0 = c0;
+    return v;
+}
+
+// Translates the member's operations into kernel argument blocks bound to the worker's arena.
+static int build_launches(ens_handle* h, Worker& w) {
+    const Member& m = h->members[w.member];
+    const int es = m.bf16 ? 2 : 4;
+    w.launches.clear();
+    for (const OpPlan& pl : m.ops) {
+        const ens_op& o = pl.op;
+        const TensorInfo& ts = m.tensors[o.src];
+        const TensorInfo& td = m.tensors[o.dst];
+        Launch L;
+        const char* P = m.dev_params;
+        const double nb = w.batch;
+        switch (o.kind) {
+            case ENS_OP_CONV: {
+                L.kind = L_CONV;
+                ConvArgs& a = L.conv;
+                a.x = view_of(w, m, o.src, o.src_c0);
+                a.y = view_of(w, m, o.dst, o.dst_c0);
+                a.res.p = nullptr; a.res.stride = 0; a.res.c0 = 0;
+                if (o.res >= 0) a.res = view_of(w, m, o.res, o.res_c0);
+                a.w = P + pl.w;
+                a.bias = (const float*)(P + pl.b);
+                a.pre_scale = pl.pre_scale != SIZE_MAX ? (const float*)(P + pl.pre_scale) : nullptr;
+                a.pre_shift = pl.pre_shift != SIZE_MAX ? (const float*)(P + pl.pre_shift) : nullptr;
+                a.nb = w.batch; a.H = ts.h; a.W = ts.w; a.cin = pl.cin_s; a.Ho = td.h; a.Wo = td.w; a.cout = o.cout;
+                a.kh = o.kh; a.kw = o.kw; a.sh = o.sh; a.sw = o.sw; a.pt = o.pt; a.pl = o.pl; a.act = o.act;
+                L.flop = 2.0 * nb * td.h * td.w * o.cout * o.kh * o.kw * o.cin;
+                L.bytes = nb * ((double)ts.h * ts.w * o.cin + (double)td.h * td.w * o.cout * (o.res >= 0 ? 2 : 1)) * es +
+                          (double)o.kh * o.kw * o.cin * o.cout * es;
+                L.klass = prof_class(h, m.bf16 ? conv_bf16_variant_name(a) : "conv_f32_kernel");
+                break;
+            }
+            case ENS_OP_DWCONV:
+            case ENS_OP_MAXPOOL:
+            case ENS_OP_AVGPOOL: {
+                L.kind = o.kind == ENS_OP_DWCONV ? L_DWCONV : L_POOL;
+                L.is_max = o.kind == ENS_OP_MAXPOOL;
+                PoolArgs& a = L.pool;
+                a.x = view_of(w, m, o.src, o.src_c0);
+                a.y = view_of(w, m, o.dst, o.dst_c0);
+                a.w = o.kind == ENS_OP_DWCONV ? P + pl.w : nullptr;
+                a.bias = o.kind == ENS_OP_DWCONV ? (const float*)(P + pl.b) : nullptr;
+                a.nb = w.batch; a.H = ts.h; a.W = ts.w; a.c = o.cin; a.Ho = td.h; a.Wo = td.w;
+                a.kh = o.kh; a.kw = o.kw; a.sh = o.sh; a.sw = o.sw; a.pt = o.pt; a.pl = o.pl; a.act = o.act;
+                L.flop = o.kind == ENS_OP_DWCONV ? 2.0 * nb * td.h * td.w * o.cin * o.kh * o.kw : 0.0;
+                L.bytes = nb * ((double)ts.h * ts.w + (double)td.h * td.w) * o.cin * es;
+                L.klass = prof_class(h, o.kind == ENS_OP_DWCONV ? "window_kernel<dwconv>"
+                                        : L.is_max ? "window_kernel<maxpool>" : "window_kernel<avgpool>");
+                break;
+            }
+            case ENS_OP_GAP: {
+                L.kind = L_GAP;
+                GapArgs& a = L.gap;
+                a.x = view_of(w, m, o.src, o.src_c0);
+                a.y = (float*)(w.arena + w.layout.offset[o.dst]) + o.dst_c0;
+                a.pre_scale = pl.pre_scale != SIZE_MAX ? (const float*)(P + pl.pre_scale) : nullptr;
+                a.pre_shift = pl.pre_shift != SIZE_MAX ? (const float*)(P + pl.pre_shift) : nullptr;
+                a.nb = w.batch; a.HW = ts.h * ts.w; a.c = o.cin;
+                if (td.c != o.cin) return ENS_E_UNSUPPORTED;     // the pooled vector is dense
+                L.bytes = nb * (double)ts.h * ts.w * o.cin * es;
+                L.klass = prof_class(h, "gap_kernel");
+                break;
+            }
+            case ENS_OP_FC: {
+                L.kind = L_FC;
+                FcArgs& a = L.fc;
+                a.x = (const float*)(w.arena + w.layout.offset[o.src]);
+                a.w = P + pl.w;
+                a.bias = (const float*)(P + pl.b);
+                a.y = nullptr;                                   // bound per batch to the logits rows
+                a.nb = w.batch; a.cin = o.cin; a.cout = o.cout; a.ldy = o.cout;
+                L.flop = 2.0 * nb * o.cin * o.cout;
+                L.bytes = (double)o.cin * o.cout * es + nb * (o.cin + o.cout) * 4.0;
+                L.klass = prof_class(h, "fc_kernel");
+                break;
+            }
+            case ENS_OP_SE: {
+                L.kind = L_SE;
+                SeArgs& a = L.se;
+                a.x = view_of(w, m, o.src, o.src_c0);
+                a.y = view_of(w, m, o.dst, o.dst_c0);
+                a.w1 = (const float*)(P + pl.w); a.b1 = (const float*)(P + pl.b);
+                a.w2 = (const float*)(P + pl.w2); a.b2 = (const float*)(P + pl.b2);
+                a.scratch = (float*)(w.arena + w.layout.offset[pl.scratch]);
+                a.nb = w.batch; a.HW = ts.h * ts.w; a.c = o.cin; a.r = o.r;
+                L.flop = 4.0 * nb * o.cin * o.r;
+                L.bytes = nb * 3.0 * ts.h * ts.w * o.cin * es;
+                L.klass = prof_class(h, "se_kernels");
+                break;
+            }
+            default:
+                return ENS_E_INVALID;
+        }
+        w.launches.push_back(L);
+    }
+    return ENS_OK;
+}
+
+static void destroy_workers(ens_handle* h) {
+    for (Worker& w : h->workers) {
+        if (w.stream) (void)hipStreamSynchronize(w.stream);
+        if (w.arena) (void)hipFree(w.arena);
+        if (w.done) (void)hipEventDestroy(w.done);
+        if (w.stream) (void)hipStreamDestroy(w.stream);
+    }
+    h->workers.clear();
+    h->have_alloc = false;
+}
+
+static int64_t alloc_bytes(const ens_handle* h, const ens_alloc& a) {
+    int64_t total = 0;
+    for (const Member& m : h->members) total += (int64_t)m.weight_bytes();
+    for (int r = 0; r < a.rows; r++)
+        for (int c = 0; c < a.cols; c++)
+            if (a.batch[r][c] > 0) total += (int64_t)plan_arena(h->members[c], a.batch[r][c], h->keep_tensors).bytes;
+    return total;
+}
+
+static int install_alloc(ens_handle* h, const ens_alloc& a, int segment_size) {
+    const int M = (int)h->members.size();
+    if (a.rows <= 0 || a.rows > ENS_MAX_SLOTS || a.cols != M) return ENS_E_INVALID;
+    int max_batch = 0;
+    for (int c = 0; c < M; c++) {
+        bool any = false;
+        for (int r = 0; r < a.rows; r++) {
+            if (a.batch[r][c] < 0) return ENS_E_INVALID;
+            any = any || a.batch[r][c] > 0;
+            max_batch = std::max(max_batch, a.batch[r][c]);
+        }
+        if (!any) return ENS_E_INVALID;                          // a column of zeros is illegal
+    }
+    if (segment_size <= 0) segment_size = 128;
+    segment_size = std::max(segment_size, max_batch);           // segment >= the largest batch size
+    const int64_t need = alloc_bytes(h, a);
+    if (h->budget && (uint64_t)need > h->budget) return ENS_E_NOMEM;
+    destroy_workers(h);
+    for (int r = 0; r < a.rows; r++)
+        for (int c = 0; c < M; c++) {
+            if (a.batch[r][c] == 0) continue;
+            Worker w;
+            w.member = c; w.batch = a.batch[r][c]; w.slot = r;
+            w.layout = plan_arena(h->members[c], w.batch, h->keep_tensors);
+            w.arena_bytes = w.layout.bytes;
+            h->workers.push_back(w);
+        }
+    for (Worker& w : h->workers) {
+        hipError_t e = hipMalloc((void**)&w.arena, std::max<size_t>(w.arena_bytes, 256));
+        if (e == hipSuccess) e = hipStreamCreateWithFlags(&w.stream, hipStreamNonBlocking);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&w.done, hipEventDisableTiming);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            destroy_workers(h);
+            return e == hipErrorOutOfMemory ? ENS_E_NOMEM : ENS_E_HIP;
+        }
+        const int rc = build_launches(h, w);
+        if (rc != ENS_OK) { destroy_workers(h); return rc; }
+    }
+    h->alloc = a;
+    h->alloc.bytes = need;
+    h->segment_size = segment_size;
+    h->have_alloc = true;
+    return ENS_OK;
+}
+
+static hipEvent_t take_event(ens_handle* h) {
+    if (!h->event_pool.empty()) {
+        hipEvent_t e = h->event_pool.back();
+        h->event_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+static hipError_t issue(const Launch& L, const Member& m, hipStream_t s) {
+    switch (L.kind) {
+        case L_CONV: return m.bf16 ? launch_conv_bf16(L.conv, s) : launch_conv_f32(L.conv, s);
+        case L_DWCONV: return launch_dwconv(L.pool, m.bf16, s);
+        case L_POOL: return launch_pool(L.pool, L.is_max, m.bf16, s);
+        case L_GAP: return launch_gap(L.gap, m.bf16, s);
+        case L_FC: return launch_fc(L.fc, m.bf16, s);
+        case L_SE: return launch_se(L.se, m.bf16, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+// One batch of one worker: stage the images into the arena, run the member, write logits rows.
+static int forward_batch(ens_handle* h, Worker& w, const float* d_images, int64_t first, int nb) {
+    const Member& m = h->members[w.member];
+    StageArgs st;
+    st.src = d_images + (size_t)first * h->base_h * h->base_w * 3;
+    st.dst = w.arena + w.layout.offset[0];
+    st.nb = nb; st.sh = h->base_h; st.sw = h->base_w; st.dh = m.in_h; st.dw = m.in_w; st.dc = m.tensors[0].cs;
+    const double scale = (double)nb / w.batch;
+    auto timed = [&](int klass, double flop, double bytes, auto&& fn) -> hipError_t {
+        if (!h->profiling) return fn();
+        ProfRec r{klass, take_event(h), take_event(h), flop * scale, bytes * scale};
+        if (!r.start || !r.stop) return hipErrorOutOfMemory;
+        hipError_t e = hipEventRecord(r.start, w.stream);
+        if (e == hipSuccess) e = fn();
+        if (e == hipSuccess) e = hipEventRecord(r.stop, w.stream);
+        h->prof_recs.push_back(r);
+        return e;
+    };
+    static const std::string stage_name = "stage_kernel";
+    const double stage_bytes = (double)nb * (h->base_h * h->base_w * 12.0 + (double)m.in_h * m.in_w * st.dc * (m.bf16 ? 2 : 4));
+    HIP_TRY(timed(prof_class(h, stage_name), 0.0, stage_bytes / scale, [&] { return launch_stage(st, m.bf16, w.stream); }));
+    for (Launch& L0 : w.launches) {
+        Launch L = L0;
+        switch (L.kind) {
+            case L_CONV: L.conv.nb = nb; break;
+            case L_DWCONV:
+            case L_POOL: L.pool.nb = nb; break;
+            case L_GAP: L.gap.nb = nb; break;
+            case L_FC:
+                L.fc.nb = nb;
+                L.fc.y = h->d_logits[w.member] + (size_t)first * m.classes;
+                break;
+            case L_SE: L.se.nb = nb; break;
+        }
+        HIP_TRY(timed(L.klass, L.flop, L.bytes, [&] { return issue(L, m, w.stream); }));
+    }
+    w.last_nb = nb;
+    return ENS_OK;
+}
+
+static int ensure_buffers(ens_handle* h, int64_t n) {
+    const size_t rows = (size_t)n;
+    if (rows > h->d_logits_rows) {
+        for (float*& p : h->d_logits) {
+            if (p) (void)hipFree(p);
+            p = nullptr;
+        }
+        h->d_logits.assign(h->members.size(), nullptr);
+        h->d_logits_rows = 0;
+        for (size_t m = 0; m < h->members.size(); m++)
+            HIP_TRY(hipMalloc((void**)&h->d_logits[m], rows * h->members[m].classes * sizeof(float)));
+        h->d_logits_rows = rows;
+        if (!h->d_logit_ptrs) HIP_TRY(hipMalloc((void**)&h->d_logit_ptrs, ENS_MAX_MEMBERS * sizeof(float*)));
+        HIP_TRY(hipMemcpy((void*)h->d_logit_ptrs, h->d_logits.data(), h->members.size() * sizeof(float*), hipMemcpyHostToDevice));
+    }
+    return ENS_OK;
+}
+
+static int grow(float** p, size_t* cap, size_t want_floats) {
+    if (want_floats <= *cap) return ENS_OK;
+    if (*p) (void)hipFree(*p);
+    *p = nullptr;
+    *cap = 0;
+    HIP_TRY(hipMalloc((void**)p, want_floats * sizeof(float)));
+    *cap = want_floats;
+    return ENS_OK;
+}
+
+// f(X, A) -> Y with X and Y on the device.  `mask` selects the members that take part (all
+// members for a real request; a single member when the BBS baseline times it alone).
+static int run_device(ens_handle* h, const float* d_images, int64_t n, float* d_probs, uint64_t mask) {
+    if (n == 0) return ENS_OK;
+    int rc = ensure_buffers(h, n);
+    if (rc != ENS_OK) return rc;
+    const int M = (int)h->members.size();
+    const int seg = h->segment_size;
+    const int64_t n_seg = (n + seg - 1) / seg;
+    std::vector<std::vector<int>> of_member(M);
+    for (size_t i = 0; i < h->workers.size(); i++) of_member[h->workers[i].member].push_back((int)i);
+    // the workers start once the request images are in place on the main stream
+    HIP_TRY(hipEventRecord(h->input_ready, h->main_stream));
+    for (Worker& w : h->workers) HIP_TRY(hipStreamWaitEvent(w.stream, h->input_ready, 0));
+    // every segment id goes once to every member; a member's workers take its segments in turn
+    for (int64_t s = 0; s < n_seg; s++) {
+        const int64_t start = s * seg, end = std::min<int64_t>((s + 1) * seg, n);
+        for (int m = 0; m < M; m++) {
+            if (!((mask >> m) & 1)) continue;
+            Worker& w = h->workers[of_member[m][s % of_member[m].size()]];
+            for (int64_t a = start; a < end; a += w.batch) {
+                rc = forward_batch(h, w, d_images, a, (int)std::min<int64_t>(w.batch, end - a));
+                if (rc != ENS_OK) return rc;
+            }
+        }
+    }
+    for (Worker& w : h->workers) {
+        HIP_TRY(hipEventRecord(w.done, w.stream));
+        HIP_TRY(hipStreamWaitEvent(h->main_stream, w.done, 0));
+    }
+    if (mask == ~0ull || M == 1) {
+        ProfRec r{prof_class(h, "combine_kernel"), nullptr, nullptr, 0.0, (double)n * h->classes * 4.0 * (M + 1)};
+        if (h->profiling) {
+            r.start = take_event(h); r.stop = take_event(h);
+            if (!r.start || !r.stop) return ENS_E_HIP;
+            HIP_TRY(hipEventRecord(r.start, h->main_stream));
+        }
+        HIP_TRY(launch_combine(h->d_logit_ptrs, M, n, h->classes, d_probs, h->main_stream));
+        if (h->profiling) {
+            HIP_TRY(hipEventRecord(r.stop, h->main_stream));
+            h->prof_recs.push_back(r);
+        }
+    }
+    return ENS_OK;
+}
+
+static int finish_profile(ens_handle* h) {
+    for (ProfRec& r : h->prof_recs) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
+            ProfClass& c = h->prof[r.klass];
+            c.ms += ms; c.flop += r.flop; c.bytes += r.bytes; c.launches++;
+        }
+        h->event_pool.push_back(r.start);
+        h->event_pool.push_back(r.stop);
+    }
+    h->prof_recs.clear();
+    return ENS_OK;
+}
+
+static void reset_profile(ens_handle* h) {
+    for (ProfClass& c : h->prof) { c.ms = 0; c.flop = 0; c.bytes = 0; c.launches = 0; }
+}
+
+static int default_alloc(ens_handle* h) {
+    ens_alloc a;
+    memset(&a, 0, sizeof(a));
+    a.rows = 1;
+    a.cols = (int)h->members.size();
+    for (int c = 0; c < a.cols; c++) a.batch[0][c] = 8;
+    return install_alloc(h, a, 128);
+}
+
+static int ensure_calib(ens_handle* h, int64_t n) {
+    if ((size_t)n <= h->d_calib_images) return ENS_OK;
+    if (h->d_calib) (void)hipFree(h->d_calib);
+    h->d_calib = nullptr;
+    h->d_calib_images = 0;
+    const size_t count = (size_t)n * h->base_h * h->base_w * 3;
+    HIP_TRY(hipMalloc((void**)&h->d_calib, count * sizeof(float)));
+    HIP_TRY(launch_fill_noise(h->d_calib, (int64_t)count, 0x5EEDCA11Bull, h->main_stream));
+    HIP_TRY(hipStreamSynchronize(h->main_stream));
+    h->d_calib_images = (size_t)n;
+    return ENS_OK;
+}
+
+// Benchmark Mode on the installed allocation: median images/s of `repeats` runs after a warm-up.
+static int time_installed(ens_handle* h, int64_t n, int repeats, uint64_t mask, double* ips) {
+    int rc = ensure_calib(h, n);
+    if (rc != ENS_OK) return rc;
+    rc = grow(&h->d_probs, &h->d_probs_cap, (size_t)n * h->classes);
+    if (rc != ENS_OK) return rc;
+    std::vector<double> secs;
+    for (int i = 0; i < repeats + 1; i++) {
+        const auto t0 = std::chrono::steady_clock::now();
+        rc = run_device(h, h->d_calib, n, h->d_probs, mask);
+        if (rc != ENS_OK) return rc;
+        HIP_TRY(hipStreamSynchronize(h->main_stream));
+        const auto t1 = std::chrono::steady_clock::now();
+        if (i > 0) secs.push_back(std::chrono::duration<double>(t1 - t0).count());
+    }
+    if (h->profiling) finish_profile(h);
+    std::sort(secs.begin(), secs.end());
+    *ips = (double)n / secs[secs.size() / 2];
+    return ENS_OK;
+}
+
+}  // namespace ens
+
+// ------------------------------------------------------------------------------------ C API
+extern "C" {
+
+int ens_load(const ens_member_spec* specs, int32_t n_members, uint64_t seed, ens_handle** out) {
+    if (!specs || !out || n_members <= 0 || n_members > ENS_MAX_MEMBERS) return ENS_E_INVALID;
+    *out = nullptr;
+    ens_handle* h = new ens_handle();
+    memset(&h->alloc, 0, sizeof(h->alloc));
+    for (int i = 0; i < n_members; i++) {
+        const ens_member_spec& sp = specs[i];
+        std::vector<float> drawn;
+        const float* params = sp.params;
+        if (!params) {
+            if (!sp.param_specs || sp.n_params <= 0) { delete h; return ENS_E_INVALID; }
+            drawn.assign((size_t)sp.n_params, 0.f);
+            const int rc = draw_params(sp.param_specs, sp.n_param_specs, seed, i, drawn.data(), sp.n_params);
+            if (rc != ENS_OK) { delete h; return rc; }
+            params = drawn.data();
+        }
+        Member m;
+        const int rc = build_member(sp, params, &m);
+        if (rc != ENS_OK) { delete h; return rc; }
+        h->members.push_back(std::move(m));
+    }
+    h->classes = h->members[0].classes;
+    for (const Member& m : h->members)
+        if (m.classes != h->classes) { delete h; return ENS_E_INVALID; }
+    h->base_h = h->members[0].in_h;
+    h->base_w = h->members[0].in_w;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) {
+        (void)hipGetLastError();
+        delete h;
+        return ENS_E_NODEVICE;
+    }
+    auto fail = [&](int rc) { ens_free(h); return rc; };
+    for (Member& m : h->members) {
+        hipError_t e = hipMalloc((void**)&m.dev_params, std::max<size_t>(m.host_params.size(), 256));
+        if (e == hipSuccess)
+            e = hipMemcpy(m.dev_params, m.host_params.data(), m.host_params.size(), hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(e == hipErrorOutOfMemory ? ENS_E_NOMEM : ENS_E_HIP);
+        }
+    }
+    if (hipStreamCreateWithFlags(&h->main_stream, hipStreamNonBlocking) != hipSuccess) return fail(ENS_E_HIP);
+    if (hipEventCreateWithFlags(&h->input_ready, hipEventDisableTiming) != hipSuccess) return fail(ENS_E_HIP);
+    h->d_logits.assign(h->members.size(), nullptr);
+    *out = h;
+    return ENS_OK;
+}
+
+void ens_free(ens_handle* h) {
+    if (!h) return;
+    (void)hipDeviceSynchronize();
+    destroy_workers(h);
+    for (Member& m : h->members)
+        if (m.dev_params) (void)hipFree(m.dev_params);
+    for (float* p : h->d_logits)
+        if (p) (void)hipFree(p);
+    if (h->d_logit_ptrs) (void)hipFree((void*)h->d_logit_ptrs);
+    if (h->d_images) (void)hipFree(h->d_images);
+    if (h->d_probs) (void)hipFree(h->d_probs);
+    if (h->d_calib) (void)hipFree(h->d_calib);
+    for (ProfRec& r : h->prof_recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+    for (hipEvent_t e : h->event_pool) (void)hipEventDestroy(e);
+    if (h->input_ready) (void)hipEventDestroy(h->input_ready);
+    if (h->main_stream) (void)hipStreamDestroy(h->main_stream);
+    delete h;
+}
+
+int ens_set_io(ens_handle* h, int32_t base_h, int32_t base_w, int32_t images_on_device, int32_t probs_on_device) {
+    if (!h || base_h <= 0 || base_w <= 0) return ENS_E_INVALID;
+    if (base_h != h->base_h || base_w != h->base_w) {
+        if (h->d_calib) (void)hipFree(h->d_calib);
+        h->d_calib = nullptr;
+        h->d_calib_images = 0;
+    }
+    h->base_h = base_h;
+    h->base_w = base_w;
+    h->images_on_device = images_on_device != 0;
+    h->probs_on_device = probs_on_device != 0;
+    return ENS_OK;
+}
+
+int ens_set_alloc(ens_handle* h, const ens_alloc* a, int32_t segment_size) {
+    if (!h || !a) return ENS_E_INVALID;
+    return install_alloc(h, *a, segment_size);
+}
+
+int ens_predict(ens_handle* h, const float* images, int64_t n, float* probs_out) {
+    if (!h || n < 0 || (n > 0 && (!images || !probs_out))) return ENS_E_INVALID;
+    if (n == 0) return ENS_OK;
+    if (!h->have_alloc) {
+        const int rc = default_alloc(h);
+        if (rc != ENS_OK) return rc;
+    }
+    const auto t0 = std::chrono::steady_clock::now();
+    const size_t img_floats = (size_t)n * h->base_h * h->base_w * 3;
+    const float* d_in = images;
+    if (!h->images_on_device) {
+        int rc = grow(&h->d_images, &h->d_images_cap, img_floats);
+        if (rc != ENS_OK) return rc;
+        HIP_TRY(hipMemcpyAsync(h->d_images, images, img_floats * sizeof(float), hipMemcpyHostToDevice, h->main_stream));
+        d_in = h->d_images;
+    }
+    float* d_out = probs_out;
+    if (!h->probs_on_device) {
+        int rc = grow(&h->d_probs, &h->d_probs_cap, (size_t)n * h->classes);
+        if (rc != ENS_OK) return rc;
+        d_out = h->d_probs;
+    }
+    if (h->profiling) reset_profile(h);
+    int rc = run_device(h, d_in, n, d_out, ~0ull);
+    if (rc != ENS_OK) { (void)hipDeviceSynchronize(); return rc; }
+    if (!h->probs_on_device)
+        HIP_TRY(hipMemcpyAsync(probs_out, d_out, (size_t)n * h->classes * sizeof(float), hipMemcpyDeviceToHost, h->main_stream));
+    HIP_TRY(hipStreamSynchronize(h->main_stream));
+    if (h->profiling) finish_profile(h);
+    h->last_n = n;
+    h->last_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    return ENS_OK;
+}
+
+int ens_bench(ens_handle* h, const ens_alloc* a, int32_t segment_size, int64_t n_calib, int32_t repeats,
+              double* img_per_sec) {
+    if (!h || !a || !img_per_sec || n_calib <= 0) return ENS_E_INVALID;
+    if (repeats <= 0) repeats = 3;
+    *img_per_sec = 0.0;
+    int rc = install_alloc(h, *a, segment_size);
+    if (rc == ENS_E_NOMEM) return ENS_OK;                        // "0 if a DNN instance does not fit in memory"
+    if (rc != ENS_OK) return rc;
+    if (h->profiling) reset_profile(h);
+    return time_installed(h, n_calib, repeats, ~0ull, img_per_sec);
+}
+
+int ens_plan(ens_handle* h, uint64_t mem_budget_bytes, const ens_plan_opts* opts, ens_alloc* out) {
+    if (!h || !out) return ENS_E_INVALID;
+    ens_plan_opts o;
+    memset(&o, 0, sizeof(o));
+    if (opts) o = *opts;
+    if (o.n_domain <= 0) {
+        const int d[5] = {8, 16, 32, 64, 128};
+        o.n_domain = 5;
+        memcpy(o.domain, d, sizeof(d));
+    }
+    if (o.n_domain > ENS_MAX_DOMAIN) return ENS_E_INVALID;
+    if (o.default_batch <= 0) o.default_batch = *std::min_element(o.domain, o.domain + o.n_domain);
+    if (o.segment_size <= 0) o.segment_size = 128;
+    if (o.max_neighs <= 0) o.max_neighs = 100;
+    if (o.max_iter <= 0) o.max_iter = 10;
+    if (o.slots <= 0) o.slots = 1;
+    if (o.slots > ENS_MAX_SLOTS) return ENS_E_INVALID;
+    if (o.n_calib <= 0) o.n_calib = 1024;
+    if (o.repeats <= 0) o.repeats = 3;
+    const int M = (int)h->members.size();
+    if (mem_budget_bytes == 0) {
+        size_t fr = 0, tot = 0;
+        HIP_TRY(hipMemGetInfo(&fr, &tot));
+        mem_budget_bytes = tot;
+    }
+    h->budget = mem_budget_bytes;
+
+    std::vector<int64_t> wbytes(M), abytes((size_t)M * o.n_domain);
+    for (int m = 0; m < M; m++) {
+        wbytes[m] = (int64_t)h->members[m].weight_bytes();
+        for (int j = 0; j < o.n_domain; j++) abytes[(size_t)m * o.n_domain + j] = (int64_t)plan_arena(h->members[m], o.domain[j]).bytes;
+    }
+    std::vector<int32_t> row_pool(o.slots, 0), row_gpu(o.slots, 1);
+    // request buffers (images, logits, probabilities) come out of the same budget
+    int64_t reserve = (int64_t)o.n_calib * ((int64_t)h->base_h * h->base_w * 3 + (int64_t)h->classes * (M + 1)) * 4;
+    int64_t cap = (int64_t)mem_budget_bytes - reserve;
+    if (cap < 0) cap = 0;
+    ens_plan_problem p;
+    p.n_models = M; p.n_rows = o.slots; p.n_pools = 1; p.n_domain = o.n_domain;
+    p.domain = o.domain; p.default_batch = o.default_batch;
+    p.weight_bytes = wbytes.data(); p.arena_bytes = abytes.data();
+    p.row_pool = row_pool.data(); p.row_is_gpu = row_gpu.data(); p.pool_cap = &cap;
+    p.max_iter = o.max_iter; p.max_neighs = o.max_neighs; p.seed = o.seed;
+    if (!problem_ok(&p)) return ENS_E_INVALID;
+
+    std::vector<int32_t> A((size_t)o.slots * M, 0);
+    int rc = wfd(p, A.data());
+    if (rc != ENS_OK) return rc;
+    auto to_alloc = [&](const int32_t* mat) {
+        ens_alloc a;
+        memset(&a, 0, sizeof(a));
+        a.rows = o.slots; a.cols = M;
+        for (int r = 0; r < o.slots; r++)
+            for (int c = 0; c < M; c++) a.batch[r][c] = mat[r * M + c];
+        return a;
+    };
+    int hip_rc = ENS_OK;
+    auto bench = [&](const int32_t* mat) -> double {
+        if (!fit_mem(p, mat)) return 0.0;
+        const ens_alloc a = to_alloc(mat);
+        double ips = 0.0;
+        const int r = ens_bench(h, &a, o.segment_size, o.n_calib, o.repeats, &ips);
+        if (r != ENS_OK) { hip_rc = r; return 0.0; }
+        return ips;
+    };
+    double score = 0.0;
+    int32_t n_bench = 0;
+    if (o.strategy == 0) {
+        rc = greedy(p, A.data(), bench, &score, &n_bench);
+    } else if (o.strategy == 1) {
+        score = bench(A.data());
+        n_bench = 1;
+    } else if (o.strategy == 2) {
+        // each member alone on the GPU, its batch size scanned; then the combined matrix is timed
+        std::vector<int32_t> best(M, o.default_batch);
+        auto single = [&](int m, int b) -> double {
+            std::vector<int32_t> mat((size_t)o.slots * M, 0);
+            for (int c = 0; c < M; c++) mat[c] = c == m ? b : o.default_batch;
+            if (!fit_mem(p, mat.data())) return 0.0;
+            const ens_alloc a = to_alloc(mat.data());
+            int r = install_alloc(h, a, o.segment_size);
+            if (r == ENS_E_NOMEM) return 0.0;
+            if (r != ENS_OK) { hip_rc = r; return 0.0; }
+            double ips = 0.0;
+            r = time_installed(h, o.n_calib, o.repeats, 1ull << m, &ips);
+            if (r != ENS_OK) { hip_rc = r; return 0.0; }
+            return ips;
+        };
+        rc = bbs(p, single, best.data(), &n_bench);
+        std::fill(A.begin(), A.end(), 0);
+        for (int c = 0; c < M; c++) A[c] = best[c];
+        score = bench(A.data());
+    } else {
+        return ENS_E_INVALID;
+    }
+    if (rc != ENS_OK) return rc;
+    if (hip_rc != ENS_OK) return hip_rc;
+    ens_alloc a = to_alloc(A.data());
+    rc = install_alloc(h, a, o.segment_size);
+    if (rc != ENS_OK) return rc;
+    *out = h->alloc;
+    out->score = score;
+    out->n_bench = n_bench;
+    h->alloc = *out;
+    return ENS_OK;
+}
+
+int ens_member_logits(ens_handle* h, int32_t member, int64_t n, float* logits_out) {
+    if (!h || member < 0 || member >= (int)h->members.size() || !logits_out) return ENS_E_INVALID;
+    if (n <= 0 || n > h->last_n || (size_t)n > h->d_logits_rows) return ENS_E_INVALID;
+    HIP_TRY(hipMemcpy(logits_out, h->d_logits[member], (size_t)n * h->members[member].classes * sizeof(float),
+                      hipMemcpyDeviceToHost));
+    return ENS_OK;
+}
+
+int ens_debug_tensor(ens_handle* h, int32_t member, int32_t tensor, int32_t n_images, float* out) {
+    if (!h || !out || member < 0 || member >= (int)h->members.size()) return ENS_E_INVALID;
+    const Member& m = h->members[member];
+    if (tensor < 0 || tensor >= (int)m.tensors.size() || m.tensors[tensor].external) return ENS_E_INVALID;
+    const Worker* w = nullptr;
+    for (const Worker& x : h->workers)
+        if (x.member == member) { w = &x; break; }
+    if (!w || n_images <= 0 || n_images > w->last_nb) return ENS_E_INVALID;
+    const TensorInfo& ti = m.tensors[tensor];
+    const size_t elems = (size_t)n_images * ti.elems_per_image();
+    std::vector<uint8_t> raw(elems * (ti.f32 ? 4 : 2));
+    HIP_TRY(hipMemcpy(raw.data(), w->arena + w->layout.offset[tensor], raw.size(), hipMemcpyDeviceToHost));
+    const size_t pixels = (size_t)n_images * ti.h * ti.w;
+    for (size_t p = 0; p < pixels; p++)
+        for (int c = 0; c < ti.c; c++) {
+            float v;
+            if (ti.f32) {
+                v = ((const float*)raw.data())[p * ti.cs + c];
+            } else {
+                const uint32_t u = ((uint32_t)((const uint16_t*)raw.data())[p * ti.cs + c]) << 16;
+                memcpy(&v, &u, 4);
+            }
+            out[p * ti.c + c] = v;
+        }
+    return ENS_OK;
+}
+
+int ens_debug_keep_tensors(ens_handle* h, int32_t on) {
+    if (!h) return ENS_E_INVALID;
+    h->keep_tensors = on != 0;
+    return ENS_OK;
+}
+
+int ens_classes(const ens_handle* h) { return h ? h->classes : ENS_E_INVALID; }
+int ens_n_members(const ens_handle* h) { return h ? (int)h->members.size() : ENS_E_INVALID; }
+
+int ens_member_bytes(const ens_handle* h, int32_t member, int32_t batch, int64_t* weight_bytes, int64_t* arena_bytes) {
+    if (!h || member < 0 || member >= (int)h->members.size() || batch <= 0) return ENS_E_INVALID;
+    if (weight_bytes) *weight_bytes = (int64_t)h->members[member].weight_bytes();
+    if (arena_bytes) *arena_bytes = (int64_t)plan_arena(h->members[member], batch).bytes;
+    return ENS_OK;
+}
+
+int ens_spec_bytes(const ens_member_spec* spec, int32_t batch, int64_t* weight_bytes, int64_t* arena_bytes) {
+    if (!spec || batch <= 0) return ENS_E_INVALID;
+    std::vector<float> zeros;
+    const float* params = spec->params;
+    if (!params) {
+        if (spec->n_params <= 0) return ENS_E_INVALID;
+        zeros.assign((size_t)spec->n_params, 0.f);
+        params = zeros.data();
+    }
+    Member m;
+    const int rc = build_member(*spec, params, &m);
+    if (rc != ENS_OK) return rc;
+    if (weight_bytes) *weight_bytes = (int64_t)m.weight_bytes();
+    if (arena_bytes) *arena_bytes = (int64_t)plan_arena(m, batch).bytes;
+    return ENS_OK;
+}
+
+int ens_set_profiling(ens_handle* h, int32_t on) {
+    if (!h) return ENS_E_INVALID;
+    h->profiling = on != 0;
+    return ENS_OK;
+}
+
+int ens_profile_get(const ens_handle* h, int32_t idx, char* name, int32_t name_len, double* ms, int64_t* launches,
+                    double* flop, double* bytes) {
+    if (!h || idx < 0 || idx >= (int)h->prof.size()) return ENS_E_INVALID;
+    const ProfClass& c = h->prof[idx];
+    if (name && name_len > 0) {
+        strncpy(name, c.name.c_str(), (size_t)name_len - 1);
+        name[name_len - 1] = 0;
+    }
+    if (ms) *ms = c.ms;
+    if (launches) *launches = c.launches;
+    if (flop) *flop = c.flop;
+    if (bytes) *bytes = c.bytes;
+    return ENS_OK;
+}
+
+double ens_last_ms(const ens_handle* h) { return h ? h->last_ms : 0.0; }
+
+const char* ens_strerror(int status) {
+    switch (status) {
+        case ENS_OK: return "ok";
+        case ENS_E_INVALID: return "invalid description, matrix or argument";
+        case ENS_E_NOMEM: return "not enough device memory for a member or worker";
+        case ENS_E_NOFIT: return "no device has enough memory for a member";
+        case ENS_E_HIP: return "HIP runtime error";
+        case ENS_E_NODEVICE: return "no GPU visible";
+        case ENS_E_UNSUPPORTED: return "shape not covered by the GPU kernels";
+    }
+    return "unknown status";
+}
+
+const char* ens_version(void) { return "ens-mi355x 0.1 (gfx950)"; }
+
+}  // extern "C"

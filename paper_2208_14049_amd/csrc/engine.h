@@ -1,0 +1,114 @@
+// The inference-system core on one GPU: members resident in HBM, workers (one per non-zero
+// cell of the allocation matrix) with their own stream and activation arena, the segment /
+// batch partition of a request and the fused combination kernel.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/ens.h"
+#include "kernels.h"
+
+namespace ens {
+
+struct TensorInfo {
+    int h, w, c;
+    int cs;          // stored channels (bf16 tensors are padded to a multiple of 8)
+    bool f32;        // stored as fp32
+    int def, last;   // first writing / last reading operation (-1: written by the input staging)
+    bool external;   // the logits tensor lives in the member's logits buffer, not in an arena
+    size_t elems_per_image() const { return (size_t)h * w * cs; }
+    size_t bytes(int batch) const { return (size_t)batch * elems_per_image() * (f32 ? 4 : 2); }
+};
+
+struct OpPlan {
+    ens_op op;
+    // byte offsets into the member's device parameter block (SIZE_MAX: absent)
+    size_t w, b, pre_scale, pre_shift, w2, b2;
+    int cin_s;       // stored input channels of the convolution's K axis
+    int scratch;     // index of the scratch pseudo-tensor (squeeze-excite), -1 otherwise
+};
+
+struct Member {
+    bool bf16 = false;
+    int in_h = 0, in_w = 0, classes = 0, out_tensor = -1;
+    std::vector<TensorInfo> tensors;     // description tensors, then scratch pseudo-tensors
+    std::vector<OpPlan> ops;
+    std::vector<uint8_t> host_params;    // folded, converted, laid out for the device
+    char* dev_params = nullptr;
+    size_t weight_bytes() const { return host_params.size(); }
+};
+
+struct ArenaLayout {
+    std::vector<size_t> offset;          // per tensor (unused for external ones)
+    size_t bytes = 0;
+};
+
+// Builds the device-side form of a member from its description.  Host only.
+int build_member(const ens_member_spec& spec, const float* params, Member* out);
+// Places the member's tensors for `batch` images by liveness; host only.
+// keep_all gives every tensor its own region (debug read-back of intermediate tensors).
+ArenaLayout plan_arena(const Member& m, int batch, bool keep_all = false);
+
+enum LaunchKind { L_CONV, L_DWCONV, L_POOL, L_GAP, L_FC, L_SE };
+
+struct Launch {
+    int kind = 0;
+    bool is_max = false;
+    int klass = 0;                 // profile class
+    double flop = 0, bytes = 0;    // algorithmic work of the full-batch launch
+    ConvArgs conv;
+    PoolArgs pool;
+    GapArgs gap;
+    FcArgs fc;
+    SeArgs se;
+};
+
+struct Worker {
+    int member = 0, batch = 0, slot = 0;
+    hipStream_t stream = nullptr;
+    hipEvent_t done = nullptr;
+    char* arena = nullptr;
+    size_t arena_bytes = 0;
+    ArenaLayout layout;
+    std::vector<Launch> launches;
+    int last_nb = 0;
+};
+
+struct ProfClass {
+    std::string name;
+    double ms = 0, flop = 0, bytes = 0;
+    int64_t launches = 0;
+};
+
+struct ProfRec { int klass; hipEvent_t start, stop; double flop, bytes; };
+
+}  // namespace ens
+
+struct ens_handle {
+    std::vector<ens::Member> members;
+    std::vector<ens::Worker> workers;
+    ens_alloc alloc;
+    bool have_alloc = false;
+    int segment_size = 128;
+    int base_h = 0, base_w = 0, classes = 0;
+    bool images_on_device = false, probs_on_device = false;
+    uint64_t budget = 0;                         // 0: whatever the device has
+    hipStream_t main_stream = nullptr;
+    hipEvent_t input_ready = nullptr;
+    // request buffers, grown on demand
+    float* d_images = nullptr;  size_t d_images_cap = 0;
+    float* d_probs = nullptr;   size_t d_probs_cap = 0;
+    std::vector<float*> d_logits; size_t d_logits_rows = 0;
+    const float** d_logit_ptrs = nullptr;
+    float* d_calib = nullptr;   size_t d_calib_images = 0;
+    int64_t last_n = 0;
+    double last_ms = 0;
+    // profiling
+    bool profiling = false;
+    bool keep_tensors = false;                   // debug: no reuse of arena regions
+    std::vector<ens::ProfClass> prof;
+    std::vector<ens::ProfRec> prof_recs;
+    std::vector<hipEvent_t> event_pool;
+};

@@ -1,0 +1,92 @@
+// Device kernels of the ensemble library: argument blocks and host-side launchers.
+// Every launcher validates what its kernel assumes and returns hipErrorInvalidValue
+// instead of launching when a shape does not fit.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ens {
+
+typedef uint16_t bf16_t;   // raw bf16 bits in memory
+
+enum { ACT_NONE = 0, ACT_RELU = 1, ACT_SILU = 2 };
+
+// A slice [c0, c0 + c) of the channels of an NHWC tensor whose pixels are `stride` elements apart.
+struct View {
+    void* p;
+    int stride;
+    int c0;
+};
+
+// Convolution (and its fused epilogue) over a batch of `nb` images.
+//   y[n, ho, wo, co] = act( sum_{kh,kw,ci} pre(x[n, ho*sh-pt+kh, wo*sw-pl+kw, ci]) * w[co][kh][kw][ci]
+//                           + bias[co] + res[n, ho, wo, co] )
+// Weights are stored [cout][kh][kw][cin] (K contiguous per output channel) with the batch-norm
+// folded in; bias is fp32.  pre_scale / pre_shift (fp32, per input channel) apply
+// relu(x * scale + shift) to in-bounds inputs when non-null.
+struct ConvArgs {
+    View x, y, res;            // res.p == nullptr: no residual
+    const void* w;
+    const float* bias;         // never null (zeros when the layer has none)
+    const float* pre_scale;
+    const float* pre_shift;
+    int nb, H, W, cin, Ho, Wo, cout;
+    int kh, kw, sh, sw, pt, pl;
+    int act;
+};
+
+struct PoolArgs {              // max / average pooling, depthwise convolution
+    View x, y;
+    const void* w;             // depthwise: [kh][kw][c] in the member's dtype, folded
+    const float* bias;         // depthwise only
+    int nb, H, W, c, Ho, Wo;
+    int kh, kw, sh, sw, pt, pl;
+    int act;
+};
+
+struct GapArgs {               // global average pool to fp32 [nb][c]
+    View x;
+    float* y;
+    const float* pre_scale;
+    const float* pre_shift;
+    int nb, HW, c;
+};
+
+struct FcArgs {                // logits[n][cout] = pooled[n][cin] . W[cin][cout] + bias
+    const float* x;
+    const void* w;             // [cin][cout] in the member's dtype
+    const float* bias;
+    float* y;                  // row stride ldy
+    int nb, cin, cout;
+    int64_t ldy;
+};
+
+struct SeArgs {                // squeeze-excite
+    View x, y;
+    const float* w1; const float* b1; const float* w2; const float* b2;   // fp32
+    float* scratch;            // nb * (c + r + c) floats
+    int nb, HW, c, r;
+};
+
+struct StageArgs {             // request images -> a worker's input tensor (convert, pad, resize)
+    const float* src;          // nb x sh x sw x 3 fp32 (first image of the batch)
+    void* dst;                 // nb x dh x dw x dc, dtype of the member
+    int nb, sh, sw, dh, dw, dc;
+};
+
+hipError_t launch_conv_bf16(const ConvArgs& a, hipStream_t s);
+hipError_t launch_conv_f32(const ConvArgs& a, hipStream_t s);
+hipError_t launch_dwconv(const PoolArgs& a, bool bf16, hipStream_t s);
+hipError_t launch_pool(const PoolArgs& a, bool is_max, bool bf16, hipStream_t s);
+hipError_t launch_gap(const GapArgs& a, bool bf16, hipStream_t s);
+hipError_t launch_fc(const FcArgs& a, bool bf16, hipStream_t s);
+hipError_t launch_se(const SeArgs& a, bool bf16, hipStream_t s);
+hipError_t launch_stage(const StageArgs& a, bool bf16, hipStream_t s);
+// Y[i, :] = sum_m softmax(logits_m[i, :]) / M ; logits: n_members pointers (device array).
+hipError_t launch_combine(const float* const* logits, int n_members, int64_t n, int classes,
+                          float* y, hipStream_t s);
+hipError_t launch_fill_noise(float* p, int64_t count, uint64_t seed, hipStream_t s);
+
+double conv_flops(const ConvArgs& a);
+
+}  // namespace ens

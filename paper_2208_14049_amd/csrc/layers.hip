@@ -1,0 +1,433 @@
+// Bandwidth-bound layers and the fp32 reference-precision convolution:
+// input staging (convert / pad / bilinear resize), depthwise convolution, pooling, global
+// average pool, squeeze-excite, the FC head and the fused softmax-and-mean combination.
+// Activations are NHWC; the bf16 kernels move 8 channels (16 bytes) per lane so that a
+// wavefront reads and writes whole 128-byte lines; all arithmetic is fp32.
+#include "kernels.h"
+
+namespace ens {
+
+__device__ __forceinline__ float bf2f(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+__device__ __forceinline__ uint16_t f2bf(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float act_f(float v, int act) {
+    if (act == ACT_RELU) return fmaxf(v, 0.f);
+    if (act == ACT_SILU) return v / (1.f + __expf(-v));
+    return v;
+}
+__device__ __forceinline__ void unpack8(const uint4 v, float* f) {
+    const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+        f[2 * e] = bf2f((uint16_t)(u[e] & 0xFFFF));
+        f[2 * e + 1] = bf2f((uint16_t)(u[e] >> 16));
+    }
+}
+__device__ __forceinline__ uint4 pack8(const float* f) {
+    uint32_t u[4];
+#pragma unroll
+    for (int e = 0; e < 4; e++) u[e] = (uint32_t)f2bf(f[2 * e]) | ((uint32_t)f2bf(f[2 * e + 1]) << 16);
+    return make_uint4(u[0], u[1], u[2], u[3]);
+}
+
+static inline int blocks_for(long long work, int threads) { return (int)((work + threads - 1) / threads); }
+
+// ------------------------------------------------------------------ input staging
+// One thread per destination pixel: bilinear sample (half-pixel centres, edge clamp) of the three
+// source channels, written as dc channels (zero padded) in the member's dtype.
+template <bool BF16>
+__global__ void stage_kernel(const StageArgs a) {
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long total = (long long)a.nb * a.dh * a.dw;
+    if (idx >= total) return;
+    const int x = (int)(idx % a.dw);
+    const int y = (int)((idx / a.dw) % a.dh);
+    const long long n = idx / ((long long)a.dw * a.dh);
+    const float* src = a.src + n * (long long)a.sh * a.sw * 3;
+    float v[3];
+    if (a.sh == a.dh && a.sw == a.dw) {
+        const float* p = src + ((long long)y * a.sw + x) * 3;
+        v[0] = p[0]; v[1] = p[1]; v[2] = p[2];
+    } else {
+        float fy = (y + 0.5f) * ((float)a.sh / (float)a.dh) - 0.5f;
+        float fx = (x + 0.5f) * ((float)a.sw / (float)a.dw) - 0.5f;
+        fy = fminf(fmaxf(fy, 0.f), (float)(a.sh - 1));
+        fx = fminf(fmaxf(fx, 0.f), (float)(a.sw - 1));
+        const int y0 = (int)floorf(fy), x0 = (int)floorf(fx);
+        const int y1 = min(y0 + 1, a.sh - 1), x1 = min(x0 + 1, a.sw - 1);
+        const float wy = fy - y0, wx = fx - x0;
+#pragma unroll
+        for (int c = 0; c < 3; c++) {
+            const float p00 = src[((long long)y0 * a.sw + x0) * 3 + c], p01 = src[((long long)y0 * a.sw + x1) * 3 + c];
+            const float p10 = src[((long long)y1 * a.sw + x0) * 3 + c], p11 = src[((long long)y1 * a.sw + x1) * 3 + c];
+            const float top = p00 * (1.f - wx) + p01 * wx, bot = p10 * (1.f - wx) + p11 * wx;
+            v[c] = top * (1.f - wy) + bot * wy;
+        }
+    }
+    if (BF16) {
+        uint16_t* d = (uint16_t*)a.dst + idx * a.dc;
+        if (a.dc == 8) {
+            const float f[8] = {v[0], v[1], v[2], 0.f, 0.f, 0.f, 0.f, 0.f};
+            *(uint4*)d = pack8(f);
+        } else {
+            for (int c = 0; c < a.dc; c++) d[c] = c < 3 ? f2bf(v[c]) : (uint16_t)0;
+        }
+    } else {
+        float* d = (float*)a.dst + idx * a.dc;
+        for (int c = 0; c < a.dc; c++) d[c] = c < 3 ? v[c] : 0.f;
+    }
+}
+
+hipError_t launch_stage(const StageArgs& a, bool bf16, hipStream_t s) {
+    if (a.nb <= 0 || a.dc < 3) return hipErrorInvalidValue;
+    const long long total = (long long)a.nb * a.dh * a.dw;
+    if (bf16) hipLaunchKernelGGL(stage_kernel<true>, dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(stage_kernel<false>, dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ fp32 convolution
+// Reference-precision path (fp32 members): one thread per output element, taps and input
+// channels accumulated in the order kh, kw, ci.  Weights [cout][kh][kw][cin] fp32.
+__global__ void conv_f32_kernel(const ConvArgs a) {
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long total = (long long)a.nb * a.Ho * a.Wo * a.cout;
+    if (idx >= total) return;
+    const int co = (int)(idx % a.cout);
+    const long long p = idx / a.cout;
+    const int wo = (int)(p % a.Wo), ho = (int)((p / a.Wo) % a.Ho);
+    const long long n = p / ((long long)a.Wo * a.Ho);
+    const float* x = (const float*)a.x.p + n * (long long)a.H * a.W * a.x.stride + a.x.c0;
+    const float* w = (const float*)a.w + (long long)co * a.kh * a.kw * a.cin;
+    float acc = 0.f;
+    for (int kh = 0; kh < a.kh; kh++) {
+        const int hi = ho * a.sh - a.pt + kh;
+        if (hi < 0 || hi >= a.H) continue;
+        for (int kw = 0; kw < a.kw; kw++) {
+            const int wi = wo * a.sw - a.pl + kw;
+            if (wi < 0 || wi >= a.W) continue;
+            const float* px = x + ((long long)hi * a.W + wi) * a.x.stride;
+            const float* wk = w + (kh * a.kw + kw) * a.cin;
+            for (int ci = 0; ci < a.cin; ci++) {
+                float v = px[ci];
+                if (a.pre_scale) v = fmaxf(v * a.pre_scale[ci] + a.pre_shift[ci], 0.f);
+                acc = fmaf(v, wk[ci], acc);
+            }
+        }
+    }
+    acc += a.bias[co];
+    if (a.res.p) acc += ((const float*)a.res.p)[p * a.res.stride + a.res.c0 + co];
+    ((float*)a.y.p)[p * a.y.stride + a.y.c0 + co] = act_f(acc, a.act);
+}
+
+hipError_t launch_conv_f32(const ConvArgs& a, hipStream_t s) {
+    if (a.nb <= 0 || a.cin <= 0 || a.cout <= 0 || !a.bias) return hipErrorInvalidValue;
+    const long long total = (long long)a.nb * a.Ho * a.Wo * a.cout;
+    if (total >= (1LL << 31) * 256) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(conv_f32_kernel, dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ depthwise conv / pooling
+// MODE 0: depthwise convolution (+bias, activation), 1: max pool, 2: average pool over the
+// in-bounds part of the window.  bf16: one lane per (pixel, 8 channels); fp32: per element.
+template <int MODE, bool BF16>
+__global__ void window_kernel(const PoolArgs a) {
+    constexpr int V = BF16 ? 8 : 1;
+    const int cv = a.c / V;
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long total = (long long)a.nb * a.Ho * a.Wo * cv;
+    if (idx >= total) return;
+    const int c = (int)(idx % cv) * V;
+    const long long p = idx / cv;
+    const int wo = (int)(p % a.Wo), ho = (int)((p / a.Wo) % a.Ho);
+    const long long n = p / ((long long)a.Wo * a.Ho);
+    float acc[V];
+#pragma unroll
+    for (int e = 0; e < V; e++) acc[e] = MODE == 1 ? -3.0e38f : 0.f;
+    int cnt = 0;
+    for (int kh = 0; kh < a.kh; kh++) {
+        const int hi = ho * a.sh - a.pt + kh;
+        if (hi < 0 || hi >= a.H) continue;
+        for (int kw = 0; kw < a.kw; kw++) {
+            const int wi = wo * a.sw - a.pl + kw;
+            if (wi < 0 || wi >= a.W) continue;
+            const long long off = ((n * a.H + hi) * a.W + wi) * (long long)a.x.stride + a.x.c0 + c;
+            float xv[V], wv[V];
+            if (BF16) {
+                unpack8(*(const uint4*)((const uint16_t*)a.x.p + off), xv);
+                if (MODE == 0) unpack8(*(const uint4*)((const uint16_t*)a.w + (long long)(kh * a.kw + kw) * a.c + c), wv);
+            } else {
+                xv[0] = ((const float*)a.x.p)[off];
+                if (MODE == 0) wv[0] = ((const float*)a.w)[(long long)(kh * a.kw + kw) * a.c + c];
+            }
+#pragma unroll
+            for (int e = 0; e < V; e++) {
+                if (MODE == 0) acc[e] = fmaf(xv[e], wv[e], acc[e]);
+                else if (MODE == 1) acc[e] = fmaxf(acc[e], xv[e]);
+                else acc[e] += xv[e];
+            }
+            cnt++;
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < V; e++) {
+        if (MODE == 0) acc[e] = act_f(acc[e] + a.bias[c + e], a.act);
+        else if (MODE == 2) acc[e] = cnt ? acc[e] / (float)cnt : 0.f;
+        else if (cnt == 0) acc[e] = 0.f;
+    }
+    const long long yoff = p * (long long)a.y.stride + a.y.c0 + c;
+    if (BF16) *(uint4*)((uint16_t*)a.y.p + yoff) = pack8(acc);
+    else ((float*)a.y.p)[yoff] = acc[0];
+}
+
+static hipError_t check_window(const PoolArgs& a, bool bf16) {
+    if (a.nb <= 0 || a.c <= 0) return hipErrorInvalidValue;
+    if (bf16 && (a.c % 8 || a.x.stride % 8 || a.x.c0 % 8 || a.y.stride % 8 || a.y.c0 % 8)) return hipErrorInvalidValue;
+    return hipSuccess;
+}
+
+hipError_t launch_dwconv(const PoolArgs& a, bool bf16, hipStream_t s) {
+    if (check_window(a, bf16) != hipSuccess || !a.w || !a.bias) return hipErrorInvalidValue;
+    const long long total = (long long)a.nb * a.Ho * a.Wo * (a.c / (bf16 ? 8 : 1));
+    if (bf16) hipLaunchKernelGGL((window_kernel<0, true>), dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((window_kernel<0, false>), dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_pool(const PoolArgs& a, bool is_max, bool bf16, hipStream_t s) {
+    if (check_window(a, bf16) != hipSuccess) return hipErrorInvalidValue;
+    const long long total = (long long)a.nb * a.Ho * a.Wo * (a.c / (bf16 ? 8 : 1));
+    const dim3 g(blocks_for(total, 256)), b(256);
+    if (is_max) {
+        if (bf16) hipLaunchKernelGGL((window_kernel<1, true>), g, b, 0, s, a);
+        else hipLaunchKernelGGL((window_kernel<1, false>), g, b, 0, s, a);
+    } else {
+        if (bf16) hipLaunchKernelGGL((window_kernel<2, true>), g, b, 0, s, a);
+        else hipLaunchKernelGGL((window_kernel<2, false>), g, b, 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ global average pool
+// One thread per (image, channel); consecutive lanes take consecutive channels.
+template <bool BF16>
+__global__ void gap_kernel(const GapArgs a) {
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long long)a.nb * a.c) return;
+    const int c = (int)(idx % a.c);
+    const long long n = idx / a.c;
+    float sc = 1.f, sf = 0.f;
+    const bool pre = a.pre_scale != nullptr;
+    if (pre) { sc = a.pre_scale[c]; sf = a.pre_shift[c]; }
+    float acc = 0.f;
+    for (int p = 0; p < a.HW; p++) {
+        const long long off = (n * a.HW + p) * (long long)a.x.stride + a.x.c0 + c;
+        float v = BF16 ? bf2f(((const uint16_t*)a.x.p)[off]) : ((const float*)a.x.p)[off];
+        if (pre) v = fmaxf(v * sc + sf, 0.f);
+        acc += v;
+    }
+    a.y[idx] = acc / (float)a.HW;
+}
+
+hipError_t launch_gap(const GapArgs& a, bool bf16, hipStream_t s) {
+    if (a.nb <= 0 || a.c <= 0 || a.HW <= 0) return hipErrorInvalidValue;
+    const long long total = (long long)a.nb * a.c;
+    if (bf16) hipLaunchKernelGGL(gap_kernel<true>, dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(gap_kernel<false>, dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ FC head
+// One thread per (image, class); lanes run along the classes so the weight rows are read
+// coalesced; the pooled features of the image are broadcast reads.
+template <bool BF16>
+__global__ void fc_kernel(const FcArgs a) {
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long long)a.nb * a.cout) return;
+    const int co = (int)(idx % a.cout);
+    const long long n = idx / a.cout;
+    const float* x = a.x + n * a.cin;
+    float acc = 0.f;
+    for (int ci = 0; ci < a.cin; ci++) {
+        const long long off = (long long)ci * a.cout + co;
+        const float w = BF16 ? bf2f(((const uint16_t*)a.w)[off]) : ((const float*)a.w)[off];
+        acc = fmaf(x[ci], w, acc);
+    }
+    a.y[n * a.ldy + co] = acc + a.bias[co];
+}
+
+hipError_t launch_fc(const FcArgs& a, bool bf16, hipStream_t s) {
+    if (a.nb <= 0 || a.cin <= 0 || a.cout <= 0 || !a.bias) return hipErrorInvalidValue;
+    const long long total = (long long)a.nb * a.cout;
+    if (bf16) hipLaunchKernelGGL(fc_kernel<true>, dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(fc_kernel<false>, dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ squeeze-excite
+// Three small kernels on the worker's stream: channel means, the two tiny FC layers (one
+// workgroup per image), then the channel-wise rescale of the activation tensor.
+template <bool BF16>
+__global__ void se_mean_kernel(const SeArgs a) {
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long long)a.nb * a.c) return;
+    const int c = (int)(idx % a.c);
+    const long long n = idx / a.c;
+    float acc = 0.f;
+    for (int p = 0; p < a.HW; p++) {
+        const long long off = (n * a.HW + p) * (long long)a.x.stride + a.x.c0 + c;
+        acc += BF16 ? bf2f(((const uint16_t*)a.x.p)[off]) : ((const float*)a.x.p)[off];
+    }
+    a.scratch[n * (2 * a.c + a.r) + c] = acc / (float)a.HW;
+}
+
+__global__ void se_gate_kernel(const SeArgs a) {
+    const int n = blockIdx.x;
+    float* s = a.scratch + (long long)n * (2 * a.c + a.r);
+    float* z = s + a.c;
+    float* g = z + a.r;
+    for (int r = threadIdx.x; r < a.r; r += blockDim.x) {
+        float acc = 0.f;
+        for (int c = 0; c < a.c; c++) acc = fmaf(s[c], a.w1[(long long)c * a.r + r], acc);
+        acc += a.b1[r];
+        z[r] = acc / (1.f + __expf(-acc));
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < a.c; c += blockDim.x) {
+        float acc = 0.f;
+        for (int r = 0; r < a.r; r++) acc = fmaf(z[r], a.w2[(long long)r * a.c + c], acc);
+        acc += a.b2[c];
+        g[c] = 1.f / (1.f + __expf(-acc));
+    }
+}
+
+template <bool BF16>
+__global__ void se_scale_kernel(const SeArgs a) {
+    constexpr int V = BF16 ? 8 : 1;
+    const int cv = a.c / V;
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long long)a.nb * a.HW * cv) return;
+    const int c = (int)(idx % cv) * V;
+    const long long p = idx / cv;
+    const long long n = p / a.HW;
+    const float* g = a.scratch + n * (2 * a.c + a.r) + a.c + a.r + c;
+    const long long xo = p * (long long)a.x.stride + a.x.c0 + c, yo = p * (long long)a.y.stride + a.y.c0 + c;
+    if (BF16) {
+        float f[8];
+        unpack8(*(const uint4*)((const uint16_t*)a.x.p + xo), f);
+#pragma unroll
+        for (int e = 0; e < 8; e++) f[e] *= g[e];
+        *(uint4*)((uint16_t*)a.y.p + yo) = pack8(f);
+    } else {
+        ((float*)a.y.p)[yo] = ((const float*)a.x.p)[xo] * g[0];
+    }
+}
+
+hipError_t launch_se(const SeArgs& a, bool bf16, hipStream_t s) {
+    if (a.nb <= 0 || a.c <= 0 || a.r <= 0 || !a.scratch) return hipErrorInvalidValue;
+    if (bf16 && (a.c % 8 || a.x.stride % 8 || a.x.c0 % 8 || a.y.stride % 8 || a.y.c0 % 8)) return hipErrorInvalidValue;
+    const long long nc = (long long)a.nb * a.c;
+    const long long tot = (long long)a.nb * a.HW * (a.c / (bf16 ? 8 : 1));
+    if (bf16) hipLaunchKernelGGL(se_mean_kernel<true>, dim3(blocks_for(nc, 256)), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(se_mean_kernel<false>, dim3(blocks_for(nc, 256)), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(se_gate_kernel, dim3(a.nb), dim3(256), 0, s, a);
+    if (bf16) hipLaunchKernelGGL(se_scale_kernel<true>, dim3(blocks_for(tot, 256)), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(se_scale_kernel<false>, dim3(blocks_for(tot, 256)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ combination rule
+// One wavefront per sample: for each member a max-subtracted softmax of its logits row
+// (wavefront shuffles for the maximum and the sum), each term divided by M and added in
+// member order, one write of the combined row.
+constexpr int COMBINE_MAX_PER_LANE = 32;    // classes <= 64 * 32
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+template <int PER>
+__global__ __launch_bounds__(256) void combine_kernel(const float* const* logits, int n_members, long long n,
+                                                      int classes, float* y) {
+    const int lane = threadIdx.x & 63;
+    const long long row = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (row >= n) return;
+    float acc[PER];
+#pragma unroll
+    for (int e = 0; e < PER; e++) acc[e] = 0.f;
+    const float inv_m = 1.f / (float)n_members;
+    for (int m = 0; m < n_members; m++) {
+        const float* z = logits[m] + row * classes;
+        float v[PER];
+        float mx = -3.0e38f;
+#pragma unroll
+        for (int e = 0; e < PER; e++) {
+            const int c = lane + 64 * e;
+            v[e] = c < classes ? z[c] : -3.0e38f;
+            mx = fmaxf(mx, v[e]);
+        }
+        mx = wave_max(mx);
+        float sum = 0.f;
+#pragma unroll
+        for (int e = 0; e < PER; e++) {
+            const int c = lane + 64 * e;
+            v[e] = c < classes ? expf(v[e] - mx) : 0.f;
+            sum += v[e];
+        }
+        sum = wave_sum(sum);
+#pragma unroll
+        for (int e = 0; e < PER; e++) acc[e] += (v[e] / sum) * inv_m;
+    }
+#pragma unroll
+    for (int e = 0; e < PER; e++) {
+        const int c = lane + 64 * e;
+        if (c < classes) y[row * classes + c] = acc[e];
+    }
+}
+
+hipError_t launch_combine(const float* const* logits, int n_members, int64_t n, int classes, float* y,
+                          hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    if (n_members <= 0 || classes <= 0 || classes > 64 * COMBINE_MAX_PER_LANE) return hipErrorInvalidValue;
+    const dim3 g((unsigned)((n + 3) / 4)), b(256);
+    const int per = (classes + 63) / 64;
+    if (per <= 1) hipLaunchKernelGGL(combine_kernel<1>, g, b, 0, s, logits, n_members, (long long)n, classes, y);
+    else if (per <= 4) hipLaunchKernelGGL(combine_kernel<4>, g, b, 0, s, logits, n_members, (long long)n, classes, y);
+    else if (per <= 16) hipLaunchKernelGGL(combine_kernel<16>, g, b, 0, s, logits, n_members, (long long)n, classes, y);
+    else hipLaunchKernelGGL(combine_kernel<32>, g, b, 0, s, logits, n_members, (long long)n, classes, y);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ calibration images
+// Content does not matter for classification throughput (section "Offline benchmark settings",
+// "Calibration data samples"): hashed values uniform in [-1.73, 1.73) (unit variance).
+__global__ void fill_noise_kernel(float* p, long long count, unsigned long long seed) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    unsigned long long z = seed + (unsigned long long)(i + 1) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    p[i] = ((float)(z >> 40) * (1.0f / 16777216.0f) - 0.5f) * 3.4641016f;
+}
+
+hipError_t launch_fill_noise(float* p, int64_t count, uint64_t seed, hipStream_t s) {
+    if (count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_noise_kernel, dim3(blocks_for(count, 256)), dim3(256), 0, s, p, (long long)count,
+                       (unsigned long long)seed);
+    return hipGetLastError();
+}
+
+}  // namespace ens

@@ -1,0 +1,285 @@
+// Host-side preparation of a member: validation of its description, batch-norm folding,
+// conversion of the parameters to the device layout, and liveness-based placement of its
+// activation tensors in a worker's arena.  No GPU calls in this file.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+
+#include "engine.h"
+
+namespace ens {
+
+static const double BN_EPS = 1e-5;
+static const size_t ALIGN = 256;
+
+static uint16_t to_bf16(float f) {
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+static size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct BlobWriter {
+    std::vector<uint8_t>& buf;
+    size_t reserve(size_t bytes) {
+        const size_t off = align_up(buf.size());
+        buf.resize(off + bytes, 0);
+        return off;
+    }
+    size_t put_f32(const std::vector<float>& v) {
+        const size_t off = reserve(v.size() * 4);
+        memcpy(buf.data() + off, v.data(), v.size() * 4);
+        return off;
+    }
+    size_t put(const std::vector<float>& v, bool bf16) {
+        if (!bf16) return put_f32(v);
+        const size_t off = reserve(v.size() * 2);
+        uint16_t* d = (uint16_t*)(buf.data() + off);
+        for (size_t i = 0; i < v.size(); i++) d[i] = to_bf16(v[i]);
+        return off;
+    }
+};
+
+static bool in_blob(int64_t off, int64_t n, int64_t total) { return off >= 0 && n >= 0 && off + n <= total; }
+
+// scale[c] = gamma / sqrt(var + eps), shift[c] = beta - mean * scale
+static void bn_affine(const float* bn, int C, std::vector<float>* scale, std::vector<float>* shift) {
+    scale->resize(C);
+    shift->resize(C);
+    for (int c = 0; c < C; c++) {
+        const double s = (double)bn[c] / std::sqrt((double)bn[3 * C + c] + BN_EPS);
+        (*scale)[c] = (float)s;
+        (*shift)[c] = (float)((double)bn[C + c] - (double)bn[2 * C + c] * s);
+    }
+}
+
+int build_member(const ens_member_spec& spec, const float* params, Member* out) {
+    if (!spec.tensors || !spec.ops || spec.n_tensors <= 0 || spec.n_ops <= 0 || !params) return ENS_E_INVALID;
+    if (spec.out_tensor <= 0 || spec.out_tensor >= spec.n_tensors) return ENS_E_INVALID;
+    if (spec.dtype != ENS_FP32 && spec.dtype != ENS_BF16) return ENS_E_INVALID;
+    Member m;
+    m.bf16 = spec.dtype == ENS_BF16;
+    const int NT = spec.n_tensors;
+    const int64_t NP = spec.n_params;
+    if (spec.tensors[0].c != 3) return ENS_E_UNSUPPORTED;       // requests are 3-channel images
+    m.in_h = spec.tensors[0].h;
+    m.in_w = spec.tensors[0].w;
+    m.out_tensor = spec.out_tensor;
+    m.classes = spec.tensors[spec.out_tensor].c;
+    if (spec.tensors[spec.out_tensor].h != 1 || spec.tensors[spec.out_tensor].w != 1) return ENS_E_INVALID;
+
+    m.tensors.resize(NT);
+    for (int t = 0; t < NT; t++) {
+        const ens_tensor& s = spec.tensors[t];
+        if (s.h <= 0 || s.w <= 0 || s.c <= 0) return ENS_E_INVALID;
+        TensorInfo& ti = m.tensors[t];
+        ti.h = s.h; ti.w = s.w; ti.c = s.c;
+        ti.cs = s.c;
+        ti.f32 = !m.bf16;
+        ti.def = t == 0 ? -1 : INT32_MAX;
+        ti.last = -1;
+        ti.external = false;
+    }
+    // outputs of the global pool and the FC head are fp32 vectors whatever the member's dtype
+    for (int i = 0; i < spec.n_ops; i++) {
+        const ens_op& o = spec.ops[i];
+        if (o.dst <= 0 || o.dst >= NT || o.src < 0 || o.src >= NT) return ENS_E_INVALID;
+        if (o.kind == ENS_OP_GAP || o.kind == ENS_OP_FC) m.tensors[o.dst].f32 = true;
+    }
+    if (m.bf16)
+        for (int t = 0; t < NT; t++)
+            if (!m.tensors[t].f32) m.tensors[t].cs = (m.tensors[t].c + 7) / 8 * 8;
+
+    BlobWriter bw{m.host_params};
+    bool seen_out = false;
+    for (int i = 0; i < spec.n_ops; i++) {
+        const ens_op& o = spec.ops[i];
+        OpPlan pl;
+        pl.op = o;
+        pl.w = pl.b = pl.pre_scale = pl.pre_shift = pl.w2 = pl.b2 = SIZE_MAX;
+        pl.cin_s = o.cin;
+        pl.scratch = -1;
+        TensorInfo& ts = m.tensors[o.src];
+        TensorInfo& td = m.tensors[o.dst];
+        if (o.cin <= 0 || o.cout <= 0 || o.src_c0 < 0 || o.dst_c0 < 0) return ENS_E_INVALID;
+        if (o.src_c0 + o.cin > ts.c || o.dst_c0 + o.cout > td.c) return ENS_E_INVALID;
+        if (ts.def == INT32_MAX) return ENS_E_INVALID;           // read before written
+        if (o.dst == spec.out_tensor) {
+            if (o.kind != ENS_OP_FC || seen_out) return ENS_E_UNSUPPORTED;
+            seen_out = true;
+        }
+        ts.last = std::max(ts.last, i);
+        td.def = std::min(td.def, i);
+        td.last = std::max(td.last, i);
+        const bool windowed = o.kind == ENS_OP_CONV || o.kind == ENS_OP_DWCONV || o.kind == ENS_OP_MAXPOOL ||
+                              o.kind == ENS_OP_AVGPOOL;
+        if (windowed) {
+            if (o.kh <= 0 || o.kw <= 0 || o.sh <= 0 || o.sw <= 0 || o.pt < 0 || o.pl < 0) return ENS_E_INVALID;
+            if (ts.f32 != !m.bf16 || td.f32 != !m.bf16) return ENS_E_UNSUPPORTED;
+            // every output pixel must have its window origin inside the padded input
+            if ((td.h - 1) * o.sh - o.pt >= ts.h || (td.w - 1) * o.sw - o.pl >= ts.w) return ENS_E_INVALID;
+        }
+        // 16-byte channel granularity of the bf16 kernels
+        auto aligned8 = [&](int c0, int c) { return c0 % 8 == 0 && c % 8 == 0; };
+        switch (o.kind) {
+            case ENS_OP_CONV: {
+                const int64_t nw = (int64_t)o.kh * o.kw * o.cin * o.cout;
+                if (!in_blob(o.off_w, nw, NP)) return ENS_E_INVALID;
+                if (o.off_b >= 0 && !in_blob(o.off_b, o.cout, NP)) return ENS_E_INVALID;
+                if (o.off_bn >= 0 && !in_blob(o.off_bn, 4 * (int64_t)o.cout, NP)) return ENS_E_INVALID;
+                if (o.pre && !in_blob(o.off_pre, 4 * (int64_t)o.cin, NP)) return ENS_E_INVALID;
+                if (m.bf16) {
+                    if (o.src == 0 && ts.c % 8) {               // the padded input image
+                        if (o.src_c0 != 0 || o.cin != ts.c) return ENS_E_UNSUPPORTED;
+                        pl.cin_s = ts.cs;
+                    } else if (!aligned8(o.src_c0, o.cin)) {
+                        return ENS_E_UNSUPPORTED;
+                    }
+                    if (!aligned8(o.dst_c0, o.cout)) return ENS_E_UNSUPPORTED;
+                }
+                if (o.res >= 0) {
+                    if (o.res >= NT || o.res_c0 < 0 || o.res_c0 + o.cout > m.tensors[o.res].c) return ENS_E_INVALID;
+                    TensorInfo& tr = m.tensors[o.res];
+                    if (tr.h != td.h || tr.w != td.w || tr.def == INT32_MAX) return ENS_E_INVALID;
+                    if (m.bf16 && o.res_c0 % 8) return ENS_E_UNSUPPORTED;
+                    tr.last = std::max(tr.last, i);
+                }
+                std::vector<float> scale(o.cout, 1.f), shift(o.cout, 0.f);
+                if (o.off_bn >= 0) bn_affine(params + o.off_bn, o.cout, &scale, &shift);
+                const float* w = params + o.off_w;               // [kh][kw][cin][cout]
+                std::vector<float> wf((size_t)o.cout * o.kh * o.kw * pl.cin_s, 0.f);
+                for (int co = 0; co < o.cout; co++)
+                    for (int k = 0; k < o.kh * o.kw; k++)
+                        for (int ci = 0; ci < o.cin; ci++)
+                            wf[((size_t)co * o.kh * o.kw + k) * pl.cin_s + ci] =
+                                w[((size_t)k * o.cin + ci) * o.cout + co] * scale[co];
+                std::vector<float> bias(o.cout);
+                for (int co = 0; co < o.cout; co++)
+                    bias[co] = (o.off_b >= 0 ? params[o.off_b + co] * scale[co] : 0.f) + shift[co];
+                pl.w = bw.put(wf, m.bf16);
+                pl.b = bw.put_f32(bias);
+                if (o.pre) {
+                    std::vector<float> ps, ph;
+                    bn_affine(params + o.off_pre, o.cin, &ps, &ph);
+                    ps.resize(pl.cin_s, 0.f);
+                    ph.resize(pl.cin_s, 0.f);
+                    pl.pre_scale = bw.put_f32(ps);
+                    pl.pre_shift = bw.put_f32(ph);
+                }
+                break;
+            }
+            case ENS_OP_DWCONV: {
+                if (o.cin != o.cout) return ENS_E_INVALID;
+                const int64_t nw = (int64_t)o.kh * o.kw * o.cin;
+                if (!in_blob(o.off_w, nw, NP)) return ENS_E_INVALID;
+                if (o.off_b >= 0 && !in_blob(o.off_b, o.cout, NP)) return ENS_E_INVALID;
+                if (o.off_bn >= 0 && !in_blob(o.off_bn, 4 * (int64_t)o.cout, NP)) return ENS_E_INVALID;
+                if (m.bf16 && (!aligned8(o.src_c0, o.cin) || o.dst_c0 % 8)) return ENS_E_UNSUPPORTED;
+                if (o.pre || o.res >= 0) return ENS_E_UNSUPPORTED;
+                std::vector<float> scale(o.cout, 1.f), shift(o.cout, 0.f);
+                if (o.off_bn >= 0) bn_affine(params + o.off_bn, o.cout, &scale, &shift);
+                std::vector<float> wf((size_t)nw), bias(o.cout);
+                for (int k = 0; k < o.kh * o.kw; k++)
+                    for (int c = 0; c < o.cin; c++) wf[(size_t)k * o.cin + c] = params[o.off_w + (size_t)k * o.cin + c] * scale[c];
+                for (int c = 0; c < o.cout; c++)
+                    bias[c] = (o.off_b >= 0 ? params[o.off_b + c] * scale[c] : 0.f) + shift[c];
+                pl.w = bw.put(wf, m.bf16);
+                pl.b = bw.put_f32(bias);
+                break;
+            }
+            case ENS_OP_MAXPOOL:
+            case ENS_OP_AVGPOOL:
+                if (o.cin != o.cout) return ENS_E_INVALID;
+                if (m.bf16 && (!aligned8(o.src_c0, o.cin) || o.dst_c0 % 8)) return ENS_E_UNSUPPORTED;
+                break;
+            case ENS_OP_GAP: {
+                if (o.cin != o.cout || td.h != 1 || td.w != 1) return ENS_E_INVALID;
+                if (ts.f32 != !m.bf16) return ENS_E_UNSUPPORTED;
+                if (o.pre) {
+                    if (!in_blob(o.off_pre, 4 * (int64_t)o.cin, NP)) return ENS_E_INVALID;
+                    std::vector<float> ps, ph;
+                    bn_affine(params + o.off_pre, o.cin, &ps, &ph);
+                    pl.pre_scale = bw.put_f32(ps);
+                    pl.pre_shift = bw.put_f32(ph);
+                }
+                break;
+            }
+            case ENS_OP_FC: {
+                if (ts.h != 1 || ts.w != 1 || td.h != 1 || td.w != 1 || !ts.f32) return ENS_E_UNSUPPORTED;
+                if (o.src_c0 != 0 || o.cin != ts.c || o.dst_c0 != 0 || o.cout != td.c) return ENS_E_UNSUPPORTED;
+                if (!in_blob(o.off_w, (int64_t)o.cin * o.cout, NP) || !in_blob(o.off_b, o.cout, NP)) return ENS_E_INVALID;
+                std::vector<float> wf(params + o.off_w, params + o.off_w + (size_t)o.cin * o.cout);
+                std::vector<float> bias(params + o.off_b, params + o.off_b + o.cout);
+                pl.w = bw.put(wf, m.bf16);
+                pl.b = bw.put_f32(bias);
+                break;
+            }
+            case ENS_OP_SE: {
+                if (o.cin != o.cout || o.r <= 0 || ts.h != td.h || ts.w != td.w) return ENS_E_INVALID;
+                if (ts.f32 != !m.bf16 || td.f32 != !m.bf16) return ENS_E_UNSUPPORTED;
+                if (m.bf16 && (!aligned8(o.src_c0, o.cin) || o.dst_c0 % 8)) return ENS_E_UNSUPPORTED;
+                const int64_t n1 = (int64_t)o.cin * o.r;
+                if (!in_blob(o.off_w, n1, NP) || !in_blob(o.off_b, o.r, NP) || !in_blob(o.off_w2, n1, NP) ||
+                    !in_blob(o.off_b2, o.cin, NP))
+                    return ENS_E_INVALID;
+                pl.w = bw.put_f32(std::vector<float>(params + o.off_w, params + o.off_w + n1));
+                pl.b = bw.put_f32(std::vector<float>(params + o.off_b, params + o.off_b + o.r));
+                pl.w2 = bw.put_f32(std::vector<float>(params + o.off_w2, params + o.off_w2 + n1));
+                pl.b2 = bw.put_f32(std::vector<float>(params + o.off_b2, params + o.off_b2 + o.cin));
+                TensorInfo sc;                                   // per-image scratch: means, hidden, gates
+                sc.h = 1; sc.w = 1; sc.c = sc.cs = 2 * o.cin + o.r;
+                sc.f32 = true; sc.def = i; sc.last = i; sc.external = false;
+                pl.scratch = (int)m.tensors.size();
+                m.tensors.push_back(sc);
+                break;
+            }
+            default:
+                return ENS_E_INVALID;
+        }
+        m.ops.push_back(pl);
+    }
+    if (!seen_out) return ENS_E_INVALID;
+    m.tensors[spec.out_tensor].external = true;
+    bw.reserve(0);
+    m.host_params.resize(align_up(m.host_params.size()), 0);
+    *out = std::move(m);
+    return ENS_OK;
+}
+
+// Lowest-offset placement of every tensor among the tensors alive at the same time.
+ArenaLayout plan_arena(const Member& m, int batch, bool keep_all) {
+    ArenaLayout L;
+    const int NT = (int)m.tensors.size();
+    L.offset.assign(NT, 0);
+    std::vector<int> order;
+    for (int t = 0; t < NT; t++)
+        if (!m.tensors[t].external && m.tensors[t].def != INT32_MAX) order.push_back(t);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return m.tensors[a].def < m.tensors[b].def; });
+    std::vector<int> placed;
+    for (int t : order) {
+        const TensorInfo& ti = m.tensors[t];
+        const size_t need = align_up(ti.bytes(batch));
+        const int last = std::max(ti.last, ti.def);
+        std::vector<std::pair<size_t, size_t>> busy;
+        for (int u : placed) {
+            const TensorInfo& tu = m.tensors[u];
+            const int ulast = std::max(tu.last, tu.def);
+            if (keep_all || (tu.def <= last && ti.def <= ulast)) busy.push_back({L.offset[u], L.offset[u] + align_up(tu.bytes(batch))});
+        }
+        std::sort(busy.begin(), busy.end());
+        size_t off = 0;
+        for (const auto& iv : busy) {
+            if (off + need <= iv.first) break;
+            off = std::max(off, iv.second);
+        }
+        L.offset[t] = off;
+        L.bytes = std::max(L.bytes, off + need);
+        placed.push_back(t);
+    }
+    return L;
+}
+
+}  // namespace ens

@@ -1,0 +1,169 @@
+"""Host-side checks of the GPU library that need no GPU: the C interface loads and exports
+what include/ens.h declares, and the C++ planner / partition / memory model agree with the
+oracle's literal Algorithms 1 and 2 on the same inputs."""
+import ctypes
+import os
+import random
+import re
+
+import pytest
+
+import oracle
+from oracle import planner as P
+import paper_2208_14049_amd as ens
+from synth import nets as N
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "ens.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(ens_[a-z_0-9]+)\s*\(", header))
+    declared -= {"ens_bench_fn", "ens_bench_single_fn"}
+    assert len(declared) >= 20
+    L = ens.lib()
+    for name in sorted(declared):
+        assert hasattr(L, name), name
+    assert set(ens.EXPORTS) == declared
+    assert b"gfx950" in L.ens_version()
+    assert L.ens_strerror(ens.ENS_E_NOFIT) != L.ens_strerror(ens.ENS_E_NOMEM)
+
+
+def random_problem(rnd, pooled=False):
+    M = rnd.randint(1, 4)
+    R = rnd.randint(1, 4)
+    domain = [8, 16, 32]
+    weights = [rnd.randint(1, 40) for _ in range(M)]
+    arena = [[rnd.randint(1, 10) * b // 8 for b in domain] for _ in range(M)]
+    if pooled:
+        row_pool, caps = [0] * R, [rnd.randint(30, 200)]
+    else:
+        row_pool, caps = list(range(R)), [rnd.randint(10, 90) for _ in range(R)]
+    kinds = [rnd.random() < 0.7 for _ in range(R)]
+    return M, R, domain, weights, arena, row_pool, kinds, caps
+
+
+def both(M, R, domain, weights, arena, row_pool, kinds, caps, **kw):
+    prob = ens.PlanProblem(weights, arena, domain, 8, row_pool, kinds, caps, **kw)
+    mem = P.Memory(weights, lambda m, b: arena[m][domain.index(b)], row_pool,
+                   ["GPU" if k else "CPU" for k in kinds], caps)
+    return prob, mem
+
+
+def test_wfd_matches_oracle_on_random_instances():
+    rnd = random.Random(1)
+    n_fail = n_ok = 0
+    for it in range(300):
+        args = random_problem(rnd, pooled=(it % 3 == 0))
+        prob, mem = both(*args)
+        try:
+            exp = P.worst_fit_decreasing(args[0], mem, 8)
+        except MemoryError:
+            exp = None
+        if exp is None:
+            with pytest.raises(ens.EnsError) as e:
+                prob.wfd()
+            assert e.value.status == ens.ENS_E_NOFIT
+            n_fail += 1
+        else:
+            got = prob.wfd()
+            assert got == exp
+            assert prob.fit_mem(got) and P.fit_mem(exp, mem)
+            n_ok += 1
+    assert n_fail > 10 and n_ok > 50
+
+
+def test_fit_mem_and_neighbors_match_oracle():
+    rnd = random.Random(2)
+    for it in range(100):
+        M, R, domain, weights, arena, row_pool, kinds, caps = random_problem(rnd, pooled=(it % 2 == 0))
+        prob, mem = both(M, R, domain, weights, arena, row_pool, kinds, caps)
+        A = [[rnd.choice([0] + domain) for _ in range(M)] for _ in range(R)]
+        assert prob.fit_mem(A) == P.fit_mem(A, mem)
+        if P.is_valid(A):
+            assert prob.neighbors(A) == P.neighborhood(A, domain)
+        else:
+            with pytest.raises(ens.EnsError):
+                prob.neighbors(A)
+
+
+def test_greedy_matches_oracle_with_injected_cost_model():
+    rnd = random.Random(3)
+    for it in range(40):
+        M, R, domain, weights, arena, row_pool, kinds, caps = random_problem(rnd, pooled=True)
+        caps = [10 ** 6]
+        table = {}
+        seed_cost = rnd.randint(0, 10 ** 6)
+
+        def bench(A):
+            key = tuple(map(tuple, A))
+            if key not in table:
+                table[key] = random.Random(hash(key) ^ seed_cost).random()
+            return table[key]
+
+        max_iter, max_neighs, seed = rnd.randint(1, 6), rnd.choice([3, 10, 1000]), rnd.randint(0, 2 ** 40)
+        prob, mem = both(M, R, domain, weights, arena, row_pool, kinds, caps,
+                         max_iter=max_iter, max_neighs=max_neighs, seed=seed)
+        start = P.worst_fit_decreasing(M, mem, 8)
+        exp_a, exp_s, exp_n = P.bounded_greedy(start, bench, domain, max_iter, max_neighs, seed)
+        got_a, got_s, got_n = prob.greedy(start, bench)
+        assert (got_a, got_n) == (exp_a, exp_n)
+        assert got_s == exp_s >= bench(start)
+
+
+def test_bbs_matches_oracle():
+    domain = [8, 16, 32, 64, 128]
+    prob = ens.PlanProblem([1] * 4, [[1] * 5] * 4, domain, 8, [0], [1], [10 ** 9])
+    speed = lambda m, b: -abs(b - [8, 32, 128, 64][m])
+    got, n = prob.bbs(speed)
+    exp, n2 = P.best_batch_size(4, speed, domain)
+    assert got == exp == [8, 32, 128, 64] and n == n2 == 20
+
+
+@pytest.mark.parametrize("n,seg,b", [(300, 128, 8), (300, 128, 128), (1024, 128, 32), (1, 128, 8), (0, 128, 8),
+                                      (129, 128, 64), (2048, 256, 256), (77, 16, 5)])
+def test_partition_matches_oracle(n, seg, b):
+    exp = [bt for (a, e) in oracle.segments(n, seg) for bt in oracle.batches(a, e, b)]
+    assert ens.ens_partition(n, seg, b) == exp
+
+
+def test_memory_model_from_description():
+    net = N.resnet18()
+    w, a8 = ens.ens_spec_bytes(net, 8)
+    _, a32 = ens.ens_spec_bytes(net, 32)
+    n_w = sum(p["size"] for p in net.params if p["role"] == "conv_w")
+    assert 2 * n_w <= w <= 2 * n_w + 4 * 20000 + 256 * 4 * len(net.ops) + 2 * 8 * 64 * 49
+    # the arena is at least the two largest tensors alive together (stem output and its input)
+    stem_in, stem_out = 224 * 224 * 8 * 2, 112 * 112 * 64 * 2
+    assert a8 >= 8 * (stem_in + stem_out)
+    assert a8 <= 8 * (stem_in + 3 * stem_out)
+    assert abs(a32 / a8 - 4.0) < 0.05
+    tiny = N.tiny_a()
+    w, a = ens.ens_spec_bytes(tiny, 8)
+    assert w >= 4 * (432 + 16 + 4608 + 32 + 320 + 10)
+    assert a >= 8 * 4 * (32 * 32 * 3 + 32 * 32 * 16)
+
+
+def test_load_reports_missing_gpu_or_succeeds():
+    import torch
+    nets = N.config_members(1)
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present; covered by the gpu tests")
+    with pytest.raises(ens.EnsError) as e:
+        ens.Ensemble(nets, seed=1)
+    assert e.value.status == ens.ENS_E_NODEVICE
+
+
+def test_invalid_descriptions_are_rejected():
+    net = N.tiny_a()
+    net.ops[0]["off_w"] = net.blob_size        # weights beyond the blob
+    with pytest.raises(ens.EnsError) as e:
+        ens.ens_spec_bytes(net, 8)
+    assert e.value.status == ens.ENS_E_INVALID
+    net = N.Net("odd", 16, 16, 10, dtype="bf16")
+    t = net.conv(0, 12, 3)                       # 12 output channels: not a multiple of 8
+    net.fc(net.gap(t), 10)
+    with pytest.raises(ens.EnsError) as e:
+        ens.ens_spec_bytes(net, 8)
+    assert e.value.status == ens.ENS_E_UNSUPPORTED
