@@ -87,6 +87,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("%s is missing: build it first (python -m paper_2208_14049_amd.build); "
                                "there is no fallback path" % LIB_PATH)
+        # PyTorch owns the process's HIP runtime (its device tensors are what callers hand in):
+        # import it first so that the library binds to the same runtime instead of a second copy.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, i64, u64, dbl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64, ctypes.c_double
         P = ctypes.POINTER

@@ -214,58 +214,122 @@ hipError_t launch_pool(const PoolArgs& a, bool is_max, bool bf16, hipStream_t s)
 }
 
 // ------------------------------------------------------------------ global average pool
-// One thread per (image, channel); consecutive lanes take consecutive channels.
+// One workgroup per image.  Lanes run along the channels (16-byte groups of 8 for bf16) so that
+// every pixel row is read in whole lines; the pixels are dealt round-robin to the thread rows
+// and the partial sums are added through LDS.
 template <bool BF16>
-__global__ void gap_kernel(const GapArgs a) {
-    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (long long)a.nb * a.c) return;
-    const int c = (int)(idx % a.c);
-    const long long n = idx / a.c;
-    float sc = 1.f, sf = 0.f;
+__global__ __launch_bounds__(256) void gap_kernel(const GapArgs a) {
+    constexpr int V = BF16 ? 8 : 1;
+    __shared__ float part[256 * V];
+    const int n = blockIdx.x;
+    const int cv = (a.c + V - 1) / V;                 // channel groups
+    const int cols = min(cv, 256);                    // groups handled side by side
+    const int rows = 256 / cols;                      // pixel phases
+    const int col = threadIdx.x % cols, row = threadIdx.x / cols;
     const bool pre = a.pre_scale != nullptr;
-    if (pre) { sc = a.pre_scale[c]; sf = a.pre_shift[c]; }
-    float acc = 0.f;
-    for (int p = 0; p < a.HW; p++) {
-        const long long off = (n * a.HW + p) * (long long)a.x.stride + a.x.c0 + c;
-        float v = BF16 ? bf2f(((const uint16_t*)a.x.p)[off]) : ((const float*)a.x.p)[off];
-        if (pre) v = fmaxf(v * sc + sf, 0.f);
-        acc += v;
+    for (int g0 = 0; g0 < cv; g0 += cols) {
+        const int g = g0 + col;
+        float acc[V];
+#pragma unroll
+        for (int e = 0; e < V; e++) acc[e] = 0.f;
+        if (g < cv && row < rows) {
+            const int c = g * V;
+            float sc[V], sf[V];
+#pragma unroll
+            for (int e = 0; e < V; e++) {
+                sc[e] = pre && c + e < a.c ? a.pre_scale[c + e] : 1.f;
+                sf[e] = pre && c + e < a.c ? a.pre_shift[c + e] : 0.f;
+            }
+            for (int p = row; p < a.HW; p += rows) {
+                const long long off = ((long long)n * a.HW + p) * a.x.stride + a.x.c0 + c;
+                float v[V];
+                if (BF16) unpack8(*(const uint4*)((const uint16_t*)a.x.p + off), v);
+                else v[0] = ((const float*)a.x.p)[off];
+#pragma unroll
+                for (int e = 0; e < V; e++) acc[e] += pre ? fmaxf(v[e] * sc[e] + sf[e], 0.f) : v[e];
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < V; e++) part[threadIdx.x * V + e] = acc[e];
+        __syncthreads();
+        if (row == 0 && g < cv) {
+#pragma unroll
+            for (int e = 0; e < V; e++) {
+                float s = 0.f;
+                for (int r = 0; r < rows; r++) s += part[(r * cols + col) * V + e];
+                if (g * V + e < a.c) a.y[(long long)n * a.c + g * V + e] = s / (float)a.HW;
+            }
+        }
+        __syncthreads();
     }
-    a.y[idx] = acc / (float)a.HW;
 }
 
 hipError_t launch_gap(const GapArgs& a, bool bf16, hipStream_t s) {
     if (a.nb <= 0 || a.c <= 0 || a.HW <= 0) return hipErrorInvalidValue;
-    const long long total = (long long)a.nb * a.c;
-    if (bf16) hipLaunchKernelGGL(gap_kernel<true>, dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(gap_kernel<false>, dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
+    if (bf16 && (a.c % 8 || a.x.stride % 8 || a.x.c0 % 8)) return hipErrorInvalidValue;
+    if (bf16) hipLaunchKernelGGL(gap_kernel<true>, dim3(a.nb), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(gap_kernel<false>, dim3(a.nb), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ FC head
-// One thread per (image, class); lanes run along the classes so the weight rows are read
-// coalesced; the pooled features of the image are broadcast reads.
+// A workgroup owns 64 classes and up to 8 images.  The pooled features of those images sit in
+// LDS; each of the four wavefronts walks a quarter of the input features with its lanes along
+// the classes (coalesced weight rows, every weight used for all 8 images), and the four partial
+// sums meet in LDS.
+constexpr int FC_IMGS = 8;
+constexpr int FC_KCH = 1024;       // input features staged in LDS at a time
+
 template <bool BF16>
-__global__ void fc_kernel(const FcArgs a) {
-    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (long long)a.nb * a.cout) return;
-    const int co = (int)(idx % a.cout);
-    const long long n = idx / a.cout;
-    const float* x = a.x + n * a.cin;
-    float acc = 0.f;
-    for (int ci = 0; ci < a.cin; ci++) {
-        const long long off = (long long)ci * a.cout + co;
-        const float w = BF16 ? bf2f(((const uint16_t*)a.w)[off]) : ((const float*)a.w)[off];
-        acc = fmaf(x[ci], w, acc);
+__global__ __launch_bounds__(256) void fc_kernel(const FcArgs a) {
+    __shared__ float xs[FC_IMGS * FC_KCH];
+    __shared__ float part[4 * FC_IMGS * 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int co = blockIdx.x * 64 + lane;
+    const int n0 = blockIdx.y * FC_IMGS;
+    const int ni = min(FC_IMGS, a.nb - n0);
+    float acc[FC_IMGS];
+#pragma unroll
+    for (int e = 0; e < FC_IMGS; e++) acc[e] = 0.f;
+    for (int kc = 0; kc < a.cin; kc += FC_KCH) {
+        const int kn = min(FC_KCH, a.cin - kc);
+        for (int i = threadIdx.x; i < FC_IMGS * kn; i += 256) {
+            const int img = i / kn, k = i - img * kn;
+            xs[img * FC_KCH + k] = img < ni ? a.x[(long long)(n0 + img) * a.cin + kc + k] : 0.f;
+        }
+        __syncthreads();
+        const int per = (kn + 3) / 4;
+        const int k0 = wave * per, k1 = min(kn, k0 + per);
+        if (co < a.cout) {
+#pragma unroll 4
+            for (int k = k0; k < k1; k++) {
+                const long long off = (long long)(kc + k) * a.cout + co;
+                const float w = BF16 ? bf2f(((const uint16_t*)a.w)[off]) : ((const float*)a.w)[off];
+#pragma unroll
+                for (int e = 0; e < FC_IMGS; e++) acc[e] = fmaf(xs[e * FC_KCH + k], w, acc[e]);
+            }
+        }
+        __syncthreads();
     }
-    a.y[n * a.ldy + co] = acc + a.bias[co];
+#pragma unroll
+    for (int e = 0; e < FC_IMGS; e++) part[(wave * FC_IMGS + e) * 64 + lane] = acc[e];
+    __syncthreads();
+    for (int i = threadIdx.x; i < FC_IMGS * 64; i += 256) {
+        const int e = i >> 6, l = i & 63;
+        const int c = blockIdx.x * 64 + l;
+        if (e < ni && c < a.cout) {
+            const float s = part[(0 * FC_IMGS + e) * 64 + l] + part[(1 * FC_IMGS + e) * 64 + l] +
+                            part[(2 * FC_IMGS + e) * 64 + l] + part[(3 * FC_IMGS + e) * 64 + l];
+            a.y[(long long)(n0 + e) * a.ldy + c] = s + a.bias[c];
+        }
+    }
 }
 
 hipError_t launch_fc(const FcArgs& a, bool bf16, hipStream_t s) {
-    if (a.nb <= 0 || a.cin <= 0 || a.cout <= 0 || !a.bias) return hipErrorInvalidValue;
-    const long long total = (long long)a.nb * a.cout;
-    if (bf16) hipLaunchKernelGGL(fc_kernel<true>, dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(fc_kernel<false>, dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
+    if (a.nb <= 0 || a.cin <= 0 || a.cout <= 0 || !a.bias || !a.y) return hipErrorInvalidValue;
+    const dim3 g((a.cout + 63) / 64, (a.nb + FC_IMGS - 1) / FC_IMGS), b(256);
+    if (bf16) hipLaunchKernelGGL(fc_kernel<true>, g, b, 0, s, a);
+    else hipLaunchKernelGGL(fc_kernel<false>, g, b, 0, s, a);
     return hipGetLastError();
 }
 

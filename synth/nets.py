@@ -151,11 +151,11 @@ class Net:
                  pre=int(pre), off_pre=off_pre)
         return dt
 
-    def fc(self, src, cout):
+    def fc(self, src, cout, gain=1.0):
         h, w, c = self.tensors[src]
         assert (h, w) == (1, 1)
         dt = self.tensor(1, 1, cout)
-        off_w = self._param("conv_w", c * cout, std=math.sqrt(1.0 / c))
+        off_w = self._param("conv_w", c * cout, std=math.sqrt(gain / c))
         off_b = self._param("bias", cout)
         self._op(kind=FC, src=src, cin=c, dst=dt, cout=cout, kh=1, kw=1, sh=1, sw=1,
                  off_w=off_w, off_b=off_b)
@@ -259,7 +259,9 @@ def resnet_bottleneck(name, blocks, classes=1000, size=224, widths=(64, 128, 256
             t = n.conv(u, 4 * w, 1, gamma=RES_ALPHA, res=idt)
             cin = 4 * w
     t = n.gap(t)
-    n.fc(t, classes)
+    # the residual stream's spread grows about 6 % per block; the head is scaled so that the
+    # logits keep a spread of about 3 whatever the depth (no saturated softmax)
+    n.fc(t, classes, gain=0.25 * 1.126 ** (16 - sum(blocks)))
     return n
 
 
@@ -350,7 +352,7 @@ def efficientnet(variant=0, classes=1000, size=224, dtype="bf16"):
             cin = cout
     t = n.conv(t, _round8(1280 * wm), 1, act="silu")
     t = n.gap(t)
-    n.fc(t, classes)
+    n.fc(t, classes, gain=400.0)     # squeeze-excite gates and SiLU shrink the signal; keep logits O(1)
     return n
 
 
@@ -444,7 +446,7 @@ def inception_v3(classes=1000, size=299, dtype="bf16"):
     t = mod_e(t)
     t = mod_e(t)
     t = n.gap(t)
-    n.fc(t, classes)
+    n.fc(t, classes, gain=0.15)
     return n
 
 

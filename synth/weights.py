@@ -35,12 +35,21 @@ def make_blob(net, seed, member):
     return blob
 
 
-def make_images(seed, n, h, w, c=3, first=0):
+def make_images(seed, n, h, w, c=3, first=0, varied=False):
+    """N(0, 1) images.  varied=True additionally gives every image its own contrast
+    (uniform in [0.25, 1.75]) and per-channel offset (N(0, 1)), so that random-weight members,
+    which average white noise away, answer differently from image to image."""
     out = np.empty((n, h, w, c), dtype=np.float32)
     per = h * w * c
     for i in range(n):
         k = rng.stream_key(seed, first + i, 0, rng.KIND_IMAGE)
-        out[i] = rng.normal(k, per).astype(np.float32).reshape(h, w, c)
+        img = rng.normal(k, per).reshape(h, w, c)
+        if varied:
+            k2 = rng.stream_key(seed, first + i, 1, rng.KIND_IMAGE)
+            gain = rng.uniform_range(k2, 1, 0.25, 1.75)[0]
+            off = rng.normal(k2, c, start=1)
+            img = img * gain + off.reshape(1, 1, c)
+        out[i] = img.astype(np.float32)
     return out
 
 

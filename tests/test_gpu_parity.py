@@ -38,9 +38,13 @@ def top1_agreement(y_gpu, y_ref, tol):
     return strict, near
 
 
-def prepared(nets, seed, n, size, bf16):
+def prepared(nets, seed, n, size, bf16, varied_from=None):
+    """Seeded parameters and images; images from index `varied_from` on get their own contrast and
+    offset so that the members' answers (and the arg-max) differ from image to image."""
     blobs = [W.make_blob(net, seed, i) for i, net in enumerate(nets)]
     imgs = W.make_images(seed + 1000, n, size, size)
+    if varied_from is not None:
+        imgs[varied_from:] = W.make_images(seed + 1000, n - varied_from, size, size, first=varied_from, varied=True)
     if bf16:
         blobs = [W.quantise_weights_bf16(net, b) for net, b in zip(nets, blobs)]
         imgs = W.round_bf16(imgs)
@@ -243,8 +247,9 @@ def test_resize_staging(ens):
 def config2():
     nets = N.config_members(2)
     n = 64
-    blobs, imgs = prepared(nets, synth.BASE_SEED, n, 224, bf16=True)
+    blobs, imgs = prepared(nets, synth.BASE_SEED, n, 224, bf16=True, varied_from=24)
     y_ref, p_ref = oracle.ensemble_predict(nets, blobs, imgs, real="f32")
+    assert len(set(np.argmax(y_ref, 1))) >= 8                # the arg-max is not one constant class
     z_ref = [oracle.forward_logits(net, b, imgs[:8], real="f32") for net, b in zip(nets, blobs)]
     return nets, blobs, imgs, y_ref, z_ref
 
