@@ -1,0 +1,42 @@
+// Pieces shared by the convolution kernels: bf16 conversion, activations, the workgroup-to-tile
+// mapping.
+#pragma once
+#include "kernels.h"
+
+namespace ens {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);                                              // nearest even
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float apply_act(float v, int act) {
+    if (act == ACT_RELU) return fmaxf(v, 0.f);
+    if (act == ACT_SILU) return v / (1.f + __expf(-v));
+    return v;
+}
+
+constexpr int BK = 64;          // K elements per LDS tile: one 128-byte row, 8 chunks of 16 bytes
+
+// Workgroup id -> (pixel tile, channel tile).  Consecutive workgroup ids go to different XCDs
+// (8 of them, each with its own L2), so ids are first regrouped per XCD and the channel tiles of
+// one pixel tile are made neighbours there: they read the same activations from one L2.
+__device__ __forceinline__ void tile_of_block(int n_ptiles, int n_ctiles, int* ptile, int* ctile) {
+    const int total = n_ptiles * n_ctiles;
+    int v = blockIdx.x;
+    const int per = total / 8;
+    if (v < per * 8) v = (v % 8) * per + v / 8;
+    *ctile = v % n_ctiles;
+    *ptile = v / n_ctiles;
+}
+
+// Register-staged variant (pre-activated inputs); defined in conv_regstage.hip.
+hipError_t launch_conv_regstage(const ConvArgs& a, int P, int K, hipStream_t s);
+const char* conv_regstage_name(const ConvArgs& a, int P);
+
+}  // namespace ens

@@ -5,146 +5,174 @@
 //   columns cout output channels
 //   depth   K = kh*kw*cin, input channel fastest, so 8 consecutive k are 16 contiguous bytes
 //           both in the activation tensor (one pixel, one tap) and in the [cout][K] weights.
-// A workgroup of 4 wavefronts computes a BP x BC tile of the output; the K loop walks tiles of
-// 32 through double-buffered LDS.  The weights are the A operand of v_mfma_f32_32x32x16_bf16 and
-// the pixels the B operand, so a lane of the accumulator holds one pixel and runs of four
-// consecutive output channels: the epilogue (bias, residual, activation) packs each run into one
-// 8-byte store.
-#include "kernels.h"
+//
+// A workgroup of 4 wavefronts computes a BP x BC tile of the output.  The K loop walks tiles of 64
+// through a ring of NS LDS stages that is filled by asynchronous global-to-LDS loads
+// (global_load_lds_dwordx4): a lane names a 16-byte chunk in global memory and the hardware drops
+// it at "stage base + lane * 16" in LDS without passing through registers, so NS-1 tiles are in
+// flight per workgroup while the matrix cores work on the oldest one.  What a load must not read
+// (padding taps, rows past the end of the tensor, K tail) is redirected to a block of zeros.
+//
+// LDS layout: one 128-byte row per pixel / output channel and K tile; the 16-byte chunk c of row
+// r sits in slot c ^ ((r >> 1) & 7), so that the 16 rows a quarter-wavefront reads for one
+// matrix-core fragment cover all 64 banks.  Because the hardware fixes a lane's LDS slot, the
+// swizzle is applied on the global side: the lane in slot s of row r fetches chunk s ^ key(r).
+// A thread serves rows r0 + 32*i (r0 = thread / 8), for which key(r) is the same: one chunk
+// column, hence one filter tap, per thread and K tile.
+//
+// The weights are the A operand of v_mfma_f32_32x32x16_bf16 and the pixels the B operand.  The
+// finished tile is turned round in LDS so that the epilogue (bias, residual, activation, bf16)
+// reads the residual and writes the output in whole 16-byte groups of 8 channels.
+//
+// Layers with few output pixels and a deep K cannot fill 256 compute units with output tiles
+// alone; their K range is split over gridDim.y workgroups that store fp32 partial tiles into a
+// workspace, and a second small kernel sums the slices and applies the epilogue.
+#include "conv_common.h"
+
+#include <cstdlib>
 
 namespace ens {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* global_ptr_t;
 
-__device__ __forceinline__ float bf16_to_f32(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
-__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
-    u += 0x7FFFu + ((u >> 16) & 1u);                                              // nearest even
-    return (uint16_t)(u >> 16);
-}
-__device__ __forceinline__ float apply_act(float v, int act) {
-    if (act == ACT_RELU) return fmaxf(v, 0.f);
-    if (act == ACT_SILU) return v / (1.f + __expf(-v));
+// LDS reads are issued as inline assembly so that the compiler does not serialise them against
+// the asynchronous loads still in flight for later stages; the waits are placed by hand.
+template <int OFFSET>
+__device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr) {
+    bf16x8 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET));
     return v;
 }
 
-constexpr int BK = 32;          // K elements per LDS tile
-constexpr int LDK = BK + 8;     // padded LDS row (elements): rows start 80 bytes apart
-
-template <int BP, int BC, int WP, int WC, bool PRE>
+template <int BP, int BC, int WP, int WC, int NS, int BKT>
 __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs a, const int P, const int K) {
     static_assert(WP * WC == 4, "four wavefronts per workgroup");
     constexpr int WTP = BP / WP, WTC = BC / WC;      // wave tile
     constexpr int TP = WTP / 32, TC = WTC / 32;      // 32x32 blocks per wave
-    static_assert(TP >= 1 && TC >= 1, "wave tile must hold a 32x32 block");
-    constexpr int NPL = (BP + 63) / 64, NCL = (BC + 63) / 64;   // 16-byte chunks per thread and tile
+    static_assert(TP >= 1 && TC >= 1 && TP <= 4 && TC <= 4, "wave tile of 1..4 blocks per side");
+    static_assert(BKT == 32 || BKT == 64, "K tile of 32 or 64 elements");
+    constexpr int CH = BKT / 8;                      // 16-byte chunks per LDS row
+    constexpr int RS = 256 / CH;                     // a thread serves rows r0 + RS*i
+    constexpr int ROWB = BKT * 2;                    // bytes per LDS row
+    static_assert(BP % RS == 0 && BC % RS == 0, "tiles are multiples of the row step");
+    constexpr int NPL = BP / RS, NCL = BC / RS;      // asynchronous loads per thread and K tile
+    constexpr int NLOAD = NPL + NCL;
+    constexpr int STAGE = (BP + BC) * ROWB;          // bytes per ring stage
+    static_assert(NS >= 2 && (NS - 2) * NLOAD <= 63, "outstanding loads must fit the wait counter");
 
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][BP][LDK];
-    __shared__ __attribute__((aligned(16))) uint16_t Ws[2][BC][LDK];
+    constexpr int OROW = BC + 4;                     // floats per pixel row of the staged output tile
+    constexpr int RING = NS * STAGE > 32 * OROW * 4 ? NS * STAGE : 32 * OROW * 4;
+    // the output tile is staged through the ring in chunks of HROWS pixel rows
+    constexpr int HFIT = RING / (OROW * 4) / 32 * 32;
+    constexpr int HROWS = HFIT >= BP ? BP : (HFIT >= BP / 2 ? BP / 2 : (HFIT >= BP / 4 ? BP / 4 : 32));
+    static_assert(HROWS >= 32 && BP % HROWS == 0 && HROWS * OROW * 4 <= RING, "output staging chunk");
+    __shared__ __attribute__((aligned(1024))) unsigned char ring[RING];
 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wp0 = (wave % WP) * WTP, wc0 = (wave / WP) * WTC;
-    const int n_ptiles = (P + BP - 1) / BP;
-    const int ptile = blockIdx.x % n_ptiles, ctile = blockIdx.x / n_ptiles;
+    const int n_ptiles = (P + BP - 1) / BP, n_ctiles = (a.cout + BC - 1) / BC;
+    int ptile, ctile;
+    tile_of_block(n_ptiles, n_ctiles, &ptile, &ctile);
     const int p0 = ptile * BP, c0 = ctile * BC;
 
     const uint16_t* __restrict__ xg = (const uint16_t*)a.x.p;
     const uint16_t* __restrict__ wg = (const uint16_t*)a.w;
+    const uint16_t* __restrict__ zg = (const uint16_t*)a.zeros;
 
-    // ---- per-thread load coordinates: chunk column q (8 elements), rows r0 + 64*i
-    const int q = t & 3, r0 = t >> 2;
-    const int cpt = a.cin >> 3;                 // 16-byte chunks per filter tap
+    // ---- this workgroup's share of the K tiles
+    const int nk_all = (K + BKT - 1) / BKT;
+    const int per_split = (nk_all + gridDim.y - 1) / gridDim.y;
+    const int kt0 = blockIdx.y * per_split;
+    const int nk = max(0, min(nk_all, kt0 + per_split) - kt0);
+
+    // ---- load side: this thread fills slot (t % CH) of rows r0 + RS*i with chunk cchunk; the
+    //      swizzle key is (r >> 1) & 7 for 128-byte rows and (r >> 2) & 3 for 64-byte rows
+    const int r0 = t / CH;
+    const int cchunk = (t % CH) ^ (CH == 8 ? (r0 >> 1) & 7 : (r0 >> 2) & 3);
+    const int cpt = a.cin >> 3;                                  // 16-byte chunks per filter tap
     const int ntaps = a.kh * a.kw;
-    int hi0[NPL], wi0[NPL];
-    const uint16_t* xb[NPL];
+    int rowoff[NPL];                                             // element offset of the window origin
+    int hi0[NPL], wi0[NPL];                                      // image coordinates of the window origin
 #pragma unroll
     for (int i = 0; i < NPL; i++) {
-        const int r = r0 + 64 * i;
-        const int p = p0 + r;
-        if (r < BP && p < P) {
+        const int p = p0 + r0 + RS * i;
+        rowoff[i] = 0;
+        hi0[i] = -(1 << 28);                                     // rows past the end: never in bounds
+        wi0[i] = 0;
+        if (p < P) {
             const int n = p / (a.Ho * a.Wo);
             const int rem = p - n * (a.Ho * a.Wo);
             const int ho = rem / a.Wo, wo = rem - ho * a.Wo;
             hi0[i] = ho * a.sh - a.pt;
             wi0[i] = wo * a.sw - a.pl;
-            xb[i] = xg + (size_t)n * a.H * a.W * a.x.stride + a.x.c0;
-        } else {
-            hi0[i] = -(1 << 28);                // never in bounds
-            wi0[i] = 0;
-            xb[i] = xg;
+            rowoff[i] = ((n * a.H + hi0[i]) * a.W + wi0[i]) * a.x.stride + a.x.c0;
         }
     }
-    const uint16_t* wb[NCL];
-    bool wvalid[NCL];
+    int wrowoff[NCL];                                            // element offset of the weight row, -1: none
 #pragma unroll
     for (int i = 0; i < NCL; i++) {
-        const int r = r0 + 64 * i;
-        wvalid[i] = (r < BC) && (c0 + r < a.cout);
-        wb[i] = wg + (size_t)(wvalid[i] ? (c0 + r) : 0) * K;
+        const int r = r0 + RS * i;
+        wrowoff[i] = c0 + r < a.cout ? (c0 + r) * K : -1;
     }
 
-    // position of this thread's chunk in the K walk
-    int kc = q;                                  // chunk index along K
-    int tap = kc / cpt, cq = kc - tap * cpt;
-    int khi = tap / a.kw, kwi = tap - khi * a.kw;
+    // Position of this thread's chunk in the K walk: chunk kc -> filter tap (khi, kwi) and channel
+    // chunk cq inside the tap; tapbase is the tap's element offset from the window origin.  The
+    // start comes from a division (the quotients are at most a few dozen, so a float multiply with
+    // a half-step guard is exact); after that every K tile moves CH chunks on with adds and
+    // selects when a tap holds at least CH chunks, and by division otherwise (narrow inputs).
+    int kc = kt0 * CH + cchunk;
+    const float inv_cpt = 1.0f / (float)cpt, inv_kw = 1.0f / (float)a.kw;
+    int tap, cq, khi, kwi, tapbase;
+    auto locate = [&]() {
+        tap = (int)(((float)kc + 0.5f) * inv_cpt);
+        cq = kc - tap * cpt;
+        khi = (int)(((float)tap + 0.5f) * inv_kw);
+        kwi = tap - khi * a.kw;
+        tapbase = (khi * a.W + kwi) * a.x.stride;
+    };
+    locate();
+    const bool wide = cpt >= CH;
+    const int row_step = (a.W - a.kw) * a.x.stride;              // from the last tap of a filter row to the next row
+    int issued = 0;                                              // K tiles issued so far
 
-    uint4 xr[NPL], wr[NCL];
-    auto load_tile = [&]() {
+    // Issues the NLOAD asynchronous loads of the next K tile into ring stage `stage`.  Tiles past
+    // the end of this workgroup's range are all zeros: the number of loads per iteration stays
+    // constant, which the wait counter arithmetic below relies on.
+    auto issue_tile = [&](int stage) {
+        const bool in_range = issued < nk;
+        const bool live = in_range && tap < ntaps;
+        const int off = tapbase + cq * 8;
+        unsigned char* base = ring + stage * STAGE + wave * 1024;
 #pragma unroll
         for (int i = 0; i < NPL; i++) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            const int hi = hi0[i] + khi, wi = wi0[i] + kwi;
-            if (tap < ntaps && hi >= 0 && hi < a.H && wi >= 0 && wi < a.W) {
-                v = *(const uint4*)(xb[i] + ((size_t)hi * a.W + wi) * a.x.stride + cq * 8);
-                if (PRE) {
-                    const float4 s0 = *(const float4*)(a.pre_scale + cq * 8);
-                    const float4 s1 = *(const float4*)(a.pre_scale + cq * 8 + 4);
-                    const float4 h0 = *(const float4*)(a.pre_shift + cq * 8);
-                    const float4 h1 = *(const float4*)(a.pre_shift + cq * 8 + 4);
-                    const float sc[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
-                    const float sf[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
-                    uint32_t in[4] = {v.x, v.y, v.z, v.w}, out[4];
-#pragma unroll
-                    for (int e = 0; e < 4; e++) {
-                        float lo = bf16_to_f32((uint16_t)(in[e] & 0xFFFF));
-                        float hi_ = bf16_to_f32((uint16_t)(in[e] >> 16));
-                        lo = fmaxf(lo * sc[2 * e] + sf[2 * e], 0.f);
-                        hi_ = fmaxf(hi_ * sc[2 * e + 1] + sf[2 * e + 1], 0.f);
-                        out[e] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi_) << 16);
-                    }
-                    v = make_uint4(out[0], out[1], out[2], out[3]);
-                }
-            }
-            xr[i] = v;
+            const bool ok = live && (unsigned)(hi0[i] + khi) < (unsigned)a.H && (unsigned)(wi0[i] + kwi) < (unsigned)a.W;
+            const uint16_t* src = ok ? xg + (rowoff[i] + off) : zg;
+            __builtin_amdgcn_global_load_lds((global_ptr_t)src, (lds_ptr_t)(base + i * 4096), 16, 0, 0);
         }
+        const bool k_ok = in_range && kc * 8 < K;
 #pragma unroll
         for (int i = 0; i < NCL; i++) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (wvalid[i] && kc * 8 < K) v = *(const uint4*)(wb[i] + (size_t)kc * 8);
-            wr[i] = v;
+            const bool ok = k_ok && wrowoff[i] >= 0;
+            const uint16_t* src = ok ? wg + ((long long)wrowoff[i] + kc * 8) : zg;
+            __builtin_amdgcn_global_load_lds((global_ptr_t)src, (lds_ptr_t)(base + (NPL + i) * 4096), 16, 0, 0);
         }
-    };
-    auto advance = [&]() {
-        kc += 4;
-        cq += 4;
-        while (cq >= cpt) {
-            cq -= cpt;
-            tap++;
-            if (++kwi == a.kw) { kwi = 0; khi++; }
-        }
-    };
-    auto store_tile = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < NPL; i++) {
-            const int r = r0 + 64 * i;
-            if (r < BP) *(uint4*)&Xs[buf][r][q * 8] = xr[i];
-        }
-#pragma unroll
-        for (int i = 0; i < NCL; i++) {
-            const int r = r0 + 64 * i;
-            if (r < BC) *(uint4*)&Ws[buf][r][q * 8] = wr[i];
+        // on to the next K tile
+        issued++;
+        kc += CH;
+        if (wide) {
+            cq += CH;
+            const bool wrap = cq >= cpt;
+            cq -= wrap ? cpt : 0;
+            tap += wrap ? 1 : 0;
+            kwi += wrap ? 1 : 0;
+            tapbase += wrap ? a.x.stride : 0;
+            const bool wrap2 = kwi == a.kw;
+            kwi = wrap2 ? 0 : kwi;
+            khi += wrap2 ? 1 : 0;
+            tapbase += wrap2 ? row_step : 0;
+        } else {
+            locate();
         }
     };
 
@@ -156,113 +184,257 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs a, const i
 #pragma unroll
             for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
 
-    const int nk = (K + BK - 1) / BK;
-    load_tile();
-    store_tile(0);
-    __syncthreads();
-    const int lrow = lane & 31, lk = (lane >> 5) * 8;
+    // ---- fragment side: lane reads row (lane & 31) of each 32-row block, chunk 2*ks + lane/32
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int lsw = CH == 8 ? (lrow >> 1) & 7 : (lrow >> 2) & 3;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)ring;
+    const uint32_t xrow_addr = lds0 + (uint32_t)(wp0 + lrow) * ROWB;
+    const uint32_t wrow_addr = lds0 + (uint32_t)(BP + wc0 + lrow) * ROWB;
+    constexpr int BLK = 32 * ROWB;                               // bytes between 32-row blocks
+    uint32_t koff[BKT / 16];
+#pragma unroll
+    for (int ks = 0; ks < BKT / 16; ks++) koff[ks] = (uint32_t)(((ks * 2 + lhalf) ^ lsw) * 16);
+
+#pragma unroll
+    for (int s = 0; s < NS - 1; s++) issue_tile(s);
+
+    int stage = 0;
     for (int kt = 0; kt < nk; kt++) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) {
-            advance();
-            load_tile();
+        // tile kt has landed once at most (NS-2) younger tiles of this wave are still in flight;
+        // the barrier extends that to every wave's loads and also says that everybody is done
+        // reading the stage that is refilled next
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NLOAD) : "memory");
+        __builtin_amdgcn_s_barrier();
+        {
+            int nxt = stage + NS - 1;
+            if (nxt >= NS) nxt -= NS;
+            issue_tile(nxt);
         }
+        const uint32_t xs = xrow_addr + (uint32_t)stage * STAGE, ws = wrow_addr + (uint32_t)stage * STAGE;
+        bf16x8 wf[2][TC], xf[2][TP];
+        auto read_frags = [&](int ks, int b) {
+            const uint32_t xa = xs + koff[ks], wa = ws + koff[ks];
+            wf[b][0] = lds_read_b128<0>(wa);
+            if (TC > 1) wf[b][1 % TC] = lds_read_b128<BLK>(wa);
+            if (TC > 2) wf[b][2 % TC] = lds_read_b128<2 * BLK>(wa);
+            if (TC > 3) wf[b][3 % TC] = lds_read_b128<3 * BLK>(wa);
+            xf[b][0] = lds_read_b128<0>(xa);
+            if (TP > 1) xf[b][1 % TP] = lds_read_b128<BLK>(xa);
+            if (TP > 2) xf[b][2 % TP] = lds_read_b128<2 * BLK>(xa);
+            if (TP > 3) xf[b][3 % TP] = lds_read_b128<3 * BLK>(xa);
+        };
+        read_frags(0, 0);
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ks++) {
-            bf16x8 wf[TC], xf[TP];
-#pragma unroll
-            for (int i = 0; i < TC; i++) wf[i] = *(const bf16x8*)&Ws[buf][wc0 + i * 32 + lrow][ks * 16 + lk];
-#pragma unroll
-            for (int j = 0; j < TP; j++) xf[j] = *(const bf16x8*)&Xs[buf][wp0 + j * 32 + lrow][ks * 16 + lk];
+        for (int ks = 0; ks < BKT / 16; ks++) {
+            const int b = ks & 1;
+            // the fragments of this step are complete; tie them to the wait so that no matrix-core
+            // instruction is scheduled ahead of it
+            if constexpr (TC == 1 && TP == 1) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[b][0]), "+v"(xf[b][0]));
+            else if constexpr (TC == 1 && TP == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[b][0]), "+v"(xf[b][0]), "+v"(xf[b][1]));
+            else if constexpr (TC == 2 && TP == 1) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[b][0]), "+v"(wf[b][1]), "+v"(xf[b][0]));
+            else if constexpr (TC == 2 && TP == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[b][0]), "+v"(wf[b][1]), "+v"(xf[b][0]), "+v"(xf[b][1]));
+            else if constexpr (TC == 1 && TP == 4) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[b][0]), "+v"(xf[b][0]), "+v"(xf[b][1]), "+v"(xf[b][2]), "+v"(xf[b][3]));
+            else if constexpr (TC == 2 && TP == 4) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[b][0]), "+v"(wf[b][1]), "+v"(xf[b][0]), "+v"(xf[b][1]), "+v"(xf[b][2]), "+v"(xf[b][3]));
+            else if constexpr (TC == 4 && TP == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[b][0]), "+v"(wf[b][1]), "+v"(wf[b][2]), "+v"(wf[b][3]), "+v"(xf[b][0]), "+v"(xf[b][1]));
+            else static_assert(TC * TP == 0, "unsupported wave tile");
+            if (ks + 1 < BKT / 16) read_frags(ks + 1, b ^ 1);     // next step's reads fly under this step's MFMAs
 #pragma unroll
             for (int i = 0; i < TC; i++)
 #pragma unroll
                 for (int j = 0; j < TP; j++)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[b][i], xf[b][j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < nk) {
-            store_tile(buf ^ 1);
-            __syncthreads();
-        }
+        if (++stage == NS) stage = 0;
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");             // drain the trailing (all-zero) loads
+    __syncthreads();                                             // everybody is done with the ring
 
-    // ---- epilogue: accumulator lane = pixel (lane & 31), register v = channel
-    //      8*(v/4) + 4*(lane/32) + v%4 of the 32x32 block
+    // ---- epilogue.  An accumulator lane holds one pixel (lane & 31) and, in register v, channel
+    // 8*(v/4) + 4*(lane/32) + v%4 of its 32x32 block: runs of four channels at a stride of one
+    // pixel, which would reach memory as scattered 8-byte pieces.  The tile is therefore turned
+    // round in LDS (fp32, rows padded by 16 bytes against bank conflicts) and leaves the workgroup
+    // as whole 16-byte groups of 8 channels, a pixel's channels side by side in one line.
+    float* otile = (float*)ring;
+    constexpr int G = BC / 8;                                    // 8-channel groups per pixel row
+    const bool split = gridDim.y > 1;
+    float* mine = split ? a.ws + (size_t)blockIdx.y * P * a.cout : nullptr;
     uint16_t* __restrict__ yg = (uint16_t*)a.y.p;
     const uint16_t* __restrict__ rg = (const uint16_t*)a.res.p;
 #pragma unroll
-    for (int j = 0; j < TP; j++) {
-        const int p = p0 + wp0 + j * 32 + lrow;
-        if (p >= P) continue;
+    for (int h0 = 0; h0 < BP; h0 += HROWS) {
+        if (h0 > 0) __syncthreads();                             // previous chunk has left LDS
 #pragma unroll
-        for (int i = 0; i < TC; i++) {
+        for (int j = 0; j < TP; j++) {
+            const int rb = wp0 + j * 32;                         // first pixel row of this block
+            if (rb < h0 || rb >= h0 + HROWS) continue;
 #pragma unroll
-            for (int g = 0; g < 4; g++) {
-                const int co = c0 + wc0 + i * 32 + g * 8 + (lane >> 5) * 4;
-                if (co >= a.cout) continue;
-                const float4 b = *(const float4*)(a.bias + co);
-                float v0 = acc[i][j][g * 4 + 0] + b.x, v1 = acc[i][j][g * 4 + 1] + b.y;
-                float v2 = acc[i][j][g * 4 + 2] + b.z, v3 = acc[i][j][g * 4 + 3] + b.w;
-                if (rg) {
-                    const uint2 r = *(const uint2*)(rg + (size_t)p * a.res.stride + a.res.c0 + co);
-                    v0 += bf16_to_f32((uint16_t)(r.x & 0xFFFF));
-                    v1 += bf16_to_f32((uint16_t)(r.x >> 16));
-                    v2 += bf16_to_f32((uint16_t)(r.y & 0xFFFF));
-                    v3 += bf16_to_f32((uint16_t)(r.y >> 16));
-                }
-                v0 = apply_act(v0, a.act); v1 = apply_act(v1, a.act);
-                v2 = apply_act(v2, a.act); v3 = apply_act(v3, a.act);
-                uint2 o;
-                o.x = (uint32_t)f32_to_bf16(v0) | ((uint32_t)f32_to_bf16(v1) << 16);
-                o.y = (uint32_t)f32_to_bf16(v2) | ((uint32_t)f32_to_bf16(v3) << 16);
-                *(uint2*)(yg + (size_t)p * a.y.stride + a.y.c0 + co) = o;
+            for (int i = 0; i < TC; i++)
+#pragma unroll
+                for (int g = 0; g < 4; g++)
+                    *(float4*)&otile[(rb - h0 + lrow) * OROW + wc0 + i * 32 + g * 8 + lhalf * 4] =
+                        make_float4(acc[i][j][g * 4], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < HROWS * G / 256; it++) {
+            const int e = t + 256 * it;
+            const int row = e / G, g = e - row * G;
+            const int p = p0 + h0 + row, co = c0 + g * 8;
+            if (p >= P || co >= a.cout) continue;
+            const float4 lo = *(const float4*)&otile[row * OROW + g * 8];
+            const float4 hi = *(const float4*)&otile[row * OROW + g * 8 + 4];
+            if (split) {                                         // fp32 partial sums of this K split
+                float* d = mine + (size_t)p * a.cout + co;
+                *(float4*)d = lo;
+                *(float4*)(d + 4) = hi;
+                continue;
             }
+            const float4 b0 = *(const float4*)(a.bias + co), b1 = *(const float4*)(a.bias + co + 4);
+            float v[8] = {lo.x + b0.x, lo.y + b0.y, lo.z + b0.z, lo.w + b0.w, hi.x + b1.x, hi.y + b1.y, hi.z + b1.z, hi.w + b1.w};
+            if (rg) {
+                const uint4 r = *(const uint4*)(rg + (size_t)p * a.res.stride + a.res.c0 + co);
+                const uint32_t rr[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    v[2 * q] += bf16_to_f32((uint16_t)(rr[q] & 0xFFFF));
+                    v[2 * q + 1] += bf16_to_f32((uint16_t)(rr[q] >> 16));
+                }
+            }
+            uint32_t o[4];
+#pragma unroll
+            for (int q = 0; q < 4; q++)
+                o[q] = (uint32_t)f32_to_bf16(apply_act(v[2 * q], a.act)) | ((uint32_t)f32_to_bf16(apply_act(v[2 * q + 1], a.act)) << 16);
+            *(uint4*)(yg + (size_t)p * a.y.stride + a.y.c0 + co) = make_uint4(o[0], o[1], o[2], o[3]);
         }
     }
+}
+
+// Second pass of a split convolution: sums the fp32 slices and applies bias, residual and
+// activation; one thread per pixel and run of four output channels.
+__global__ void conv_splitk_epilogue(const ConvArgs a, const int P, const int splits) {
+    const int cq = a.cout >> 2;
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long long)P * cq) return;
+    const int co = (int)(idx % cq) * 4;
+    const long long p = idx / cq;
+    const size_t slice = (size_t)P * a.cout;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int sp = 0; sp < splits; sp++) {
+        const float4 v = *(const float4*)(a.ws + sp * slice + (size_t)p * a.cout + co);
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    const float4 b = *(const float4*)(a.bias + co);
+    float v0 = s.x + b.x, v1 = s.y + b.y, v2 = s.z + b.z, v3 = s.w + b.w;
+    if (a.res.p) {
+        const uint2 r = *(const uint2*)((const uint16_t*)a.res.p + (size_t)p * a.res.stride + a.res.c0 + co);
+        v0 += bf16_to_f32((uint16_t)(r.x & 0xFFFF));
+        v1 += bf16_to_f32((uint16_t)(r.x >> 16));
+        v2 += bf16_to_f32((uint16_t)(r.y & 0xFFFF));
+        v3 += bf16_to_f32((uint16_t)(r.y >> 16));
+    }
+    v0 = apply_act(v0, a.act); v1 = apply_act(v1, a.act);
+    v2 = apply_act(v2, a.act); v3 = apply_act(v3, a.act);
+    uint2 o;
+    o.x = (uint32_t)f32_to_bf16(v0) | ((uint32_t)f32_to_bf16(v1) << 16);
+    o.y = (uint32_t)f32_to_bf16(v2) | ((uint32_t)f32_to_bf16(v3) << 16);
+    *(uint2*)((uint16_t*)a.y.p + (size_t)p * a.y.stride + a.y.c0 + co) = o;
 }
 
 double conv_flops(const ConvArgs& a) {
     return 2.0 * (double)a.nb * a.Ho * a.Wo * a.cout * a.kh * a.kw * a.cin;
 }
 
-template <int BP, int BC, int WP, int WC>
-static hipError_t launch_variant(const ConvArgs& a, int P, int K, hipStream_t s) {
-    const int grid = ((P + BP - 1) / BP) * ((a.cout + BC - 1) / BC);
-    if (a.pre_scale)
-        hipLaunchKernelGGL((conv_igemm_bf16<BP, BC, WP, WC, true>), dim3(grid), dim3(256), 0, s, a, P, K);
-    else
-        hipLaunchKernelGGL((conv_igemm_bf16<BP, BC, WP, WC, false>), dim3(grid), dim3(256), 0, s, a, P, K);
-    return hipGetLastError();
+// ---- tile and split choice ---------------------------------------------------------------
+// Measured on MI355X over the layer shapes of residual, dense and inception networks at batch
+// 8-128: what counts most is how many workgroups a compute unit holds at once (their load,
+// matrix-core and store phases overlap), so the tiles are small and the ring is two stages deep:
+// 32 KB of LDS per workgroup, five workgroups per compute unit.
+struct Variant { int bp, bc, bk; const char* name; };
+static const Variant VARIANTS[] = {
+    {128, 32, 64, "conv_igemm_bf16<128,32,k64>"},    // narrow outputs (dense-block growth layers)
+    {64, 64, 64, "conv_igemm_bf16<64,64,k64>"},      // default
+    {64, 64, 32, "conv_igemm_bf16<64,64,k32>"},      // shallow K (1x1 convolutions on few channels)
+    {128, 64, 64, "conv_igemm_bf16<128,64,k64>"},    // few pixels, deep K: used with K splitting
+#ifdef ENS_CONV_TUNING
+    {128, 64, 64, "t4"}, {128, 128, 64, "t5"}, {256, 128, 64, "t6"}, {128, 128, 32, "t7"}, {256, 64, 64, "t8"},
+#endif
+};
+constexpr int CUS = 256;
+
+static int pick_variant(const ConvArgs& a, long long P, long long K) {
+    if (a.cout <= 32) return 0;
+    if (K <= 256) return 2;
+    if (P <= 2048 && K >= 2048) return 3;
+    return 1;
 }
 
-// Tile choice: narrow layers take a 32- or 64-channel tile so no matrix-core work is spent on
-// padding channels; everything else takes the square 128 x 128 tile.
-static int pick_variant(const ConvArgs& a) {
-    if (a.cout <= 32) return 0;
-    if (a.cout <= 64 || (a.cout % 128 != 0 && a.cout % 128 <= 64)) return 1;
-    return 2;
+// Splits of the K range for launches that would leave compute units idle.  Each split keeps at
+// least four K tiles; the workspace holds one P * cout slice of floats per split.
+static int pick_splits(const ConvArgs& a, long long P, long long K, int variant) {
+    if (!a.ws) return 1;
+    const Variant& v = VARIANTS[variant];
+    const long long tiles = ((P + v.bp - 1) / v.bp) * ((a.cout + v.bc - 1) / v.bc);
+    const long long nk = (K + v.bk - 1) / v.bk;
+    if (tiles >= 2 * CUS || nk < 8) return 1;
+    long long s = (3 * CUS + tiles - 1) / tiles;
+    s = s < nk / 4 ? s : nk / 4;
+    if (s > 16) s = 16;
+    while (s > 1 && s * P * a.cout > a.ws_floats) s--;
+    return s < 1 ? 1 : (int)s;
 }
 
 const char* conv_bf16_variant_name(const ConvArgs& a) {
-    static const char* names[3] = {"conv_igemm_bf16<256,32>", "conv_igemm_bf16<128,64>", "conv_igemm_bf16<128,128>"};
-    return names[pick_variant(a)];
+    const long long P = (long long)a.nb * a.Ho * a.Wo;
+    if (a.pre_scale) return conv_regstage_name(a, (int)P);
+    return VARIANTS[pick_variant(a, P, (long long)a.kh * a.kw * a.cin)].name;
+}
+
+template <int BP, int BC, int WP, int WC, int NS, int BKT = 64>
+static hipError_t launch_variant(const ConvArgs& a, int P, int K, int splits, hipStream_t s) {
+    const dim3 grid(((P + BP - 1) / BP) * ((a.cout + BC - 1) / BC), splits);
+    hipLaunchKernelGGL((conv_igemm_bf16<BP, BC, WP, WC, NS, BKT>), grid, dim3(256), 0, s, a, P, K);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && splits > 1) {
+        const long long work = (long long)P * (a.cout / 4);
+        hipLaunchKernelGGL(conv_splitk_epilogue, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, a, P, splits);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 hipError_t launch_conv_bf16(const ConvArgs& a, hipStream_t s) {
-    // shapes the kernel assumes: 16-byte chunks along the channels, 8-byte runs on the way out
+    // shapes the kernels assume: 16-byte groups of 8 channels on the way in and on the way out
     if (a.cin % 8 || a.x.stride % 8 || a.x.c0 % 8) return hipErrorInvalidValue;
-    if (a.cout % 8 || a.y.stride % 4 || a.y.c0 % 4) return hipErrorInvalidValue;
-    if (a.res.p && (a.res.stride % 4 || a.res.c0 % 4)) return hipErrorInvalidValue;
+    if (a.cout % 8 || a.y.stride % 8 || a.y.c0 % 8) return hipErrorInvalidValue;
+    if (a.res.p && (a.res.stride % 8 || a.res.c0 % 8)) return hipErrorInvalidValue;
     if (a.nb <= 0 || a.cin <= 0 || a.cout <= 0 || !a.bias) return hipErrorInvalidValue;
     if ((a.pre_scale == nullptr) != (a.pre_shift == nullptr)) return hipErrorInvalidValue;
     const long long P64 = (long long)a.nb * a.Ho * a.Wo;
     const long long K64 = (long long)a.kh * a.kw * a.cin;
     if (P64 <= 0 || P64 >= (1LL << 31) || K64 >= (1LL << 31)) return hipErrorInvalidValue;
     const int P = (int)P64, K = (int)K64;
-    switch (pick_variant(a)) {
-        case 0: return launch_variant<256, 32, 4, 1>(a, P, K, s);
-        case 1: return launch_variant<128, 64, 2, 2>(a, P, K, s);
-        default: return launch_variant<128, 128, 2, 2>(a, P, K, s);
+    if (a.pre_scale) return launch_conv_regstage(a, P, K, s);
+    if (!a.zeros) return hipErrorInvalidValue;
+    // element offsets inside the kernel are 32-bit
+    if ((long long)a.nb * a.H * a.W * a.x.stride >= (1LL << 31) || (long long)a.cout * K64 >= (1LL << 31)) return hipErrorInvalidValue;
+    int variant = pick_variant(a, P64, K64);
+    int splits = pick_splits(a, P64, K64, variant);
+#ifdef ENS_CONV_TUNING   // tile / split override for kernel experiments only
+    if (const char* e = getenv("ENS_CONV_VARIANT")) { if (a.cout > 32 || atoi(e) == 0) variant = atoi(e); splits = pick_splits(a, P64, K64, variant); }
+    if (const char* e = getenv("ENS_CONV_SPLITS")) { splits = atoi(e); if (splits > 1 && (!a.ws || (long long)splits * P64 * a.cout > a.ws_floats)) splits = 1; }
+#endif
+    switch (variant) {
+        case 0: return launch_variant<128, 32, 4, 1, 2, 64>(a, P, K, splits, s);
+        case 2: return launch_variant<64, 64, 2, 2, 2, 32>(a, P, K, splits, s);
+        case 3: return launch_variant<128, 64, 2, 2, 2, 64>(a, P, K, splits, s);
+#ifdef ENS_CONV_TUNING
+        case 4: return launch_variant<128, 64, 2, 2, 3, 64>(a, P, K, splits, s);
+        case 5: return launch_variant<128, 128, 2, 2, 2, 64>(a, P, K, splits, s);
+        case 6: return launch_variant<256, 128, 2, 2, 2, 64>(a, P, K, splits, s);
+        case 7: return launch_variant<128, 128, 2, 2, 3, 32>(a, P, K, splits, s);
+        case 8: return launch_variant<256, 64, 4, 1, 2, 64>(a, P, K, splits, s);
+#endif
+        default: return launch_variant<64, 64, 2, 2, 2, 64>(a, P, K, splits, s);
     }
 }
 

@@ -69,6 +69,12 @@ static int build_launches(ens_handle* h, Worker& w) {
                 a.bias = (const float*)(P + pl.b);
                 a.pre_scale = pl.pre_scale != SIZE_MAX ? (const float*)(P + pl.pre_scale) : nullptr;
                 a.pre_shift = pl.pre_shift != SIZE_MAX ? (const float*)(P + pl.pre_shift) : nullptr;
+                a.ws = nullptr; a.ws_floats = 0;
+                a.zeros = P + m.zeros_off;
+                if (w.layout.scratch_offset != SIZE_MAX) {
+                    a.ws = (float*)(w.arena + w.layout.scratch_offset);
+                    a.ws_floats = (long long)SPLIT_WS_FLOATS;
+                }
                 a.nb = w.batch; a.H = ts.h; a.W = ts.w; a.cin = pl.cin_s; a.Ho = td.h; a.Wo = td.w; a.cout = o.cout;
                 a.kh = o.kh; a.kw = o.kw; a.sh = o.sh; a.sw = o.sw; a.pt = o.pt; a.pl = o.pl; a.act = o.act;
                 L.flop = 2.0 * nb * td.h * td.w * o.cout * o.kh * o.kw * o.cin;

@@ -36,12 +36,18 @@ struct Member {
     std::vector<TensorInfo> tensors;     // description tensors, then scratch pseudo-tensors
     std::vector<OpPlan> ops;
     std::vector<uint8_t> host_params;    // folded, converted, laid out for the device
+    size_t zeros_off = 0;                // 256 zero bytes inside the parameter block (padding source)
     char* dev_params = nullptr;
     size_t weight_bytes() const { return host_params.size(); }
 };
 
+// Scratch the convolution kernel uses when it splits a layer's K range over several workgroups:
+// one fp32 slice of partial sums per split.
+constexpr size_t SPLIT_WS_FLOATS = 4u << 20;
+
 struct ArenaLayout {
     std::vector<size_t> offset;          // per tensor (unused for external ones)
+    size_t scratch_offset = SIZE_MAX;    // split-K scratch (bf16 members)
     size_t bytes = 0;
 };
 

@@ -30,6 +30,10 @@ struct ConvArgs {
     const float* bias;         // never null (zeros when the layer has none)
     const float* pre_scale;
     const float* pre_shift;
+    // split-K scratch of the worker (may be null: no splitting): room for ws_floats partial sums
+    float* ws;
+    long long ws_floats;
+    const void* zeros;         // at least 16 bytes of zeros in device memory (source of padding)
     int nb, H, W, cin, Ho, Wo, cout;
     int kh, kw, sh, sw, pt, pl;
     int act;

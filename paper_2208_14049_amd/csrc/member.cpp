@@ -94,6 +94,7 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
             if (!m.tensors[t].f32) m.tensors[t].cs = (m.tensors[t].c + 7) / 8 * 8;
 
     BlobWriter bw{m.host_params};
+    m.zeros_off = bw.reserve(256);
     bool seen_out = false;
     for (int i = 0; i < spec.n_ops; i++) {
         const ens_op& o = spec.ops[i];
@@ -278,6 +279,10 @@ ArenaLayout plan_arena(const Member& m, int batch, bool keep_all) {
         L.offset[t] = off;
         L.bytes = std::max(L.bytes, off + need);
         placed.push_back(t);
+    }
+    if (m.bf16) {                      // split-K workspace and tickets of the convolution kernel
+        L.scratch_offset = align_up(L.bytes);
+        L.bytes = L.scratch_offset + align_up(SPLIT_WS_FLOATS * sizeof(float));
     }
     return L;
 }
