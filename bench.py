@@ -25,6 +25,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--images", type=int, default=1024)
     ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--instances", type=int, default=1, help="workers per member (rows of the allocation matrix)")
     ap.add_argument("--cpu-sample", type=int, default=16, help="images the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -41,7 +42,8 @@ def main():
     nets = N.config_members(2)                                  # 3 x ResNet-18-shaped, bf16
     blobs = [W.quantise_weights_bf16(n, W.make_blob(n, synth.BASE_SEED, i)) for i, n in enumerate(nets)]
     E = ens.Ensemble(nets, blobs)
-    E.ens_set_alloc([[args.batch] * len(nets)])
+    alloc = [[args.batch] * len(nets) for _ in range(args.instances)]
+    E.ens_set_alloc(alloc)
     n = args.images
     g = torch.Generator(device="cuda").manual_seed(synth.BASE_SEED + 1000)
     images = torch.randn((n, 224, 224, 3), generator=g, device="cuda", dtype=torch.float32)
@@ -100,7 +102,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "3 x ResNet-18-shaped ensemble, 1000 classes, 224x224x3 N(0,1) images, "
                                "batch %d per member, mean of softmax" % args.batch,
-                   "request_images": n, "allocation": [[args.batch] * len(nets)], "input": "fp32 NHWC resident in HBM"},
+                   "request_images": n, "allocation": alloc, "input": "fp32 NHWC resident in HBM"},
         "roofline": roofline, "cpu_baseline": cpu,
     }))
 

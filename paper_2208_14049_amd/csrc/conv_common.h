@@ -36,7 +36,7 @@ __device__ __forceinline__ void tile_of_block(int n_ptiles, int n_ctiles, int* p
 }
 
 // Register-staged variant (pre-activated inputs); defined in conv_regstage.hip.
-hipError_t launch_conv_regstage(const ConvArgs& a, int P, int K, hipStream_t s);
+hipError_t launch_conv_regstage(const ConvArgs& a, const ConvArgs* argv, int G, int nb, int P, hipStream_t s);
 const char* conv_regstage_name(const ConvArgs& a, int P);
 
 }  // namespace ens

@@ -46,7 +46,10 @@ __device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr) {
 }
 
 template <int BP, int BC, int WP, int WC, int NS, int BKT>
-__global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs a, const int P, const int K) {
+__global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restrict__ argv, const int nb_) {
+    ConvArgs a = argv[blockIdx.z];
+    a.nb = nb_;
+    const int P = nb_ * a.Ho * a.Wo, K = a.kh * a.kw * a.cin;
     static_assert(WP * WC == 4, "four wavefronts per workgroup");
     constexpr int WTP = BP / WP, WTC = BC / WC;      // wave tile
     constexpr int TP = WTP / 32, TC = WTC / 32;      // 32x32 blocks per wave
@@ -311,7 +314,9 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs a, const i
 
 // Second pass of a split convolution: sums the fp32 slices and applies bias, residual and
 // activation; one thread per pixel and run of four output channels.
-__global__ void conv_splitk_epilogue(const ConvArgs a, const int P, const int splits) {
+__global__ void conv_splitk_epilogue(const ConvArgs* __restrict__ argv, const int nb_, const int splits) {
+    const ConvArgs a = argv[blockIdx.z];
+    const int P = nb_ * a.Ho * a.Wo;
     const int cq = a.cout >> 2;
     const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (long long)P * cq) return;
@@ -340,8 +345,8 @@ __global__ void conv_splitk_epilogue(const ConvArgs a, const int P, const int sp
     *(uint2*)((uint16_t*)a.y.p + (size_t)p * a.y.stride + a.y.c0 + co) = o;
 }
 
-double conv_flops(const ConvArgs& a) {
-    return 2.0 * (double)a.nb * a.Ho * a.Wo * a.cout * a.kh * a.kw * a.cin;
+double conv_flops(const ConvArgs& a, int nb) {
+    return 2.0 * (double)nb * a.Ho * a.Wo * a.cout * a.kh * a.kw * a.cin;
 }
 
 // ---- tile and split choice ---------------------------------------------------------------
@@ -356,7 +361,7 @@ static const Variant VARIANTS[] = {
     {64, 64, 32, "conv_igemm_bf16<64,64,k32>"},      // shallow K (1x1 convolutions on few channels)
     {128, 64, 64, "conv_igemm_bf16<128,64,k64>"},    // few pixels, deep K: used with K splitting
 #ifdef ENS_CONV_TUNING
-    {128, 64, 64, "t4"}, {128, 128, 64, "t5"}, {256, 128, 64, "t6"}, {128, 128, 32, "t7"}, {256, 64, 64, "t8"},
+    {128, 64, 64, "t4"}, {128, 128, 64, "t5"}, {256, 128, 64, "t6"}, {128, 128, 32, "t7"}, {256, 64, 64, "t8"}, {128, 128, 32, "t9"}, {128, 64, 32, "t10"}, {128, 64, 32, "t11"}, {128, 128, 32, "t12"}, {64, 64, 32, "t13"},
 #endif
 };
 constexpr int CUS = 256;
@@ -370,10 +375,10 @@ static int pick_variant(const ConvArgs& a, long long P, long long K) {
 
 // Splits of the K range for launches that would leave compute units idle.  Each split keeps at
 // least four K tiles; the workspace holds one P * cout slice of floats per split.
-static int pick_splits(const ConvArgs& a, long long P, long long K, int variant) {
+static int pick_splits(const ConvArgs& a, long long P, long long K, int variant, int G) {
     if (!a.ws) return 1;
     const Variant& v = VARIANTS[variant];
-    const long long tiles = ((P + v.bp - 1) / v.bp) * ((a.cout + v.bc - 1) / v.bc);
+    const long long tiles = G * ((P + v.bp - 1) / v.bp) * ((a.cout + v.bc - 1) / v.bc);
     const long long nk = (K + v.bk - 1) / v.bk;
     if (tiles >= 2 * CUS || nk < 8) return 1;
     long long s = (3 * CUS + tiles - 1) / tiles;
@@ -390,51 +395,56 @@ const char* conv_bf16_variant_name(const ConvArgs& a) {
 }
 
 template <int BP, int BC, int WP, int WC, int NS, int BKT = 64>
-static hipError_t launch_variant(const ConvArgs& a, int P, int K, int splits, hipStream_t s) {
-    const dim3 grid(((P + BP - 1) / BP) * ((a.cout + BC - 1) / BC), splits);
-    hipLaunchKernelGGL((conv_igemm_bf16<BP, BC, WP, WC, NS, BKT>), grid, dim3(256), 0, s, a, P, K);
+static hipError_t launch_variant(const ConvArgs& a, const ConvArgs* argv, int G, int nb, int P, int splits, hipStream_t s) {
+    const dim3 grid(((P + BP - 1) / BP) * ((a.cout + BC - 1) / BC), splits, G);
+    hipLaunchKernelGGL((conv_igemm_bf16<BP, BC, WP, WC, NS, BKT>), grid, dim3(256), 0, s, argv, nb);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && splits > 1) {
         const long long work = (long long)P * (a.cout / 4);
-        hipLaunchKernelGGL(conv_splitk_epilogue, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, a, P, splits);
+        hipLaunchKernelGGL(conv_splitk_epilogue, dim3((unsigned)((work + 255) / 256), 1, G), dim3(256), 0, s, argv, nb, splits);
         e = hipGetLastError();
     }
     return e;
 }
 
-hipError_t launch_conv_bf16(const ConvArgs& a, hipStream_t s) {
+hipError_t launch_conv_bf16(const ConvArgs& a, const ConvArgs* argv, int G, int nb, hipStream_t s) {
     // shapes the kernels assume: 16-byte groups of 8 channels on the way in and on the way out
     if (a.cin % 8 || a.x.stride % 8 || a.x.c0 % 8) return hipErrorInvalidValue;
     if (a.cout % 8 || a.y.stride % 8 || a.y.c0 % 8) return hipErrorInvalidValue;
     if (a.res.p && (a.res.stride % 8 || a.res.c0 % 8)) return hipErrorInvalidValue;
-    if (a.nb <= 0 || a.cin <= 0 || a.cout <= 0 || !a.bias) return hipErrorInvalidValue;
+    if (nb <= 0 || a.cin <= 0 || a.cout <= 0 || !a.bias || G <= 0 || !argv) return hipErrorInvalidValue;
     if ((a.pre_scale == nullptr) != (a.pre_shift == nullptr)) return hipErrorInvalidValue;
-    const long long P64 = (long long)a.nb * a.Ho * a.Wo;
+    const long long P64 = (long long)nb * a.Ho * a.Wo;
     const long long K64 = (long long)a.kh * a.kw * a.cin;
     if (P64 <= 0 || P64 >= (1LL << 31) || K64 >= (1LL << 31)) return hipErrorInvalidValue;
-    const int P = (int)P64, K = (int)K64;
-    if (a.pre_scale) return launch_conv_regstage(a, P, K, s);
+    const int P = (int)P64;
+    if (a.pre_scale) return launch_conv_regstage(a, argv, G, nb, P, s);
     if (!a.zeros) return hipErrorInvalidValue;
     // element offsets inside the kernel are 32-bit
-    if ((long long)a.nb * a.H * a.W * a.x.stride >= (1LL << 31) || (long long)a.cout * K64 >= (1LL << 31)) return hipErrorInvalidValue;
+    if ((long long)nb * a.H * a.W * a.x.stride >= (1LL << 31) || (long long)a.cout * K64 >= (1LL << 31)) return hipErrorInvalidValue;
     int variant = pick_variant(a, P64, K64);
-    int splits = pick_splits(a, P64, K64, variant);
+    int splits = pick_splits(a, P64, K64, variant, G);
 #ifdef ENS_CONV_TUNING   // tile / split override for kernel experiments only
-    if (const char* e = getenv("ENS_CONV_VARIANT")) { if (a.cout > 32 || atoi(e) == 0) variant = atoi(e); splits = pick_splits(a, P64, K64, variant); }
+    if (const char* e = getenv("ENS_CONV_VARIANT")) { if (a.cout > 32 || atoi(e) == 0) variant = atoi(e); splits = pick_splits(a, P64, K64, variant, G); }
     if (const char* e = getenv("ENS_CONV_SPLITS")) { splits = atoi(e); if (splits > 1 && (!a.ws || (long long)splits * P64 * a.cout > a.ws_floats)) splits = 1; }
 #endif
     switch (variant) {
-        case 0: return launch_variant<128, 32, 4, 1, 2, 64>(a, P, K, splits, s);
-        case 2: return launch_variant<64, 64, 2, 2, 2, 32>(a, P, K, splits, s);
-        case 3: return launch_variant<128, 64, 2, 2, 2, 64>(a, P, K, splits, s);
+        case 0: return launch_variant<128, 32, 4, 1, 2, 64>(a, argv, G, nb, P, splits, s);
+        case 2: return launch_variant<64, 64, 2, 2, 2, 32>(a, argv, G, nb, P, splits, s);
+        case 3: return launch_variant<128, 64, 2, 2, 2, 64>(a, argv, G, nb, P, splits, s);
 #ifdef ENS_CONV_TUNING
-        case 4: return launch_variant<128, 64, 2, 2, 3, 64>(a, P, K, splits, s);
-        case 5: return launch_variant<128, 128, 2, 2, 2, 64>(a, P, K, splits, s);
-        case 6: return launch_variant<256, 128, 2, 2, 2, 64>(a, P, K, splits, s);
-        case 7: return launch_variant<128, 128, 2, 2, 3, 32>(a, P, K, splits, s);
-        case 8: return launch_variant<256, 64, 4, 1, 2, 64>(a, P, K, splits, s);
+        case 4: return launch_variant<128, 64, 2, 2, 3, 64>(a, argv, G, nb, P, splits, s);
+        case 5: return launch_variant<128, 128, 2, 2, 2, 64>(a, argv, G, nb, P, splits, s);
+        case 6: return launch_variant<256, 128, 2, 2, 2, 64>(a, argv, G, nb, P, splits, s);
+        case 7: return launch_variant<128, 128, 2, 2, 3, 32>(a, argv, G, nb, P, splits, s);
+        case 8: return launch_variant<256, 64, 4, 1, 2, 64>(a, argv, G, nb, P, splits, s);
+        case 9: return launch_variant<128, 128, 2, 2, 2, 32>(a, argv, G, nb, P, splits, s);
+        case 10: return launch_variant<128, 64, 2, 2, 2, 32>(a, argv, G, nb, P, splits, s);
+        case 11: return launch_variant<128, 64, 2, 2, 3, 32>(a, argv, G, nb, P, splits, s);
+        case 12: return launch_variant<128, 128, 2, 2, 4, 32>(a, argv, G, nb, P, splits, s);
+        case 13: return launch_variant<64, 64, 2, 2, 3, 32>(a, argv, G, nb, P, splits, s);
 #endif
-        default: return launch_variant<64, 64, 2, 2, 2, 64>(a, P, K, splits, s);
+        default: return launch_variant<64, 64, 2, 2, 2, 64>(a, argv, G, nb, P, splits, s);
     }
 }
 

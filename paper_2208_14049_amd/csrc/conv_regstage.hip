@@ -8,7 +8,10 @@
 namespace ens {
 
 template <int BP, int BC, int WP, int WC, bool PRE>
-__global__ __launch_bounds__(256) void conv_regstage_bf16(const ConvArgs a, const int P, const int K) {
+__global__ __launch_bounds__(256) void conv_regstage_bf16(const ConvArgs* __restrict__ argv, const int nb_) {
+    ConvArgs a = argv[blockIdx.z];
+    a.nb = nb_;
+    const int P = nb_ * a.Ho * a.Wo, K = a.kh * a.kw * a.cin;
     static_assert(WP * WC == 4, "four wavefronts per workgroup");
     constexpr int WTP = BP / WP, WTC = BC / WC;      // wave tile
     constexpr int TP = WTP / 32, TC = WTC / 32;      // 32x32 blocks per wave
@@ -211,12 +214,12 @@ __global__ __launch_bounds__(256) void conv_regstage_bf16(const ConvArgs a, cons
 
 
 template <int BP, int BC, int WP, int WC>
-static hipError_t launch_rs(const ConvArgs& a, int P, int K, hipStream_t s) {
-    const dim3 grid(((P + BP - 1) / BP) * ((a.cout + BC - 1) / BC));
+static hipError_t launch_rs(const ConvArgs& a, const ConvArgs* argv, int G, int nb, int P, hipStream_t s) {
+    const dim3 grid(((P + BP - 1) / BP) * ((a.cout + BC - 1) / BC), 1, G);
     if (a.pre_scale)
-        hipLaunchKernelGGL((conv_regstage_bf16<BP, BC, WP, WC, true>), grid, dim3(256), 0, s, a, P, K);
+        hipLaunchKernelGGL((conv_regstage_bf16<BP, BC, WP, WC, true>), grid, dim3(256), 0, s, argv, nb);
     else
-        hipLaunchKernelGGL((conv_regstage_bf16<BP, BC, WP, WC, false>), grid, dim3(256), 0, s, a, P, K);
+        hipLaunchKernelGGL((conv_regstage_bf16<BP, BC, WP, WC, false>), grid, dim3(256), 0, s, argv, nb);
     return hipGetLastError();
 }
 
@@ -226,10 +229,10 @@ const char* conv_regstage_name(const ConvArgs& a, int P) {
     return "conv_regstage_bf16<64,64>";
 }
 
-hipError_t launch_conv_regstage(const ConvArgs& a, int P, int K, hipStream_t s) {
-    if (a.cout <= 32) return launch_rs<256, 32, 4, 1>(a, P, K, s);
-    if (((P + 127) / 128) * ((a.cout + 63) / 64) >= 512) return launch_rs<128, 64, 2, 2>(a, P, K, s);
-    return launch_rs<64, 64, 2, 2>(a, P, K, s);
+hipError_t launch_conv_regstage(const ConvArgs& a, const ConvArgs* argv, int G, int nb, int P, hipStream_t s) {
+    if (a.cout <= 32) return launch_rs<256, 32, 4, 1>(a, argv, G, nb, P, s);
+    if (((P + 127) / 128) * ((a.cout + 63) / 64) >= 512) return launch_rs<128, 64, 2, 2>(a, argv, G, nb, P, s);
+    return launch_rs<64, 64, 2, 2>(a, argv, G, nb, P, s);
 }
 
 }  // namespace ens

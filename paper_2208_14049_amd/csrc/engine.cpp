@@ -37,125 +37,188 @@ static int prof_class(ens_handle* h, const std::string& name) {
     return (int)h->prof.size() - 1;
 }
 
-static View view_of(const Worker& w, const Member& m, int t, int c0) {
+// Tensor 0 (the staged input) is shared by a gang: only the leader's copy is written.
+static View view_of(const Worker& w, const Worker& leader, const Member& m, int t, int c0) {
+    const Worker& src = t == 0 ? leader : w;
     View v;
-    v.p = w.arena + w.layout.offset[t];
+    v.p = src.arena + src.layout.offset[t];
     v.stride = m.tensors[t].cs;
     v.c0 = c0;
     return v;
 }
 
-// Translates the member's operations into kernel argument blocks bound to the worker's arena.
-static int build_launches(ens_handle* h, Worker& w) {
+static bool same_network(const Member& a, const Member& b) {
+    if (a.bf16 != b.bf16 || a.ops.size() != b.ops.size() || a.tensors.size() != b.tensors.size()) return false;
+    for (size_t t = 0; t < a.tensors.size(); t++)
+        if (a.tensors[t].h != b.tensors[t].h || a.tensors[t].w != b.tensors[t].w || a.tensors[t].c != b.tensors[t].c) return false;
+    for (size_t i = 0; i < a.ops.size(); i++)
+        if (memcmp(&a.ops[i].op, &b.ops[i].op, sizeof(ens_op)) != 0) return false;
+    return true;
+}
+
+// Fills one member's argument block for operation `pl`; `L` receives kind, class and work.
+static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, const OpPlan& pl, Launch& L) {
     const Member& m = h->members[w.member];
     const int es = m.bf16 ? 2 : 4;
-    w.launches.clear();
-    for (const OpPlan& pl : m.ops) {
-        const ens_op& o = pl.op;
-        const TensorInfo& ts = m.tensors[o.src];
-        const TensorInfo& td = m.tensors[o.dst];
-        Launch L;
-        const char* P = m.dev_params;
-        const double nb = w.batch;
-        switch (o.kind) {
-            case ENS_OP_CONV: {
-                L.kind = L_CONV;
-                ConvArgs& a = L.conv;
-                a.x = view_of(w, m, o.src, o.src_c0);
-                a.y = view_of(w, m, o.dst, o.dst_c0);
-                a.res.p = nullptr; a.res.stride = 0; a.res.c0 = 0;
-                if (o.res >= 0) a.res = view_of(w, m, o.res, o.res_c0);
-                a.w = P + pl.w;
-                a.bias = (const float*)(P + pl.b);
-                a.pre_scale = pl.pre_scale != SIZE_MAX ? (const float*)(P + pl.pre_scale) : nullptr;
-                a.pre_shift = pl.pre_shift != SIZE_MAX ? (const float*)(P + pl.pre_shift) : nullptr;
-                a.ws = nullptr; a.ws_floats = 0;
-                a.zeros = P + m.zeros_off;
-                if (w.layout.scratch_offset != SIZE_MAX) {
-                    a.ws = (float*)(w.arena + w.layout.scratch_offset);
-                    a.ws_floats = (long long)SPLIT_WS_FLOATS;
-                }
-                a.nb = w.batch; a.H = ts.h; a.W = ts.w; a.cin = pl.cin_s; a.Ho = td.h; a.Wo = td.w; a.cout = o.cout;
-                a.kh = o.kh; a.kw = o.kw; a.sh = o.sh; a.sw = o.sw; a.pt = o.pt; a.pl = o.pl; a.act = o.act;
-                L.flop = 2.0 * nb * td.h * td.w * o.cout * o.kh * o.kw * o.cin;
-                L.bytes = nb * ((double)ts.h * ts.w * o.cin + (double)td.h * td.w * o.cout * (o.res >= 0 ? 2 : 1)) * es +
-                          (double)o.kh * o.kw * o.cin * o.cout * es;
-                L.klass = prof_class(h, m.bf16 ? conv_bf16_variant_name(a) : "conv_f32_kernel");
-                break;
+    const ens_op& o = pl.op;
+    const TensorInfo& ts = m.tensors[o.src];
+    const TensorInfo& td = m.tensors[o.dst];
+    const char* P = m.dev_params;
+    const double nb = w.batch;
+    switch (o.kind) {
+        case ENS_OP_CONV: {
+            L.kind = L_CONV;
+            ConvArgs& a = L.conv;
+            a.x = view_of(w, leader, m, o.src, o.src_c0);
+            a.y = view_of(w, leader, m, o.dst, o.dst_c0);
+            a.res.p = nullptr; a.res.stride = 0; a.res.c0 = 0;
+            if (o.res >= 0) a.res = view_of(w, leader, m, o.res, o.res_c0);
+            a.w = P + pl.w;
+            a.bias = (const float*)(P + pl.b);
+            a.pre_scale = pl.pre_scale != SIZE_MAX ? (const float*)(P + pl.pre_scale) : nullptr;
+            a.pre_shift = pl.pre_shift != SIZE_MAX ? (const float*)(P + pl.pre_shift) : nullptr;
+            a.ws = nullptr; a.ws_floats = 0;
+            a.zeros = P + m.zeros_off;
+            if (w.layout.scratch_offset != SIZE_MAX) {
+                a.ws = (float*)(w.arena + w.layout.scratch_offset);
+                a.ws_floats = (long long)SPLIT_WS_FLOATS;
             }
-            case ENS_OP_DWCONV:
-            case ENS_OP_MAXPOOL:
-            case ENS_OP_AVGPOOL: {
-                L.kind = o.kind == ENS_OP_DWCONV ? L_DWCONV : L_POOL;
-                L.is_max = o.kind == ENS_OP_MAXPOOL;
-                PoolArgs& a = L.pool;
-                a.x = view_of(w, m, o.src, o.src_c0);
-                a.y = view_of(w, m, o.dst, o.dst_c0);
-                a.w = o.kind == ENS_OP_DWCONV ? P + pl.w : nullptr;
-                a.bias = o.kind == ENS_OP_DWCONV ? (const float*)(P + pl.b) : nullptr;
-                a.nb = w.batch; a.H = ts.h; a.W = ts.w; a.c = o.cin; a.Ho = td.h; a.Wo = td.w;
-                a.kh = o.kh; a.kw = o.kw; a.sh = o.sh; a.sw = o.sw; a.pt = o.pt; a.pl = o.pl; a.act = o.act;
-                L.flop = o.kind == ENS_OP_DWCONV ? 2.0 * nb * td.h * td.w * o.cin * o.kh * o.kw : 0.0;
-                L.bytes = nb * ((double)ts.h * ts.w + (double)td.h * td.w) * o.cin * es;
-                L.klass = prof_class(h, o.kind == ENS_OP_DWCONV ? "window_kernel<dwconv>"
-                                        : L.is_max ? "window_kernel<maxpool>" : "window_kernel<avgpool>");
-                break;
-            }
-            case ENS_OP_GAP: {
-                L.kind = L_GAP;
-                GapArgs& a = L.gap;
-                a.x = view_of(w, m, o.src, o.src_c0);
-                a.y = (float*)(w.arena + w.layout.offset[o.dst]) + o.dst_c0;
-                a.pre_scale = pl.pre_scale != SIZE_MAX ? (const float*)(P + pl.pre_scale) : nullptr;
-                a.pre_shift = pl.pre_shift != SIZE_MAX ? (const float*)(P + pl.pre_shift) : nullptr;
-                a.nb = w.batch; a.HW = ts.h * ts.w; a.c = o.cin;
-                if (td.c != o.cin) return ENS_E_UNSUPPORTED;     // the pooled vector is dense
-                L.bytes = nb * (double)ts.h * ts.w * o.cin * es;
-                L.klass = prof_class(h, "gap_kernel");
-                break;
-            }
-            case ENS_OP_FC: {
-                L.kind = L_FC;
-                FcArgs& a = L.fc;
-                a.x = (const float*)(w.arena + w.layout.offset[o.src]);
-                a.w = P + pl.w;
-                a.bias = (const float*)(P + pl.b);
-                a.y = nullptr;                                   // bound per batch to the logits rows
-                a.nb = w.batch; a.cin = o.cin; a.cout = o.cout; a.ldy = o.cout;
-                L.flop = 2.0 * nb * o.cin * o.cout;
-                L.bytes = (double)o.cin * o.cout * es + nb * (o.cin + o.cout) * 4.0;
-                L.klass = prof_class(h, "fc_kernel");
-                break;
-            }
-            case ENS_OP_SE: {
-                L.kind = L_SE;
-                SeArgs& a = L.se;
-                a.x = view_of(w, m, o.src, o.src_c0);
-                a.y = view_of(w, m, o.dst, o.dst_c0);
-                a.w1 = (const float*)(P + pl.w); a.b1 = (const float*)(P + pl.b);
-                a.w2 = (const float*)(P + pl.w2); a.b2 = (const float*)(P + pl.b2);
-                a.scratch = (float*)(w.arena + w.layout.offset[pl.scratch]);
-                a.nb = w.batch; a.HW = ts.h * ts.w; a.c = o.cin; a.r = o.r;
-                L.flop = 4.0 * nb * o.cin * o.r;
-                L.bytes = nb * 3.0 * ts.h * ts.w * o.cin * es;
-                L.klass = prof_class(h, "se_kernels");
-                break;
-            }
-            default:
-                return ENS_E_INVALID;
+            a.nb = w.batch; a.H = ts.h; a.W = ts.w; a.cin = pl.cin_s; a.Ho = td.h; a.Wo = td.w; a.cout = o.cout;
+            a.kh = o.kh; a.kw = o.kw; a.sh = o.sh; a.sw = o.sw; a.pt = o.pt; a.pl = o.pl; a.act = o.act;
+            L.flop = 2.0 * nb * td.h * td.w * o.cout * o.kh * o.kw * o.cin;
+            L.bytes = nb * ((double)ts.h * ts.w * o.cin + (double)td.h * td.w * o.cout * (o.res >= 0 ? 2 : 1)) * es +
+                      (double)o.kh * o.kw * o.cin * o.cout * es;
+            L.klass = prof_class(h, m.bf16 ? conv_bf16_variant_name(a) : "conv_f32_kernel");
+            break;
         }
-        w.launches.push_back(L);
+        case ENS_OP_DWCONV:
+        case ENS_OP_MAXPOOL:
+        case ENS_OP_AVGPOOL: {
+            L.kind = o.kind == ENS_OP_DWCONV ? L_DWCONV : L_POOL;
+            L.is_max = o.kind == ENS_OP_MAXPOOL;
+            PoolArgs& a = L.pool;
+            a.x = view_of(w, leader, m, o.src, o.src_c0);
+            a.y = view_of(w, leader, m, o.dst, o.dst_c0);
+            a.w = o.kind == ENS_OP_DWCONV ? P + pl.w : nullptr;
+            a.bias = o.kind == ENS_OP_DWCONV ? (const float*)(P + pl.b) : nullptr;
+            a.nb = w.batch; a.H = ts.h; a.W = ts.w; a.c = o.cin; a.Ho = td.h; a.Wo = td.w;
+            a.kh = o.kh; a.kw = o.kw; a.sh = o.sh; a.sw = o.sw; a.pt = o.pt; a.pl = o.pl; a.act = o.act;
+            L.flop = o.kind == ENS_OP_DWCONV ? 2.0 * nb * td.h * td.w * o.cin * o.kh * o.kw : 0.0;
+            L.bytes = nb * ((double)ts.h * ts.w + (double)td.h * td.w) * o.cin * es;
+            L.klass = prof_class(h, o.kind == ENS_OP_DWCONV ? "window_kernel<dwconv>"
+                                    : L.is_max ? "window_kernel<maxpool>" : "window_kernel<avgpool>");
+            break;
+        }
+        case ENS_OP_GAP: {
+            L.kind = L_GAP;
+            GapArgs& a = L.gap;
+            a.x = view_of(w, leader, m, o.src, o.src_c0);
+            a.y = (float*)(w.arena + w.layout.offset[o.dst]) + o.dst_c0;
+            a.pre_scale = pl.pre_scale != SIZE_MAX ? (const float*)(P + pl.pre_scale) : nullptr;
+            a.pre_shift = pl.pre_shift != SIZE_MAX ? (const float*)(P + pl.pre_shift) : nullptr;
+            a.nb = w.batch; a.HW = ts.h * ts.w; a.c = o.cin;
+            if (td.c != o.cin) return ENS_E_UNSUPPORTED;         // the pooled vector is dense
+            L.bytes = nb * (double)ts.h * ts.w * o.cin * es;
+            L.klass = prof_class(h, "gap_kernel");
+            break;
+        }
+        case ENS_OP_FC: {
+            L.kind = L_FC;
+            FcArgs& a = L.fc;
+            a.x = (const float*)(w.arena + w.layout.offset[o.src]);
+            a.w = P + pl.w;
+            a.bias = (const float*)(P + pl.b);
+            a.y = h->d_logits[w.member];                         // rows of the whole request
+            a.nb = w.batch; a.cin = o.cin; a.cout = o.cout; a.ldy = o.cout;
+            L.flop = 2.0 * nb * o.cin * o.cout;
+            L.bytes = (double)o.cin * o.cout * es + nb * (o.cin + o.cout) * 4.0;
+            L.klass = prof_class(h, "fc_kernel");
+            break;
+        }
+        case ENS_OP_SE: {
+            L.kind = L_SE;
+            SeArgs& a = L.se;
+            a.x = view_of(w, leader, m, o.src, o.src_c0);
+            a.y = view_of(w, leader, m, o.dst, o.dst_c0);
+            a.w1 = (const float*)(P + pl.w); a.b1 = (const float*)(P + pl.b);
+            a.w2 = (const float*)(P + pl.w2); a.b2 = (const float*)(P + pl.b2);
+            a.scratch = (float*)(w.arena + w.layout.offset[pl.scratch]);
+            a.nb = w.batch; a.HW = ts.h * ts.w; a.c = o.cin; a.r = o.r;
+            L.flop = 4.0 * nb * o.cin * o.r;
+            L.bytes = nb * 3.0 * ts.h * ts.w * o.cin * es;
+            L.klass = prof_class(h, "se_kernels");
+            break;
+        }
+        default:
+            return ENS_E_INVALID;
     }
     return ENS_OK;
 }
 
-static void destroy_workers(ens_handle* h) {
-    for (Worker& w : h->workers) {
-        if (w.stream) (void)hipStreamSynchronize(w.stream);
-        if (w.arena) (void)hipFree(w.arena);
-        if (w.done) (void)hipEventDestroy(w.done);
-        if (w.stream) (void)hipStreamDestroy(w.stream);
+// Translates the gang's operations into kernel argument arrays in device memory.
+static int build_launches(ens_handle* h, Gang& g) {
+    const Worker& leader = h->workers[g.workers[0]];
+    const Member& m = h->members[leader.member];
+    const int G = (int)g.workers.size();
+    const size_t slot = 512;                                     // bytes reserved per argument block
+    static_assert(sizeof(ConvArgs) <= 512 && sizeof(PoolArgs) <= 512 && sizeof(SeArgs) <= 512, "argument block");
+    std::vector<char> host((m.ops.size() + 1) * G * slot, 0);
+    if (!g.d_args) HIP_TRY(hipMalloc((void**)&g.d_args, host.size()));
+    g.launches.clear();
+    for (size_t i = 0; i < m.ops.size(); i++) {
+        Launch L;
+        for (int k = G - 1; k >= 0; k--) {                       // k == 0 last: L keeps the leader's copy
+            const int rc = fill_args(h, h->workers[g.workers[k]], leader, h->members[h->workers[g.workers[k]].member].ops[i], L);
+            if (rc != ENS_OK) return rc;
+            char* dst = host.data() + (i * G + k) * slot;
+            switch (L.kind) {
+                case L_CONV: memcpy(dst, &L.conv, sizeof(ConvArgs)); break;
+                case L_DWCONV:
+                case L_POOL: memcpy(dst, &L.pool, sizeof(PoolArgs)); break;
+                case L_GAP: memcpy(dst, &L.gap, sizeof(GapArgs)); break;
+                case L_FC: memcpy(dst, &L.fc, sizeof(FcArgs)); break;
+                case L_SE: memcpy(dst, &L.se, sizeof(SeArgs)); break;
+            }
+        }
+        L.d_argv = g.d_args + i * G * slot;
+        g.launches.push_back(L);
     }
+    // The device arrays are indexed by element size, so every block is re-packed densely.
+    for (size_t i = 0; i < m.ops.size(); i++) {
+        const Launch& L = g.launches[i];
+        size_t sz = 0;
+        switch (L.kind) {
+            case L_CONV: sz = sizeof(ConvArgs); break;
+            case L_DWCONV:
+            case L_POOL: sz = sizeof(PoolArgs); break;
+            case L_GAP: sz = sizeof(GapArgs); break;
+            case L_FC: sz = sizeof(FcArgs); break;
+            case L_SE: sz = sizeof(SeArgs); break;
+        }
+        char* base = host.data() + i * G * slot;
+        for (int k = 1; k < G; k++) memmove(base + k * sz, base + k * slot, sz);
+    }
+    g.stage.src = nullptr;                                       // bound per request
+    g.stage.dst = leader.arena + leader.layout.offset[0];
+    g.stage.nb = leader.batch; g.stage.sh = h->base_h; g.stage.sw = h->base_w;
+    g.stage.dh = m.in_h; g.stage.dw = m.in_w; g.stage.dc = m.tensors[0].cs;
+    g.d_stage = (const StageArgs*)(g.d_args + m.ops.size() * G * slot);
+    HIP_TRY(hipMemcpy(g.d_args, host.data(), host.size(), hipMemcpyHostToDevice));
+    return ENS_OK;
+}
+
+static int ensure_buffers(ens_handle* h, int64_t n);
+
+static void destroy_workers(ens_handle* h) {
+    for (Gang& g : h->gangs) {
+        if (g.stream) (void)hipStreamSynchronize(g.stream);
+        if (g.d_args) (void)hipFree(g.d_args);
+        if (g.done) (void)hipEventDestroy(g.done);
+        if (g.stream) (void)hipStreamDestroy(g.stream);
+    }
+    h->gangs.clear();
+    for (Worker& w : h->workers)
+        if (w.arena) (void)hipFree(w.arena);
     h->workers.clear();
     h->have_alloc = false;
 }
@@ -196,18 +259,55 @@ static int install_alloc(ens_handle* h, const ens_alloc& a, int segment_size) {
             w.arena_bytes = w.layout.bytes;
             h->workers.push_back(w);
         }
+    for (Worker& w : h->workers) {                               // rank among the member's workers
+        w.rank = 0; w.of = 0;
+        for (const Worker& u : h->workers)
+            if (u.member == w.member) { if (u.slot < w.slot) w.rank++; w.of++; }
+    }
     for (Worker& w : h->workers) {
         hipError_t e = hipMalloc((void**)&w.arena, std::max<size_t>(w.arena_bytes, 256));
-        if (e == hipSuccess) e = hipStreamCreateWithFlags(&w.stream, hipStreamNonBlocking);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&w.done, hipEventDisableTiming);
         if (e != hipSuccess) {
             (void)hipGetLastError();
             destroy_workers(h);
             return e == hipErrorOutOfMemory ? ENS_E_NOMEM : ENS_E_HIP;
         }
-        const int rc = build_launches(h, w);
+    }
+    // gangs: same row, same batch size, same share of the segments, same network shape
+    for (size_t i = 0; i < h->workers.size(); i++) {
+        Worker& w = h->workers[i];
+        for (size_t gi = 0; gi < h->gangs.size() && w.gang < 0 && h->gangs_enabled; gi++) {
+            const Worker& l = h->workers[h->gangs[gi].workers[0]];
+            if (l.slot == w.slot && l.batch == w.batch && l.rank == w.rank && l.of == w.of &&
+                same_network(h->members[l.member], h->members[w.member])) {
+                w.gang = (int)gi;
+                h->gangs[gi].workers.push_back((int)i);
+            }
+        }
+        if (w.gang < 0) {
+            Gang g;
+            g.workers.push_back((int)i);
+            g.rank = w.rank; g.of = w.of;
+            w.gang = (int)h->gangs.size();
+            h->gangs.push_back(g);
+        }
+    }
+    if (!h->d_logits.empty() && !h->d_logits[0]) {               // argument blocks hold the logits pointers
+        const int rc0 = ensure_buffers(h, 1);
+        if (rc0 != ENS_OK) { destroy_workers(h); return rc0; }
+    }
+    for (Gang& g : h->gangs) {
+        hipError_t e = hipStreamCreateWithFlags(&g.stream, hipStreamNonBlocking);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&g.done, hipEventDisableTiming);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            destroy_workers(h);
+            return ENS_E_HIP;
+        }
+        const int rc = build_launches(h, g);
         if (rc != ENS_OK) { destroy_workers(h); return rc; }
     }
+    h->args_stale = false;
+    h->bound_images = nullptr;
     h->alloc = a;
     h->alloc.bytes = need;
     h->segment_size = segment_size;
@@ -226,55 +326,41 @@ static hipEvent_t take_event(ens_handle* h) {
     return e;
 }
 
-static hipError_t issue(const Launch& L, const Member& m, hipStream_t s) {
+static hipError_t issue(const Launch& L, bool bf16, int G, int nb, long long first, hipStream_t s) {
     switch (L.kind) {
-        case L_CONV: return m.bf16 ? launch_conv_bf16(L.conv, s) : launch_conv_f32(L.conv, s);
-        case L_DWCONV: return launch_dwconv(L.pool, m.bf16, s);
-        case L_POOL: return launch_pool(L.pool, L.is_max, m.bf16, s);
-        case L_GAP: return launch_gap(L.gap, m.bf16, s);
-        case L_FC: return launch_fc(L.fc, m.bf16, s);
-        case L_SE: return launch_se(L.se, m.bf16, s);
+        case L_CONV: return bf16 ? launch_conv_bf16(L.conv, (const ConvArgs*)L.d_argv, G, nb, s)
+                                 : launch_conv_f32(L.conv, (const ConvArgs*)L.d_argv, G, nb, s);
+        case L_DWCONV: return launch_dwconv(L.pool, (const PoolArgs*)L.d_argv, G, nb, bf16, s);
+        case L_POOL: return launch_pool(L.pool, (const PoolArgs*)L.d_argv, G, nb, L.is_max, bf16, s);
+        case L_GAP: return launch_gap(L.gap, (const GapArgs*)L.d_argv, G, nb, bf16, s);
+        case L_FC: return launch_fc(L.fc, (const FcArgs*)L.d_argv, G, nb, first, bf16, s);
+        case L_SE: return launch_se(L.se, (const SeArgs*)L.d_argv, G, nb, bf16, s);
     }
     return hipErrorInvalidValue;
 }
 
-// One batch of one worker: stage the images into the arena, run the member, write logits rows.
-static int forward_batch(ens_handle* h, Worker& w, const float* d_images, int64_t first, int nb) {
-    const Member& m = h->members[w.member];
-    StageArgs st;
-    st.src = d_images + (size_t)first * h->base_h * h->base_w * 3;
-    st.dst = w.arena + w.layout.offset[0];
-    st.nb = nb; st.sh = h->base_h; st.sw = h->base_w; st.dh = m.in_h; st.dw = m.in_w; st.dc = m.tensors[0].cs;
-    const double scale = (double)nb / w.batch;
+// One batch of one gang: stage the images into the leader's arena, run every member, write the
+// logits rows of the batch.
+static int forward_batch(ens_handle* h, Gang& g, int64_t first, int nb) {
+    const Worker& leader = h->workers[g.workers[0]];
+    const Member& m = h->members[leader.member];
+    const int G = (int)g.workers.size();
+    const double scale = (double)nb / leader.batch;
     auto timed = [&](int klass, double flop, double bytes, auto&& fn) -> hipError_t {
         if (!h->profiling) return fn();
         ProfRec r{klass, take_event(h), take_event(h), flop * scale, bytes * scale};
         if (!r.start || !r.stop) return hipErrorOutOfMemory;
-        hipError_t e = hipEventRecord(r.start, w.stream);
+        hipError_t e = hipEventRecord(r.start, g.stream);
         if (e == hipSuccess) e = fn();
-        if (e == hipSuccess) e = hipEventRecord(r.stop, w.stream);
+        if (e == hipSuccess) e = hipEventRecord(r.stop, g.stream);
         h->prof_recs.push_back(r);
         return e;
     };
-    static const std::string stage_name = "stage_kernel";
-    const double stage_bytes = (double)nb * (h->base_h * h->base_w * 12.0 + (double)m.in_h * m.in_w * st.dc * (m.bf16 ? 2 : 4));
-    HIP_TRY(timed(prof_class(h, stage_name), 0.0, stage_bytes / scale, [&] { return launch_stage(st, m.bf16, w.stream); }));
-    for (Launch& L0 : w.launches) {
-        Launch L = L0;
-        switch (L.kind) {
-            case L_CONV: L.conv.nb = nb; break;
-            case L_DWCONV:
-            case L_POOL: L.pool.nb = nb; break;
-            case L_GAP: L.gap.nb = nb; break;
-            case L_FC:
-                L.fc.nb = nb;
-                L.fc.y = h->d_logits[w.member] + (size_t)first * m.classes;
-                break;
-            case L_SE: L.se.nb = nb; break;
-        }
-        HIP_TRY(timed(L.klass, L.flop, L.bytes, [&] { return issue(L, m, w.stream); }));
-    }
-    w.last_nb = nb;
+    const double stage_bytes = (double)leader.batch * (h->base_h * h->base_w * 12.0 + (double)m.in_h * m.in_w * g.stage.dc * (m.bf16 ? 2 : 4));
+    HIP_TRY(timed(h->stage_klass, 0.0, stage_bytes, [&] { return launch_stage(g.stage, g.d_stage, 1, nb, first, m.bf16, g.stream); }));
+    for (const Launch& L : g.launches)
+        HIP_TRY(timed(L.klass, L.flop * G, L.bytes * G, [&] { return issue(L, m.bf16, G, nb, first, g.stream); }));
+    for (int wi : g.workers) h->workers[wi].last_nb = nb;
     return ENS_OK;
 }
 
@@ -290,6 +376,7 @@ static int ensure_buffers(ens_handle* h, int64_t n) {
         for (size_t m = 0; m < h->members.size(); m++)
             HIP_TRY(hipMalloc((void**)&h->d_logits[m], rows * h->members[m].classes * sizeof(float)));
         h->d_logits_rows = rows;
+        h->args_stale = true;                                  // the FC argument blocks name these buffers
         if (!h->d_logit_ptrs) HIP_TRY(hipMalloc((void**)&h->d_logit_ptrs, ENS_MAX_MEMBERS * sizeof(float*)));
         HIP_TRY(hipMemcpy((void*)h->d_logit_ptrs, h->d_logits.data(), h->members.size() * sizeof(float*), hipMemcpyHostToDevice));
     }
@@ -315,26 +402,40 @@ static int run_device(ens_handle* h, const float* d_images, int64_t n, float* d_
     const int M = (int)h->members.size();
     const int seg = h->segment_size;
     const int64_t n_seg = (n + seg - 1) / seg;
-    std::vector<std::vector<int>> of_member(M);
-    for (size_t i = 0; i < h->workers.size(); i++) of_member[h->workers[i].member].push_back((int)i);
+    if (h->args_stale || h->bound_images != d_images) {          // (re)bind request buffers in the argument blocks
+        for (Gang& g : h->gangs) {
+            if (h->args_stale) {
+                rc = build_launches(h, g);
+                if (rc != ENS_OK) return rc;
+            }
+            g.stage.src = d_images;
+            g.stage.sh = h->base_h; g.stage.sw = h->base_w;
+            HIP_TRY(hipMemcpyAsync((void*)g.d_stage, &g.stage, sizeof(StageArgs), hipMemcpyHostToDevice, h->main_stream));
+        }
+        h->args_stale = false;
+        h->bound_images = d_images;
+    }
     // the workers start once the request images are in place on the main stream
     HIP_TRY(hipEventRecord(h->input_ready, h->main_stream));
-    for (Worker& w : h->workers) HIP_TRY(hipStreamWaitEvent(w.stream, h->input_ready, 0));
+    for (Gang& g : h->gangs) HIP_TRY(hipStreamWaitEvent(g.stream, h->input_ready, 0));
     // every segment id goes once to every member; a member's workers take its segments in turn
     for (int64_t s = 0; s < n_seg; s++) {
         const int64_t start = s * seg, end = std::min<int64_t>((s + 1) * seg, n);
-        for (int m = 0; m < M; m++) {
-            if (!((mask >> m) & 1)) continue;
-            Worker& w = h->workers[of_member[m][s % of_member[m].size()]];
-            for (int64_t a = start; a < end; a += w.batch) {
-                rc = forward_batch(h, w, d_images, a, (int)std::min<int64_t>(w.batch, end - a));
+        for (Gang& g : h->gangs) {
+            if ((int)(s % g.of) != g.rank) continue;
+            bool wanted = false;
+            for (int wi : g.workers) wanted = wanted || ((mask >> h->workers[wi].member) & 1);
+            if (!wanted) continue;
+            const int b = h->workers[g.workers[0]].batch;
+            for (int64_t a = start; a < end; a += b) {
+                rc = forward_batch(h, g, a, (int)std::min<int64_t>(b, end - a));
                 if (rc != ENS_OK) return rc;
             }
         }
     }
-    for (Worker& w : h->workers) {
-        HIP_TRY(hipEventRecord(w.done, w.stream));
-        HIP_TRY(hipStreamWaitEvent(h->main_stream, w.done, 0));
+    for (Gang& g : h->gangs) {
+        HIP_TRY(hipEventRecord(g.done, g.stream));
+        HIP_TRY(hipStreamWaitEvent(h->main_stream, g.done, 0));
     }
     if (mask == ~0ull || M == 1) {
         ProfRec r{prof_class(h, "combine_kernel"), nullptr, nullptr, 0.0, (double)n * h->classes * 4.0 * (M + 1)};
@@ -463,6 +564,7 @@ int ens_load(const ens_member_spec* specs, int32_t n_members, uint64_t seed, ens
     if (hipStreamCreateWithFlags(&h->main_stream, hipStreamNonBlocking) != hipSuccess) return fail(ENS_E_HIP);
     if (hipEventCreateWithFlags(&h->input_ready, hipEventDisableTiming) != hipSuccess) return fail(ENS_E_HIP);
     h->d_logits.assign(h->members.size(), nullptr);
+    h->stage_klass = prof_class(h, "stage_kernel");
     *out = h;
     return ENS_OK;
 }
@@ -495,6 +597,7 @@ int ens_set_io(ens_handle* h, int32_t base_h, int32_t base_w, int32_t images_on_
     }
     h->base_h = base_h;
     h->base_w = base_w;
+    h->bound_images = nullptr;
     h->images_on_device = images_on_device != 0;
     h->probs_on_device = probs_on_device != 0;
     return ENS_OK;
@@ -631,7 +734,9 @@ int ens_plan(ens_handle* h, uint64_t mem_budget_bytes, const ens_plan_opts* opts
             for (int c = 0; c < M; c++) mat[c] = c == m ? b : o.default_batch;
             if (!fit_mem(p, mat.data())) return 0.0;
             const ens_alloc a = to_alloc(mat.data());
+            h->gangs_enabled = false;                            // the member is timed alone
             int r = install_alloc(h, a, o.segment_size);
+            h->gangs_enabled = true;
             if (r == ENS_E_NOMEM) return 0.0;
             if (r != ENS_OK) { hip_rc = r; return 0.0; }
             double ips = 0.0;
@@ -674,6 +779,7 @@ int ens_debug_tensor(ens_handle* h, int32_t member, int32_t tensor, int32_t n_im
     for (const Worker& x : h->workers)
         if (x.member == member) { w = &x; break; }
     if (!w || n_images <= 0 || n_images > w->last_nb) return ENS_E_INVALID;
+    if (tensor == 0) w = &h->workers[h->gangs[w->gang].workers[0]];   // the staged input lives with the gang's leader
     const TensorInfo& ti = m.tensors[tensor];
     const size_t elems = (size_t)n_images * ti.elems_per_image();
     std::vector<uint8_t> raw(elems * (ti.f32 ? 4 : 2));

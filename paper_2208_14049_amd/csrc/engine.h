@@ -59,27 +59,43 @@ ArenaLayout plan_arena(const Member& m, int batch, bool keep_all = false);
 
 enum LaunchKind { L_CONV, L_DWCONV, L_POOL, L_GAP, L_FC, L_SE };
 
+// One operation of a gang: host copy of the first member's arguments (validation, grid sizing)
+// and the device array holding the arguments of every member of the gang.
 struct Launch {
     int kind = 0;
     bool is_max = false;
     int klass = 0;                 // profile class
-    double flop = 0, bytes = 0;    // algorithmic work of the full-batch launch
+    double flop = 0, bytes = 0;    // algorithmic work of one member's full-batch launch
     ConvArgs conv;
     PoolArgs pool;
     GapArgs gap;
     FcArgs fc;
     SeArgs se;
+    const void* d_argv = nullptr;  // device: G argument blocks of this operation's kind
 };
 
 struct Worker {
     int member = 0, batch = 0, slot = 0;
-    hipStream_t stream = nullptr;
-    hipEvent_t done = nullptr;
+    int rank = 0, of = 1;          // this is worker `rank` of the member's `of` workers
+    int gang = -1;
     char* arena = nullptr;
     size_t arena_bytes = 0;
     ArenaLayout layout;
-    std::vector<Launch> launches;
     int last_nb = 0;
+};
+
+// Workers that run the same network shape at the same batch size on the same segments (the
+// replicas of a homogeneous ensemble in one row of the allocation matrix) advance in lockstep:
+// one stream, and one kernel launch per operation whose grid spans all of them.
+struct Gang {
+    std::vector<int> workers;      // indices into ens_handle::workers; [0] leads (its input tensor is shared)
+    int rank = 0, of = 1;
+    hipStream_t stream = nullptr;
+    hipEvent_t done = nullptr;
+    std::vector<Launch> launches;
+    StageArgs stage;
+    const StageArgs* d_stage = nullptr;
+    char* d_args = nullptr;        // device block holding every argument array of the gang
 };
 
 struct ProfClass {
@@ -95,6 +111,9 @@ struct ProfRec { int klass; hipEvent_t start, stop; double flop, bytes; };
 struct ens_handle {
     std::vector<ens::Member> members;
     std::vector<ens::Worker> workers;
+    std::vector<ens::Gang> gangs;
+    bool gangs_enabled = true;                   // false: every worker is a gang of its own
+    bool args_stale = false;                     // request buffers moved: argument arrays need rebuilding
     ens_alloc alloc;
     bool have_alloc = false;
     int segment_size = 128;
@@ -109,6 +128,8 @@ struct ens_handle {
     std::vector<float*> d_logits; size_t d_logits_rows = 0;
     const float** d_logit_ptrs = nullptr;
     float* d_calib = nullptr;   size_t d_calib_images = 0;
+    const float* bound_images = nullptr;         // request images the staging arguments point at
+    int stage_klass = 0;
     int64_t last_n = 0;
     double last_ms = 0;
     // profiling

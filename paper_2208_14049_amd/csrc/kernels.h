@@ -60,7 +60,7 @@ struct FcArgs {                // logits[n][cout] = pooled[n][cin] . W[cin][cout
     const float* x;
     const void* w;             // [cin][cout] in the member's dtype
     const float* bias;
-    float* y;                  // row stride ldy
+    float* y;                  // logits of the whole request, row stride ldy
     int nb, cin, cout;
     int64_t ldy;
 };
@@ -73,24 +73,29 @@ struct SeArgs {                // squeeze-excite
 };
 
 struct StageArgs {             // request images -> a worker's input tensor (convert, pad, resize)
-    const float* src;          // nb x sh x sw x 3 fp32 (first image of the batch)
+    const float* src;          // request images, n x sh x sw x 3 fp32
     void* dst;                 // nb x dh x dw x dc, dtype of the member
     int nb, sh, sw, dh, dw, dc;
 };
 
-hipError_t launch_conv_bf16(const ConvArgs& a, hipStream_t s);
-hipError_t launch_conv_f32(const ConvArgs& a, hipStream_t s);
-hipError_t launch_dwconv(const PoolArgs& a, bool bf16, hipStream_t s);
-hipError_t launch_pool(const PoolArgs& a, bool is_max, bool bf16, hipStream_t s);
-hipError_t launch_gap(const GapArgs& a, bool bf16, hipStream_t s);
-hipError_t launch_fc(const FcArgs& a, bool bf16, hipStream_t s);
-hipError_t launch_se(const SeArgs& a, bool bf16, hipStream_t s);
-hipError_t launch_stage(const StageArgs& a, bool bf16, hipStream_t s);
+// Every launcher runs one kernel for a gang of G members that execute the same operation on
+// tensors of the same shape (the co-located replicas of a homogeneous ensemble): argv is a device
+// array of G argument blocks, blockIdx.z picks the member, `a` is the host copy of argv[0] used
+// for validation and grid sizing.  nb is the number of images of this batch; `first` is the index
+// of the batch's first image in the request (input staging reads there, the FC head writes there).
+hipError_t launch_conv_bf16(const ConvArgs& a, const ConvArgs* argv, int G, int nb, hipStream_t s);
+hipError_t launch_conv_f32(const ConvArgs& a, const ConvArgs* argv, int G, int nb, hipStream_t s);
+hipError_t launch_dwconv(const PoolArgs& a, const PoolArgs* argv, int G, int nb, bool bf16, hipStream_t s);
+hipError_t launch_pool(const PoolArgs& a, const PoolArgs* argv, int G, int nb, bool is_max, bool bf16, hipStream_t s);
+hipError_t launch_gap(const GapArgs& a, const GapArgs* argv, int G, int nb, bool bf16, hipStream_t s);
+hipError_t launch_fc(const FcArgs& a, const FcArgs* argv, int G, int nb, long long first, bool bf16, hipStream_t s);
+hipError_t launch_se(const SeArgs& a, const SeArgs* argv, int G, int nb, bool bf16, hipStream_t s);
+hipError_t launch_stage(const StageArgs& a, const StageArgs* argv, int G, int nb, long long first, bool bf16, hipStream_t s);
 // Y[i, :] = sum_m softmax(logits_m[i, :]) / M ; logits: n_members pointers (device array).
 hipError_t launch_combine(const float* const* logits, int n_members, int64_t n, int classes,
                           float* y, hipStream_t s);
 hipError_t launch_fill_noise(float* p, int64_t count, uint64_t seed, hipStream_t s);
 
-double conv_flops(const ConvArgs& a);
+double conv_flops(const ConvArgs& a, int nb);
 
 }  // namespace ens

@@ -40,7 +40,10 @@ static inline int blocks_for(long long work, int threads) { return (int)((work +
 // One thread per destination pixel: bilinear sample (half-pixel centres, edge clamp) of the three
 // source channels, written as dc channels (zero padded) in the member's dtype.
 template <bool BF16>
-__global__ void stage_kernel(const StageArgs a) {
+__global__ void stage_kernel(const StageArgs* __restrict__ argv, const int nb_, const long long first) {
+    StageArgs a = argv[blockIdx.z];
+    a.nb = nb_;
+    a.src += first * a.sh * a.sw * 3;
     const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const long long total = (long long)a.nb * a.dh * a.dw;
     if (idx >= total) return;
@@ -82,18 +85,21 @@ __global__ void stage_kernel(const StageArgs a) {
     }
 }
 
-hipError_t launch_stage(const StageArgs& a, bool bf16, hipStream_t s) {
-    if (a.nb <= 0 || a.dc < 3) return hipErrorInvalidValue;
-    const long long total = (long long)a.nb * a.dh * a.dw;
-    if (bf16) hipLaunchKernelGGL(stage_kernel<true>, dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(stage_kernel<false>, dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
+hipError_t launch_stage(const StageArgs& a, const StageArgs* argv, int G, int nb, long long first, bool bf16, hipStream_t s) {
+    if (nb <= 0 || a.dc < 3 || G <= 0 || !argv) return hipErrorInvalidValue;
+    const long long total = (long long)nb * a.dh * a.dw;
+    const dim3 g(blocks_for(total, 256), 1, G);
+    if (bf16) hipLaunchKernelGGL(stage_kernel<true>, g, dim3(256), 0, s, argv, nb, first);
+    else hipLaunchKernelGGL(stage_kernel<false>, g, dim3(256), 0, s, argv, nb, first);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ fp32 convolution
 // Reference-precision path (fp32 members): one thread per output element, taps and input
 // channels accumulated in the order kh, kw, ci.  Weights [cout][kh][kw][cin] fp32.
-__global__ void conv_f32_kernel(const ConvArgs a) {
+__global__ void conv_f32_kernel(const ConvArgs* __restrict__ argv, const int nb_) {
+    ConvArgs a = argv[blockIdx.z];
+    a.nb = nb_;
     const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const long long total = (long long)a.nb * a.Ho * a.Wo * a.cout;
     if (idx >= total) return;
@@ -124,11 +130,11 @@ __global__ void conv_f32_kernel(const ConvArgs a) {
     ((float*)a.y.p)[p * a.y.stride + a.y.c0 + co] = act_f(acc, a.act);
 }
 
-hipError_t launch_conv_f32(const ConvArgs& a, hipStream_t s) {
-    if (a.nb <= 0 || a.cin <= 0 || a.cout <= 0 || !a.bias) return hipErrorInvalidValue;
-    const long long total = (long long)a.nb * a.Ho * a.Wo * a.cout;
+hipError_t launch_conv_f32(const ConvArgs& a, const ConvArgs* argv, int G, int nb, hipStream_t s) {
+    if (nb <= 0 || a.cin <= 0 || a.cout <= 0 || !a.bias || G <= 0 || !argv) return hipErrorInvalidValue;
+    const long long total = (long long)nb * a.Ho * a.Wo * a.cout;
     if (total >= (1LL << 31) * 256) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(conv_f32_kernel, dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(conv_f32_kernel, dim3(blocks_for(total, 256), 1, G), dim3(256), 0, s, argv, nb);
     return hipGetLastError();
 }
 
@@ -136,7 +142,9 @@ hipError_t launch_conv_f32(const ConvArgs& a, hipStream_t s) {
 // MODE 0: depthwise convolution (+bias, activation), 1: max pool, 2: average pool over the
 // in-bounds part of the window.  bf16: one lane per (pixel, 8 channels); fp32: per element.
 template <int MODE, bool BF16>
-__global__ void window_kernel(const PoolArgs a) {
+__global__ void window_kernel(const PoolArgs* __restrict__ argv, const int nb_) {
+    PoolArgs a = argv[blockIdx.z];
+    a.nb = nb_;
     constexpr int V = BF16 ? 8 : 1;
     const int cv = a.c / V;
     const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -186,29 +194,30 @@ __global__ void window_kernel(const PoolArgs a) {
 }
 
 static hipError_t check_window(const PoolArgs& a, bool bf16) {
-    if (a.nb <= 0 || a.c <= 0) return hipErrorInvalidValue;
+    if (a.c <= 0) return hipErrorInvalidValue;
     if (bf16 && (a.c % 8 || a.x.stride % 8 || a.x.c0 % 8 || a.y.stride % 8 || a.y.c0 % 8)) return hipErrorInvalidValue;
     return hipSuccess;
 }
 
-hipError_t launch_dwconv(const PoolArgs& a, bool bf16, hipStream_t s) {
-    if (check_window(a, bf16) != hipSuccess || !a.w || !a.bias) return hipErrorInvalidValue;
-    const long long total = (long long)a.nb * a.Ho * a.Wo * (a.c / (bf16 ? 8 : 1));
-    if (bf16) hipLaunchKernelGGL((window_kernel<0, true>), dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((window_kernel<0, false>), dim3(blocks_for(total, 256)), dim3(256), 0, s, a);
+hipError_t launch_dwconv(const PoolArgs& a, const PoolArgs* argv, int G, int nb, bool bf16, hipStream_t s) {
+    if (check_window(a, bf16) != hipSuccess || !a.w || !a.bias || nb <= 0 || G <= 0 || !argv) return hipErrorInvalidValue;
+    const long long total = (long long)nb * a.Ho * a.Wo * (a.c / (bf16 ? 8 : 1));
+    const dim3 g(blocks_for(total, 256), 1, G);
+    if (bf16) hipLaunchKernelGGL((window_kernel<0, true>), g, dim3(256), 0, s, argv, nb);
+    else hipLaunchKernelGGL((window_kernel<0, false>), g, dim3(256), 0, s, argv, nb);
     return hipGetLastError();
 }
 
-hipError_t launch_pool(const PoolArgs& a, bool is_max, bool bf16, hipStream_t s) {
-    if (check_window(a, bf16) != hipSuccess) return hipErrorInvalidValue;
-    const long long total = (long long)a.nb * a.Ho * a.Wo * (a.c / (bf16 ? 8 : 1));
-    const dim3 g(blocks_for(total, 256)), b(256);
+hipError_t launch_pool(const PoolArgs& a, const PoolArgs* argv, int G, int nb, bool is_max, bool bf16, hipStream_t s) {
+    if (check_window(a, bf16) != hipSuccess || nb <= 0 || G <= 0 || !argv) return hipErrorInvalidValue;
+    const long long total = (long long)nb * a.Ho * a.Wo * (a.c / (bf16 ? 8 : 1));
+    const dim3 g(blocks_for(total, 256), 1, G), b(256);
     if (is_max) {
-        if (bf16) hipLaunchKernelGGL((window_kernel<1, true>), g, b, 0, s, a);
-        else hipLaunchKernelGGL((window_kernel<1, false>), g, b, 0, s, a);
+        if (bf16) hipLaunchKernelGGL((window_kernel<1, true>), g, b, 0, s, argv, nb);
+        else hipLaunchKernelGGL((window_kernel<1, false>), g, b, 0, s, argv, nb);
     } else {
-        if (bf16) hipLaunchKernelGGL((window_kernel<2, true>), g, b, 0, s, a);
-        else hipLaunchKernelGGL((window_kernel<2, false>), g, b, 0, s, a);
+        if (bf16) hipLaunchKernelGGL((window_kernel<2, true>), g, b, 0, s, argv, nb);
+        else hipLaunchKernelGGL((window_kernel<2, false>), g, b, 0, s, argv, nb);
     }
     return hipGetLastError();
 }
@@ -218,7 +227,9 @@ hipError_t launch_pool(const PoolArgs& a, bool is_max, bool bf16, hipStream_t s)
 // every pixel row is read in whole lines; the pixels are dealt round-robin to the thread rows
 // and the partial sums are added through LDS.
 template <bool BF16>
-__global__ __launch_bounds__(256) void gap_kernel(const GapArgs a) {
+__global__ __launch_bounds__(256) void gap_kernel(const GapArgs* __restrict__ argv, const int nb_) {
+    GapArgs a = argv[blockIdx.z];
+    a.nb = nb_;
     constexpr int V = BF16 ? 8 : 1;
     __shared__ float part[256 * V];
     const int n = blockIdx.x;
@@ -264,11 +275,11 @@ __global__ __launch_bounds__(256) void gap_kernel(const GapArgs a) {
     }
 }
 
-hipError_t launch_gap(const GapArgs& a, bool bf16, hipStream_t s) {
-    if (a.nb <= 0 || a.c <= 0 || a.HW <= 0) return hipErrorInvalidValue;
+hipError_t launch_gap(const GapArgs& a, const GapArgs* argv, int G, int nb, bool bf16, hipStream_t s) {
+    if (nb <= 0 || a.c <= 0 || a.HW <= 0 || G <= 0 || !argv) return hipErrorInvalidValue;
     if (bf16 && (a.c % 8 || a.x.stride % 8 || a.x.c0 % 8)) return hipErrorInvalidValue;
-    if (bf16) hipLaunchKernelGGL(gap_kernel<true>, dim3(a.nb), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(gap_kernel<false>, dim3(a.nb), dim3(256), 0, s, a);
+    if (bf16) hipLaunchKernelGGL(gap_kernel<true>, dim3(nb, 1, G), dim3(256), 0, s, argv, nb);
+    else hipLaunchKernelGGL(gap_kernel<false>, dim3(nb, 1, G), dim3(256), 0, s, argv, nb);
     return hipGetLastError();
 }
 
@@ -281,7 +292,10 @@ constexpr int FC_IMGS = 8;
 constexpr int FC_KCH = 1024;       // input features staged in LDS at a time
 
 template <bool BF16>
-__global__ __launch_bounds__(256) void fc_kernel(const FcArgs a) {
+__global__ __launch_bounds__(256) void fc_kernel(const FcArgs* __restrict__ argv, const int nb_, const long long first) {
+    FcArgs a = argv[blockIdx.z];
+    a.nb = nb_;
+    a.y += first * a.ldy;
     __shared__ float xs[FC_IMGS * FC_KCH];
     __shared__ float part[4 * FC_IMGS * 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -325,11 +339,11 @@ __global__ __launch_bounds__(256) void fc_kernel(const FcArgs a) {
     }
 }
 
-hipError_t launch_fc(const FcArgs& a, bool bf16, hipStream_t s) {
-    if (a.nb <= 0 || a.cin <= 0 || a.cout <= 0 || !a.bias || !a.y) return hipErrorInvalidValue;
-    const dim3 g((a.cout + 63) / 64, (a.nb + FC_IMGS - 1) / FC_IMGS), b(256);
-    if (bf16) hipLaunchKernelGGL(fc_kernel<true>, g, b, 0, s, a);
-    else hipLaunchKernelGGL(fc_kernel<false>, g, b, 0, s, a);
+hipError_t launch_fc(const FcArgs& a, const FcArgs* argv, int G, int nb, long long first, bool bf16, hipStream_t s) {
+    if (nb <= 0 || a.cin <= 0 || a.cout <= 0 || !a.bias || !a.y || G <= 0 || !argv) return hipErrorInvalidValue;
+    const dim3 g((a.cout + 63) / 64, (nb + FC_IMGS - 1) / FC_IMGS, G), b(256);
+    if (bf16) hipLaunchKernelGGL(fc_kernel<true>, g, b, 0, s, argv, nb, first);
+    else hipLaunchKernelGGL(fc_kernel<false>, g, b, 0, s, argv, nb, first);
     return hipGetLastError();
 }
 
@@ -337,7 +351,9 @@ hipError_t launch_fc(const FcArgs& a, bool bf16, hipStream_t s) {
 // Three small kernels on the worker's stream: channel means, the two tiny FC layers (one
 // workgroup per image), then the channel-wise rescale of the activation tensor.
 template <bool BF16>
-__global__ void se_mean_kernel(const SeArgs a) {
+__global__ void se_mean_kernel(const SeArgs* __restrict__ argv, const int nb_) {
+    SeArgs a = argv[blockIdx.z];
+    a.nb = nb_;
     const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (long long)a.nb * a.c) return;
     const int c = (int)(idx % a.c);
@@ -350,7 +366,9 @@ __global__ void se_mean_kernel(const SeArgs a) {
     a.scratch[n * (2 * a.c + a.r) + c] = acc / (float)a.HW;
 }
 
-__global__ void se_gate_kernel(const SeArgs a) {
+__global__ void se_gate_kernel(const SeArgs* __restrict__ argv, const int nb_) {
+    SeArgs a = argv[blockIdx.z];
+    a.nb = nb_;
     const int n = blockIdx.x;
     float* s = a.scratch + (long long)n * (2 * a.c + a.r);
     float* z = s + a.c;
@@ -371,7 +389,9 @@ __global__ void se_gate_kernel(const SeArgs a) {
 }
 
 template <bool BF16>
-__global__ void se_scale_kernel(const SeArgs a) {
+__global__ void se_scale_kernel(const SeArgs* __restrict__ argv, const int nb_) {
+    SeArgs a = argv[blockIdx.z];
+    a.nb = nb_;
     constexpr int V = BF16 ? 8 : 1;
     const int cv = a.c / V;
     const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -392,16 +412,16 @@ __global__ void se_scale_kernel(const SeArgs a) {
     }
 }
 
-hipError_t launch_se(const SeArgs& a, bool bf16, hipStream_t s) {
-    if (a.nb <= 0 || a.c <= 0 || a.r <= 0 || !a.scratch) return hipErrorInvalidValue;
+hipError_t launch_se(const SeArgs& a, const SeArgs* argv, int G, int nb, bool bf16, hipStream_t s) {
+    if (nb <= 0 || a.c <= 0 || a.r <= 0 || !a.scratch || G <= 0 || !argv) return hipErrorInvalidValue;
     if (bf16 && (a.c % 8 || a.x.stride % 8 || a.x.c0 % 8 || a.y.stride % 8 || a.y.c0 % 8)) return hipErrorInvalidValue;
-    const long long nc = (long long)a.nb * a.c;
-    const long long tot = (long long)a.nb * a.HW * (a.c / (bf16 ? 8 : 1));
-    if (bf16) hipLaunchKernelGGL(se_mean_kernel<true>, dim3(blocks_for(nc, 256)), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(se_mean_kernel<false>, dim3(blocks_for(nc, 256)), dim3(256), 0, s, a);
-    hipLaunchKernelGGL(se_gate_kernel, dim3(a.nb), dim3(256), 0, s, a);
-    if (bf16) hipLaunchKernelGGL(se_scale_kernel<true>, dim3(blocks_for(tot, 256)), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(se_scale_kernel<false>, dim3(blocks_for(tot, 256)), dim3(256), 0, s, a);
+    const long long nc = (long long)nb * a.c;
+    const long long tot = (long long)nb * a.HW * (a.c / (bf16 ? 8 : 1));
+    if (bf16) hipLaunchKernelGGL(se_mean_kernel<true>, dim3(blocks_for(nc, 256), 1, G), dim3(256), 0, s, argv, nb);
+    else hipLaunchKernelGGL(se_mean_kernel<false>, dim3(blocks_for(nc, 256), 1, G), dim3(256), 0, s, argv, nb);
+    hipLaunchKernelGGL(se_gate_kernel, dim3(nb, 1, G), dim3(256), 0, s, argv, nb);
+    if (bf16) hipLaunchKernelGGL(se_scale_kernel<true>, dim3(blocks_for(tot, 256), 1, G), dim3(256), 0, s, argv, nb);
+    else hipLaunchKernelGGL(se_scale_kernel<false>, dim3(blocks_for(tot, 256), 1, G), dim3(256), 0, s, argv, nb);
     return hipGetLastError();
 }
 
