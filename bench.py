@@ -13,6 +13,7 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
+os.environ.setdefault("GPU_MAX_HW_QUEUES", "8")   # one hardware queue per worker stream (before HIP starts)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
@@ -25,7 +26,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--images", type=int, default=1024)
     ap.add_argument("--batch", type=int, default=32)
-    ap.add_argument("--instances", type=int, default=1, help="workers per member (rows of the allocation matrix)")
+    ap.add_argument("--instances", type=int, default=2, help="workers per member (rows of the allocation matrix)")
     ap.add_argument("--cpu-sample", type=int, default=16, help="images the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -357,20 +357,26 @@ double conv_flops(const ConvArgs& a, int nb) {
 struct Variant { int bp, bc, bk; const char* name; };
 static const Variant VARIANTS[] = {
     {128, 32, 64, "conv_igemm_bf16<128,32,k64>"},    // narrow outputs (dense-block growth layers)
-    {64, 64, 64, "conv_igemm_bf16<64,64,k64>"},      // default
-    {64, 64, 32, "conv_igemm_bf16<64,64,k32>"},      // shallow K (1x1 convolutions on few channels)
-    {128, 64, 64, "conv_igemm_bf16<128,64,k64>"},    // few pixels, deep K: used with K splitting
+    {64, 64, 64, "conv_igemm_bf16<64,64,k64>"},      // small grids
+    {64, 64, 32, "conv_igemm_bf16<64,64,k32>"},      // small grids, shallow K
+    {128, 64, 64, "conv_igemm_bf16<128,64,k64>"},    // grids that fill the chip, deep K
+    {128, 64, 32, "conv_igemm_bf16<128,64,k32>"},    // grids that fill the chip, shallow K
 #ifdef ENS_CONV_TUNING
-    {128, 64, 64, "t4"}, {128, 128, 64, "t5"}, {256, 128, 64, "t6"}, {128, 128, 32, "t7"}, {256, 64, 64, "t8"}, {128, 128, 32, "t9"}, {128, 64, 32, "t10"}, {128, 64, 32, "t11"}, {128, 128, 32, "t12"}, {64, 64, 32, "t13"},
+    {128, 128, 64, "t5"}, {256, 128, 64, "t6"}, {128, 128, 32, "t7"}, {256, 64, 64, "t8"}, {128, 128, 32, "t9"},
+    {128, 64, 32, "t10"}, {128, 64, 32, "t11"}, {128, 128, 32, "t12"}, {64, 64, 32, "t13"},
 #endif
 };
 constexpr int CUS = 256;
 
-static int pick_variant(const ConvArgs& a, long long P, long long K) {
+// A gang of G members multiplies the grid by G.  When 128x64 tiles still give two workgroups per
+// compute unit they are taken (a third less L2-to-LDS traffic per flop than 64x64); otherwise
+// the 64x64 tile keeps more workgroups in flight.
+static int pick_variant(const ConvArgs& a, long long P, long long K, int G) {
     if (a.cout <= 32) return 0;
-    if (K <= 256) return 2;
+    const long long t12864 = G * ((P + 127) / 128) * ((a.cout + 63) / 64);
+    if (t12864 >= 2 * CUS) return K <= 640 ? 4 : 3;
     if (P <= 2048 && K >= 2048) return 3;
-    return 1;
+    return K <= 256 ? 2 : 1;
 }
 
 // Splits of the K range for launches that would leave compute units idle.  Each split keeps at
@@ -388,10 +394,10 @@ static int pick_splits(const ConvArgs& a, long long P, long long K, int variant,
     return s < 1 ? 1 : (int)s;
 }
 
-const char* conv_bf16_variant_name(const ConvArgs& a) {
+const char* conv_bf16_variant_name(const ConvArgs& a, int G) {
     const long long P = (long long)a.nb * a.Ho * a.Wo;
     if (a.pre_scale) return conv_regstage_name(a, (int)P);
-    return VARIANTS[pick_variant(a, P, (long long)a.kh * a.kw * a.cin)].name;
+    return VARIANTS[pick_variant(a, P, (long long)a.kh * a.kw * a.cin, G)].name;
 }
 
 template <int BP, int BC, int WP, int WC, int NS, int BKT = 64>
@@ -422,7 +428,7 @@ hipError_t launch_conv_bf16(const ConvArgs& a, const ConvArgs* argv, int G, int 
     if (!a.zeros) return hipErrorInvalidValue;
     // element offsets inside the kernel are 32-bit
     if ((long long)nb * a.H * a.W * a.x.stride >= (1LL << 31) || (long long)a.cout * K64 >= (1LL << 31)) return hipErrorInvalidValue;
-    int variant = pick_variant(a, P64, K64);
+    int variant = pick_variant(a, P64, K64, G);
     int splits = pick_splits(a, P64, K64, variant, G);
 #ifdef ENS_CONV_TUNING   // tile / split override for kernel experiments only
     if (const char* e = getenv("ENS_CONV_VARIANT")) { if (a.cout > 32 || atoi(e) == 0) variant = atoi(e); splits = pick_splits(a, P64, K64, variant, G); }
@@ -432,8 +438,8 @@ hipError_t launch_conv_bf16(const ConvArgs& a, const ConvArgs* argv, int G, int 
         case 0: return launch_variant<128, 32, 4, 1, 2, 64>(a, argv, G, nb, P, splits, s);
         case 2: return launch_variant<64, 64, 2, 2, 2, 32>(a, argv, G, nb, P, splits, s);
         case 3: return launch_variant<128, 64, 2, 2, 2, 64>(a, argv, G, nb, P, splits, s);
+        case 4: return launch_variant<128, 64, 2, 2, 2, 32>(a, argv, G, nb, P, splits, s);
 #ifdef ENS_CONV_TUNING
-        case 4: return launch_variant<128, 64, 2, 2, 3, 64>(a, argv, G, nb, P, splits, s);
         case 5: return launch_variant<128, 128, 2, 2, 2, 64>(a, argv, G, nb, P, splits, s);
         case 6: return launch_variant<256, 128, 2, 2, 2, 64>(a, argv, G, nb, P, splits, s);
         case 7: return launch_variant<128, 128, 2, 2, 3, 32>(a, argv, G, nb, P, splits, s);

@@ -28,7 +28,7 @@ using namespace ens;
 
 namespace ens {
 
-const char* conv_bf16_variant_name(const ConvArgs& a);
+const char* conv_bf16_variant_name(const ConvArgs& a, int G);
 
 static int prof_class(ens_handle* h, const std::string& name) {
     for (size_t i = 0; i < h->prof.size(); i++)
@@ -57,7 +57,7 @@ static bool same_network(const Member& a, const Member& b) {
 }
 
 // Fills one member's argument block for operation `pl`; `L` receives kind, class and work.
-static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, const OpPlan& pl, Launch& L) {
+static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G, const OpPlan& pl, Launch& L) {
     const Member& m = h->members[w.member];
     const int es = m.bf16 ? 2 : 4;
     const ens_op& o = pl.op;
@@ -88,7 +88,7 @@ static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, const
             L.flop = 2.0 * nb * td.h * td.w * o.cout * o.kh * o.kw * o.cin;
             L.bytes = nb * ((double)ts.h * ts.w * o.cin + (double)td.h * td.w * o.cout * (o.res >= 0 ? 2 : 1)) * es +
                       (double)o.kh * o.kw * o.cin * o.cout * es;
-            L.klass = prof_class(h, m.bf16 ? conv_bf16_variant_name(a) : "conv_f32_kernel");
+            L.klass = prof_class(h, m.bf16 ? conv_bf16_variant_name(a, G) : "conv_f32_kernel");
             break;
         }
         case ENS_OP_DWCONV:
@@ -168,7 +168,7 @@ static int build_launches(ens_handle* h, Gang& g) {
     for (size_t i = 0; i < m.ops.size(); i++) {
         Launch L;
         for (int k = G - 1; k >= 0; k--) {                       // k == 0 last: L keeps the leader's copy
-            const int rc = fill_args(h, h->workers[g.workers[k]], leader, h->members[h->workers[g.workers[k]].member].ops[i], L);
+            const int rc = fill_args(h, h->workers[g.workers[k]], leader, G, h->members[h->workers[g.workers[k]].member].ops[i], L);
             if (rc != ENS_OK) return rc;
             char* dst = host.data() + (i * G + k) * slot;
             switch (L.kind) {
