@@ -28,6 +28,8 @@ def main():
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--instances", type=int, default=2, help="workers per member (rows of the allocation matrix)")
     ap.add_argument("--cpu-sample", type=int, default=16, help="images the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the path uses no second device (run with --gpus 1)")
@@ -51,6 +53,12 @@ def main():
     out = torch.empty((n, E.classes), device="cuda", dtype=torch.float32)
     torch.cuda.synchronize()
 
+    if args.copy_calibration:
+        src = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                                          # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         E.ens_predict(images, out)
     torch.cuda.synchronize()
