@@ -15,6 +15,14 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
     u += 0x7FFFu + ((u >> 16) & 1u);                                              // nearest even
     return (uint16_t)(u >> 16);
 }
+// Two floats to a packed pair of bf16 (round to nearest even) with the hardware conversion.
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, b);
+}
 __device__ __forceinline__ float apply_act(float v, int act) {
     if (act == ACT_RELU) return fmaxf(v, 0.f);
     if (act == ACT_SILU) return v / (1.f + __expf(-v));

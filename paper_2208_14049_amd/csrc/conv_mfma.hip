@@ -79,10 +79,6 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restric
     tile_of_block(n_ptiles, n_ctiles, &ptile, &ctile);
     const int p0 = ptile * BP, c0 = ctile * BC;
 
-    const uint16_t* __restrict__ xg = (const uint16_t*)a.x.p;
-    const uint16_t* __restrict__ wg = (const uint16_t*)a.w;
-    const uint16_t* __restrict__ zg = (const uint16_t*)a.zeros;
-
     // ---- this workgroup's share of the K tiles
     const int nk_all = (K + BKT - 1) / BKT;
     const int per_split = (nk_all + gridDim.y - 1) / gridDim.y;
@@ -90,37 +86,52 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restric
     const int nk = max(0, min(nk_all, kt0 + per_split) - kt0);
 
     // ---- load side: this thread fills slot (t % CH) of rows r0 + RS*i with chunk cchunk; the
-    //      swizzle key is (r >> 1) & 7 for 128-byte rows and (r >> 2) & 3 for 64-byte rows
+    //      swizzle key is (r >> 1) & 7 for 128-byte rows and (r >> 2) & 3 for 64-byte rows.
+    // Loads go through buffer descriptors: a lane whose byte offset lies past the end of the
+    // buffer gets zeros written to its LDS slot, which is how padding taps, rows past the last
+    // pixel, channels past the last output channel and the K tail are filled.
+    constexpr unsigned OOB = 0xFFFFFFF0u;
+    const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)a.x.p, 0, (int)((unsigned)nb_ * (unsigned)(a.H * a.W) * (unsigned)a.x.stride * 2u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)a.w, 0, (int)((unsigned)a.cout * (unsigned)K * 2u), 0x00020000);
     const int r0 = t / CH;
     const int cchunk = (t % CH) ^ (CH == 8 ? (r0 >> 1) & 7 : (r0 >> 2) & 3);
     const int cpt = a.cin >> 3;                                  // 16-byte chunks per filter tap
     const int ntaps = a.kh * a.kw;
-    int rowoff[NPL];                                             // element offset of the window origin
-    int hi0[NPL], wi0[NPL];                                      // image coordinates of the window origin
+    // Per pixel row: byte offset of the window origin and the taps that fall inside the image,
+    // bit kh of the low half-word for filter rows, bit 16 + kw for filter columns.
+    unsigned rowoff[NPL], tapmask[NPL];
 #pragma unroll
     for (int i = 0; i < NPL; i++) {
         const int p = p0 + r0 + RS * i;
         rowoff[i] = 0;
-        hi0[i] = -(1 << 28);                                     // rows past the end: never in bounds
-        wi0[i] = 0;
+        tapmask[i] = 0;                                          // rows past the end: no tap is valid
         if (p < P) {
-            const int n = p / (a.Ho * a.Wo);
-            const int rem = p - n * (a.Ho * a.Wo);
-            const int ho = rem / a.Wo, wo = rem - ho * a.Wo;
-            hi0[i] = ho * a.sh - a.pt;
-            wi0[i] = wo * a.sw - a.pl;
-            rowoff[i] = ((n * a.H + hi0[i]) * a.W + wi0[i]) * a.x.stride + a.x.c0;
+            // p -> (image, row, column) with one double multiply per division and a correction step
+            int n = (int)((double)p * a.inv_hw);
+            int rem = p - n * (a.Ho * a.Wo);
+            if (rem < 0) { n--; rem += a.Ho * a.Wo; } else if (rem >= a.Ho * a.Wo) { n++; rem -= a.Ho * a.Wo; }
+            int ho = (int)((double)rem * a.inv_w);
+            int wo = rem - ho * a.Wo;
+            if (wo < 0) { ho--; wo += a.Wo; } else if (wo >= a.Wo) { ho++; wo -= a.Wo; }
+            const int hi0 = ho * a.sh - a.pt, wi0 = wo * a.sw - a.pl;
+            unsigned m = 0;
+            for (int k = 0; k < a.kh; k++) m |= (unsigned)(hi0 + k) < (unsigned)a.H ? 1u << k : 0u;
+            for (int k = 0; k < a.kw; k++) m |= (unsigned)(wi0 + k) < (unsigned)a.W ? 0x10000u << k : 0u;
+            tapmask[i] = m;
+            rowoff[i] = (unsigned)((((n * a.H + hi0) * a.W + wi0) * a.x.stride + a.x.c0) * 2);
         }
     }
-    int wrowoff[NCL];                                            // element offset of the weight row, -1: none
+    unsigned wrowoff[NCL];                                       // byte offset of the weight row
 #pragma unroll
     for (int i = 0; i < NCL; i++) {
         const int r = r0 + RS * i;
-        wrowoff[i] = c0 + r < a.cout ? (c0 + r) * K : -1;
+        wrowoff[i] = c0 + r < a.cout ? (unsigned)(c0 + r) * (unsigned)K * 2u : OOB;
     }
 
     // Position of this thread's chunk in the K walk: chunk kc -> filter tap (khi, kwi) and channel
-    // chunk cq inside the tap; tapbase is the tap's element offset from the window origin.  The
+    // chunk cq inside the tap; tapbase is the tap's byte offset from the window origin.  The
     // start comes from a division (the quotients are at most a few dozen, so a float multiply with
     // a half-step guard is exact); after that every K tile moves CH chunks on with adds and
     // selects when a tap holds at least CH chunks, and by division otherwise (narrow inputs).
@@ -132,11 +143,12 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restric
         cq = kc - tap * cpt;
         khi = (int)(((float)tap + 0.5f) * inv_kw);
         kwi = tap - khi * a.kw;
-        tapbase = (khi * a.W + kwi) * a.x.stride;
+        tapbase = (khi * a.W + kwi) * a.x.stride * 2;
     };
     locate();
     const bool wide = cpt >= CH;
-    const int row_step = (a.W - a.kw) * a.x.stride;              // from the last tap of a filter row to the next row
+    const int col_step = a.x.stride * 2;                         // one tap to the right
+    const int row_step = (a.W - a.kw) * a.x.stride * 2;          // from past the last tap of a filter row to the next row
     int issued = 0;                                              // K tiles issued so far
 
     // Issues the NLOAD asynchronous loads of the next K tile into ring stage `stage`.  Tiles past
@@ -145,20 +157,20 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restric
     auto issue_tile = [&](int stage) {
         const bool in_range = issued < nk;
         const bool live = in_range && tap < ntaps;
-        const int off = tapbase + cq * 8;
+        const unsigned need = live ? (1u << khi) | (0x10000u << kwi) : 0xFFFFFFFFu;   // both bits, or never
+        const unsigned off = (unsigned)(tapbase + cq * 16);
         unsigned char* base = ring + stage * STAGE + wave * 1024;
 #pragma unroll
         for (int i = 0; i < NPL; i++) {
-            const bool ok = live && (unsigned)(hi0[i] + khi) < (unsigned)a.H && (unsigned)(wi0[i] + kwi) < (unsigned)a.W;
-            const uint16_t* src = ok ? xg + (rowoff[i] + off) : zg;
-            __builtin_amdgcn_global_load_lds((global_ptr_t)src, (lds_ptr_t)(base + i * 4096), 16, 0, 0);
+            const unsigned o = (tapmask[i] & need) == need ? rowoff[i] + off : OOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (lds_ptr_t)(base + i * 4096), 16, o, 0, 0, 0);
         }
         const bool k_ok = in_range && kc * 8 < K;
+        const unsigned koffs = (unsigned)kc * 16u;
 #pragma unroll
         for (int i = 0; i < NCL; i++) {
-            const bool ok = k_ok && wrowoff[i] >= 0;
-            const uint16_t* src = ok ? wg + ((long long)wrowoff[i] + kc * 8) : zg;
-            __builtin_amdgcn_global_load_lds((global_ptr_t)src, (lds_ptr_t)(base + (NPL + i) * 4096), 16, 0, 0);
+            const unsigned o = k_ok && wrowoff[i] != OOB ? wrowoff[i] + koffs : OOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wres, (lds_ptr_t)(base + (NPL + i) * 4096), 16, o, 0, 0, 0);
         }
         // on to the next K tile
         issued++;
@@ -169,7 +181,7 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restric
             cq -= wrap ? cpt : 0;
             tap += wrap ? 1 : 0;
             kwi += wrap ? 1 : 0;
-            tapbase += wrap ? a.x.stride : 0;
+            tapbase += wrap ? col_step : 0;
             const bool wrap2 = kwi == a.kw;
             kwi = wrap2 ? 0 : kwi;
             khi += wrap2 ? 1 : 0;
@@ -305,8 +317,7 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restric
             }
             uint32_t o[4];
 #pragma unroll
-            for (int q = 0; q < 4; q++)
-                o[q] = (uint32_t)f32_to_bf16(apply_act(v[2 * q], a.act)) | ((uint32_t)f32_to_bf16(apply_act(v[2 * q + 1], a.act)) << 16);
+            for (int q = 0; q < 4; q++) o[q] = pack_bf16x2(apply_act(v[2 * q], a.act), apply_act(v[2 * q + 1], a.act));
             *(uint4*)(yg + (size_t)p * a.y.stride + a.y.c0 + co) = make_uint4(o[0], o[1], o[2], o[3]);
         }
     }
@@ -340,8 +351,8 @@ __global__ void conv_splitk_epilogue(const ConvArgs* __restrict__ argv, const in
     v0 = apply_act(v0, a.act); v1 = apply_act(v1, a.act);
     v2 = apply_act(v2, a.act); v3 = apply_act(v3, a.act);
     uint2 o;
-    o.x = (uint32_t)f32_to_bf16(v0) | ((uint32_t)f32_to_bf16(v1) << 16);
-    o.y = (uint32_t)f32_to_bf16(v2) | ((uint32_t)f32_to_bf16(v3) << 16);
+    o.x = pack_bf16x2(v0, v1);
+    o.y = pack_bf16x2(v2, v3);
     *(uint2*)((uint16_t*)a.y.p + (size_t)p * a.y.stride + a.y.c0 + co) = o;
 }
 
@@ -425,9 +436,8 @@ hipError_t launch_conv_bf16(const ConvArgs& a, const ConvArgs* argv, int G, int 
     if (P64 <= 0 || P64 >= (1LL << 31) || K64 >= (1LL << 31)) return hipErrorInvalidValue;
     const int P = (int)P64;
     if (a.pre_scale) return launch_conv_regstage(a, argv, G, nb, P, s);
-    if (!a.zeros) return hipErrorInvalidValue;
-    // element offsets inside the kernel are 32-bit
-    if ((long long)nb * a.H * a.W * a.x.stride >= (1LL << 31) || (long long)a.cout * K64 >= (1LL << 31)) return hipErrorInvalidValue;
+    // byte offsets inside the kernel are unsigned 32-bit, 0xFFFFFFF0 stands for 'out of range'
+    if ((long long)nb * a.H * a.W * a.x.stride >= 0x7FFFFF00LL || (long long)a.cout * K64 >= 0x70000000LL || a.kh > 16 || a.kw > 16) return hipErrorInvalidValue;
     int variant = pick_variant(a, P64, K64, G);
     int splits = pick_splits(a, P64, K64, variant, G);
 #ifdef ENS_CONV_TUNING   // tile / split override for kernel experiments only

@@ -85,6 +85,7 @@ static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G
             }
             a.nb = w.batch; a.H = ts.h; a.W = ts.w; a.cin = pl.cin_s; a.Ho = td.h; a.Wo = td.w; a.cout = o.cout;
             a.kh = o.kh; a.kw = o.kw; a.sh = o.sh; a.sw = o.sw; a.pt = o.pt; a.pl = o.pl; a.act = o.act;
+            a.inv_hw = 1.0 / ((double)td.h * td.w); a.inv_w = 1.0 / (double)td.w;
             L.flop = 2.0 * nb * td.h * td.w * o.cout * o.kh * o.kw * o.cin;
             L.bytes = nb * ((double)ts.h * ts.w * o.cin + (double)td.h * td.w * o.cout * (o.res >= 0 ? 2 : 1)) * es +
                       (double)o.kh * o.kw * o.cin * o.cout * es;

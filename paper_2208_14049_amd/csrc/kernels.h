@@ -33,7 +33,8 @@ struct ConvArgs {
     // split-K scratch of the worker (may be null: no splitting): room for ws_floats partial sums
     float* ws;
     long long ws_floats;
-    const void* zeros;         // at least 16 bytes of zeros in device memory (source of padding)
+    const void* zeros;         // at least 16 bytes of zeros in device memory (padding source of the register-staged kernel)
+    double inv_hw, inv_w;      // 1 / (Ho * Wo) and 1 / Wo, for the pixel index decomposition
     int nb, H, W, cin, Ho, Wo, cout;
     int kh, kw, sh, sw, pt, pl;
     int act;

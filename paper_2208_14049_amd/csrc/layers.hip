@@ -28,9 +28,14 @@ __device__ __forceinline__ void unpack8(const uint4 v, float* f) {
     }
 }
 __device__ __forceinline__ uint4 pack8(const float* f) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
     uint32_t u[4];
 #pragma unroll
-    for (int e = 0; e < 4; e++) u[e] = (uint32_t)f2bf(f[2 * e]) | ((uint32_t)f2bf(f[2 * e + 1]) << 16);
+    for (int e = 0; e < 4; e++) {
+        const f32x2_t v = {f[2 * e], f[2 * e + 1]};
+        u[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));   // v_cvt_pk_bf16_f32, nearest even
+    }
     return make_uint4(u[0], u[1], u[2], u[3]);
 }
 
