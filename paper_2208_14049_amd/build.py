@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libens_mi355x.so")
-SOURCES = ["conv_mfma.hip", "conv_regstage.hip", "layers.hip", "member.cpp", "planner.cpp", "seedgen.cpp", "engine.cpp"]
+SOURCES = ["conv_mfma.hip", "conv_halo.hip", "conv_regstage.hip", "layers.hip", "member.cpp", "planner.cpp", "seedgen.cpp", "engine.cpp"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]
@@ -33,7 +33,7 @@ def build(verbose=False):
             print(src + ":\n" + out)
     if failed:
         raise RuntimeError("building the HIP library failed")
-    subprocess.check_call(["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs)
+    subprocess.check_call(["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-Wl,--no-undefined", "-o", LIB] + objs)
     return LIB
 
 

@@ -29,6 +29,15 @@ __device__ __forceinline__ float apply_act(float v, int act) {
     return v;
 }
 
+// Bytes per lane of an asynchronous global-to-LDS load.  The 16-byte form exists on gfx950 only and
+// the compiler checks the size against the target of the pass it is in: the host pass, which only
+// needs the kernels' signatures, would silently drop a kernel template that names it.
+#if defined(__HIP_DEVICE_COMPILE__)
+constexpr int LDS_LOAD_BYTES = 16;
+#else
+constexpr int LDS_LOAD_BYTES = 4;
+#endif
+
 constexpr int BK = 64;          // K elements per LDS tile: one 128-byte row, 8 chunks of 16 bytes
 
 // Workgroup id -> (pixel tile, channel tile).  Consecutive workgroup ids go to different XCDs
@@ -46,5 +55,15 @@ __device__ __forceinline__ void tile_of_block(int n_ptiles, int n_ctiles, int* p
 // Register-staged variant (pre-activated inputs); defined in conv_regstage.hip.
 hipError_t launch_conv_regstage(const ConvArgs& a, const ConvArgs* argv, int G, int nb, int P, hipStream_t s);
 const char* conv_regstage_name(const ConvArgs& a, int P);
+
+// Second pass of a convolution whose K range was split: sums the `splits` fp32 slices of P x cout
+// partial sums in the workspace and applies bias, residual and activation; defined in conv_mfma.hip.
+hipError_t launch_conv_splitk_epilogue(const ConvArgs& a, const ConvArgs* argv, int G, int nb, int P, int splits, hipStream_t s);
+
+// 3x3 stride-1 kernel with the input window resident in LDS; defined in conv_halo.hip.
+// conv_halo_pick returns the variant that runs the layer, or -1 when the generic kernel does.
+int conv_halo_pick(const ConvArgs& a, int nb, int G);
+const char* conv_halo_name(int variant);
+hipError_t launch_conv_halo(const ConvArgs& a, const ConvArgs* argv, int G, int nb, int variant, hipStream_t s);
 
 }  // namespace ens

@@ -72,7 +72,8 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restric
     static_assert(HROWS >= 32 && BP % HROWS == 0 && HROWS * OROW * 4 <= RING, "output staging chunk");
     __shared__ __attribute__((aligned(1024))) unsigned char ring[RING];
 
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);     // wave-uniform: LDS stage bases stay scalar
     const int wp0 = (wave % WP) * WTP, wc0 = (wave / WP) * WTC;
     const int n_ptiles = (P + BP - 1) / BP, n_ctiles = (a.cout + BC - 1) / BC;
     int ptile, ctile;
@@ -163,14 +164,14 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restric
 #pragma unroll
         for (int i = 0; i < NPL; i++) {
             const unsigned o = (tapmask[i] & need) == need ? rowoff[i] + off : OOB;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (lds_ptr_t)(base + i * 4096), 16, o, 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (lds_ptr_t)(base + i * 4096), LDS_LOAD_BYTES, o, 0, 0, 0);
         }
         const bool k_ok = in_range && kc * 8 < K;
         const unsigned koffs = (unsigned)kc * 16u;
 #pragma unroll
         for (int i = 0; i < NCL; i++) {
             const unsigned o = k_ok && wrowoff[i] != OOB ? wrowoff[i] + koffs : OOB;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(wres, (lds_ptr_t)(base + (NPL + i) * 4096), 16, o, 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wres, (lds_ptr_t)(base + (NPL + i) * 4096), LDS_LOAD_BYTES, o, 0, 0, 0);
         }
         // on to the next K tile
         issued++;
@@ -356,6 +357,12 @@ __global__ void conv_splitk_epilogue(const ConvArgs* __restrict__ argv, const in
     *(uint2*)((uint16_t*)a.y.p + (size_t)p * a.y.stride + a.y.c0 + co) = o;
 }
 
+hipError_t launch_conv_splitk_epilogue(const ConvArgs& a, const ConvArgs* argv, int G, int nb, int P, int splits, hipStream_t s) {
+    const long long work = (long long)P * (a.cout / 4);
+    hipLaunchKernelGGL(conv_splitk_epilogue, dim3((unsigned)((work + 255) / 256), 1, G), dim3(256), 0, s, argv, nb, splits);
+    return hipGetLastError();
+}
+
 double conv_flops(const ConvArgs& a, int nb) {
     return 2.0 * (double)nb * a.Ho * a.Wo * a.cout * a.kh * a.kw * a.cin;
 }
@@ -386,7 +393,6 @@ static int pick_variant(const ConvArgs& a, long long P, long long K, int G) {
     if (a.cout <= 32) return 0;
     const long long t12864 = G * ((P + 127) / 128) * ((a.cout + 63) / 64);
     if (t12864 >= 2 * CUS) return K <= 640 ? 4 : 3;
-    if (P <= 2048 && K >= 2048) return 3;
     return K <= 256 ? 2 : 1;
 }
 
@@ -408,6 +414,7 @@ static int pick_splits(const ConvArgs& a, long long P, long long K, int variant,
 const char* conv_bf16_variant_name(const ConvArgs& a, int G) {
     const long long P = (long long)a.nb * a.Ho * a.Wo;
     if (a.pre_scale) return conv_regstage_name(a, (int)P);
+    if (const int hv = conv_halo_pick(a, a.nb, G); hv >= 0) return conv_halo_name(hv);
     return VARIANTS[pick_variant(a, P, (long long)a.kh * a.kw * a.cin, G)].name;
 }
 
@@ -416,11 +423,7 @@ static hipError_t launch_variant(const ConvArgs& a, const ConvArgs* argv, int G,
     const dim3 grid(((P + BP - 1) / BP) * ((a.cout + BC - 1) / BC), splits, G);
     hipLaunchKernelGGL((conv_igemm_bf16<BP, BC, WP, WC, NS, BKT>), grid, dim3(256), 0, s, argv, nb);
     hipError_t e = hipGetLastError();
-    if (e == hipSuccess && splits > 1) {
-        const long long work = (long long)P * (a.cout / 4);
-        hipLaunchKernelGGL(conv_splitk_epilogue, dim3((unsigned)((work + 255) / 256), 1, G), dim3(256), 0, s, argv, nb, splits);
-        e = hipGetLastError();
-    }
+    if (e == hipSuccess && splits > 1) e = launch_conv_splitk_epilogue(a, argv, G, nb, P, splits, s);
     return e;
 }
 
@@ -436,6 +439,7 @@ hipError_t launch_conv_bf16(const ConvArgs& a, const ConvArgs* argv, int G, int 
     if (P64 <= 0 || P64 >= (1LL << 31) || K64 >= (1LL << 31)) return hipErrorInvalidValue;
     const int P = (int)P64;
     if (a.pre_scale) return launch_conv_regstage(a, argv, G, nb, P, s);
+    if (const int hv = conv_halo_pick(a, nb, G); hv >= 0) return launch_conv_halo(a, argv, G, nb, hv, s);
     // byte offsets inside the kernel are unsigned 32-bit, 0xFFFFFFF0 stands for 'out of range'
     if ((long long)nb * a.H * a.W * a.x.stride >= 0x7FFFFF00LL || (long long)a.cout * K64 >= 0x70000000LL || a.kh > 16 || a.kw > 16) return hipErrorInvalidValue;
     int variant = pick_variant(a, P64, K64, G);

@@ -135,6 +135,11 @@ def oracle_tensor(net, blob, imgs, t):
 CONV_LAYERS = [
     # (H, W, cin, cout, k, stride, pad, extra)       shapes span several tiles and ragged tails
     (56, 56, 64, 64, 3, 1, "same", {}),
+    (28, 28, 128, 128, 3, 1, "same", {}),
+    (28, 28, 64, 64, 3, 1, "same", {"res": True}),             # residual read from the layer's own input
+    (14, 14, 256, 256, 1, 1, "same", {"res": True}),
+    (14, 14, 256, 96, 3, 1, "same", {}),
+    (20, 37, 64, 72, 3, 1, "same", {"act": None}),
     (56, 56, 64, 256, 1, 1, "same", {}),
     (28, 28, 128, 128, 3, 2, "same", {}),
     (14, 14, 256, 512, 1, 2, "same", {"act": None}),
@@ -156,7 +161,10 @@ CONV_LAYERS = [
 @pytest.mark.parametrize("case", CONV_LAYERS, ids=lambda c: "%dx%dx%d-%d-k%s-s%d" % (c[0], c[1], c[2], c[3], c[4], c[5]))
 def test_conv_layer_bf16(ens, case):
     h, w, cin, cout, k, stride, pad, extra = case
-    net, t = layer_net(h, w, cin, lambda n, s: n.conv(s, cout, k, stride=stride, pad=pad, **extra), "bf16")
+    extra = dict(extra)
+    with_res = extra.pop("res", False)
+    net, t = layer_net(h, w, cin, lambda n, s: n.conv(s, cout, k, stride=stride, pad=pad,
+                                                      res=s if with_res else None, **extra), "bf16")
     nb = 3
     blobs, imgs = prepared([net], 11, nb, h, bf16=True)
     imgs = W.round_bf16(W.make_images(4, nb, h, w))
@@ -174,6 +182,8 @@ def test_conv_layer_bf16(ens, case):
         sub.ops, sub.params, sub.blob_size = [dict(net.ops[-3])], net.params, net.blob_size
         sub.tensors = [net.tensors[src], net.tensors[t]]
         sub.ops[0].update(src=0, dst=1)
+        if with_res:
+            sub.ops[0].update(res=0)
         sub.out_tensor = 1
         ref = oracle.forward_logits(sub, blobs[0], x_in, real="f64").reshape(got.shape)
     else:
