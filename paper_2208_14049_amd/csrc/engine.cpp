@@ -86,7 +86,7 @@ static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G
             a.nb = w.batch; a.H = ts.h; a.W = ts.w; a.cin = pl.cin_s; a.Ho = td.h; a.Wo = td.w; a.cout = o.cout;
             a.kh = o.kh; a.kw = o.kw; a.sh = o.sh; a.sw = o.sw; a.pt = o.pt; a.pl = o.pl; a.act = o.act;
             a.inv_hw = 1.0 / ((double)td.h * td.w); a.inv_w = 1.0 / (double)td.w;
-            L.flop = 2.0 * nb * td.h * td.w * o.cout * o.kh * o.kw * o.cin;
+            L.flop = 2.0 * nb * td.h * td.w * o.cout * (pl.alg_k > 0 ? pl.alg_k : o.kh * o.kw * o.cin);
             L.bytes = nb * ((double)ts.h * ts.w * o.cin + (double)td.h * td.w * o.cout * (o.res >= 0 ? 2 : 1)) * es +
                       (double)o.kh * o.kw * o.cin * o.cout * es;
             L.klass = prof_class(h, m.bf16 ? conv_bf16_variant_name(a, G) : "conv_f32_kernel");
@@ -202,7 +202,7 @@ static int build_launches(ens_handle* h, Gang& g) {
     g.stage.src = nullptr;                                       // bound per request
     g.stage.dst = leader.arena + leader.layout.offset[0];
     g.stage.nb = leader.batch; g.stage.sh = h->base_h; g.stage.sw = h->base_w;
-    g.stage.dh = m.in_h; g.stage.dw = m.in_w; g.stage.dc = m.tensors[0].cs;
+    g.stage.dh = m.in_h; g.stage.dw = m.in_w; g.stage.dc = m.tensors[0].cs; g.stage.s2d = m.stem_s2d ? 1 : 0;
     g.d_stage = (const StageArgs*)(g.d_args + m.ops.size() * G * slot);
     HIP_TRY(hipMemcpy(g.d_args, host.data(), host.size(), hipMemcpyHostToDevice));
     return ENS_OK;
@@ -357,7 +357,7 @@ static int forward_batch(ens_handle* h, Gang& g, int64_t first, int nb) {
         h->prof_recs.push_back(r);
         return e;
     };
-    const double stage_bytes = (double)leader.batch * (h->base_h * h->base_w * 12.0 + (double)m.in_h * m.in_w * g.stage.dc * (m.bf16 ? 2 : 4));
+    const double stage_bytes = (double)leader.batch * (h->base_h * h->base_w * 12.0 + (double)m.tensors[0].h * m.tensors[0].w * g.stage.dc * (m.bf16 ? 2 : 4));
     HIP_TRY(timed(h->stage_klass, 0.0, stage_bytes, [&] { return launch_stage(g.stage, g.d_stage, 1, nb, first, m.bf16, g.stream); }));
     for (const Launch& L : g.launches)
         HIP_TRY(timed(L.klass, L.flop * G, L.bytes * G, [&] { return issue(L, m.bf16, G, nb, first, g.stream); }));

@@ -28,6 +28,7 @@ struct OpPlan {
     size_t w, b, pre_scale, pre_shift, w2, b2;
     int cin_s;       // stored input channels of the convolution's K axis
     int scratch;     // index of the scratch pseudo-tensor (squeeze-excite), -1 otherwise
+    int alg_k;       // multiply-adds per output element as the network defines the layer (0: kh*kw*cin of op)
 };
 
 struct Member {
@@ -37,6 +38,9 @@ struct Member {
     std::vector<OpPlan> ops;
     std::vector<uint8_t> host_params;    // folded, converted, laid out for the device
     size_t zeros_off = 0;                // 256 zero bytes inside the parameter block (padding source)
+    // The stride-2 convolution that reads the input image runs as a stride-1 convolution over the
+    // image stored space-to-depth (tensor 0 is then ceil(h/2) x ceil(w/2) x 12, stored 16 wide).
+    bool stem_s2d = false;
     char* dev_params = nullptr;
     size_t weight_bytes() const { return host_params.size(); }
 };

@@ -75,8 +75,13 @@ struct SeArgs {                // squeeze-excite
 
 struct StageArgs {             // request images -> a worker's input tensor (convert, pad, resize)
     const float* src;          // request images, n x sh x sw x 3 fp32
-    void* dst;                 // nb x dh x dw x dc, dtype of the member
+    void* dst;                 // nb x dh x dw x dc, dtype of the member; see s2d
     int nb, sh, sw, dh, dw, dc;
+    // s2d != 0 (bf16, dc == 16): the dh x dw image is stored "space to depth", as
+    // ceil(dh/2) x ceil(dw/2) pixels whose channel (2*by + bx)*3 + c is channel c of image pixel
+    // (2*r + by, 2*q + bx); channels 12..15 and pixels past the image are zero.  A stride-2
+    // convolution over the image is a stride-1 convolution over this tensor.
+    int s2d;
 };
 
 // Every launcher runs one kernel for a gang of G members that execute the same operation on

@@ -42,8 +42,31 @@ __device__ __forceinline__ uint4 pack8(const float* f) {
 static inline int blocks_for(long long work, int threads) { return (int)((work + threads - 1) / threads); }
 
 // ------------------------------------------------------------------ input staging
-// One thread per destination pixel: bilinear sample (half-pixel centres, edge clamp) of the three
-// source channels, written as dc channels (zero padded) in the member's dtype.
+// Bilinear sample (half-pixel centres, edge clamp) of the three source channels at destination
+// pixel (y, x) of a dh x dw image; a plain copy when the sizes agree.
+__device__ __forceinline__ void stage_sample(const StageArgs& a, const float* __restrict__ src, int y, int x, float* v) {
+    if (a.sh == a.dh && a.sw == a.dw) {
+        const float* p = src + ((long long)y * a.sw + x) * 3;
+        v[0] = p[0]; v[1] = p[1]; v[2] = p[2];
+        return;
+    }
+    float fy = (y + 0.5f) * ((float)a.sh / (float)a.dh) - 0.5f;
+    float fx = (x + 0.5f) * ((float)a.sw / (float)a.dw) - 0.5f;
+    fy = fminf(fmaxf(fy, 0.f), (float)(a.sh - 1));
+    fx = fminf(fmaxf(fx, 0.f), (float)(a.sw - 1));
+    const int y0 = (int)floorf(fy), x0 = (int)floorf(fx);
+    const int y1 = min(y0 + 1, a.sh - 1), x1 = min(x0 + 1, a.sw - 1);
+    const float wy = fy - y0, wx = fx - x0;
+#pragma unroll
+    for (int c = 0; c < 3; c++) {
+        const float p00 = src[((long long)y0 * a.sw + x0) * 3 + c], p01 = src[((long long)y0 * a.sw + x1) * 3 + c];
+        const float p10 = src[((long long)y1 * a.sw + x0) * 3 + c], p11 = src[((long long)y1 * a.sw + x1) * 3 + c];
+        const float top = p00 * (1.f - wx) + p01 * wx, bot = p10 * (1.f - wx) + p11 * wx;
+        v[c] = top * (1.f - wy) + bot * wy;
+    }
+}
+
+// One thread per destination pixel, written as dc channels (zero padded) in the member's dtype.
 template <bool BF16>
 __global__ void stage_kernel(const StageArgs* __restrict__ argv, const int nb_, const long long first) {
     StageArgs a = argv[blockIdx.z];
@@ -57,25 +80,7 @@ __global__ void stage_kernel(const StageArgs* __restrict__ argv, const int nb_, 
     const long long n = idx / ((long long)a.dw * a.dh);
     const float* src = a.src + n * (long long)a.sh * a.sw * 3;
     float v[3];
-    if (a.sh == a.dh && a.sw == a.dw) {
-        const float* p = src + ((long long)y * a.sw + x) * 3;
-        v[0] = p[0]; v[1] = p[1]; v[2] = p[2];
-    } else {
-        float fy = (y + 0.5f) * ((float)a.sh / (float)a.dh) - 0.5f;
-        float fx = (x + 0.5f) * ((float)a.sw / (float)a.dw) - 0.5f;
-        fy = fminf(fmaxf(fy, 0.f), (float)(a.sh - 1));
-        fx = fminf(fmaxf(fx, 0.f), (float)(a.sw - 1));
-        const int y0 = (int)floorf(fy), x0 = (int)floorf(fx);
-        const int y1 = min(y0 + 1, a.sh - 1), x1 = min(x0 + 1, a.sw - 1);
-        const float wy = fy - y0, wx = fx - x0;
-#pragma unroll
-        for (int c = 0; c < 3; c++) {
-            const float p00 = src[((long long)y0 * a.sw + x0) * 3 + c], p01 = src[((long long)y0 * a.sw + x1) * 3 + c];
-            const float p10 = src[((long long)y1 * a.sw + x0) * 3 + c], p11 = src[((long long)y1 * a.sw + x1) * 3 + c];
-            const float top = p00 * (1.f - wx) + p01 * wx, bot = p10 * (1.f - wx) + p11 * wx;
-            v[c] = top * (1.f - wy) + bot * wy;
-        }
-    }
+    stage_sample(a, src, y, x, v);
     if (BF16) {
         uint16_t* d = (uint16_t*)a.dst + idx * a.dc;
         if (a.dc == 8) {
@@ -90,8 +95,43 @@ __global__ void stage_kernel(const StageArgs* __restrict__ argv, const int nb_, 
     }
 }
 
+// Space-to-depth staging (bf16): one thread per destination pixel (r, q) gathers the 2x2 image
+// pixels (2r + by, 2q + bx) into channels (2*by + bx)*3 + c of a 16-channel pixel.
+__global__ void stage_s2d_kernel(const StageArgs* __restrict__ argv, const int nb_, const long long first) {
+    StageArgs a = argv[blockIdx.z];
+    a.nb = nb_;
+    a.src += first * a.sh * a.sw * 3;
+    const int h2 = (a.dh + 1) / 2, w2 = (a.dw + 1) / 2;
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long total = (long long)a.nb * h2 * w2;
+    if (idx >= total) return;
+    const int q = (int)(idx % w2);
+    const int r = (int)((idx / w2) % h2);
+    const long long n = idx / ((long long)w2 * h2);
+    const float* src = a.src + n * (long long)a.sh * a.sw * 3;
+    float f[16];
+#pragma unroll
+    for (int c = 0; c < 16; c++) f[c] = 0.f;
+#pragma unroll
+    for (int by = 0; by < 2; by++)
+#pragma unroll
+        for (int bx = 0; bx < 2; bx++) {
+            const int y = 2 * r + by, x = 2 * q + bx;
+            if (y < a.dh && x < a.dw) stage_sample(a, src, y, x, &f[(by * 2 + bx) * 3]);
+        }
+    uint4* d = (uint4*)((uint16_t*)a.dst + idx * 16);
+    d[0] = pack8(f);
+    d[1] = pack8(f + 8);
+}
+
 hipError_t launch_stage(const StageArgs& a, const StageArgs* argv, int G, int nb, long long first, bool bf16, hipStream_t s) {
     if (nb <= 0 || a.dc < 3 || G <= 0 || !argv) return hipErrorInvalidValue;
+    if (a.s2d) {
+        if (!bf16 || a.dc != 16) return hipErrorInvalidValue;
+        const long long px = (long long)nb * ((a.dh + 1) / 2) * ((a.dw + 1) / 2);
+        hipLaunchKernelGGL(stage_s2d_kernel, dim3(blocks_for(px, 256), 1, G), dim3(256), 0, s, argv, nb, first);
+        return hipGetLastError();
+    }
     const long long total = (long long)nb * a.dh * a.dw;
     const dim3 g(blocks_for(total, 256), 1, G);
     if (bf16) hipLaunchKernelGGL(stage_kernel<true>, g, dim3(256), 0, s, argv, nb, first);

@@ -93,6 +93,28 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         for (int t = 0; t < NT; t++)
             if (!m.tensors[t].f32) m.tensors[t].cs = (m.tensors[t].c + 7) / 8 * 8;
 
+    // A stride-2 convolution that is the only reader of the 3-channel input image is run as a
+    // stride-1 convolution over the image stored space-to-depth: with image row 2r + b in channel
+    // group b of row r, filter row k at padding p becomes filter row floor((k - p) / 2) of group
+    // (k - p) mod 2.  A 7x7 filter turns into 4x4 taps of 12 channels, stored 16 wide: K drops
+    // from 49 x 8 to 16 x 16 and every tap is a 32-byte run instead of 16 bytes.
+    int stem_op = -1;
+    if (m.bf16) {
+        int readers = 0;
+        for (int i = 0; i < spec.n_ops; i++) {
+            const ens_op& o = spec.ops[i];
+            if (o.src == 0) { readers++; stem_op = i; }
+            if (o.kind == ENS_OP_CONV && o.res == 0) readers += 2;
+        }
+        if (readers != 1) stem_op = -1;
+        if (stem_op >= 0) {
+            const ens_op& o = spec.ops[stem_op];
+            if (o.kind != ENS_OP_CONV || o.sh != 2 || o.sw != 2 || o.cin != 3 || o.src_c0 != 0 || o.pre ||
+                o.kh < 2 || o.kw < 2 || o.kh > 8 || o.kw > 8)
+                stem_op = -1;
+        }
+    }
+
     BlobWriter bw{m.host_params};
     m.zeros_off = bw.reserve(256);
     bool seen_out = false;
@@ -103,6 +125,7 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         pl.w = pl.b = pl.pre_scale = pl.pre_shift = pl.w2 = pl.b2 = SIZE_MAX;
         pl.cin_s = o.cin;
         pl.scratch = -1;
+        pl.alg_k = 0;
         TensorInfo& ts = m.tensors[o.src];
         TensorInfo& td = m.tensors[o.dst];
         if (o.cin <= 0 || o.cout <= 0 || o.src_c0 < 0 || o.dst_c0 < 0) return ENS_E_INVALID;
@@ -151,12 +174,34 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
                 std::vector<float> scale(o.cout, 1.f), shift(o.cout, 0.f);
                 if (o.off_bn >= 0) bn_affine(params + o.off_bn, o.cout, &scale, &shift);
                 const float* w = params + o.off_w;               // [kh][kw][cin][cout]
-                std::vector<float> wf((size_t)o.cout * o.kh * o.kw * pl.cin_s, 0.f);
-                for (int co = 0; co < o.cout; co++)
-                    for (int k = 0; k < o.kh * o.kw; k++)
-                        for (int ci = 0; ci < o.cin; ci++)
-                            wf[((size_t)co * o.kh * o.kw + k) * pl.cin_s + ci] =
-                                w[((size_t)k * o.cin + ci) * o.cout + co] * scale[co];
+                std::vector<float> wf;
+                if (i == stem_op) {
+                    auto floor2 = [](int v) { return v >= 0 ? v / 2 : -((1 - v) / 2); };
+                    const int ah0 = floor2(-o.pt), ah1 = floor2(o.kh - 1 - o.pt);
+                    const int aw0 = floor2(-o.pl), aw1 = floor2(o.kw - 1 - o.pl);
+                    const int kh2 = ah1 - ah0 + 1, kw2 = aw1 - aw0 + 1;
+                    wf.assign((size_t)o.cout * kh2 * kw2 * 16, 0.f);
+                    for (int co = 0; co < o.cout; co++)
+                        for (int kh = 0; kh < o.kh; kh++)
+                            for (int kw = 0; kw < o.kw; kw++) {
+                                const int ah = floor2(kh - o.pt), bh = kh - o.pt - 2 * ah;
+                                const int aw = floor2(kw - o.pl), bw2 = kw - o.pl - 2 * aw;
+                                for (int ci = 0; ci < 3; ci++)
+                                    wf[(((size_t)co * kh2 + (ah - ah0)) * kw2 + (aw - aw0)) * 16 + (bh * 2 + bw2) * 3 + ci] =
+                                        w[((size_t)(kh * o.kw + kw) * 3 + ci) * o.cout + co] * scale[co];
+                            }
+                    pl.alg_k = o.kh * o.kw * o.cin;
+                    pl.op.kh = kh2; pl.op.kw = kw2; pl.op.sh = 1; pl.op.sw = 1;
+                    pl.op.pt = -ah0; pl.op.pl = -aw0; pl.op.cin = 12;
+                    pl.cin_s = 16;
+                } else {
+                    wf.assign((size_t)o.cout * o.kh * o.kw * pl.cin_s, 0.f);
+                    for (int co = 0; co < o.cout; co++)
+                        for (int k = 0; k < o.kh * o.kw; k++)
+                            for (int ci = 0; ci < o.cin; ci++)
+                                wf[((size_t)co * o.kh * o.kw + k) * pl.cin_s + ci] =
+                                    w[((size_t)k * o.cin + ci) * o.cout + co] * scale[co];
+                }
                 std::vector<float> bias(o.cout);
                 for (int co = 0; co < o.cout; co++)
                     bias[co] = (o.off_b >= 0 ? params[o.off_b + co] * scale[co] : 0.f) + shift[co];
@@ -243,6 +288,11 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         m.ops.push_back(pl);
     }
     if (!seen_out) return ENS_E_INVALID;
+    if (stem_op >= 0) {                                          // tensor 0 as the staging kernel writes it
+        m.stem_s2d = true;
+        TensorInfo& t0 = m.tensors[0];
+        t0.h = (t0.h + 1) / 2; t0.w = (t0.w + 1) / 2; t0.c = 12; t0.cs = 16;
+    }
     m.tensors[spec.out_tensor].external = true;
     bw.reserve(0);
     m.host_params.resize(align_up(m.host_params.size()), 0);

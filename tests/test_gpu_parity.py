@@ -135,6 +135,9 @@ def oracle_tensor(net, blob, imgs, t):
 CONV_LAYERS = [
     # (H, W, cin, cout, k, stride, pad, extra)       shapes span several tiles and ragged tails
     (56, 56, 64, 64, 3, 1, "same", {}),
+    (64, 64, 3, 64, 7, 2, "same", {}),                         # input stems: run space-to-depth at stride 1
+    (35, 35, 3, 32, 3, 2, "valid", {}),
+    (32, 48, 3, 24, 3, 2, "same", {"act": "silu"}),
     (28, 28, 128, 128, 3, 1, "same", {}),
     (28, 28, 64, 64, 3, 1, "same", {"res": True}),             # residual read from the layer's own input
     (14, 14, 256, 256, 1, 1, "same", {"res": True}),
