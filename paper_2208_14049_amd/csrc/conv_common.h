@@ -52,6 +52,144 @@ __device__ __forceinline__ void tile_of_block(int n_ptiles, int n_ctiles, int* p
     *ptile = v / n_ctiles;
 }
 
+// ---- pieces shared by the kernels that hold their input window in LDS ----------------------
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// Loads that must not wait for asynchronous LDS loads in flight are made through pointers that
+// name global memory: a generic pointer could point into LDS and the compiler would drain every
+// outstanding LDS write first.
+#define ENS_GLOBAL(T, p) ((const __attribute__((address_space(1))) T*)(p))
+
+// Pixels in a padded raster: image n, row hi, column wi sits at position (n * H1 + hi) * W1 + wi
+// with H1 >= H, W1 >= W; the positions with hi >= H or wi >= W hold no pixel.  Fills
+// tbl[q] for q in [0, rows) with the pixel index (n * H + hi) * W + wi of position first + q,
+// or -1 for positions without a pixel or outside [0, PP).  All threads of the workgroup call it.
+__device__ __forceinline__ void raster_table(int* tbl, int rows, int first, int PP, int H1, int W1, int H, int W) {
+    const int img = H1 * W1;
+    const float inv_img = __builtin_amdgcn_rcpf((float)img), inv_w1 = __builtin_amdgcn_rcpf((float)W1);
+    for (int q = threadIdx.x; q < rows; q += blockDim.x) {
+        const int pp = first + q;
+        int p = -1;
+        if (pp >= 0 && pp < PP) {
+            // the float quotients are off by one at most (pp < 2^24): one correction step each
+            int n = (int)((float)pp * inv_img);
+            int rem = pp - n * img;
+            n += (rem >= img ? 1 : 0) - (rem < 0 ? 1 : 0);
+            rem = pp - n * img;
+            int hi = (int)((float)rem * inv_w1);
+            int wi = rem - hi * W1;
+            hi += (wi >= W1 ? 1 : 0) - (wi < 0 ? 1 : 0);
+            wi = rem - hi * W1;
+            if (hi < H && wi < W) p = (n * H + hi) * W + wi;
+        }
+        tbl[q] = p;
+    }
+}
+
+// What the epilogue of a BP x BC tile needs from memory, asked for before the main loop: the bias
+// of this thread's 8 channels and the residual values of its BP * BC / 2048 output groups.
+template <int BP, int BC>
+struct TilePrefetch {
+    static constexpr int G = BC / 8;                 // 8-channel groups per output row
+    static constexpr int RPI = 256 / G;              // output rows the workgroup stores per pass
+    static constexpr int NI = BP / RPI;              // 16-byte output groups per thread
+    f32x4 bias0, bias1;
+    u32x4 res[NI];
+    int co;                                          // first of this thread's 8 channels
+    bool cok, has_res;
+    // own: this tile's output rows in the table (own[r] = pixel of output row r, -1: none)
+    __device__ __forceinline__ void load(const ConvArgs& a, const int* own, int c0, bool partial) {
+        const int t = threadIdx.x;
+        co = c0 + (t % G) * 8;
+        cok = co < a.cout;
+        bias0 = f32x4{0.f, 0.f, 0.f, 0.f};
+        bias1 = bias0;
+        if (cok && !partial) {
+            bias0 = *ENS_GLOBAL(f32x4, a.bias + co);
+            bias1 = *ENS_GLOBAL(f32x4, a.bias + co + 4);
+        }
+        const uint16_t* rg = partial ? nullptr : (const uint16_t*)a.res.p;
+        has_res = rg != nullptr;
+#pragma unroll
+        for (int i = 0; i < NI; i++) res[i] = u32x4{0u, 0u, 0u, 0u};
+        if (rg) {
+#pragma unroll
+            for (int i = 0; i < NI; i++) {
+                const int p = own[t / G + RPI * i];
+                if (p >= 0 && cok) res[i] = *ENS_GLOBAL(u32x4, rg + (size_t)p * a.res.stride + a.res.c0 + co);
+            }
+        }
+    }
+};
+
+// Epilogue of a BP x BC tile held in the accumulators of 4 waves (wave tile TP x TC blocks of
+// 32 x 32 at rows wp0, channels wc0): the tile is turned round in LDS (fp32, HROWS rows at a time,
+// rows padded by 16 bytes) and leaves as 16-byte groups of 8 channels with bias, residual and
+// activation applied, or, when `partial` (a share of the K range), as fp32 sums into slice
+// `slice` of the workspace.  Rows whose table entry is negative are dropped.  The caller has
+// made sure that nobody still uses the LDS behind otile.
+template <int BP, int BC, int TP, int TC, int HROWS>
+__device__ __forceinline__ void store_tile(const ConvArgs& a, f32x16 (&acc)[TC][TP], float* otile, const int* own,
+                                           const TilePrefetch<BP, BC>& pf, int wp0, int wc0, bool partial, int slice,
+                                           int P) {
+    constexpr int OROW = BC + 4, G = BC / 8, RPI = 256 / G;
+    static_assert(256 % G == 0 && HROWS % RPI == 0 && BP % HROWS == 0, "a thread keeps its channel group over the passes");
+    const int t = threadIdx.x, lane = t & 63, lrow = lane & 31, lhalf = lane >> 5;
+    const int g8 = t % G, rbase = t / G;
+    uint16_t* __restrict__ yg = (uint16_t*)a.y.p;
+#pragma unroll
+    for (int h0 = 0; h0 < BP; h0 += HROWS) {
+        if (h0 > 0) __syncthreads();
+#pragma unroll
+        for (int j = 0; j < TP; j++) {
+            const int rb = wp0 + j * 32;
+            if (rb < h0 || rb >= h0 + HROWS) continue;
+#pragma unroll
+            for (int i = 0; i < TC; i++)
+#pragma unroll
+                for (int g = 0; g < 4; g++)
+                    *(float4*)&otile[(rb - h0 + lrow) * OROW + wc0 + i * 32 + g * 8 + lhalf * 4] =
+                        make_float4(acc[i][j][g * 4], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < HROWS / RPI; it++) {
+            const int row = rbase + RPI * it;                    // within this chunk
+            const int item = h0 / RPI + it;                      // among this thread's groups
+            const int p = own[h0 + row];
+            if (p < 0 || !pf.cok) continue;
+            const float4 lo = *(const float4*)&otile[row * OROW + g8 * 8];
+            const float4 hi = *(const float4*)&otile[row * OROW + g8 * 8 + 4];
+            if (partial) {
+                float* d = a.ws + ((size_t)slice * (size_t)P + (size_t)p) * a.cout + pf.co;
+                *(float4*)d = lo;
+                *(float4*)(d + 4) = hi;
+                continue;
+            }
+            float v[8] = {lo.x + pf.bias0.x, lo.y + pf.bias0.y, lo.z + pf.bias0.z, lo.w + pf.bias0.w,
+                          hi.x + pf.bias1.x, hi.y + pf.bias1.y, hi.z + pf.bias1.z, hi.w + pf.bias1.w};
+            if (pf.has_res) {
+                const uint32_t rr[4] = {pf.res[item].x, pf.res[item].y, pf.res[item].z, pf.res[item].w};
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    v[2 * q] += bf16_to_f32((uint16_t)(rr[q] & 0xFFFF));
+                    v[2 * q + 1] += bf16_to_f32((uint16_t)(rr[q] >> 16));
+                }
+            }
+            uint32_t o[4];
+#pragma unroll
+            for (int q = 0; q < 4; q++) o[q] = pack_bf16x2(apply_act(v[2 * q], a.act), apply_act(v[2 * q + 1], a.act));
+            *(uint4*)(yg + (size_t)p * a.y.stride + a.y.c0 + pf.co) = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+    }
+}
+
+// Stride-1 convolution over a 16-channel input with filter and window resident in LDS (the input
+// stems after the space-to-depth rewrite); defined in conv_taps.hip.
+bool conv_taps_applicable(const ConvArgs& a, int nb);
+const char* conv_taps_name(const ConvArgs& a);
+hipError_t launch_conv_taps(const ConvArgs& a, const ConvArgs* argv, int G, int nb, hipStream_t s);
+
 // Register-staged variant (pre-activated inputs); defined in conv_regstage.hip.
 hipError_t launch_conv_regstage(const ConvArgs& a, const ConvArgs* argv, int G, int nb, int P, hipStream_t s);
 const char* conv_regstage_name(const ConvArgs& a, int P);

@@ -26,13 +26,6 @@
 namespace ens {
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-// Loads that must not wait for the asynchronous LDS loads in flight are made through pointers
-// that name global memory: a generic pointer could point into LDS and the compiler would drain
-// every outstanding LDS write first.
-#define ENS_GLOBAL(T, p) ((const __attribute__((address_space(1))) T*)(p))
 
 template <int OFFSET>
 __device__ __forceinline__ bf16x8 halo_lds_read(uint32_t addr) {
@@ -65,10 +58,6 @@ __global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restr
     constexpr int HFIT = MINLDS / (OROW * 4) / 32 * 32;
     constexpr int HROWS = HFIT >= BP ? BP : (HFIT >= BP / 2 ? BP / 2 : (HFIT >= BP / 4 ? BP / 4 : 32));
     static_assert(HROWS >= 32 && BP % HROWS == 0 && HROWS * OROW * 4 <= MINLDS, "output staging chunk");
-    constexpr int G = BC / 8;                        // 8-channel groups per output row
-    constexpr int RPI = 256 / G;                     // output rows the workgroup stores per pass
-    constexpr int NI = BP / RPI;                     // 16-byte output groups per thread
-    static_assert(256 % G == 0 && HROWS % RPI == 0, "a thread keeps its channel group over the passes");
 
     const int W1 = a.W + 1, img = (a.H + 1) * W1;
     const int PP = nb_ * img;                        // padded positions of the batch
@@ -92,26 +81,7 @@ __global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restr
     int* const tbl = (int*)(halo + nbuf * hbytes);   // halo row -> pixel index (n*H + hi)*W + wi, -1: padding
 
     // ---- which pixel each halo row is; row 0 is the top-left tap of the tile's first output
-    {
-        const float inv_img = __builtin_amdgcn_rcpf((float)img), inv_w1 = __builtin_amdgcn_rcpf((float)W1);
-        for (int q = t; q < hrows; q += 256) {
-            const int pp = pp0 - (W1 + 1) + q;
-            int p = -1;
-            if (pp >= 0 && pp < PP) {
-                // the float quotients are off by one at most (pp < 2^24): one correction step each
-                int n = (int)((float)pp * inv_img);
-                int rem = pp - n * img;
-                n += (rem >= img ? 1 : 0) - (rem < 0 ? 1 : 0);
-                rem = pp - n * img;
-                int hi = (int)((float)rem * inv_w1);
-                int wi = rem - hi * W1;
-                hi += (wi >= W1 ? 1 : 0) - (wi < 0 ? 1 : 0);
-                wi = rem - hi * W1;
-                if (hi < a.H && wi < a.W) p = (n * a.H + hi) * a.W + wi;
-            }
-            tbl[q] = p;
-        }
-    }
+    raster_table(tbl, hrows, pp0 - (W1 + 1), PP, a.H + 1, W1, a.H, a.W);
     __syncthreads();
 
     // ---- load side.  Offsets past the end of a buffer give zeros in LDS; 2^31 is past the end of
@@ -160,28 +130,11 @@ __global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restr
     }
     issue_weights(0, cb_begin, 0);
 
-    // ---- what the epilogue needs from memory is asked for now and is there long before it is
-    //      used: the bias of this thread's 8 channels and the residual values of its NI groups.
+    // ---- what the epilogue needs from memory is asked for now and is there long before it is used
     const bool split = gridDim.y > 1;
-    const uint16_t* __restrict__ rg = split ? nullptr : (const uint16_t*)a.res.p;
-    const int g8 = t % G, rbase = t / G;
-    const int co = c0 + g8 * 8;
-    const bool cok = co < a.cout;
-    f32x4 bias0 = {0.f, 0.f, 0.f, 0.f}, bias1 = bias0;
-    if (cok && !split) {
-        bias0 = *ENS_GLOBAL(f32x4, a.bias + co);
-        bias1 = *ENS_GLOBAL(f32x4, a.bias + co + 4);
-    }
-    u32x4 rres[NI];
-#pragma unroll
-    for (int i = 0; i < NI; i++) rres[i] = u32x4{0u, 0u, 0u, 0u};
-    if (rg) {
-#pragma unroll
-        for (int i = 0; i < NI; i++) {
-            const int p = tbl[rbase + RPI * i + W1 + 1];         // the centre tap's halo row
-            if (p >= 0 && cok) rres[i] = *ENS_GLOBAL(u32x4, rg + (size_t)p * a.res.stride + a.res.c0 + co);
-        }
-    }
+    const int* own = tbl + W1 + 1;                               // the centre tap's halo rows: this tile's outputs
+    TilePrefetch<BP, BC> pf;
+    pf.load(a, own, c0, split);
 
     f32x16 acc[TC][TP];
 #pragma unroll
@@ -258,57 +211,10 @@ __global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restr
             stage ^= 1;
         }
     }
-    uint16_t* __restrict__ yg = (uint16_t*)a.y.p;
     __syncthreads();                                             // everybody is done with ring and halo
 
-    // ---- epilogue: the tile is turned round in LDS (fp32) and leaves as 16-byte groups of 8
-    //      channels; positions of the padded raster that hold no pixel are dropped here.
-    float* otile = (float*)lds;
-#pragma unroll
-    for (int h0 = 0; h0 < BP; h0 += HROWS) {
-        if (h0 > 0) __syncthreads();
-#pragma unroll
-        for (int j = 0; j < TP; j++) {
-            const int rb = wp0 + j * 32;
-            if (rb < h0 || rb >= h0 + HROWS) continue;
-#pragma unroll
-            for (int i = 0; i < TC; i++)
-#pragma unroll
-                for (int g = 0; g < 4; g++)
-                    *(float4*)&otile[(rb - h0 + lrow) * OROW + wc0 + i * 32 + g * 8 + lhalf * 4] =
-                        make_float4(acc[i][j][g * 4], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int it = 0; it < HROWS / RPI; it++) {
-            const int row = rbase + RPI * it;                    // within this chunk
-            const int item = h0 / RPI + it;                      // among this thread's NI groups
-            const int p = tbl[h0 + row + W1 + 1];
-            if (p < 0 || !cok) continue;
-            const float4 lo = *(const float4*)&otile[row * OROW + g8 * 8];
-            const float4 hi = *(const float4*)&otile[row * OROW + g8 * 8 + 4];
-            if (split) {                                         // fp32 partial sums of this share of the channels
-                float* d = a.ws + ((size_t)blockIdx.y * (size_t)(nb_ * a.H * a.W) + (size_t)p) * a.cout + co;
-                *(float4*)d = lo;
-                *(float4*)(d + 4) = hi;
-                continue;
-            }
-            float v[8] = {lo.x + bias0.x, lo.y + bias0.y, lo.z + bias0.z, lo.w + bias0.w,
-                          hi.x + bias1.x, hi.y + bias1.y, hi.z + bias1.z, hi.w + bias1.w};
-            if (rg) {
-                const uint32_t rr[4] = {rres[item].x, rres[item].y, rres[item].z, rres[item].w};
-#pragma unroll
-                for (int q = 0; q < 4; q++) {
-                    v[2 * q] += bf16_to_f32((uint16_t)(rr[q] & 0xFFFF));
-                    v[2 * q + 1] += bf16_to_f32((uint16_t)(rr[q] >> 16));
-                }
-            }
-            uint32_t o[4];
-#pragma unroll
-            for (int q = 0; q < 4; q++) o[q] = pack_bf16x2(apply_act(v[2 * q], a.act), apply_act(v[2 * q + 1], a.act));
-            *(uint4*)(yg + (size_t)p * a.y.stride + a.y.c0 + co) = make_uint4(o[0], o[1], o[2], o[3]);
-        }
-    }
+    // ---- epilogue; positions of the padded raster that hold no pixel are dropped there
+    store_tile<BP, BC, TP, TC, HROWS>(a, acc, (float*)lds, own, pf, wp0, wc0, split, blockIdx.y, nb_ * a.H * a.W);
 }
 
 // ---- host side -----------------------------------------------------------------------------

@@ -414,6 +414,7 @@ static int pick_splits(const ConvArgs& a, long long P, long long K, int variant,
 const char* conv_bf16_variant_name(const ConvArgs& a, int G) {
     const long long P = (long long)a.nb * a.Ho * a.Wo;
     if (a.pre_scale) return conv_regstage_name(a, (int)P);
+    if (conv_taps_applicable(a, a.nb)) return conv_taps_name(a);
     if (const int hv = conv_halo_pick(a, a.nb, G); hv >= 0) return conv_halo_name(hv);
     return VARIANTS[pick_variant(a, P, (long long)a.kh * a.kw * a.cin, G)].name;
 }
@@ -439,6 +440,7 @@ hipError_t launch_conv_bf16(const ConvArgs& a, const ConvArgs* argv, int G, int 
     if (P64 <= 0 || P64 >= (1LL << 31) || K64 >= (1LL << 31)) return hipErrorInvalidValue;
     const int P = (int)P64;
     if (a.pre_scale) return launch_conv_regstage(a, argv, G, nb, P, s);
+    if (conv_taps_applicable(a, nb)) return launch_conv_taps(a, argv, G, nb, s);
     if (const int hv = conv_halo_pick(a, nb, G); hv >= 0) return launch_conv_halo(a, argv, G, nb, hv, s);
     // byte offsets inside the kernel are unsigned 32-bit, 0xFFFFFFF0 stands for 'out of range'
     if ((long long)nb * a.H * a.W * a.x.stride >= 0x7FFFFF00LL || (long long)a.cout * K64 >= 0x70000000LL || a.kh > 16 || a.kw > 16) return hipErrorInvalidValue;
