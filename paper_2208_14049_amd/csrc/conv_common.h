@@ -23,10 +23,18 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
     return __builtin_bit_cast(uint32_t, b);
 }
-__device__ __forceinline__ float apply_act(float v, int act) {
-    if (act == ACT_RELU) return fmaxf(v, 0.f);
-    if (act == ACT_SILU) return v / (1.f + __expf(-v));
-    return v;
+// Activation of N values at once.  `act` is the same for the whole launch: one uniform branch
+// per call (SiLU or not) and a select for ReLU, instead of a chain of branches per value.
+template <int N>
+__device__ __forceinline__ void apply_act_n(float* v, int act) {
+    if (act == ACT_SILU) {
+#pragma unroll
+        for (int i = 0; i < N; i++) v[i] = v[i] / (1.f + __expf(-v[i]));
+    } else {
+        const bool relu = act == ACT_RELU;
+#pragma unroll
+        for (int i = 0; i < N; i++) v[i] = relu ? fmaxf(v[i], 0.f) : v[i];
+    }
 }
 
 // Bytes per lane of an asynchronous global-to-LDS load.  The 16-byte form exists on gfx950 only and
@@ -59,6 +67,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // name global memory: a generic pointer could point into LDS and the compiler would drain every
 // outstanding LDS write first.
 #define ENS_GLOBAL(T, p) ((const __attribute__((address_space(1))) T*)(p))
+// Stores likewise: a store through a generic pointer is a flat instruction, which also counts as
+// an LDS operation, so the next LDS read would wait for the store to leave the wave.
+#define ENS_GLOBAL_W(T, p) ((__attribute__((address_space(1))) T*)(p))
 
 // Pixels in a padded raster: image n, row hi, column wi sits at position (n * H1 + hi) * W1 + wi
 // with H1 >= H, W1 >= W; the positions with hi >= H or wi >= W hold no pixel.  Fills
@@ -162,8 +173,8 @@ __device__ __forceinline__ void store_tile(const ConvArgs& a, f32x16 (&acc)[TC][
             const float4 hi = *(const float4*)&otile[row * OROW + g8 * 8 + 4];
             if (partial) {
                 float* d = a.ws + ((size_t)slice * (size_t)P + (size_t)p) * a.cout + pf.co;
-                *(float4*)d = lo;
-                *(float4*)(d + 4) = hi;
+                *ENS_GLOBAL_W(f32x4, d) = f32x4{lo.x, lo.y, lo.z, lo.w};
+                *ENS_GLOBAL_W(f32x4, d + 4) = f32x4{hi.x, hi.y, hi.z, hi.w};
                 continue;
             }
             float v[8] = {lo.x + pf.bias0.x, lo.y + pf.bias0.y, lo.z + pf.bias0.z, lo.w + pf.bias0.w,
@@ -176,10 +187,11 @@ __device__ __forceinline__ void store_tile(const ConvArgs& a, f32x16 (&acc)[TC][
                     v[2 * q + 1] += bf16_to_f32((uint16_t)(rr[q] >> 16));
                 }
             }
+            apply_act_n<8>(v, a.act);
             uint32_t o[4];
 #pragma unroll
-            for (int q = 0; q < 4; q++) o[q] = pack_bf16x2(apply_act(v[2 * q], a.act), apply_act(v[2 * q + 1], a.act));
-            *(uint4*)(yg + (size_t)p * a.y.stride + a.y.c0 + pf.co) = make_uint4(o[0], o[1], o[2], o[3]);
+            for (int q = 0; q < 4; q++) o[q] = pack_bf16x2(v[2 * q], v[2 * q + 1]);
+            *ENS_GLOBAL_W(u32x4, yg + (size_t)p * a.y.stride + a.y.c0 + pf.co) = u32x4{o[0], o[1], o[2], o[3]};
         }
     }
 }

@@ -301,14 +301,14 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restric
             const float4 hi = *(const float4*)&otile[row * OROW + g * 8 + 4];
             if (split) {                                         // fp32 partial sums of this K split
                 float* d = mine + (size_t)p * a.cout + co;
-                *(float4*)d = lo;
-                *(float4*)(d + 4) = hi;
+                *ENS_GLOBAL_W(f32x4, d) = f32x4{lo.x, lo.y, lo.z, lo.w};
+                *ENS_GLOBAL_W(f32x4, d + 4) = f32x4{hi.x, hi.y, hi.z, hi.w};
                 continue;
             }
-            const float4 b0 = *(const float4*)(a.bias + co), b1 = *(const float4*)(a.bias + co + 4);
+            const f32x4 b0 = *ENS_GLOBAL(f32x4, a.bias + co), b1 = *ENS_GLOBAL(f32x4, a.bias + co + 4);
             float v[8] = {lo.x + b0.x, lo.y + b0.y, lo.z + b0.z, lo.w + b0.w, hi.x + b1.x, hi.y + b1.y, hi.z + b1.z, hi.w + b1.w};
             if (rg) {
-                const uint4 r = *(const uint4*)(rg + (size_t)p * a.res.stride + a.res.c0 + co);
+                const u32x4 r = *ENS_GLOBAL(u32x4, rg + (size_t)p * a.res.stride + a.res.c0 + co);
                 const uint32_t rr[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
                 for (int q = 0; q < 4; q++) {
@@ -316,10 +316,11 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restric
                     v[2 * q + 1] += bf16_to_f32((uint16_t)(rr[q] >> 16));
                 }
             }
+            apply_act_n<8>(v, a.act);
             uint32_t o[4];
 #pragma unroll
-            for (int q = 0; q < 4; q++) o[q] = pack_bf16x2(apply_act(v[2 * q], a.act), apply_act(v[2 * q + 1], a.act));
-            *(uint4*)(yg + (size_t)p * a.y.stride + a.y.c0 + co) = make_uint4(o[0], o[1], o[2], o[3]);
+            for (int q = 0; q < 4; q++) o[q] = pack_bf16x2(v[2 * q], v[2 * q + 1]);
+            *ENS_GLOBAL_W(u32x4, yg + (size_t)p * a.y.stride + a.y.c0 + co) = u32x4{o[0], o[1], o[2], o[3]};
         }
     }
 }
@@ -341,19 +342,18 @@ __global__ void conv_splitk_epilogue(const ConvArgs* __restrict__ argv, const in
         s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
     const float4 b = *(const float4*)(a.bias + co);
-    float v0 = s.x + b.x, v1 = s.y + b.y, v2 = s.z + b.z, v3 = s.w + b.w;
+    float v[4] = {s.x + b.x, s.y + b.y, s.z + b.z, s.w + b.w};
     if (a.res.p) {
         const uint2 r = *(const uint2*)((const uint16_t*)a.res.p + (size_t)p * a.res.stride + a.res.c0 + co);
-        v0 += bf16_to_f32((uint16_t)(r.x & 0xFFFF));
-        v1 += bf16_to_f32((uint16_t)(r.x >> 16));
-        v2 += bf16_to_f32((uint16_t)(r.y & 0xFFFF));
-        v3 += bf16_to_f32((uint16_t)(r.y >> 16));
+        v[0] += bf16_to_f32((uint16_t)(r.x & 0xFFFF));
+        v[1] += bf16_to_f32((uint16_t)(r.x >> 16));
+        v[2] += bf16_to_f32((uint16_t)(r.y & 0xFFFF));
+        v[3] += bf16_to_f32((uint16_t)(r.y >> 16));
     }
-    v0 = apply_act(v0, a.act); v1 = apply_act(v1, a.act);
-    v2 = apply_act(v2, a.act); v3 = apply_act(v3, a.act);
+    apply_act_n<4>(v, a.act);
     uint2 o;
-    o.x = pack_bf16x2(v0, v1);
-    o.y = pack_bf16x2(v2, v3);
+    o.x = pack_bf16x2(v[0], v[1]);
+    o.y = pack_bf16x2(v[2], v[3]);
     *(uint2*)((uint16_t*)a.y.p + (size_t)p * a.y.stride + a.y.c0 + co) = o;
 }
 

@@ -201,8 +201,7 @@ __global__ __launch_bounds__(256) void conv_regstage_bf16(const ConvArgs* __rest
                     v2 += bf16_to_f32((uint16_t)(r.y & 0xFFFF));
                     v3 += bf16_to_f32((uint16_t)(r.y >> 16));
                 }
-                v0 = apply_act(v0, a.act); v1 = apply_act(v1, a.act);
-                v2 = apply_act(v2, a.act); v3 = apply_act(v3, a.act);
+                { float vv[4] = {v0, v1, v2, v3}; apply_act_n<4>(vv, a.act); v0 = vv[0]; v1 = vv[1]; v2 = vv[2]; v3 = vv[3]; }
                 uint2 o;
                 o.x = (uint32_t)f32_to_bf16(v0) | ((uint32_t)f32_to_bf16(v1) << 16);
                 o.y = (uint32_t)f32_to_bf16(v2) | ((uint32_t)f32_to_bf16(v3) << 16);

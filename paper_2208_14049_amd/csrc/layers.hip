@@ -227,11 +227,24 @@ __global__ void window_kernel(const PoolArgs* __restrict__ argv, const int nb_) 
             cnt++;
         }
     }
+    if (MODE == 0) {
+        // one uniform branch for the launch's activation instead of a chain per value
 #pragma unroll
-    for (int e = 0; e < V; e++) {
-        if (MODE == 0) acc[e] = act_f(acc[e] + a.bias[c + e], a.act);
-        else if (MODE == 2) acc[e] = cnt ? acc[e] / (float)cnt : 0.f;
-        else if (cnt == 0) acc[e] = 0.f;
+        for (int e = 0; e < V; e++) acc[e] += a.bias[c + e];
+        if (a.act == ACT_SILU) {
+#pragma unroll
+            for (int e = 0; e < V; e++) acc[e] = acc[e] / (1.f + __expf(-acc[e]));
+        } else {
+            const bool relu = a.act == ACT_RELU;
+#pragma unroll
+            for (int e = 0; e < V; e++) acc[e] = relu ? fmaxf(acc[e], 0.f) : acc[e];
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < V; e++) {
+            if (MODE == 2) acc[e] = cnt ? acc[e] / (float)cnt : 0.f;
+            else if (cnt == 0) acc[e] = 0.f;
+        }
     }
     const long long yoff = p * (long long)a.y.stride + a.y.c0 + c;
     if (BF16) *(uint4*)((uint16_t*)a.y.p + yoff) = pack8(acc);
