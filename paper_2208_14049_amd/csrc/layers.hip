@@ -186,19 +186,24 @@ hipError_t launch_conv_f32(const ConvArgs& a, const ConvArgs* argv, int G, int n
 // ------------------------------------------------------------------ depthwise conv / pooling
 // MODE 0: depthwise convolution (+bias, activation), 1: max pool, 2: average pool over the
 // in-bounds part of the window.  bf16: one lane per (pixel, 8 channels); fp32: per element.
+// The launcher admits fewer than 2^31 work items, so the index split runs in 32-bit arithmetic
+// (64-bit division is a long instruction sequence); only the final element offsets are 64-bit.
 template <int MODE, bool BF16>
 __global__ void window_kernel(const PoolArgs* __restrict__ argv, const int nb_) {
     PoolArgs a = argv[blockIdx.z];
     a.nb = nb_;
     constexpr int V = BF16 ? 8 : 1;
-    const int cv = a.c / V;
-    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const long long total = (long long)a.nb * a.Ho * a.Wo * cv;
+    const unsigned cv = (unsigned)(a.c / V);
+    const unsigned idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const unsigned total = (unsigned)a.nb * (unsigned)(a.Ho * a.Wo) * cv;
     if (idx >= total) return;
-    const int c = (int)(idx % cv) * V;
-    const long long p = idx / cv;
-    const int wo = (int)(p % a.Wo), ho = (int)((p / a.Wo) % a.Ho);
-    const long long n = p / ((long long)a.Wo * a.Ho);
+    const unsigned pu = idx / cv;
+    const int c = (int)(idx - pu * cv) * V;
+    const unsigned row = pu / (unsigned)a.Wo;
+    const int wo = (int)(pu - row * (unsigned)a.Wo);
+    const unsigned nu = row / (unsigned)a.Ho;
+    const int ho = (int)(row - nu * (unsigned)a.Ho);
+    const long long p = pu, n = nu;
     float acc[V];
 #pragma unroll
     for (int e = 0; e < V; e++) acc[e] = MODE == 1 ? -3.0e38f : 0.f;
@@ -260,6 +265,7 @@ static hipError_t check_window(const PoolArgs& a, bool bf16) {
 hipError_t launch_dwconv(const PoolArgs& a, const PoolArgs* argv, int G, int nb, bool bf16, hipStream_t s) {
     if (check_window(a, bf16) != hipSuccess || !a.w || !a.bias || nb <= 0 || G <= 0 || !argv) return hipErrorInvalidValue;
     const long long total = (long long)nb * a.Ho * a.Wo * (a.c / (bf16 ? 8 : 1));
+    if (total >= (1LL << 31) - 256) return hipErrorInvalidValue;   // 32-bit work item index in the kernel
     const dim3 g(blocks_for(total, 256), 1, G);
     if (bf16) hipLaunchKernelGGL((window_kernel<0, true>), g, dim3(256), 0, s, argv, nb);
     else hipLaunchKernelGGL((window_kernel<0, false>), g, dim3(256), 0, s, argv, nb);
@@ -269,6 +275,7 @@ hipError_t launch_dwconv(const PoolArgs& a, const PoolArgs* argv, int G, int nb,
 hipError_t launch_pool(const PoolArgs& a, const PoolArgs* argv, int G, int nb, bool is_max, bool bf16, hipStream_t s) {
     if (check_window(a, bf16) != hipSuccess || nb <= 0 || G <= 0 || !argv) return hipErrorInvalidValue;
     const long long total = (long long)nb * a.Ho * a.Wo * (a.c / (bf16 ? 8 : 1));
+    if (total >= (1LL << 31) - 256) return hipErrorInvalidValue;   // 32-bit work item index in the kernel
     const dim3 g(blocks_for(total, 256), 1, G), b(256);
     if (is_max) {
         if (bf16) hipLaunchKernelGGL((window_kernel<1, true>), g, b, 0, s, argv, nb);
@@ -349,13 +356,14 @@ hipError_t launch_gap(const GapArgs& a, const GapArgs* argv, int G, int nb, bool
 constexpr int FC_IMGS = 8;
 constexpr int FC_KCH = 1024;       // input features staged in LDS at a time
 
+constexpr int FC_WAVES = 16;       // waves per workgroup: each takes 1/16 of the K range of a chunk
 template <bool BF16>
-__global__ __launch_bounds__(256) void fc_kernel(const FcArgs* __restrict__ argv, const int nb_, const long long first) {
+__global__ __launch_bounds__(FC_WAVES * 64) void fc_kernel(const FcArgs* __restrict__ argv, const int nb_, const long long first) {
     FcArgs a = argv[blockIdx.z];
     a.nb = nb_;
     a.y += first * a.ldy;
     __shared__ float xs[FC_IMGS * FC_KCH];
-    __shared__ float part[4 * FC_IMGS * 64];
+    __shared__ float part[FC_WAVES * FC_IMGS * 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int co = blockIdx.x * 64 + lane;
     const int n0 = blockIdx.y * FC_IMGS;
@@ -365,15 +373,16 @@ __global__ __launch_bounds__(256) void fc_kernel(const FcArgs* __restrict__ argv
     for (int e = 0; e < FC_IMGS; e++) acc[e] = 0.f;
     for (int kc = 0; kc < a.cin; kc += FC_KCH) {
         const int kn = min(FC_KCH, a.cin - kc);
-        for (int i = threadIdx.x; i < FC_IMGS * kn; i += 256) {
+        for (int i = threadIdx.x; i < FC_IMGS * kn; i += FC_WAVES * 64) {
             const int img = i / kn, k = i - img * kn;
             xs[img * FC_KCH + k] = img < ni ? a.x[(long long)(n0 + img) * a.cin + kc + k] : 0.f;
         }
         __syncthreads();
-        const int per = (kn + 3) / 4;
+        const int per = (kn + FC_WAVES - 1) / FC_WAVES;
         const int k0 = wave * per, k1 = min(kn, k0 + per);
         if (co < a.cout) {
-#pragma unroll 4
+            // the weight loads of a wave are independent: many in flight hide the memory latency
+#pragma unroll 16
             for (int k = k0; k < k1; k++) {
                 const long long off = (long long)(kc + k) * a.cout + co;
                 const float w = BF16 ? bf2f(((const uint16_t*)a.w)[off]) : ((const float*)a.w)[off];
@@ -386,12 +395,13 @@ __global__ __launch_bounds__(256) void fc_kernel(const FcArgs* __restrict__ argv
 #pragma unroll
     for (int e = 0; e < FC_IMGS; e++) part[(wave * FC_IMGS + e) * 64 + lane] = acc[e];
     __syncthreads();
-    for (int i = threadIdx.x; i < FC_IMGS * 64; i += 256) {
+    for (int i = threadIdx.x; i < FC_IMGS * 64; i += FC_WAVES * 64) {
         const int e = i >> 6, l = i & 63;
         const int c = blockIdx.x * 64 + l;
         if (e < ni && c < a.cout) {
-            const float s = part[(0 * FC_IMGS + e) * 64 + l] + part[(1 * FC_IMGS + e) * 64 + l] +
-                            part[(2 * FC_IMGS + e) * 64 + l] + part[(3 * FC_IMGS + e) * 64 + l];
+            float s = 0.f;
+#pragma unroll
+            for (int w = 0; w < FC_WAVES; w++) s += part[(w * FC_IMGS + e) * 64 + l];
             a.y[(long long)(n0 + e) * a.ldy + c] = s + a.bias[c];
         }
     }
@@ -399,7 +409,7 @@ __global__ __launch_bounds__(256) void fc_kernel(const FcArgs* __restrict__ argv
 
 hipError_t launch_fc(const FcArgs& a, const FcArgs* argv, int G, int nb, long long first, bool bf16, hipStream_t s) {
     if (nb <= 0 || a.cin <= 0 || a.cout <= 0 || !a.bias || !a.y || G <= 0 || !argv) return hipErrorInvalidValue;
-    const dim3 g((a.cout + 63) / 64, (nb + FC_IMGS - 1) / FC_IMGS, G), b(256);
+    const dim3 g((a.cout + 63) / 64, (nb + FC_IMGS - 1) / FC_IMGS, G), b(FC_WAVES * 64);
     if (bf16) hipLaunchKernelGGL(fc_kernel<true>, g, b, 0, s, argv, nb, first);
     else hipLaunchKernelGGL(fc_kernel<false>, g, b, 0, s, argv, nb, first);
     return hipGetLastError();
