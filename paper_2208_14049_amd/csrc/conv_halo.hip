@@ -157,8 +157,12 @@ __global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restr
     const uint32_t lq = (uint32_t)(wp0 + lrow);
 
     int stage = 0;
+    // With one halo buffer (nbuf == 1) a block's halo is loaded when the previous block is done
+    // with: the load is exposed once per block and the LDS saved lets more workgroups share the
+    // compute unit; with two buffers it arrives during the previous block's taps.
+    const bool single = nbuf == 1;
     for (int cb = cb_begin; cb < ncb; cb++) {
-        const int hb = (cb - cb_begin) & 1;                      // halo buffer of this block
+        const int hb = single ? 0 : (cb - cb_begin) & 1;         // halo buffer of this block
         const uint32_t hbuf = halo0 + (uint32_t)(hb * hbytes);
         const bool more = cb + 1 < ncb;
 #pragma unroll
@@ -167,9 +171,14 @@ __global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restr
             // that to the other waves' loads and says that nobody still reads what is refilled next
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __builtin_amdgcn_s_barrier();
+            if (tap == 0 && single && cb > cb_begin) {           // everybody is done with the previous block's halo
+                for (int s = 0; s < nsl; s++) issue_halo(0, s, cb);
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+            }
             if (tap < 8) issue_weights(stage ^ 1, cb, tap + 1);
             else if (more) issue_weights(stage ^ 1, cb + 1, 0);
-            if (more) {
+            if (more && !single) {
 #pragma unroll
                 for (int j = 0; j < NHL; j++)
                     if (tap * NHL + j < nsl) issue_halo(hb ^ 1, tap * NHL + j, cb + 1);
@@ -218,14 +227,17 @@ __global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restr
 }
 
 // ---- host side -----------------------------------------------------------------------------
-struct HaloVariant { int bp, bc, cb, nhl; const char* name; };
+struct HaloVariant { int bp, bc, cb, nhl; bool single; const char* name; };
 static const HaloVariant HALO_VARIANTS[] = {
-    {128, 64, 64, 1, "conv3x3_halo_bf16<128,64,c64>"},
-    {256, 64, 64, 2, "conv3x3_halo_bf16<256,64,c64>"},
-    {128, 128, 64, 1, "conv3x3_halo_bf16<128,128,c64>"},
-    {256, 64, 32, 1, "conv3x3_halo_bf16<256,64,c32>"},
-    {128, 64, 32, 1, "conv3x3_halo_bf16<128,64,c32>"},
-    {128, 128, 32, 1, "conv3x3_halo_bf16<128,128,c32>"},
+    {128, 64, 64, 1, false, "conv3x3_halo_bf16<128,64,c64>"},
+    {256, 64, 64, 2, false, "conv3x3_halo_bf16<256,64,c64>"},
+    {128, 128, 64, 1, false, "conv3x3_halo_bf16<128,128,c64>"},
+    {256, 64, 32, 1, false, "conv3x3_halo_bf16<256,64,c32>"},
+    {128, 64, 32, 1, false, "conv3x3_halo_bf16<128,64,c32>"},
+    {128, 128, 32, 1, false, "conv3x3_halo_bf16<128,128,c32>"},
+    {128, 64, 64, 1, true, "conv3x3_halo_bf16<128,64,c64,1buf>"},
+    {256, 64, 64, 2, true, "conv3x3_halo_bf16<256,64,c64,1buf>"},
+    {128, 128, 64, 1, true, "conv3x3_halo_bf16<128,128,c64,1buf>"},
 };
 constexpr int N_HALO_VARIANTS = sizeof(HALO_VARIANTS) / sizeof(HALO_VARIANTS[0]);
 constexpr int LDS_LIMIT = 160 * 1024;
@@ -259,7 +271,7 @@ static bool halo_layout(const ConvArgs& a, const HaloVariant& v, int splits, int
     const int rows = (need + rs - 1) / rs * rs;
     const int ncb = a.cin / v.cb, per = (ncb + splits - 1) / splits;
     *hrows = rows;
-    *nbuf = per > 1 ? 2 : 1;
+    *nbuf = per > 1 && !v.single ? 2 : 1;
     // the blocks after the first arrive nhl load slots per tap
     if (*nbuf == 2 && rows / rs > 9 * v.nhl) return false;
     *bytes = (size_t)2 * v.bc * v.cb * 2 + (size_t)*nbuf * rows * v.cb * 2 + (size_t)rows * 4;
@@ -278,12 +290,19 @@ static bool halo_shape_ok(const ConvArgs& a, int nb) {
 // Which variant runs this layer, -1: the generic kernel.  Measured on MI355X over the 3x3 layers
 // of residual networks at batch 32 (56x56x64 to 7x7x512): the 128x64 tile with 64-channel blocks
 // is the fastest or within 2 % of it everywhere; larger tiles lose more to the lower number of
-// workgroups a compute unit can hold than they gain in traffic.
+// workgroups a compute unit can hold than they gain in traffic.  For the same reason a layer with
+// several channel blocks and enough tiles to put more than two workgroups on every compute unit
+// runs with one halo buffer (28x28x128: 27 us against 32, 14x14x256: 28 against 36).
 int conv_halo_pick(const ConvArgs& a, int nb, int G) {
     if (!halo_shape_ok(a, nb)) return -1;
     int choice = -1;
-    if (a.cin % 64 == 0) choice = 0;
-    else if (a.cin >= 96) choice = 4;                            // multiples of 32 only: 32-channel blocks
+    if (a.cin % 64 == 0) {
+        const long long PP = (long long)nb * (a.H + 1) * (a.W + 1);
+        const long long tiles = G * ((PP + 127) / 128) * ((a.cout + 63) / 64);
+        choice = a.cin > 64 && tiles > 2 * HALO_CUS ? 6 : 0;
+    } else if (a.cin >= 96) {
+        choice = 4;                                              // multiples of 32 only: 32-channel blocks
+    }
 #ifdef ENS_CONV_TUNING   // variant override for kernel experiments only (out of range: generic kernel)
     if (const char* e = getenv("ENS_CONV_HALO")) choice = atoi(e);
 #endif
@@ -337,7 +356,10 @@ hipError_t launch_conv_halo(const ConvArgs& a, const ConvArgs* argv, int G, int 
         case 2: return launch_halo_variant<128, 128, 2, 2, 64, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
         case 3: return launch_halo_variant<256, 64, 4, 1, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
         case 4: return launch_halo_variant<128, 64, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
-        default: return launch_halo_variant<128, 128, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 5: return launch_halo_variant<128, 128, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 6: return launch_halo_variant<128, 64, 2, 2, 64, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 7: return launch_halo_variant<256, 64, 4, 1, 64, 2>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        default: return launch_halo_variant<128, 128, 2, 2, 64, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
     }
 }
 

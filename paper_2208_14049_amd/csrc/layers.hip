@@ -256,6 +256,45 @@ __global__ void window_kernel(const PoolArgs* __restrict__ argv, const int nb_) 
     else ((float*)a.y.p)[yoff] = acc[0];
 }
 
+// Max pooling, bf16, one lane per (pixel, 8 channels).  Window positions outside the image are
+// replaced by the nearest position inside it: that position belongs to the window too (a window
+// the launcher admits overlaps the image), so the maximum is unchanged and all KH*KW loads are
+// unconditional and in flight together.
+template <int KH, int KW>
+__global__ void maxpool_bf16_kernel(const PoolArgs* __restrict__ argv, const int nb_) {
+    const PoolArgs a = argv[blockIdx.z];
+    const unsigned cv = (unsigned)(a.c / 8);
+    const unsigned idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const unsigned total = (unsigned)nb_ * (unsigned)(a.Ho * a.Wo) * cv;
+    if (idx >= total) return;
+    const unsigned pu = idx / cv;
+    const int c = (int)(idx - pu * cv) * 8;
+    const unsigned row = pu / (unsigned)a.Wo;
+    const int wo = (int)(pu - row * (unsigned)a.Wo);
+    const unsigned nu = row / (unsigned)a.Ho;
+    const int ho = (int)(row - nu * (unsigned)a.Ho);
+    const uint16_t* __restrict__ x = (const uint16_t*)a.x.p + (long long)nu * a.H * a.W * a.x.stride + a.x.c0 + c;
+    uint4 v[KH * KW];
+#pragma unroll
+    for (int kh = 0; kh < KH; kh++) {
+        const int hi = min(max(ho * a.sh - a.pt + kh, 0), a.H - 1);
+#pragma unroll
+        for (int kw = 0; kw < KW; kw++) {
+            const int wi = min(max(wo * a.sw - a.pl + kw, 0), a.W - 1);
+            v[kh * KW + kw] = *(const uint4*)(x + (long long)(hi * a.W + wi) * a.x.stride);
+        }
+    }
+    float acc[8], f[8];
+    unpack8(v[0], acc);
+#pragma unroll
+    for (int k = 1; k < KH * KW; k++) {
+        unpack8(v[k], f);
+#pragma unroll
+        for (int e = 0; e < 8; e++) acc[e] = fmaxf(acc[e], f[e]);
+    }
+    *(uint4*)((uint16_t*)a.y.p + (long long)pu * a.y.stride + a.y.c0 + c) = pack8(acc);
+}
+
 static hipError_t check_window(const PoolArgs& a, bool bf16) {
     if (a.c <= 0) return hipErrorInvalidValue;
     if (bf16 && (a.c % 8 || a.x.stride % 8 || a.x.c0 % 8 || a.y.stride % 8 || a.y.c0 % 8)) return hipErrorInvalidValue;
@@ -278,7 +317,11 @@ hipError_t launch_pool(const PoolArgs& a, const PoolArgs* argv, int G, int nb, b
     if (total >= (1LL << 31) - 256) return hipErrorInvalidValue;   // 32-bit work item index in the kernel
     const dim3 g(blocks_for(total, 256), 1, G), b(256);
     if (is_max) {
-        if (bf16) hipLaunchKernelGGL((window_kernel<1, true>), g, b, 0, s, argv, nb);
+        // every window must overlap the image for the clamped fast path (true for the padded layers of real networks)
+        const bool overlap = a.pt < a.kh && a.pl < a.kw && (a.Ho - 1) * a.sh - a.pt < a.H && (a.Wo - 1) * a.sw - a.pl < a.W;
+        if (bf16 && overlap && a.kh == 3 && a.kw == 3) hipLaunchKernelGGL((maxpool_bf16_kernel<3, 3>), g, b, 0, s, argv, nb);
+        else if (bf16 && overlap && a.kh == 2 && a.kw == 2) hipLaunchKernelGGL((maxpool_bf16_kernel<2, 2>), g, b, 0, s, argv, nb);
+        else if (bf16) hipLaunchKernelGGL((window_kernel<1, true>), g, b, 0, s, argv, nb);
         else hipLaunchKernelGGL((window_kernel<1, false>), g, b, 0, s, argv, nb);
     } else {
         if (bf16) hipLaunchKernelGGL((window_kernel<2, true>), g, b, 0, s, argv, nb);

@@ -139,6 +139,7 @@ CONV_LAYERS = [
     (35, 35, 3, 32, 3, 2, "valid", {}),
     (32, 48, 3, 24, 3, 2, "same", {"act": "silu"}),
     (28, 28, 128, 128, 3, 1, "same", {}),
+    (56, 56, 128, 512, 3, 1, "same", {}),                      # enough tiles for the one-halo-buffer variant
     (28, 28, 64, 64, 3, 1, "same", {"res": True}),             # residual read from the layer's own input
     (14, 14, 256, 256, 1, 1, "same", {"res": True}),
     (14, 14, 256, 96, 3, 1, "same", {}),
