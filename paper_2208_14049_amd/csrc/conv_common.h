@@ -23,17 +23,16 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
     return __builtin_bit_cast(uint32_t, b);
 }
-// Activation of N values at once.  `act` is the same for the whole launch: one uniform branch
-// per call (SiLU or not) and a select for ReLU, instead of a chain of branches per value.
+// Activation of N values at once.  `act` is the same for the whole launch: one uniform three-way
+// branch per call instead of a chain of branches (or a select) per value.
 template <int N>
 __device__ __forceinline__ void apply_act_n(float* v, int act) {
-    if (act == ACT_SILU) {
+    if (act == ACT_RELU) {
+#pragma unroll
+        for (int i = 0; i < N; i++) v[i] = fmaxf(v[i], 0.f);
+    } else if (act == ACT_SILU) {
 #pragma unroll
         for (int i = 0; i < N; i++) v[i] = v[i] / (1.f + __expf(-v[i]));
-    } else {
-        const bool relu = act == ACT_RELU;
-#pragma unroll
-        for (int i = 0; i < N; i++) v[i] = relu ? fmaxf(v[i], 0.f) : v[i];
     }
 }
 

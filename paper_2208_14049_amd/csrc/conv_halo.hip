@@ -238,6 +238,9 @@ static const HaloVariant HALO_VARIANTS[] = {
     {128, 64, 64, 1, true, "conv3x3_halo_bf16<128,64,c64,1buf>"},
     {256, 64, 64, 2, true, "conv3x3_halo_bf16<256,64,c64,1buf>"},
     {128, 128, 64, 1, true, "conv3x3_halo_bf16<128,128,c64,1buf>"},
+    {128, 64, 32, 1, true, "conv3x3_halo_bf16<128,64,c32,1buf>"},
+    {256, 64, 32, 1, true, "conv3x3_halo_bf16<256,64,c32,1buf>"},
+    {128, 128, 32, 1, true, "conv3x3_halo_bf16<128,128,c32,1buf>"},
 };
 constexpr int N_HALO_VARIANTS = sizeof(HALO_VARIANTS) / sizeof(HALO_VARIANTS[0]);
 constexpr int LDS_LIMIT = 160 * 1024;
@@ -359,7 +362,10 @@ hipError_t launch_conv_halo(const ConvArgs& a, const ConvArgs* argv, int G, int 
         case 5: return launch_halo_variant<128, 128, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
         case 6: return launch_halo_variant<128, 64, 2, 2, 64, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
         case 7: return launch_halo_variant<256, 64, 4, 1, 64, 2>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
-        default: return launch_halo_variant<128, 128, 2, 2, 64, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 8: return launch_halo_variant<128, 128, 2, 2, 64, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 9: return launch_halo_variant<128, 64, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 10: return launch_halo_variant<256, 64, 4, 1, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        default: return launch_halo_variant<128, 128, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
     }
 }
 
