@@ -227,6 +227,7 @@ __global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restr
 }
 
 // ---- host side -----------------------------------------------------------------------------
+// name: the kernel instance (the one- and two-buffer forms of a tile are the same instance)
 struct HaloVariant { int bp, bc, cb, nhl; bool single; const char* name; };
 static const HaloVariant HALO_VARIANTS[] = {
     {128, 64, 64, 1, false, "conv3x3_halo_bf16<128,64,c64>"},
@@ -235,12 +236,12 @@ static const HaloVariant HALO_VARIANTS[] = {
     {256, 64, 32, 1, false, "conv3x3_halo_bf16<256,64,c32>"},
     {128, 64, 32, 1, false, "conv3x3_halo_bf16<128,64,c32>"},
     {128, 128, 32, 1, false, "conv3x3_halo_bf16<128,128,c32>"},
-    {128, 64, 64, 1, true, "conv3x3_halo_bf16<128,64,c64,1buf>"},
-    {256, 64, 64, 2, true, "conv3x3_halo_bf16<256,64,c64,1buf>"},
-    {128, 128, 64, 1, true, "conv3x3_halo_bf16<128,128,c64,1buf>"},
-    {128, 64, 32, 1, true, "conv3x3_halo_bf16<128,64,c32,1buf>"},
-    {256, 64, 32, 1, true, "conv3x3_halo_bf16<256,64,c32,1buf>"},
-    {128, 128, 32, 1, true, "conv3x3_halo_bf16<128,128,c32,1buf>"},
+    {128, 64, 64, 1, true, "conv3x3_halo_bf16<128,64,c64>"},
+    {256, 64, 64, 2, true, "conv3x3_halo_bf16<256,64,c64>"},
+    {128, 128, 64, 1, true, "conv3x3_halo_bf16<128,128,c64>"},
+    {128, 64, 32, 1, true, "conv3x3_halo_bf16<128,64,c32>"},
+    {256, 64, 32, 1, true, "conv3x3_halo_bf16<256,64,c32>"},
+    {128, 128, 32, 1, true, "conv3x3_halo_bf16<128,128,c32>"},
 };
 constexpr int N_HALO_VARIANTS = sizeof(HALO_VARIANTS) / sizeof(HALO_VARIANTS[0]);
 constexpr int LDS_LIMIT = 160 * 1024;
@@ -330,7 +331,8 @@ static hipError_t launch_halo_variant(const ConvArgs& a, const ConvArgs* argv, i
     }
     const long long PP = (long long)nb * (a.H + 1) * (a.W + 1);
     const dim3 grid((unsigned)(((PP + BP - 1) / BP) * ((a.cout + BC - 1) / BC)), splits, G);
-    hipLaunchKernelGGL((conv3x3_halo_bf16<BP, BC, WP, WC, CB, NHL>), grid, dim3(256), bytes, s, argv, nb, hrows, nbuf);
+    if (splits > 1) ENS_LAUNCH_FIRST((conv3x3_halo_bf16<BP, BC, WP, WC, CB, NHL>), grid, dim3(256), bytes, s, argv, nb, hrows, nbuf);
+    else ENS_LAUNCH((conv3x3_halo_bf16<BP, BC, WP, WC, CB, NHL>), grid, dim3(256), bytes, s, argv, nb, hrows, nbuf);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && splits > 1) e = launch_conv_splitk_epilogue(a, argv, G, nb, nb * a.H * a.W, splits, s);
     return e;

@@ -359,7 +359,7 @@ __global__ void conv_splitk_epilogue(const ConvArgs* __restrict__ argv, const in
 
 hipError_t launch_conv_splitk_epilogue(const ConvArgs& a, const ConvArgs* argv, int G, int nb, int P, int splits, hipStream_t s) {
     const long long work = (long long)P * (a.cout / 4);
-    hipLaunchKernelGGL(conv_splitk_epilogue, dim3((unsigned)((work + 255) / 256), 1, G), dim3(256), 0, s, argv, nb, splits);
+    ENS_LAUNCH_LAST(conv_splitk_epilogue, dim3((unsigned)((work + 255) / 256), 1, G), dim3(256), 0, s, argv, nb, splits);
     return hipGetLastError();
 }
 
@@ -422,7 +422,8 @@ const char* conv_bf16_variant_name(const ConvArgs& a, int G) {
 template <int BP, int BC, int WP, int WC, int NS, int BKT = 64>
 static hipError_t launch_variant(const ConvArgs& a, const ConvArgs* argv, int G, int nb, int P, int splits, hipStream_t s) {
     const dim3 grid(((P + BP - 1) / BP) * ((a.cout + BC - 1) / BC), splits, G);
-    hipLaunchKernelGGL((conv_igemm_bf16<BP, BC, WP, WC, NS, BKT>), grid, dim3(256), 0, s, argv, nb);
+    if (splits > 1) ENS_LAUNCH_FIRST((conv_igemm_bf16<BP, BC, WP, WC, NS, BKT>), grid, dim3(256), 0, s, argv, nb);
+    else ENS_LAUNCH((conv_igemm_bf16<BP, BC, WP, WC, NS, BKT>), grid, dim3(256), 0, s, argv, nb);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && splits > 1) e = launch_conv_splitk_epilogue(a, argv, G, nb, P, splits, s);
     return e;

@@ -216,9 +216,9 @@ template <int BP, int BC, int WP, int WC>
 static hipError_t launch_rs(const ConvArgs& a, const ConvArgs* argv, int G, int nb, int P, hipStream_t s) {
     const dim3 grid(((P + BP - 1) / BP) * ((a.cout + BC - 1) / BC), 1, G);
     if (a.pre_scale)
-        hipLaunchKernelGGL((conv_regstage_bf16<BP, BC, WP, WC, true>), grid, dim3(256), 0, s, argv, nb);
+        ENS_LAUNCH((conv_regstage_bf16<BP, BC, WP, WC, true>), grid, dim3(256), 0, s, argv, nb);
     else
-        hipLaunchKernelGGL((conv_regstage_bf16<BP, BC, WP, WC, false>), grid, dim3(256), 0, s, argv, nb);
+        ENS_LAUNCH((conv_regstage_bf16<BP, BC, WP, WC, false>), grid, dim3(256), 0, s, argv, nb);
     return hipGetLastError();
 }
 

@@ -246,7 +246,7 @@ static hipError_t launch_taps_variant(const ConvArgs& a, const ConvArgs* argv, i
     if (const char* e = getenv("ENS_CONV_TAPS_WGS")) if (atoi(e) > 0) wgs = atoi(e);
 #endif
     const dim3 grid((unsigned)wgs, (unsigned)((a.cout + 63) / 64), G);
-    hipLaunchKernelGGL((conv_taps16_bf16<BP, KH, KW, HROWS>), grid, dim3(256), pl.bytes, s, argv, nb, pl.hrows, pl.gh, pl.gw);
+    ENS_LAUNCH((conv_taps16_bf16<BP, KH, KW, HROWS>), grid, dim3(256), pl.bytes, s, argv, nb, pl.hrows, pl.gh, pl.gw);
     return hipGetLastError();
 }
 

@@ -351,9 +351,9 @@ static int forward_batch(ens_handle* h, Gang& g, int64_t first, int nb) {
         if (!h->profiling) return fn();
         ProfRec r{klass, take_event(h), take_event(h), flop * scale, bytes * scale};
         if (!r.start || !r.stop) return hipErrorOutOfMemory;
-        hipError_t e = hipEventRecord(r.start, g.stream);
-        if (e == hipSuccess) e = fn();
-        if (e == hipSuccess) e = hipEventRecord(r.stop, g.stream);
+        next_launch_events() = LaunchEvents{r.start, r.stop};    // stamped with the kernels' own begin and end
+        const hipError_t e = fn();
+        next_launch_events() = LaunchEvents{};
         h->prof_recs.push_back(r);
         return e;
     };
@@ -443,11 +443,11 @@ static int run_device(ens_handle* h, const float* d_images, int64_t n, float* d_
         if (h->profiling) {
             r.start = take_event(h); r.stop = take_event(h);
             if (!r.start || !r.stop) return ENS_E_HIP;
-            HIP_TRY(hipEventRecord(r.start, h->main_stream));
+            next_launch_events() = LaunchEvents{r.start, r.stop};
         }
         HIP_TRY(launch_combine(h->d_logit_ptrs, M, n, h->classes, d_probs, h->main_stream));
         if (h->profiling) {
-            HIP_TRY(hipEventRecord(r.stop, h->main_stream));
+            next_launch_events() = LaunchEvents{};
             h->prof_recs.push_back(r);
         }
     }

@@ -3,6 +3,7 @@
 // instead of launching when a shape does not fit.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace ens {
@@ -104,4 +105,28 @@ hipError_t launch_fill_noise(float* p, int64_t count, uint64_t seed, hipStream_t
 
 double conv_flops(const ConvArgs& a, int nb);
 
+// Per-kernel timing.  Events put here are attached to the dispatch of the next kernel this thread
+// launches: the runtime stamps `start` with the begin of that kernel and `stop` with its end, with
+// no extra packet in the stream (an event recorded before and after a launch also measures the gap
+// between the two packets).  A launcher that issues several kernels gives `start` to the first
+// and `stop` to the last.  Null: no timing.
+struct LaunchEvents {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+LaunchEvents& next_launch_events();                  // per thread
+
 }  // namespace ens
+
+// The only, first, middle and last kernel of a launcher.
+#define ENS_LAUNCH_EV(take_start, take_stop, kernel, grid, block, shmem, stream, ...)                            \
+    do {                                                                                                          \
+        ens::LaunchEvents& nle_ = ens::next_launch_events();                                                      \
+        hipEvent_t ev_start_ = (take_start) ? nle_.start : nullptr, ev_stop_ = (take_stop) ? nle_.stop : nullptr; \
+        if (take_start) nle_.start = nullptr;                                                                     \
+        if (take_stop) nle_.stop = nullptr;                                                                       \
+        hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, ev_start_, ev_stop_, 0, __VA_ARGS__);           \
+    } while (0)
+#define ENS_LAUNCH(kernel, grid, block, shmem, stream, ...) ENS_LAUNCH_EV(true, true, kernel, grid, block, shmem, stream, __VA_ARGS__)
+#define ENS_LAUNCH_FIRST(kernel, grid, block, shmem, stream, ...) ENS_LAUNCH_EV(true, false, kernel, grid, block, shmem, stream, __VA_ARGS__)
+#define ENS_LAUNCH_MIDDLE(kernel, grid, block, shmem, stream, ...) ENS_LAUNCH_EV(false, false, kernel, grid, block, shmem, stream, __VA_ARGS__)
+#define ENS_LAUNCH_LAST(kernel, grid, block, shmem, stream, ...) ENS_LAUNCH_EV(false, true, kernel, grid, block, shmem, stream, __VA_ARGS__)

@@ -39,6 +39,11 @@ __device__ __forceinline__ uint4 pack8(const float* f) {
     return make_uint4(u[0], u[1], u[2], u[3]);
 }
 
+LaunchEvents& next_launch_events() {
+    static thread_local LaunchEvents ev;
+    return ev;
+}
+
 static inline int blocks_for(long long work, int threads) { return (int)((work + threads - 1) / threads); }
 
 // ------------------------------------------------------------------ input staging
@@ -129,13 +134,13 @@ hipError_t launch_stage(const StageArgs& a, const StageArgs* argv, int G, int nb
     if (a.s2d) {
         if (!bf16 || a.dc != 16) return hipErrorInvalidValue;
         const long long px = (long long)nb * ((a.dh + 1) / 2) * ((a.dw + 1) / 2);
-        hipLaunchKernelGGL(stage_s2d_kernel, dim3(blocks_for(px, 256), 1, G), dim3(256), 0, s, argv, nb, first);
+        ENS_LAUNCH(stage_s2d_kernel, dim3(blocks_for(px, 256), 1, G), dim3(256), 0, s, argv, nb, first);
         return hipGetLastError();
     }
     const long long total = (long long)nb * a.dh * a.dw;
     const dim3 g(blocks_for(total, 256), 1, G);
-    if (bf16) hipLaunchKernelGGL(stage_kernel<true>, g, dim3(256), 0, s, argv, nb, first);
-    else hipLaunchKernelGGL(stage_kernel<false>, g, dim3(256), 0, s, argv, nb, first);
+    if (bf16) ENS_LAUNCH(stage_kernel<true>, g, dim3(256), 0, s, argv, nb, first);
+    else ENS_LAUNCH(stage_kernel<false>, g, dim3(256), 0, s, argv, nb, first);
     return hipGetLastError();
 }
 
@@ -179,7 +184,7 @@ hipError_t launch_conv_f32(const ConvArgs& a, const ConvArgs* argv, int G, int n
     if (nb <= 0 || a.cin <= 0 || a.cout <= 0 || !a.bias || G <= 0 || !argv) return hipErrorInvalidValue;
     const long long total = (long long)nb * a.Ho * a.Wo * a.cout;
     if (total >= (1LL << 31) * 256) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(conv_f32_kernel, dim3(blocks_for(total, 256), 1, G), dim3(256), 0, s, argv, nb);
+    ENS_LAUNCH(conv_f32_kernel, dim3(blocks_for(total, 256), 1, G), dim3(256), 0, s, argv, nb);
     return hipGetLastError();
 }
 
@@ -306,8 +311,8 @@ hipError_t launch_dwconv(const PoolArgs& a, const PoolArgs* argv, int G, int nb,
     const long long total = (long long)nb * a.Ho * a.Wo * (a.c / (bf16 ? 8 : 1));
     if (total >= (1LL << 31) - 256) return hipErrorInvalidValue;   // 32-bit work item index in the kernel
     const dim3 g(blocks_for(total, 256), 1, G);
-    if (bf16) hipLaunchKernelGGL((window_kernel<0, true>), g, dim3(256), 0, s, argv, nb);
-    else hipLaunchKernelGGL((window_kernel<0, false>), g, dim3(256), 0, s, argv, nb);
+    if (bf16) ENS_LAUNCH((window_kernel<0, true>), g, dim3(256), 0, s, argv, nb);
+    else ENS_LAUNCH((window_kernel<0, false>), g, dim3(256), 0, s, argv, nb);
     return hipGetLastError();
 }
 
@@ -319,13 +324,13 @@ hipError_t launch_pool(const PoolArgs& a, const PoolArgs* argv, int G, int nb, b
     if (is_max) {
         // every window must overlap the image for the clamped fast path (true for the padded layers of real networks)
         const bool overlap = a.pt < a.kh && a.pl < a.kw && (a.Ho - 1) * a.sh - a.pt < a.H && (a.Wo - 1) * a.sw - a.pl < a.W;
-        if (bf16 && overlap && a.kh == 3 && a.kw == 3) hipLaunchKernelGGL((maxpool_bf16_kernel<3, 3>), g, b, 0, s, argv, nb);
-        else if (bf16 && overlap && a.kh == 2 && a.kw == 2) hipLaunchKernelGGL((maxpool_bf16_kernel<2, 2>), g, b, 0, s, argv, nb);
-        else if (bf16) hipLaunchKernelGGL((window_kernel<1, true>), g, b, 0, s, argv, nb);
-        else hipLaunchKernelGGL((window_kernel<1, false>), g, b, 0, s, argv, nb);
+        if (bf16 && overlap && a.kh == 3 && a.kw == 3) ENS_LAUNCH((maxpool_bf16_kernel<3, 3>), g, b, 0, s, argv, nb);
+        else if (bf16 && overlap && a.kh == 2 && a.kw == 2) ENS_LAUNCH((maxpool_bf16_kernel<2, 2>), g, b, 0, s, argv, nb);
+        else if (bf16) ENS_LAUNCH((window_kernel<1, true>), g, b, 0, s, argv, nb);
+        else ENS_LAUNCH((window_kernel<1, false>), g, b, 0, s, argv, nb);
     } else {
-        if (bf16) hipLaunchKernelGGL((window_kernel<2, true>), g, b, 0, s, argv, nb);
-        else hipLaunchKernelGGL((window_kernel<2, false>), g, b, 0, s, argv, nb);
+        if (bf16) ENS_LAUNCH((window_kernel<2, true>), g, b, 0, s, argv, nb);
+        else ENS_LAUNCH((window_kernel<2, false>), g, b, 0, s, argv, nb);
     }
     return hipGetLastError();
 }
@@ -386,8 +391,8 @@ __global__ __launch_bounds__(256) void gap_kernel(const GapArgs* __restrict__ ar
 hipError_t launch_gap(const GapArgs& a, const GapArgs* argv, int G, int nb, bool bf16, hipStream_t s) {
     if (nb <= 0 || a.c <= 0 || a.HW <= 0 || G <= 0 || !argv) return hipErrorInvalidValue;
     if (bf16 && (a.c % 8 || a.x.stride % 8 || a.x.c0 % 8)) return hipErrorInvalidValue;
-    if (bf16) hipLaunchKernelGGL(gap_kernel<true>, dim3(nb, 1, G), dim3(256), 0, s, argv, nb);
-    else hipLaunchKernelGGL(gap_kernel<false>, dim3(nb, 1, G), dim3(256), 0, s, argv, nb);
+    if (bf16) ENS_LAUNCH(gap_kernel<true>, dim3(nb, 1, G), dim3(256), 0, s, argv, nb);
+    else ENS_LAUNCH(gap_kernel<false>, dim3(nb, 1, G), dim3(256), 0, s, argv, nb);
     return hipGetLastError();
 }
 
@@ -453,8 +458,8 @@ __global__ __launch_bounds__(FC_WAVES * 64) void fc_kernel(const FcArgs* __restr
 hipError_t launch_fc(const FcArgs& a, const FcArgs* argv, int G, int nb, long long first, bool bf16, hipStream_t s) {
     if (nb <= 0 || a.cin <= 0 || a.cout <= 0 || !a.bias || !a.y || G <= 0 || !argv) return hipErrorInvalidValue;
     const dim3 g((a.cout + 63) / 64, (nb + FC_IMGS - 1) / FC_IMGS, G), b(FC_WAVES * 64);
-    if (bf16) hipLaunchKernelGGL(fc_kernel<true>, g, b, 0, s, argv, nb, first);
-    else hipLaunchKernelGGL(fc_kernel<false>, g, b, 0, s, argv, nb, first);
+    if (bf16) ENS_LAUNCH(fc_kernel<true>, g, b, 0, s, argv, nb, first);
+    else ENS_LAUNCH(fc_kernel<false>, g, b, 0, s, argv, nb, first);
     return hipGetLastError();
 }
 
@@ -528,11 +533,11 @@ hipError_t launch_se(const SeArgs& a, const SeArgs* argv, int G, int nb, bool bf
     if (bf16 && (a.c % 8 || a.x.stride % 8 || a.x.c0 % 8 || a.y.stride % 8 || a.y.c0 % 8)) return hipErrorInvalidValue;
     const long long nc = (long long)nb * a.c;
     const long long tot = (long long)nb * a.HW * (a.c / (bf16 ? 8 : 1));
-    if (bf16) hipLaunchKernelGGL(se_mean_kernel<true>, dim3(blocks_for(nc, 256), 1, G), dim3(256), 0, s, argv, nb);
-    else hipLaunchKernelGGL(se_mean_kernel<false>, dim3(blocks_for(nc, 256), 1, G), dim3(256), 0, s, argv, nb);
-    hipLaunchKernelGGL(se_gate_kernel, dim3(nb, 1, G), dim3(256), 0, s, argv, nb);
-    if (bf16) hipLaunchKernelGGL(se_scale_kernel<true>, dim3(blocks_for(tot, 256), 1, G), dim3(256), 0, s, argv, nb);
-    else hipLaunchKernelGGL(se_scale_kernel<false>, dim3(blocks_for(tot, 256), 1, G), dim3(256), 0, s, argv, nb);
+    if (bf16) ENS_LAUNCH_FIRST(se_mean_kernel<true>, dim3(blocks_for(nc, 256), 1, G), dim3(256), 0, s, argv, nb);
+    else ENS_LAUNCH_FIRST(se_mean_kernel<false>, dim3(blocks_for(nc, 256), 1, G), dim3(256), 0, s, argv, nb);
+    ENS_LAUNCH_MIDDLE(se_gate_kernel, dim3(nb, 1, G), dim3(256), 0, s, argv, nb);
+    if (bf16) ENS_LAUNCH_LAST(se_scale_kernel<true>, dim3(blocks_for(tot, 256), 1, G), dim3(256), 0, s, argv, nb);
+    else ENS_LAUNCH_LAST(se_scale_kernel<false>, dim3(blocks_for(tot, 256), 1, G), dim3(256), 0, s, argv, nb);
     return hipGetLastError();
 }
 
@@ -598,10 +603,10 @@ hipError_t launch_combine(const float* const* logits, int n_members, int64_t n, 
     if (n_members <= 0 || classes <= 0 || classes > 64 * COMBINE_MAX_PER_LANE) return hipErrorInvalidValue;
     const dim3 g((unsigned)((n + 3) / 4)), b(256);
     const int per = (classes + 63) / 64;
-    if (per <= 1) hipLaunchKernelGGL(combine_kernel<1>, g, b, 0, s, logits, n_members, (long long)n, classes, y);
-    else if (per <= 4) hipLaunchKernelGGL(combine_kernel<4>, g, b, 0, s, logits, n_members, (long long)n, classes, y);
-    else if (per <= 16) hipLaunchKernelGGL(combine_kernel<16>, g, b, 0, s, logits, n_members, (long long)n, classes, y);
-    else hipLaunchKernelGGL(combine_kernel<32>, g, b, 0, s, logits, n_members, (long long)n, classes, y);
+    if (per <= 1) ENS_LAUNCH(combine_kernel<1>, g, b, 0, s, logits, n_members, (long long)n, classes, y);
+    else if (per <= 4) ENS_LAUNCH(combine_kernel<4>, g, b, 0, s, logits, n_members, (long long)n, classes, y);
+    else if (per <= 16) ENS_LAUNCH(combine_kernel<16>, g, b, 0, s, logits, n_members, (long long)n, classes, y);
+    else ENS_LAUNCH(combine_kernel<32>, g, b, 0, s, logits, n_members, (long long)n, classes, y);
     return hipGetLastError();
 }
 
@@ -620,7 +625,7 @@ __global__ void fill_noise_kernel(float* p, long long count, unsigned long long 
 
 hipError_t launch_fill_noise(float* p, int64_t count, uint64_t seed, hipStream_t s) {
     if (count <= 0) return hipSuccess;
-    hipLaunchKernelGGL(fill_noise_kernel, dim3(blocks_for(count, 256)), dim3(256), 0, s, p, (long long)count,
+    ENS_LAUNCH(fill_noise_kernel, dim3(blocks_for(count, 256)), dim3(256), 0, s, p, (long long)count,
                        (unsigned long long)seed);
     return hipGetLastError();
 }
