@@ -114,6 +114,8 @@ typedef struct {
     uint64_t seed;              /* seeds the draw of neighbours                                */
     int64_t n_calib;            /* calibration images per benchmark, default 1024              */
     int32_t repeats;            /* timed repetitions per benchmark (median), default 3         */
+    int32_t verbose;            /* non-zero: one line per benchmark on stderr (a plan over many
+                                   members runs for minutes)                                   */
 } ens_plan_opts;
 
 typedef struct ens_handle ens_handle;

@@ -61,7 +61,7 @@ class EnsPlanOpts(ctypes.Structure):
                 ("default_batch", ctypes.c_int32), ("segment_size", ctypes.c_int32),
                 ("max_neighs", ctypes.c_int32), ("max_iter", ctypes.c_int32), ("slots", ctypes.c_int32),
                 ("strategy", ctypes.c_int32), ("seed", ctypes.c_uint64), ("n_calib", ctypes.c_int64),
-                ("repeats", ctypes.c_int32)]
+                ("repeats", ctypes.c_int32), ("verbose", ctypes.c_int32)]
 
 
 class EnsPlanProblem(ctypes.Structure):

@@ -712,12 +712,24 @@ int ens_plan(ens_handle* h, uint64_t mem_budget_bytes, const ens_plan_opts* opts
         return a;
     };
     int hip_rc = ENS_OK;
+    int32_t shown = 0;
+    auto show = [&](const int32_t* mat, double ips) {             // progress of a long plan
+        if (!o.verbose) return;
+        std::string line;
+        for (int r = 0; r < o.slots; r++) {
+            line += r ? " | " : "";
+            for (int c = 0; c < M; c++) line += (c ? " " : "") + std::to_string(mat[r * M + c]);
+        }
+        fprintf(stderr, "ens_plan: benchmark %d: [%s] -> %.1f images/s\n", ++shown, line.c_str(), ips);
+        fflush(stderr);
+    };
     auto bench = [&](const int32_t* mat) -> double {
         if (!fit_mem(p, mat)) return 0.0;
         const ens_alloc a = to_alloc(mat);
         double ips = 0.0;
         const int r = ens_bench(h, &a, o.segment_size, o.n_calib, o.repeats, &ips);
         if (r != ENS_OK) { hip_rc = r; return 0.0; }
+        show(mat, ips);
         return ips;
     };
     double score = 0.0;
@@ -743,6 +755,7 @@ int ens_plan(ens_handle* h, uint64_t mem_budget_bytes, const ens_plan_opts* opts
             double ips = 0.0;
             r = time_installed(h, o.n_calib, o.repeats, 1ull << m, &ips);
             if (r != ENS_OK) { hip_rc = r; return 0.0; }
+            show(mat.data(), ips);
             return ips;
         };
         rc = bbs(p, single, best.data(), &n_bench);

@@ -67,12 +67,16 @@ struct FcArgs {                // logits[n][cout] = pooled[n][cin] . W[cin][cout
     int64_t ldy;
 };
 
-struct SeArgs {                // squeeze-excite
+// Squeeze-excite.  The channel sums of an image are taken by up to SE_MAX_SPLITS workgroups, each
+// over a share of the pixels; the gate kernel adds their partial sums in a fixed order.
+constexpr int SE_MAX_SPLITS = 16;
+struct SeArgs {
     View x, y;
     const float* w1; const float* b1; const float* w2; const float* b2;   // fp32
-    float* scratch;            // nb * (c + r + c) floats
+    float* scratch;            // per image SE_MAX_SPLITS * c partial sums, r hidden values, c gates (floats)
     int nb, HW, c, r;
 };
+__host__ __device__ inline int se_scratch_floats(int c, int r) { return (SE_MAX_SPLITS + 1) * c + r; }
 
 struct StageArgs {             // request images -> a worker's input tensor (convert, pad, resize)
     const float* src;          // request images, n x sh x sw x 3 fp32

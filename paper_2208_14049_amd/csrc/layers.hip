@@ -300,6 +300,64 @@ __global__ void maxpool_bf16_kernel(const PoolArgs* __restrict__ argv, const int
     *(uint4*)((uint16_t*)a.y.p + (long long)pu * a.y.stride + a.y.c0 + c) = pack8(acc);
 }
 
+// Depthwise K x K convolution, bf16, one lane per (pixel, 8 channels).  Every tap is loaded from a
+// position clamped into the image and zeroed by a select when the tap lies outside: the K
+// activation loads and K weight loads of a filter row are unconditional and in flight together
+// (the rows stay a loop: all K*K at once would spill registers).
+template <int K>
+__global__ void dwconv_bf16_kernel(const PoolArgs* __restrict__ argv, const int nb_) {
+    const PoolArgs a = argv[blockIdx.z];
+    const unsigned cv = (unsigned)(a.c / 8);
+    const unsigned idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const unsigned total = (unsigned)nb_ * (unsigned)(a.Ho * a.Wo) * cv;
+    if (idx >= total) return;
+    const unsigned pu = idx / cv;
+    const int c = (int)(idx - pu * cv) * 8;
+    const unsigned row = pu / (unsigned)a.Wo;
+    const int wo = (int)(pu - row * (unsigned)a.Wo);
+    const unsigned nu = row / (unsigned)a.Ho;
+    const int ho = (int)(row - nu * (unsigned)a.Ho);
+    const uint16_t* __restrict__ x = (const uint16_t*)a.x.p + (long long)nu * a.H * a.W * a.x.stride + a.x.c0 + c;
+    const uint16_t* __restrict__ w = (const uint16_t*)a.w + c;
+    float acc[8];
+    {
+        const float4 b0 = *(const float4*)(a.bias + c), b1 = *(const float4*)(a.bias + c + 4);
+        acc[0] = b0.x; acc[1] = b0.y; acc[2] = b0.z; acc[3] = b0.w;
+        acc[4] = b1.x; acc[5] = b1.y; acc[6] = b1.z; acc[7] = b1.w;
+    }
+#pragma unroll 1
+    for (int kh = 0; kh < K; kh++) {
+        const int hi = ho * a.sh - a.pt + kh;
+        const bool hok = (unsigned)hi < (unsigned)a.H;
+        const int hic = min(max(hi, 0), a.H - 1);
+        uint4 xv[K], wv[K];
+#pragma unroll
+        for (int kw = 0; kw < K; kw++) {
+            const int wic = min(max(wo * a.sw - a.pl + kw, 0), a.W - 1);
+            xv[kw] = *(const uint4*)(x + (long long)(hic * a.W + wic) * a.x.stride);
+            wv[kw] = *(const uint4*)(w + (kh * K + kw) * a.c);
+        }
+#pragma unroll
+        for (int kw = 0; kw < K; kw++) {
+            const bool ok = hok && (unsigned)(wo * a.sw - a.pl + kw) < (unsigned)a.W;
+            if (!ok) xv[kw] = make_uint4(0u, 0u, 0u, 0u);
+            float xf[8], wf[8];
+            unpack8(xv[kw], xf);
+            unpack8(wv[kw], wf);
+#pragma unroll
+            for (int e = 0; e < 8; e++) acc[e] = fmaf(xf[e], wf[e], acc[e]);
+        }
+    }
+    if (a.act == ACT_SILU) {
+#pragma unroll
+        for (int e = 0; e < 8; e++) acc[e] = acc[e] / (1.f + __expf(-acc[e]));
+    } else if (a.act == ACT_RELU) {
+#pragma unroll
+        for (int e = 0; e < 8; e++) acc[e] = fmaxf(acc[e], 0.f);
+    }
+    *(uint4*)((uint16_t*)a.y.p + (long long)pu * a.y.stride + a.y.c0 + c) = pack8(acc);
+}
+
 static hipError_t check_window(const PoolArgs& a, bool bf16) {
     if (a.c <= 0) return hipErrorInvalidValue;
     if (bf16 && (a.c % 8 || a.x.stride % 8 || a.x.c0 % 8 || a.y.stride % 8 || a.y.c0 % 8)) return hipErrorInvalidValue;
@@ -311,7 +369,9 @@ hipError_t launch_dwconv(const PoolArgs& a, const PoolArgs* argv, int G, int nb,
     const long long total = (long long)nb * a.Ho * a.Wo * (a.c / (bf16 ? 8 : 1));
     if (total >= (1LL << 31) - 256) return hipErrorInvalidValue;   // 32-bit work item index in the kernel
     const dim3 g(blocks_for(total, 256), 1, G);
-    if (bf16) ENS_LAUNCH((window_kernel<0, true>), g, dim3(256), 0, s, argv, nb);
+    if (bf16 && a.kh == 3 && a.kw == 3) ENS_LAUNCH((dwconv_bf16_kernel<3>), g, dim3(256), 0, s, argv, nb);
+    else if (bf16 && a.kh == 5 && a.kw == 5) ENS_LAUNCH((dwconv_bf16_kernel<5>), g, dim3(256), 0, s, argv, nb);
+    else if (bf16) ENS_LAUNCH((window_kernel<0, true>), g, dim3(256), 0, s, argv, nb);
     else ENS_LAUNCH((window_kernel<0, false>), g, dim3(256), 0, s, argv, nb);
     return hipGetLastError();
 }
@@ -464,64 +524,126 @@ hipError_t launch_fc(const FcArgs& a, const FcArgs* argv, int G, int nb, long lo
 }
 
 // ------------------------------------------------------------------ squeeze-excite
-// Three small kernels on the worker's stream: channel means, the two tiny FC layers (one
-// workgroup per image), then the channel-wise rescale of the activation tensor.
-template <bool BF16>
-__global__ void se_mean_kernel(const SeArgs* __restrict__ argv, const int nb_) {
-    SeArgs a = argv[blockIdx.z];
-    a.nb = nb_;
-    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (long long)a.nb * a.c) return;
-    const int c = (int)(idx % a.c);
-    const long long n = idx / a.c;
-    float acc = 0.f;
-    for (int p = 0; p < a.HW; p++) {
-        const long long off = (n * a.HW + p) * (long long)a.x.stride + a.x.c0 + c;
-        acc += BF16 ? bf2f(((const uint16_t*)a.x.p)[off]) : ((const float*)a.x.p)[off];
-    }
-    a.scratch[n * (2 * a.c + a.r) + c] = acc / (float)a.HW;
+// Three kernels on the worker's stream.  (1) Channel sums: workgroup (split, image) adds its share
+// of the image's pixels; lanes run along the channels (16-byte groups of 8 for bf16) so that every
+// pixel is read in whole lines, the pixels of the share are dealt round-robin to the thread rows
+// and the rows are added through LDS.  (2) Gate: one workgroup per image adds the partial sums,
+// then the two small FC layers (SiLU, sigmoid) with all 256 threads on the first one.  (3) The
+// channel-wise rescale of the activation tensor.
+static inline int se_splits(int HW) {
+    const int s = (HW + 511) / 512;
+    return s < 1 ? 1 : (s > SE_MAX_SPLITS ? SE_MAX_SPLITS : s);
 }
 
-__global__ void se_gate_kernel(const SeArgs* __restrict__ argv, const int nb_) {
-    SeArgs a = argv[blockIdx.z];
-    a.nb = nb_;
-    const int n = blockIdx.x;
-    float* s = a.scratch + (long long)n * (2 * a.c + a.r);
-    float* z = s + a.c;
-    float* g = z + a.r;
-    for (int r = threadIdx.x; r < a.r; r += blockDim.x) {
-        float acc = 0.f;
-        for (int c = 0; c < a.c; c++) acc = fmaf(s[c], a.w1[(long long)c * a.r + r], acc);
-        acc += a.b1[r];
-        z[r] = acc / (1.f + __expf(-acc));
+template <bool BF16>
+__global__ __launch_bounds__(256) void se_sum_kernel(const SeArgs* __restrict__ argv, const int nb_) {
+    const SeArgs a = argv[blockIdx.z];
+    constexpr int V = BF16 ? 8 : 1;
+    __shared__ float part[256 * V];
+    const int split = blockIdx.x, n = blockIdx.y, splits = gridDim.x;
+    const int chunk = (a.HW + splits - 1) / splits;
+    const int p0 = split * chunk, p1 = min(a.HW, p0 + chunk);
+    const int cv = (a.c + V - 1) / V;                 // channel groups
+    const int cols = min(cv, 256);                    // groups handled side by side
+    const int rows = 256 / cols;                      // pixel phases
+    const int col = threadIdx.x % cols, row = threadIdx.x / cols;
+    float* out = a.scratch + (long long)n * se_scratch_floats(a.c, a.r) + (long long)split * a.c;
+    for (int g0 = 0; g0 < cv; g0 += cols) {
+        const int g = g0 + col;
+        float acc[V];
+#pragma unroll
+        for (int e = 0; e < V; e++) acc[e] = 0.f;
+        if (g < cv && row < rows) {
+            const long long base = (long long)n * a.HW * a.x.stride + a.x.c0 + g * V;
+            for (int p = p0 + row; p < p1; p += rows) {
+                const long long off = base + (long long)p * a.x.stride;
+                float v[V];
+                if (BF16) unpack8(*(const uint4*)((const uint16_t*)a.x.p + off), v);
+                else v[0] = ((const float*)a.x.p)[off];
+#pragma unroll
+                for (int e = 0; e < V; e++) acc[e] += v[e];
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < V; e++) part[threadIdx.x * V + e] = acc[e];
+        __syncthreads();
+        if (row == 0 && g < cv) {
+#pragma unroll
+            for (int e = 0; e < V; e++) {
+                float s = 0.f;
+                for (int r = 0; r < rows; r++) s += part[(r * cols + col) * V + e];
+                if (g * V + e < a.c) out[g * V + e] = s;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+constexpr int SE_GATE_THREADS = 1024;   // the gate is a chain of dependent memory latencies: many threads, few steps each
+constexpr int SE_GATE_MAXC = 4096;      // channels the gate kernel holds in LDS
+
+__global__ __launch_bounds__(SE_GATE_THREADS) void se_gate_kernel(const SeArgs* __restrict__ argv, const int nb_, const int splits) {
+    const SeArgs a = argv[blockIdx.z];
+    const int n = blockIdx.x, t = threadIdx.x;
+    const float* part = a.scratch + (long long)n * se_scratch_floats(a.c, a.r);   // partial sums of the image
+    float* g = a.scratch + (long long)n * se_scratch_floats(a.c, a.r) + (long long)SE_MAX_SPLITS * a.c + a.r;
+    __shared__ float mean[SE_GATE_MAXC];
+    __shared__ float red[SE_GATE_THREADS];
+    __shared__ float z[256];
+    const float inv = 1.f / (float)a.HW;
+    for (int c = t; c < a.c; c += SE_GATE_THREADS) {
+        float m = 0.f;
+        for (int k = 0; k < splits; k++) m += part[(long long)k * a.c + c];   // fixed order
+        mean[c] = m * inv;
     }
     __syncthreads();
-    for (int c = threadIdx.x; c < a.c; c += blockDim.x) {
+    // hidden layer: thread (slice, r) adds its slice of the channels; adjacent threads read adjacent weights
+    int rp = 1;
+    while (rp < a.r && rp < 256) rp <<= 1;
+    const int slices = SE_GATE_THREADS / rp;
+    for (int r0 = 0; r0 < a.r; r0 += rp) {
+        const int r = r0 + t % rp, slice = t / rp;
         float acc = 0.f;
+        if (r < a.r) {
+#pragma unroll 8
+            for (int c = slice; c < a.c; c += slices) acc = fmaf(mean[c], a.w1[(long long)c * a.r + r], acc);
+        }
+        red[t] = acc;
+        __syncthreads();
+        if (t < rp && r < a.r) {
+            float sum = a.b1[r];
+            for (int k = 0; k < slices; k++) sum += red[k * rp + t];
+            z[r] = sum / (1.f + __expf(-sum));
+        }
+        __syncthreads();
+    }
+    for (int c = t; c < a.c; c += SE_GATE_THREADS) {
+        float acc = a.b2[c];
+#pragma unroll 8
         for (int r = 0; r < a.r; r++) acc = fmaf(z[r], a.w2[(long long)r * a.c + c], acc);
-        acc += a.b2[c];
         g[c] = 1.f / (1.f + __expf(-acc));
     }
 }
 
+// The launcher admits fewer than 2^31 work items: 32-bit index arithmetic.
 template <bool BF16>
 __global__ void se_scale_kernel(const SeArgs* __restrict__ argv, const int nb_) {
-    SeArgs a = argv[blockIdx.z];
-    a.nb = nb_;
+    const SeArgs a = argv[blockIdx.z];
     constexpr int V = BF16 ? 8 : 1;
-    const int cv = a.c / V;
-    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (long long)a.nb * a.HW * cv) return;
-    const int c = (int)(idx % cv) * V;
-    const long long p = idx / cv;
-    const long long n = p / a.HW;
-    const float* g = a.scratch + n * (2 * a.c + a.r) + a.c + a.r + c;
-    const long long xo = p * (long long)a.x.stride + a.x.c0 + c, yo = p * (long long)a.y.stride + a.y.c0 + c;
+    const unsigned cv = (unsigned)(a.c / V);
+    const unsigned idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (unsigned)nb_ * (unsigned)a.HW * cv) return;
+    const unsigned p = idx / cv;
+    const int c = (int)(idx - p * cv) * V;
+    const unsigned n = p / (unsigned)a.HW;
+    const float* g = a.scratch + (long long)n * se_scratch_floats(a.c, a.r) + (long long)SE_MAX_SPLITS * a.c + a.r + c;
+    const long long xo = (long long)p * a.x.stride + a.x.c0 + c, yo = (long long)p * a.y.stride + a.y.c0 + c;
     if (BF16) {
         float f[8];
         unpack8(*(const uint4*)((const uint16_t*)a.x.p + xo), f);
-#pragma unroll
-        for (int e = 0; e < 8; e++) f[e] *= g[e];
+        const float4 g0 = *(const float4*)g, g1 = *(const float4*)(g + 4);
+        f[0] *= g0.x; f[1] *= g0.y; f[2] *= g0.z; f[3] *= g0.w;
+        f[4] *= g1.x; f[5] *= g1.y; f[6] *= g1.z; f[7] *= g1.w;
         *(uint4*)((uint16_t*)a.y.p + yo) = pack8(f);
     } else {
         ((float*)a.y.p)[yo] = ((const float*)a.x.p)[xo] * g[0];
@@ -529,13 +651,15 @@ __global__ void se_scale_kernel(const SeArgs* __restrict__ argv, const int nb_) 
 }
 
 hipError_t launch_se(const SeArgs& a, const SeArgs* argv, int G, int nb, bool bf16, hipStream_t s) {
-    if (nb <= 0 || a.c <= 0 || a.r <= 0 || !a.scratch || G <= 0 || !argv) return hipErrorInvalidValue;
+    if (nb <= 0 || a.c <= 0 || a.r <= 0 || a.HW <= 0 || !a.scratch || G <= 0 || !argv) return hipErrorInvalidValue;
+    if (a.c > SE_GATE_MAXC || a.r > 256) return hipErrorInvalidValue;   // what the gate kernel holds in LDS
     if (bf16 && (a.c % 8 || a.x.stride % 8 || a.x.c0 % 8 || a.y.stride % 8 || a.y.c0 % 8)) return hipErrorInvalidValue;
-    const long long nc = (long long)nb * a.c;
     const long long tot = (long long)nb * a.HW * (a.c / (bf16 ? 8 : 1));
-    if (bf16) ENS_LAUNCH_FIRST(se_mean_kernel<true>, dim3(blocks_for(nc, 256), 1, G), dim3(256), 0, s, argv, nb);
-    else ENS_LAUNCH_FIRST(se_mean_kernel<false>, dim3(blocks_for(nc, 256), 1, G), dim3(256), 0, s, argv, nb);
-    ENS_LAUNCH_MIDDLE(se_gate_kernel, dim3(nb, 1, G), dim3(256), 0, s, argv, nb);
+    if (tot >= (1LL << 31) - 256) return hipErrorInvalidValue;
+    const int splits = se_splits(a.HW);
+    if (bf16) ENS_LAUNCH_FIRST(se_sum_kernel<true>, dim3(splits, nb, G), dim3(256), 0, s, argv, nb);
+    else ENS_LAUNCH_FIRST(se_sum_kernel<false>, dim3(splits, nb, G), dim3(256), 0, s, argv, nb);
+    ENS_LAUNCH_MIDDLE(se_gate_kernel, dim3(nb, 1, G), dim3(SE_GATE_THREADS), 0, s, argv, nb, splits);
     if (bf16) ENS_LAUNCH_LAST(se_scale_kernel<true>, dim3(blocks_for(tot, 256), 1, G), dim3(256), 0, s, argv, nb);
     else ENS_LAUNCH_LAST(se_scale_kernel<false>, dim3(blocks_for(tot, 256), 1, G), dim3(256), 0, s, argv, nb);
     return hipGetLastError();

@@ -275,8 +275,8 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
                 pl.b = bw.put_f32(std::vector<float>(params + o.off_b, params + o.off_b + o.r));
                 pl.w2 = bw.put_f32(std::vector<float>(params + o.off_w2, params + o.off_w2 + n1));
                 pl.b2 = bw.put_f32(std::vector<float>(params + o.off_b2, params + o.off_b2 + o.cin));
-                TensorInfo sc;                                   // per-image scratch: means, hidden, gates
-                sc.h = 1; sc.w = 1; sc.c = sc.cs = 2 * o.cin + o.r;
+                TensorInfo sc;                                   // per-image scratch: partial sums, hidden, gates
+                sc.h = 1; sc.w = 1; sc.c = sc.cs = se_scratch_floats(o.cin, o.r);
                 sc.f32 = true; sc.def = i; sc.last = i; sc.external = false;
                 pl.scratch = (int)m.tensors.size();
                 m.tensors.push_back(sc);
