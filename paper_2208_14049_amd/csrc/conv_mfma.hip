@@ -33,6 +33,8 @@
 
 namespace ens {
 
+constexpr int PRE_MAXK = 2048;   // most input channels a pre-activated 1x1 layer may have in the DMA kernel
+
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* global_ptr_t;
 
@@ -45,7 +47,7 @@ __device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr) {
     return v;
 }
 
-template <int BP, int BC, int WP, int WC, int NS, int BKT>
+template <int BP, int BC, int WP, int WC, int NS, int BKT, bool PRE = false>
 __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restrict__ argv, const int nb_) {
     ConvArgs a = argv[blockIdx.z];
     a.nb = nb_;
@@ -71,6 +73,10 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restric
     constexpr int HROWS = HFIT >= BP ? BP : (HFIT >= BP / 2 ? BP / 2 : (HFIT >= BP / 4 ? BP / 4 : 32));
     static_assert(HROWS >= 32 && BP % HROWS == 0 && HROWS * OROW * 4 <= RING, "output staging chunk");
     __shared__ __attribute__((aligned(1024))) unsigned char ring[RING];
+    // PRE (1x1 layers with a pre-activation): relu(x * scale + shift) per input channel is applied to
+    // the pixel fragments on their way from LDS to the matrix cores; scale and shift of all K
+    // channels wait in LDS (zero past K, so the zero-filled K tail stays zero).
+    __shared__ __attribute__((aligned(16))) float pre_s[PRE ? PRE_MAXK + 64 : 4], pre_h[PRE ? PRE_MAXK + 64 : 4];
 
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);     // wave-uniform: LDS stage bases stay scalar
@@ -80,6 +86,13 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restric
     tile_of_block(n_ptiles, n_ctiles, &ptile, &ctile);
     const int p0 = ptile * BP, c0 = ctile * BC;
 
+    if constexpr (PRE) {
+        for (int k = threadIdx.x; k < PRE_MAXK + 64; k += 256) {
+            pre_s[k] = k < K ? a.pre_scale[k] : 0.f;
+            pre_h[k] = k < K ? a.pre_shift[k] : 0.f;
+        }
+        __syncthreads();
+    }
     // ---- this workgroup's share of the K tiles
     const int nk_all = (K + BKT - 1) / BKT;
     const int per_split = (nk_all + gridDim.y - 1) / gridDim.y;
@@ -228,7 +241,13 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restric
         }
         const uint32_t xs = xrow_addr + (uint32_t)stage * STAGE, ws = wrow_addr + (uint32_t)stage * STAGE;
         bf16x8 wf[2][TC], xf[2][TP];
+        f32x4 ps[2][2], ph[2][2];                                // PRE: scale / shift of the step's 8 channels
         auto read_frags = [&](int ks, int b) {
+            if constexpr (PRE) {
+                const int kb = (kt0 + kt) * BKT + (ks * 2 + lhalf) * 8;
+                ps[b][0] = *(const f32x4*)&pre_s[kb]; ps[b][1] = *(const f32x4*)&pre_s[kb + 4];
+                ph[b][0] = *(const f32x4*)&pre_h[kb]; ph[b][1] = *(const f32x4*)&pre_h[kb + 4];
+            }
             const uint32_t xa = xs + koff[ks], wa = ws + koff[ks];
             wf[b][0] = lds_read_b128<0>(wa);
             if (TC > 1) wf[b][1 % TC] = lds_read_b128<BLK>(wa);
@@ -254,6 +273,20 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restric
             else if constexpr (TC == 4 && TP == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wf[b][0]), "+v"(wf[b][1]), "+v"(wf[b][2]), "+v"(wf[b][3]), "+v"(xf[b][0]), "+v"(xf[b][1]));
             else static_assert(TC * TP == 0, "unsupported wave tile");
             if (ks + 1 < BKT / 16) read_frags(ks + 1, b ^ 1);     // next step's reads fly under this step's MFMAs
+            if constexpr (PRE) {
+#pragma unroll
+                for (int j = 0; j < TP; j++) {
+                    u32x4 u = __builtin_bit_cast(u32x4, xf[b][j]);
+#pragma unroll
+                    for (int q = 0; q < 4; q++) {
+                        const float lo = __uint_as_float(u[q] << 16), hi = __uint_as_float(u[q] & 0xFFFF0000u);
+                        const float sl = ps[b][q >> 1][(2 * q) & 3], sh = ps[b][q >> 1][(2 * q + 1) & 3];
+                        const float hl = ph[b][q >> 1][(2 * q) & 3], hh = ph[b][q >> 1][(2 * q + 1) & 3];
+                        u[q] = pack_bf16x2(fmaxf(fmaf(lo, sl, hl), 0.f), fmaxf(fmaf(hi, sh, hh), 0.f));
+                    }
+                    xf[b][j] = __builtin_bit_cast(bf16x8, u);
+                }
+            }
 #pragma unroll
             for (int i = 0; i < TC; i++)
 #pragma unroll
@@ -411,9 +444,19 @@ static int pick_splits(const ConvArgs& a, long long P, long long K, int variant,
     return s < 1 ? 1 : (int)s;
 }
 
+// Pre-activated layers the DMA kernel takes: 1x1, stride 1, no padding (k = input channel), K within
+// the LDS table.  Others go to the register-staged kernel.
+static bool pre_in_dma_kernel(const ConvArgs& a) {
+    bool ok = a.kh == 1 && a.kw == 1 && a.sh == 1 && a.sw == 1 && a.pt == 0 && a.pl == 0 && a.cin <= PRE_MAXK;
+#ifdef ENS_CONV_TUNING
+    if (const char* e = getenv("ENS_CONV_PRE_DMA")) ok = ok && atoi(e) != 0;
+#endif
+    return ok;
+}
+
 const char* conv_bf16_variant_name(const ConvArgs& a, int G) {
     const long long P = (long long)a.nb * a.Ho * a.Wo;
-    if (a.pre_scale) return conv_regstage_name(a, (int)P);
+    if (a.pre_scale && !pre_in_dma_kernel(a)) return conv_regstage_name(a, (int)P);
     if (conv_taps_applicable(a, a.nb)) return conv_taps_name(a);
     if (const int hv = conv_halo_pick(a, a.nb, G); hv >= 0) return conv_halo_name(hv);
     return VARIANTS[pick_variant(a, P, (long long)a.kh * a.kw * a.cin, G)].name;
@@ -422,6 +465,10 @@ const char* conv_bf16_variant_name(const ConvArgs& a, int G) {
 template <int BP, int BC, int WP, int WC, int NS, int BKT = 64>
 static hipError_t launch_variant(const ConvArgs& a, const ConvArgs* argv, int G, int nb, int P, int splits, hipStream_t s) {
     const dim3 grid(((P + BP - 1) / BP) * ((a.cout + BC - 1) / BC), splits, G);
+    if (a.pre_scale) {                                           // pre-activated 1x1: no K split (the launcher asks for none)
+        ENS_LAUNCH((conv_igemm_bf16<BP, BC, WP, WC, NS, BKT, true>), grid, dim3(256), 0, s, argv, nb);
+        return hipGetLastError();
+    }
     if (splits > 1) ENS_LAUNCH_FIRST((conv_igemm_bf16<BP, BC, WP, WC, NS, BKT>), grid, dim3(256), 0, s, argv, nb);
     else ENS_LAUNCH((conv_igemm_bf16<BP, BC, WP, WC, NS, BKT>), grid, dim3(256), 0, s, argv, nb);
     hipError_t e = hipGetLastError();
@@ -440,13 +487,13 @@ hipError_t launch_conv_bf16(const ConvArgs& a, const ConvArgs* argv, int G, int 
     const long long K64 = (long long)a.kh * a.kw * a.cin;
     if (P64 <= 0 || P64 >= (1LL << 31) || K64 >= (1LL << 31)) return hipErrorInvalidValue;
     const int P = (int)P64;
-    if (a.pre_scale) return launch_conv_regstage(a, argv, G, nb, P, s);
+    if (a.pre_scale && !pre_in_dma_kernel(a)) return launch_conv_regstage(a, argv, G, nb, P, s);
     if (conv_taps_applicable(a, nb)) return launch_conv_taps(a, argv, G, nb, s);
     if (const int hv = conv_halo_pick(a, nb, G); hv >= 0) return launch_conv_halo(a, argv, G, nb, hv, s);
     // byte offsets inside the kernel are unsigned 32-bit, 0xFFFFFFF0 stands for 'out of range'
     if ((long long)nb * a.H * a.W * a.x.stride >= 0x7FFFFF00LL || (long long)a.cout * K64 >= 0x70000000LL || a.kh > 16 || a.kw > 16) return hipErrorInvalidValue;
     int variant = pick_variant(a, P64, K64, G);
-    int splits = pick_splits(a, P64, K64, variant, G);
+    int splits = a.pre_scale ? 1 : pick_splits(a, P64, K64, variant, G);
 #ifdef ENS_CONV_TUNING   // tile / split override for kernel experiments only
     if (const char* e = getenv("ENS_CONV_VARIANT")) { if (a.cout > 32 || atoi(e) == 0) variant = atoi(e); splits = pick_splits(a, P64, K64, variant, G); }
     if (const char* e = getenv("ENS_CONV_SPLITS")) { splits = atoi(e); if (splits > 1 && (!a.ws || (long long)splits * P64 * a.cout > a.ws_floats)) splits = 1; }

@@ -358,6 +358,54 @@ __global__ void dwconv_bf16_kernel(const PoolArgs* __restrict__ argv, const int 
     *(uint4*)((uint16_t*)a.y.p + (long long)pu * a.y.stride + a.y.c0 + c) = pack8(acc);
 }
 
+// Average pooling over the in-bounds part of a K x K window, bf16, one lane per (pixel, 8
+// channels): loads from clamped positions, taps outside the image zeroed by a select and left out
+// of the divisor.
+template <int K>
+__global__ void avgpool_bf16_kernel(const PoolArgs* __restrict__ argv, const int nb_) {
+    const PoolArgs a = argv[blockIdx.z];
+    const unsigned cv = (unsigned)(a.c / 8);
+    const unsigned idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const unsigned total = (unsigned)nb_ * (unsigned)(a.Ho * a.Wo) * cv;
+    if (idx >= total) return;
+    const unsigned pu = idx / cv;
+    const int c = (int)(idx - pu * cv) * 8;
+    const unsigned row = pu / (unsigned)a.Wo;
+    const int wo = (int)(pu - row * (unsigned)a.Wo);
+    const unsigned nu = row / (unsigned)a.Ho;
+    const int ho = (int)(row - nu * (unsigned)a.Ho);
+    const uint16_t* __restrict__ x = (const uint16_t*)a.x.p + (long long)nu * a.H * a.W * a.x.stride + a.x.c0 + c;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) acc[e] = 0.f;
+    int cnt = 0;
+    uint4 xv[K * K];
+#pragma unroll
+    for (int kh = 0; kh < K; kh++) {
+        const int hic = min(max(ho * a.sh - a.pt + kh, 0), a.H - 1);
+#pragma unroll
+        for (int kw = 0; kw < K; kw++) {
+            const int wic = min(max(wo * a.sw - a.pl + kw, 0), a.W - 1);
+            xv[kh * K + kw] = *(const uint4*)(x + (long long)(hic * a.W + wic) * a.x.stride);
+        }
+    }
+#pragma unroll
+    for (int kh = 0; kh < K; kh++)
+#pragma unroll
+        for (int kw = 0; kw < K; kw++) {
+            const bool ok = (unsigned)(ho * a.sh - a.pt + kh) < (unsigned)a.H && (unsigned)(wo * a.sw - a.pl + kw) < (unsigned)a.W;
+            float f[8];
+            unpack8(xv[kh * K + kw], f);
+            cnt += ok ? 1 : 0;
+#pragma unroll
+            for (int e = 0; e < 8; e++) acc[e] += ok ? f[e] : 0.f;
+        }
+    const float inv = cnt ? 1.f / (float)cnt : 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; e++) acc[e] *= inv;
+    *(uint4*)((uint16_t*)a.y.p + (long long)pu * a.y.stride + a.y.c0 + c) = pack8(acc);
+}
+
 static hipError_t check_window(const PoolArgs& a, bool bf16) {
     if (a.c <= 0) return hipErrorInvalidValue;
     if (bf16 && (a.c % 8 || a.x.stride % 8 || a.x.c0 % 8 || a.y.stride % 8 || a.y.c0 % 8)) return hipErrorInvalidValue;
@@ -389,7 +437,9 @@ hipError_t launch_pool(const PoolArgs& a, const PoolArgs* argv, int G, int nb, b
         else if (bf16) ENS_LAUNCH((window_kernel<1, true>), g, b, 0, s, argv, nb);
         else ENS_LAUNCH((window_kernel<1, false>), g, b, 0, s, argv, nb);
     } else {
-        if (bf16) ENS_LAUNCH((window_kernel<2, true>), g, b, 0, s, argv, nb);
+        if (bf16 && a.kh == 3 && a.kw == 3) ENS_LAUNCH((avgpool_bf16_kernel<3>), g, b, 0, s, argv, nb);
+        else if (bf16 && a.kh == 2 && a.kw == 2) ENS_LAUNCH((avgpool_bf16_kernel<2>), g, b, 0, s, argv, nb);
+        else if (bf16) ENS_LAUNCH((window_kernel<2, true>), g, b, 0, s, argv, nb);
         else ENS_LAUNCH((window_kernel<2, false>), g, b, 0, s, argv, nb);
     }
     return hipGetLastError();
