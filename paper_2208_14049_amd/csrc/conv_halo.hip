@@ -242,6 +242,8 @@ static const HaloVariant HALO_VARIANTS[] = {
     {128, 64, 32, 1, true, "conv3x3_halo_bf16<128,64,c32>"},
     {256, 64, 32, 1, true, "conv3x3_halo_bf16<256,64,c32>"},
     {128, 128, 32, 1, true, "conv3x3_halo_bf16<128,128,c32>"},
+    {256, 32, 64, 2, true, "conv3x3_halo_bf16<256,32,c64>"},
+    {256, 32, 64, 2, false, "conv3x3_halo_bf16<256,32,c64>"},
 };
 constexpr int N_HALO_VARIANTS = sizeof(HALO_VARIANTS) / sizeof(HALO_VARIANTS[0]);
 constexpr int LDS_LIMIT = 160 * 1024;
@@ -304,6 +306,7 @@ int conv_halo_pick(const ConvArgs& a, int nb, int G) {
         const long long PP = (long long)nb * (a.H + 1) * (a.W + 1);
         const long long tiles = G * ((PP + 127) / 128) * ((a.cout + 63) / 64);
         choice = a.cin > 64 && tiles > 2 * HALO_CUS ? 6 : 0;
+        if (a.cout <= 32 && tiles > 2 * HALO_CUS) choice = a.cin > 64 ? 12 : 13;   // narrow outputs (dense-block growth layers)
     } else if (a.cin >= 96) {
         choice = 4;                                              // multiples of 32 only: 32-channel blocks
     }
@@ -367,7 +370,8 @@ hipError_t launch_conv_halo(const ConvArgs& a, const ConvArgs* argv, int G, int 
         case 8: return launch_halo_variant<128, 128, 2, 2, 64, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
         case 9: return launch_halo_variant<128, 64, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
         case 10: return launch_halo_variant<256, 64, 4, 1, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
-        default: return launch_halo_variant<128, 128, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 11: return launch_halo_variant<128, 128, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        default: return launch_halo_variant<256, 32, 4, 1, 64, 2>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
     }
 }
 

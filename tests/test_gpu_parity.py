@@ -140,6 +140,8 @@ CONV_LAYERS = [
     (32, 48, 3, 24, 3, 2, "same", {"act": "silu"}),
     (28, 28, 128, 128, 3, 1, "same", {}),
     (56, 56, 128, 512, 3, 1, "same", {}),                      # enough tiles for the one-halo-buffer variant
+    (150, 150, 64, 32, 3, 1, "same", {}),                      # narrow output, many tiles: the 256x32 tile
+    (100, 220, 128, 32, 3, 1, "same", {"act": None}),          # ... with two channel blocks through one halo buffer
     (28, 28, 64, 64, 3, 1, "same", {"res": True}),             # residual read from the layer's own input
     (14, 14, 256, 256, 1, 1, "same", {"res": True}),
     (14, 14, 256, 96, 3, 1, "same", {}),
