@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--slots", type=int, default=2, help="instance slots (rows of the matrix) the greedy search may use")
     ap.add_argument("--max-neighs", type=int, default=32)
     ap.add_argument("--max-iter", type=int, default=6)
+    ap.add_argument("--default-batch", type=int, default=0,
+                    help="batch size Algorithm 1 places every member at (0: the smallest of the domain)")
     ap.add_argument("--n-calib", type=int, default=512)
     ap.add_argument("--repeats", type=int, default=3)
     ap.add_argument("--grid", action="store_true", help="time every (instances, batch size) cell (single-member configs)")
@@ -71,10 +73,11 @@ def main():
     say(config=args.config, members=[m.name for m in nets], images=n)
 
     results = {}
+    db = dict(default_batch=args.default_batch) if args.default_batch > 0 else {}
     for label, opts in (("bbs", dict(strategy=2)),
-                        ("wfd", dict(strategy=1)),
+                        ("wfd", dict(strategy=1, **db)),
                         ("greedy", dict(strategy=0, slots=args.slots, max_neighs=args.max_neighs,
-                                        max_iter=args.max_iter, seed=synth.BASE_SEED))):
+                                        max_iter=args.max_iter, seed=synth.BASE_SEED, **db))):
         t0 = time.perf_counter()
         a = E.ens_plan(0, **opts, **common)
         plan_s = time.perf_counter() - t0
