@@ -5,8 +5,8 @@ the members' operation lists; imported by tests, the smoke check and the
 benchmark's CPU-baseline leg only.  Shares no code with the GPU library.
 """
 from .forward import forward_logits                      # noqa: F401
-from .combine import (softmax, combine_mean, segments, batches, broadcast,   # noqa: F401
-                      accumulate_messages, top1, resize_bilinear)
+from .combine import (softmax, combine_mean, combine_weighted, combine_vote, segments, batches,   # noqa: F401
+                      broadcast, accumulate_messages, top1, resize_bilinear)
 from . import planner                                      # noqa: F401
 
 

@@ -25,6 +25,30 @@ def combine_mean(member_probs, dtype=np.float64):
     return y
 
 
+def combine_weighted(member_probs, weights, dtype=np.float64):
+    """Weighted averaging, the first of the other combination rules the paper names (section "The
+    prediction accumulator"): Y[i] = sum over members of w_m * P_m[i], in member order.  The weights
+    are used as given; with w_m = 1/M this is combine_mean."""
+    assert len(weights) == len(member_probs)
+    y = np.zeros_like(np.asarray(member_probs[0], dtype=dtype))
+    for p, w in zip(member_probs, weights):
+        y = y + np.asarray(p, dtype=dtype) * dtype(w)
+    return y
+
+
+def combine_vote(member_logits, dtype=np.float64):
+    """Majority voting, the second rule the paper names: every member votes for its arg-max class
+    (lowest index on exact ties) and Y[i, c] = (number of members voting c for sample i) / M, so that
+    a row still sums to one.  The winner of the vote is the arg-max of the row."""
+    m = len(member_logits)
+    z0 = np.asarray(member_logits[0])
+    y = np.zeros(z0.shape, dtype=dtype)
+    rows = np.arange(z0.shape[0])
+    for z in member_logits:
+        y[rows, np.argmax(np.asarray(z), axis=-1)] += 1.0
+    return y / m
+
+
 def segments(nb_images, seg):
     """[(start, end)] of every segment of a request of nb_images samples."""
     out = []

@@ -122,3 +122,44 @@ def test_throughput_arithmetic_from_paper():
     assert g["overhead_seconds"] / g["seconds"] <= g["overhead_bound"]
     w = GOLD["weak_scaling"]
     assert round(100 * w["sixteen_gpus"] / (16 * w["one_gpu"])) == w["efficiency_percent"]
+
+
+# --------------------------------------------------------------------------- other combination rules
+def test_weighted_average_pins():
+    """Weighted averaging (named in section "The prediction accumulator"): equal weights give the mean,
+    a one-hot weight vector returns that member, rows sum to the sum of the weights, and the value
+    equals a tensor contraction written independently."""
+    rng = np.random.default_rng(5)
+    probs = [oracle.softmax(rng.normal(size=(7, 11))) for _ in range(4)]
+    w = np.array([0.1, 0.2, 0.3, 0.4])
+    y = oracle.combine_weighted(probs, w)
+    assert np.allclose(y, np.einsum("m,mic->ic", w, np.stack(probs)), atol=1e-15)
+    assert np.allclose(y.sum(axis=1), 1.0, atol=1e-14)
+    assert np.allclose(oracle.combine_weighted(probs, [0.25] * 4), oracle.combine_mean(probs), atol=1e-15)
+    assert np.array_equal(oracle.combine_weighted(probs, [0, 0, 1, 0]), probs[2])
+    assert np.allclose(oracle.combine_weighted(probs, 2 * w).sum(axis=1), 2.0)   # weights are used as given
+
+
+def test_majority_vote_pins():
+    """Majority voting: vote counts sum to M, a single member gives the one-hot of its arg-max, a
+    hand-counted example, lowest index on exact ties, and agreement with a per-sample loop."""
+    z = [np.array([[1.0, 3.0, 2.0], [5.0, 0.0, 5.0]]),
+         np.array([[9.0, 1.0, 0.0], [0.0, 1.0, 2.0]]),
+         np.array([[0.0, 2.0, 1.0], [0.0, 0.0, 1.0]])]
+    y = oracle.combine_vote(z)
+    # sample 0: votes 1, 0, 1 -> class 1 twice, class 0 once; sample 1: votes 0 (tie -> lowest), 2, 2
+    assert np.allclose(y, np.array([[1, 2, 0], [1, 0, 2]]) / 3.0)
+    assert np.allclose(y.sum(axis=1) * 3, 3.0)
+    one = oracle.combine_vote([z[0]])
+    assert np.array_equal(one, np.array([[0.0, 1.0, 0.0], [1.0, 0.0, 0.0]]))
+    rng = np.random.default_rng(6)
+    zs = [rng.normal(size=(20, 9)) for _ in range(5)]
+    y = oracle.combine_vote(zs)
+    for i in range(20):
+        counts = np.zeros(9)
+        for m in range(5):
+            best = max(range(9), key=lambda c: (zs[m][i, c], -c))
+            counts[best] += 1
+        assert np.array_equal(y[i] * 5, counts)
+    # softmax is monotone: voting on probabilities or on logits is the same
+    assert np.array_equal(oracle.combine_vote([oracle.softmax(v) for v in zs]), y)
