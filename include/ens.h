@@ -168,6 +168,22 @@ int ens_bench(ens_handle* h, const ens_alloc* a, int32_t segment_size, int64_t n
  */
 int ens_predict(ens_handle* h, const float* images, int64_t n, float* probs_out);
 
+/* Combination rule of ens_predict (section "The prediction accumulator").  The default is the
+ * paper's: the mean of the members' softmax outputs.  The same section names two more:
+ *   ENS_COMBINE_WEIGHTED  Y[i] = sum_m weights[m] * softmax(logits_m[i]); weights: n_members host
+ *                         floats, copied by the call and used as given (not normalised)
+ *   ENS_COMBINE_VOTE      majority voting: Y[i, c] = (members whose arg-max for sample i is c) / M,
+ *                         lowest class on exact ties; weights is ignored
+ * ENS_E_INVALID for an unknown rule or missing weights. */
+enum { ENS_COMBINE_MEAN = 0, ENS_COMBINE_WEIGHTED = 1, ENS_COMBINE_VOTE = 2 };
+int ens_set_combination(ens_handle* h, int32_t rule, const float* weights);
+
+/* Overhead experiment of section "Overhead of the inference system": with the fake predictor on,
+ * every member's forward pass (input staging included) is replaced by a prediction of zeros; the
+ * partition into segments and batches, the workers' streams, the event join and the combination
+ * rule still run.  The wall time of such an ens_predict is the system's own overhead. */
+int ens_debug_fake_predictor(ens_handle* h, int32_t on);
+
 /* Last per-member logits of the most recent ens_predict (n x classes fp32, host destination);
  * for tests of single members. */
 int ens_member_logits(ens_handle* h, int32_t member, int64_t n, float* logits_out);
@@ -190,9 +206,9 @@ int ens_member_bytes(const ens_handle* h, int32_t member, int32_t batch, int64_t
 /* Same figures from a description alone; host-only, needs no GPU. */
 int ens_spec_bytes(const ens_member_spec* spec, int32_t batch, int64_t* weight_bytes,
                    int64_t* arena_bytes);
-/* Per-kernel timing.  With profiling on, every kernel launch of ens_predict / ens_bench is
- * bracketed by HIP events on the stream it is launched on, and the durations are summed per
- * kernel class after the call.  ens_profile_get enumerates the classes of the last call
+/* Per-kernel timing.  With profiling on, every kernel launch of ens_predict / ens_bench carries
+ * a pair of HIP events attached to its dispatch (stamped with the kernel's own begin and end), and
+ * the durations are summed per kernel class after the call.  ens_profile_get enumerates the classes of the last call
  * (idx = 0, 1, ...; ENS_E_INVALID past the end): name, summed milliseconds, launches, the
  * algorithmic flop and the algorithmic bytes (each input, weight and output read or written
  * once) of those launches.  ens_last_ms is the wall time of the last ens_predict. */

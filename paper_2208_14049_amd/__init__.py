@@ -78,7 +78,7 @@ BENCH_SINGLE_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.c_int32, ctypes.c_int
 
 EXPORTS = ("ens_load", "ens_free", "ens_set_io", "ens_plan", "ens_set_alloc", "ens_bench", "ens_predict",
            "ens_member_logits", "ens_debug_tensor", "ens_debug_keep_tensors", "ens_classes", "ens_n_members", "ens_member_bytes",
-           "ens_spec_bytes", "ens_set_profiling", "ens_profile_get", "ens_last_ms",
+           "ens_spec_bytes", "ens_set_profiling", "ens_profile_get", "ens_last_ms", "ens_set_combination", "ens_debug_fake_predictor",
            "ens_planner_fit_mem", "ens_planner_wfd", "ens_planner_neighbors", "ens_planner_greedy",
            "ens_planner_bbs", "ens_partition", "ens_strerror", "ens_version")
 
@@ -114,6 +114,8 @@ def lib():
         L.ens_member_bytes.argtypes = [vp, i32, i32, P(i64), P(i64)]
         L.ens_spec_bytes.argtypes = [P(EnsMemberSpec), i32, P(i64), P(i64)]
         L.ens_set_profiling.argtypes = [vp, i32]
+        L.ens_set_combination.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_float)]
+        L.ens_debug_fake_predictor.argtypes = [vp, i32]
         L.ens_profile_get.argtypes = [vp, i32, ctypes.c_char_p, i32, P(dbl), P(i64), P(dbl), P(dbl)]
         L.ens_last_ms.argtypes = [vp]
         L.ens_last_ms.restype = dbl
@@ -295,6 +297,17 @@ class Ensemble:
         w, a = ctypes.c_int64(), ctypes.c_int64()
         _check(lib().ens_member_bytes(self._h, member, batch, ctypes.byref(w), ctypes.byref(a)), "ens_member_bytes")
         return w.value, a.value
+
+    def ens_set_combination(self, rule, weights=None):
+        """rule: "mean", "weighted" (weights: one float per member) or "vote"."""
+        code = {"mean": 0, "weighted": 1, "vote": 2}[rule]
+        w = None
+        if weights is not None:
+            w = (ctypes.c_float * len(weights))(*[float(v) for v in weights])
+        _check(lib().ens_set_combination(self._h, code, w), "ens_set_combination")
+
+    def ens_debug_fake_predictor(self, on):
+        _check(lib().ens_debug_fake_predictor(self._h, int(on)), "ens_debug_fake_predictor")
 
     def ens_set_profiling(self, on):
         _check(lib().ens_set_profiling(self._h, int(on)), "ens_set_profiling")

@@ -357,6 +357,14 @@ static int forward_batch(ens_handle* h, Gang& g, int64_t first, int nb) {
         h->prof_recs.push_back(r);
         return e;
     };
+    if (h->fake_predictor) {                                     // zeros for the rows of this batch, nothing else
+        for (int wi : g.workers) {
+            const Worker& w = h->workers[wi];
+            HIP_TRY(launch_fill_zero(h->d_logits[w.member] + first * h->classes, (int64_t)nb * h->classes, g.stream));
+            h->workers[wi].last_nb = nb;
+        }
+        return ENS_OK;
+    }
     const double stage_bytes = (double)leader.batch * (h->base_h * h->base_w * 12.0 + (double)m.tensors[0].h * m.tensors[0].w * g.stage.dc * (m.bf16 ? 2 : 4));
     HIP_TRY(timed(h->stage_klass, 0.0, stage_bytes, [&] { return launch_stage(g.stage, g.d_stage, 1, nb, first, m.bf16, g.stream); }));
     for (const Launch& L : g.launches)
@@ -445,7 +453,7 @@ static int run_device(ens_handle* h, const float* d_images, int64_t n, float* d_
             if (!r.start || !r.stop) return ENS_E_HIP;
             next_launch_events() = LaunchEvents{r.start, r.stop};
         }
-        HIP_TRY(launch_combine(h->d_logit_ptrs, M, n, h->classes, d_probs, h->main_stream));
+        HIP_TRY(launch_combine(h->d_logit_ptrs, h->d_weights, h->combine_rule, M, n, h->classes, d_probs, h->main_stream));
         if (h->profiling) {
             next_launch_events() = LaunchEvents{};
             h->prof_recs.push_back(r);
@@ -579,6 +587,7 @@ void ens_free(ens_handle* h) {
     for (float* p : h->d_logits)
         if (p) (void)hipFree(p);
     if (h->d_logit_ptrs) (void)hipFree((void*)h->d_logit_ptrs);
+    if (h->d_weights) (void)hipFree(h->d_weights);
     if (h->d_images) (void)hipFree(h->d_images);
     if (h->d_probs) (void)hipFree(h->d_probs);
     if (h->d_calib) (void)hipFree(h->d_calib);
@@ -843,6 +852,24 @@ int ens_spec_bytes(const ens_member_spec* spec, int32_t batch, int64_t* weight_b
     if (rc != ENS_OK) return rc;
     if (weight_bytes) *weight_bytes = (int64_t)m.weight_bytes();
     if (arena_bytes) *arena_bytes = (int64_t)plan_arena(m, batch).bytes;
+    return ENS_OK;
+}
+
+int ens_debug_fake_predictor(ens_handle* h, int32_t on) {
+    if (!h) return ENS_E_INVALID;
+    h->fake_predictor = on != 0;
+    return ENS_OK;
+}
+
+int ens_set_combination(ens_handle* h, int32_t rule, const float* weights) {
+    if (!h) return ENS_E_INVALID;
+    if (rule != ENS_COMBINE_MEAN && rule != ENS_COMBINE_WEIGHTED && rule != ENS_COMBINE_VOTE) return ENS_E_INVALID;
+    if (rule == ENS_COMBINE_WEIGHTED) {
+        if (!weights) return ENS_E_INVALID;
+        if (!h->d_weights) HIP_TRY(hipMalloc((void**)&h->d_weights, ENS_MAX_MEMBERS * sizeof(float)));
+        HIP_TRY(hipMemcpy(h->d_weights, weights, h->members.size() * sizeof(float), hipMemcpyHostToDevice));
+    }
+    h->combine_rule = rule;
     return ENS_OK;
 }
 

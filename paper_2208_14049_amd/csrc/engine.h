@@ -131,6 +131,8 @@ struct ens_handle {
     float* d_probs = nullptr;   size_t d_probs_cap = 0;
     std::vector<float*> d_logits; size_t d_logits_rows = 0;
     const float** d_logit_ptrs = nullptr;
+    int combine_rule = 0;                        // ENS_COMBINE_*
+    float* d_weights = nullptr;                  // member weights of the weighted rule (device)
     float* d_calib = nullptr;   size_t d_calib_images = 0;
     const float* bound_images = nullptr;         // request images the staging arguments point at
     int stage_klass = 0;
@@ -139,6 +141,7 @@ struct ens_handle {
     // profiling
     bool profiling = false;
     bool keep_tensors = false;                   // debug: no reuse of arena regions
+    bool fake_predictor = false;                 // overhead experiment: forward passes replaced by zeros
     std::vector<ens::ProfClass> prof;
     std::vector<ens::ProfRec> prof_recs;
     std::vector<hipEvent_t> event_pool;

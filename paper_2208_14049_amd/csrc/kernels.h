@@ -102,10 +102,15 @@ hipError_t launch_gap(const GapArgs& a, const GapArgs* argv, int G, int nb, bool
 hipError_t launch_fc(const FcArgs& a, const FcArgs* argv, int G, int nb, long long first, bool bf16, hipStream_t s);
 hipError_t launch_se(const SeArgs& a, const SeArgs* argv, int G, int nb, bool bf16, hipStream_t s);
 hipError_t launch_stage(const StageArgs& a, const StageArgs* argv, int G, int nb, long long first, bool bf16, hipStream_t s);
-// Y[i, :] = sum_m softmax(logits_m[i, :]) / M ; logits: n_members pointers (device array).
-hipError_t launch_combine(const float* const* logits, int n_members, int64_t n, int classes,
-                          float* y, hipStream_t s);
+// Combination rule; logits: n_members pointers (device array).
+//   COMBINE_MEAN      Y[i, :] = sum_m softmax(logits_m[i, :]) / M
+//   COMBINE_WEIGHTED  Y[i, :] = sum_m weights[m] * softmax(logits_m[i, :])   (weights: device, n_members floats)
+//   COMBINE_VOTE      Y[i, c] = #{m : argmax logits_m[i, :] == c} / M        (lowest index on exact ties)
+enum { COMBINE_MEAN = 0, COMBINE_WEIGHTED = 1, COMBINE_VOTE = 2 };
+hipError_t launch_combine(const float* const* logits, const float* weights, int rule, int n_members, int64_t n,
+                          int classes, float* y, hipStream_t s);
 hipError_t launch_fill_noise(float* p, int64_t count, uint64_t seed, hipStream_t s);
+hipError_t launch_fill_zero(float* p, int64_t count, hipStream_t s);
 
 double conv_flops(const ConvArgs& a, int nb);
 

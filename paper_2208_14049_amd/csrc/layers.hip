@@ -732,9 +732,9 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-template <int PER>
-__global__ __launch_bounds__(256) void combine_kernel(const float* const* logits, int n_members, long long n,
-                                                      int classes, float* y) {
+template <int PER, int RULE>
+__global__ __launch_bounds__(256) void combine_kernel(const float* const* logits, const float* __restrict__ weights,
+                                                      int n_members, long long n, int classes, float* y) {
     const int lane = threadIdx.x & 63;
     const long long row = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (row >= n) return;
@@ -746,11 +746,25 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* const* logits
         const float* z = logits[m] + row * classes;
         float v[PER];
         float mx = -3.0e38f;
+        int arg = 0x7FFFFFFF;                        // class of this lane's maximum, lowest index first
 #pragma unroll
         for (int e = 0; e < PER; e++) {
             const int c = lane + 64 * e;
             v[e] = c < classes ? z[c] : -3.0e38f;
+            if (RULE == COMBINE_VOTE && c < classes && (v[e] > mx || arg == 0x7FFFFFFF)) arg = c;
             mx = fmaxf(mx, v[e]);
+        }
+        if (RULE == COMBINE_VOTE) {
+            // arg-max over the wave: the larger value wins, the lower class on equal values
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                const float om = __shfl_xor(mx, off, 64);
+                const int oa = __shfl_xor(arg, off, 64);
+                if (om > mx || (om == mx && oa < arg)) { mx = om; arg = oa; }
+            }
+#pragma unroll
+            for (int e = 0; e < PER; e++) acc[e] += lane + 64 * e == arg ? inv_m : 0.f;
+            continue;
         }
         mx = wave_max(mx);
         float sum = 0.f;
@@ -761,8 +775,9 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* const* logits
             sum += v[e];
         }
         sum = wave_sum(sum);
+        const float wm = RULE == COMBINE_WEIGHTED ? weights[m] : inv_m;
 #pragma unroll
-        for (int e = 0; e < PER; e++) acc[e] += (v[e] / sum) * inv_m;
+        for (int e = 0; e < PER; e++) acc[e] += (v[e] / sum) * wm;
     }
 #pragma unroll
     for (int e = 0; e < PER; e++) {
@@ -771,16 +786,25 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* const* logits
     }
 }
 
-hipError_t launch_combine(const float* const* logits, int n_members, int64_t n, int classes, float* y,
-                          hipStream_t s) {
-    if (n <= 0) return hipSuccess;
-    if (n_members <= 0 || classes <= 0 || classes > 64 * COMBINE_MAX_PER_LANE) return hipErrorInvalidValue;
+template <int RULE>
+static void launch_combine_rule(const float* const* logits, const float* weights, int n_members, int64_t n, int classes,
+                                float* y, hipStream_t s) {
     const dim3 g((unsigned)((n + 3) / 4)), b(256);
     const int per = (classes + 63) / 64;
-    if (per <= 1) ENS_LAUNCH(combine_kernel<1>, g, b, 0, s, logits, n_members, (long long)n, classes, y);
-    else if (per <= 4) ENS_LAUNCH(combine_kernel<4>, g, b, 0, s, logits, n_members, (long long)n, classes, y);
-    else if (per <= 16) ENS_LAUNCH(combine_kernel<16>, g, b, 0, s, logits, n_members, (long long)n, classes, y);
-    else ENS_LAUNCH(combine_kernel<32>, g, b, 0, s, logits, n_members, (long long)n, classes, y);
+    if (per <= 1) ENS_LAUNCH((combine_kernel<1, RULE>), g, b, 0, s, logits, weights, n_members, (long long)n, classes, y);
+    else if (per <= 4) ENS_LAUNCH((combine_kernel<4, RULE>), g, b, 0, s, logits, weights, n_members, (long long)n, classes, y);
+    else if (per <= 16) ENS_LAUNCH((combine_kernel<16, RULE>), g, b, 0, s, logits, weights, n_members, (long long)n, classes, y);
+    else ENS_LAUNCH((combine_kernel<32, RULE>), g, b, 0, s, logits, weights, n_members, (long long)n, classes, y);
+}
+
+hipError_t launch_combine(const float* const* logits, const float* weights, int rule, int n_members, int64_t n,
+                          int classes, float* y, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    if (n_members <= 0 || classes <= 0 || classes > 64 * COMBINE_MAX_PER_LANE) return hipErrorInvalidValue;
+    if (rule == COMBINE_MEAN) launch_combine_rule<COMBINE_MEAN>(logits, weights, n_members, n, classes, y, s);
+    else if (rule == COMBINE_WEIGHTED && weights) launch_combine_rule<COMBINE_WEIGHTED>(logits, weights, n_members, n, classes, y, s);
+    else if (rule == COMBINE_VOTE) launch_combine_rule<COMBINE_VOTE>(logits, weights, n_members, n, classes, y, s);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
@@ -795,6 +819,17 @@ __global__ void fill_noise_kernel(float* p, long long count, unsigned long long 
     z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
     z ^= z >> 31;
     p[i] = ((float)(z >> 40) * (1.0f / 16777216.0f) - 0.5f) * 3.4641016f;
+}
+
+__global__ void fill_zero_kernel(float* __restrict__ p, long long count) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0.f;
+}
+
+hipError_t launch_fill_zero(float* p, int64_t count, hipStream_t s) {
+    if (count <= 0) return hipSuccess;
+    ENS_LAUNCH(fill_zero_kernel, dim3(blocks_for(count, 256)), dim3(256), 0, s, p, (long long)count);
+    return hipGetLastError();
 }
 
 hipError_t launch_fill_noise(float* p, int64_t count, uint64_t seed, hipStream_t s) {

@@ -90,6 +90,12 @@ def main():
     host_out = torch.empty((n, E.classes), dtype=torch.float32).pin_memory()
     ips_host = timed_predict(E, host_images, host_out, args.repeats)
     say(strategy="greedy", input="host (pinned), output to host", images_per_s=round(ips_host, 1))
+    # the paper's overhead experiment: every forward pass replaced by a prediction of zeros
+    E.ens_debug_fake_predictor(1)
+    ips_fake = timed_predict(E, images, out, args.repeats)
+    E.ens_debug_fake_predictor(0)
+    say(strategy="greedy", fake_predictor_seconds=round(n / ips_fake, 5), true_seconds=round(n / results["greedy"], 5),
+        overhead_share=round(results["greedy"] / ips_fake, 4))
     say(allocation_speedup_vs_bbs=round(results["greedy"] / results["bbs"], 3),
         wfd_vs_bbs=round(results["wfd"] / results["bbs"], 3))
 

@@ -141,3 +141,101 @@ def test_planner_on_the_gpu(ens):
     bbs = E.ens_plan(0, strategy=2, n_calib=256, repeats=2)
     assert bbs.n_bench == 10 and len(bbs.matrix()) == 1 and bbs.score > 0
     E.close()
+
+
+# --------------------------------------------------------------------------- other combination rules
+def _member_logits_oracle(nets, blobs, imgs):
+    return [oracle.forward_logits(net, blob, oracle.resize_bilinear(imgs, net.in_h, net.in_w), real="f32")
+            for net, blob in zip(nets, blobs)]
+
+
+def test_weighted_average_and_vote_fp32(ens):
+    """Weighted averaging and majority voting (section "The prediction accumulator") on config 1,
+    fp32: weighted within 1e-4; votes exact wherever no member's top two logits are closer than the
+    logit error of the fp32 path (both sides take the arg-max in fp32)."""
+    nets = N.config_members(1)
+    blobs = [W.make_blob(net, synth.BASE_SEED, i) for i, net in enumerate(nets)]
+    imgs = W.make_images(synth.BASE_SEED + 1000, 200, 32, 32)
+    imgs[100:] = W.make_images(synth.BASE_SEED + 1000, 100, 32, 32, first=100, varied=True)
+    z = _member_logits_oracle(nets, blobs, imgs)
+    probs = [oracle.softmax(v.astype(np.float32), dtype=np.float32) for v in z]
+    E = ens.Ensemble(nets, blobs)
+    E.ens_set_alloc([[8, 8]])
+    w = [0.3, 0.7]
+    E.ens_set_combination("weighted", w)
+    y = E.ens_predict(imgs)
+    assert np.abs(y - oracle.combine_weighted(probs, w)).max() <= 1e-4
+    assert np.abs(y.sum(1) - 1.0).max() <= 1e-5
+    E.ens_set_combination("vote")
+    y = E.ens_predict(imgs)
+    ref = oracle.combine_vote(z)
+    assert np.allclose(y.sum(1), 1.0, atol=1e-6)                 # M votes per sample
+    assert set(np.unique(np.round(y * len(nets)).astype(int))) <= {0, 1, 2}
+    clear = np.ones(len(imgs), bool)                             # samples where every member's arg-max is clear-cut
+    for v in z:
+        top2 = np.sort(v, axis=1)[:, -2:]
+        clear &= (top2[:, 1] - top2[:, 0]) > 1e-4
+    assert clear.mean() > 0.9
+    assert np.array_equal(y[clear], ref[clear].astype(np.float32))
+    # an ensemble of one under voting is the one-hot of its arg-max
+    E.ens_set_combination("mean")
+    y_mean = E.ens_predict(imgs)
+    assert np.abs(y_mean - oracle.combine_mean(probs)).max() <= 1e-4
+    with pytest.raises(Exception):
+        E.ens_set_combination("weighted", None)
+    E.close()
+
+
+def test_vote_bf16_resnets(ens):
+    """Majority voting over three bf16 ResNet-18-shaped members (1000 classes, batch 32): exact vote
+    shares on the samples whose members' arg-max classes are clear of the bf16 logit error."""
+    nets = N.config_members(2)
+    blobs = [W.quantise_weights_bf16(net, W.make_blob(net, synth.BASE_SEED, i)) for i, net in enumerate(nets)]
+    imgs = W.round_bf16(W.make_images(synth.BASE_SEED + 1000, 64, 224, 224, varied=True))
+    z = _member_logits_oracle(nets, blobs, imgs)
+    E = ens.Ensemble(nets, blobs)
+    E.ens_set_alloc([[32, 32, 32]])
+    E.ens_set_combination("vote")
+    y = E.ens_predict(imgs)
+    zg = [E.ens_member_logits(m, len(imgs)) for m in range(3)]
+    E.close()
+    assert np.allclose(y.sum(1), 1.0, atol=1e-6)
+    # the kernel's votes are exactly the arg-max of the logits the GPU itself produced ...
+    assert np.array_equal(y, oracle.combine_vote(zg).astype(np.float32))
+    # ... and agree with the oracle's wherever the oracle's top two logits differ by more than the bf16 path's error
+    clear = np.ones(len(imgs), bool)
+    for v, g in zip(z, zg):
+        top2 = np.sort(v, axis=1)[:, -2:]
+        clear &= (top2[:, 1] - top2[:, 0]) > 2.5 * np.abs(g - v).max()
+    assert clear.sum() >= 8
+    assert np.array_equal(y[clear], oracle.combine_vote(z)[clear].astype(np.float32))
+
+
+def test_fake_predictor_overhead_run(ens):
+    """The overhead experiment of section "Overhead of the inference system": with every forward
+    pass replaced by zeros the accumulator still gathers all rows (softmax of zeros: uniform), and
+    that run is a small fraction of the true one."""
+    import time
+    nets = N.config_members(2)
+    blobs = [W.quantise_weights_bf16(net, W.make_blob(net, synth.BASE_SEED, i)) for i, net in enumerate(nets)]
+    import torch
+    imgs = torch.from_numpy(W.round_bf16(W.make_images(synth.BASE_SEED + 1000, 300, 224, 224))).cuda()
+    E = ens.Ensemble(nets, blobs)
+    E.ens_set_alloc([[32, 32, 32], [32, 32, 32]])
+
+    def run():
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        y = E.ens_predict(imgs)
+        torch.cuda.synchronize()
+        return y.cpu().numpy(), time.perf_counter() - t0
+    y_true, _ = run()
+    _, t_true = run()
+    E.ens_debug_fake_predictor(1)
+    y, _ = run()
+    _, t_fake = run()
+    assert np.allclose(y, 1.0 / 1000, atol=1e-7)                 # every row was gathered
+    E.ens_debug_fake_predictor(0)
+    assert np.array_equal(run()[0], y_true)                      # and the true path is back, bit for bit
+    E.close()
+    assert t_fake < 0.25 * t_true, (t_fake, t_true)
