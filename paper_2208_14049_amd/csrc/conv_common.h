@@ -209,6 +209,11 @@ const char* conv_regstage_name(const ConvArgs& a, int P);
 // partial sums in the workspace and applies bias, residual and activation; defined in conv_mfma.hip.
 hipError_t launch_conv_splitk_epilogue(const ConvArgs& a, const ConvArgs* argv, int G, int nb, int P, int splits, hipStream_t s);
 
+// 3x3 stride-1 kernel with the filter in registers and persistent workgroups; defined in conv_wreg.hip.
+bool conv_wreg_applicable(const ConvArgs& a, int nb, int G);
+const char* conv_wreg_name(const ConvArgs& a);
+hipError_t launch_conv_wreg(const ConvArgs& a, const ConvArgs* argv, int G, int nb, hipStream_t s);
+
 // 3x3 stride-1 kernel with the input window resident in LDS; defined in conv_halo.hip.
 // conv_halo_pick returns the variant that runs the layer, or -1 when the generic kernel does.
 int conv_halo_pick(const ConvArgs& a, int nb, int G);

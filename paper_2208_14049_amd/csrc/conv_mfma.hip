@@ -415,6 +415,7 @@ static const Variant VARIANTS[] = {
 #ifdef ENS_CONV_TUNING
     {128, 128, 64, "t5"}, {256, 128, 64, "t6"}, {128, 128, 32, "t7"}, {256, 64, 64, "t8"}, {128, 128, 32, "t9"},
     {128, 64, 32, "t10"}, {128, 64, 32, "t11"}, {128, 128, 32, "t12"}, {64, 64, 32, "t13"},
+    {64, 64, 64, "t14"}, {64, 64, 64, "t15"}, {128, 64, 32, "t16"}, {64, 64, 32, "t17"},
 #endif
 };
 constexpr int CUS = 256;
@@ -458,6 +459,7 @@ const char* conv_bf16_variant_name(const ConvArgs& a, int G) {
     const long long P = (long long)a.nb * a.Ho * a.Wo;
     if (a.pre_scale && !pre_in_dma_kernel(a)) return conv_regstage_name(a, (int)P);
     if (conv_taps_applicable(a, a.nb)) return conv_taps_name(a);
+    if (conv_wreg_applicable(a, a.nb, G)) return conv_wreg_name(a);
     if (const int hv = conv_halo_pick(a, a.nb, G); hv >= 0) return conv_halo_name(hv);
     return VARIANTS[pick_variant(a, P, (long long)a.kh * a.kw * a.cin, G)].name;
 }
@@ -489,6 +491,7 @@ hipError_t launch_conv_bf16(const ConvArgs& a, const ConvArgs* argv, int G, int 
     const int P = (int)P64;
     if (a.pre_scale && !pre_in_dma_kernel(a)) return launch_conv_regstage(a, argv, G, nb, P, s);
     if (conv_taps_applicable(a, nb)) return launch_conv_taps(a, argv, G, nb, s);
+    if (conv_wreg_applicable(a, nb, G)) return launch_conv_wreg(a, argv, G, nb, s);
     if (const int hv = conv_halo_pick(a, nb, G); hv >= 0) return launch_conv_halo(a, argv, G, nb, hv, s);
     // byte offsets inside the kernel are unsigned 32-bit, 0xFFFFFFF0 stands for 'out of range'
     if ((long long)nb * a.H * a.W * a.x.stride >= 0x7FFFFF00LL || (long long)a.cout * K64 >= 0x70000000LL || a.kh > 16 || a.kw > 16) return hipErrorInvalidValue;
@@ -513,6 +516,10 @@ hipError_t launch_conv_bf16(const ConvArgs& a, const ConvArgs* argv, int G, int 
         case 11: return launch_variant<128, 64, 2, 2, 3, 32>(a, argv, G, nb, P, splits, s);
         case 12: return launch_variant<128, 128, 2, 2, 4, 32>(a, argv, G, nb, P, splits, s);
         case 13: return launch_variant<64, 64, 2, 2, 3, 32>(a, argv, G, nb, P, splits, s);
+        case 14: return launch_variant<64, 64, 2, 2, 4, 64>(a, argv, G, nb, P, splits, s);
+        case 15: return launch_variant<64, 64, 2, 2, 3, 64>(a, argv, G, nb, P, splits, s);
+        case 16: return launch_variant<128, 64, 2, 2, 4, 32>(a, argv, G, nb, P, splits, s);
+        case 17: return launch_variant<64, 64, 2, 2, 4, 32>(a, argv, G, nb, P, splits, s);
 #endif
         default: return launch_variant<64, 64, 2, 2, 2, 64>(a, argv, G, nb, P, splits, s);
     }

@@ -143,6 +143,9 @@ CONV_LAYERS = [
     (150, 150, 64, 32, 3, 1, "same", {}),                      # narrow output, many tiles: the 256x32 tile
     (100, 220, 128, 32, 3, 1, "same", {"act": None}),          # ... with two channel blocks through one halo buffer
     (28, 28, 64, 64, 3, 1, "same", {"res": True}),             # residual read from the layer's own input
+    (24, 40, 64, 96, 3, 1, "same", {"act": None}),             # filter-in-registers kernel: half-empty last channel tile
+    (12, 12, 64, 128, 3, 1, "same", {"act": "silu"}),          # ... fewer tiles than workgroups
+    (62, 62, 64, 32, 3, 1, "same", {}),                        # ... widest rows it takes, one channel group
     (14, 14, 256, 256, 1, 1, "same", {"res": True}),
     (14, 14, 256, 96, 3, 1, "same", {}),
     (20, 37, 64, 72, 3, 1, "same", {"act": None}),
