@@ -59,6 +59,27 @@ __device__ __forceinline__ void tile_of_block(int n_ptiles, int n_ctiles, int* p
     *ptile = v / n_ctiles;
 }
 
+// Share of the n_tiles position tiles that a persistent workgroup walks: tiles first, first + step, ...
+// below end.  Consecutive workgroup ids go to different XCDs; the tiles are cut into 8 runs, one per
+// XCD, and the workgroups of an XCD stride through its run, so that neighbouring tiles, whose input
+// windows overlap, are fetched into one L2.  lin0: linear id of the workgroup with blockIdx.x == 0
+// in this (y, z) plane of the grid.
+struct TileWalk { int first, step, end; };
+__device__ __forceinline__ TileWalk tile_walk(int n_tiles, int lin0) {
+    TileWalk w;
+    const int nx = gridDim.x, x = blockIdx.x;
+    if (nx < 8) {
+        w.first = x; w.step = nx; w.end = n_tiles;
+        return w;
+    }
+    const int xcd = (lin0 + x) & 7;
+    const int xfirst = (xcd - lin0) & 7;             // the first workgroup of this plane on that XCD
+    w.step = (nx - 1 - xfirst) / 8 + 1;
+    w.first = (int)((long long)n_tiles * xcd / 8) + (x - xfirst) / 8;
+    w.end = (int)((long long)n_tiles * (xcd + 1) / 8);
+    return w;
+}
+
 // ---- pieces shared by the kernels that hold their input window in LDS ----------------------
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));

@@ -37,8 +37,8 @@ __device__ __forceinline__ void for_each_tap(F&& f, std::integer_sequence<int, T
     (f(std::integral_constant<int, T>{}), ...);
 }
 
-// The workgroups of one (member, channel tile) are persistent: workgroup x takes position tiles
-// x, x + gridDim.x, ...  The filter is loaded once; the window of the next tile arrives in a
+// The workgroups of one (member, channel tile) are persistent: each takes a share of the position
+// tiles (tile_walk: neighbouring tiles on one XCD).  The filter is loaded once; the window of the next tile arrives in a
 // second buffer while the matrix cores work on the current one and while its output leaves
 // (staged through the window buffer it has just finished with).
 template <int BP, int KH, int KW, int HROWS>
@@ -106,8 +106,9 @@ __global__ __launch_bounds__(256) void conv_taps16_bf16(const ConvArgs* __restri
             }
         }
     };
-    int ptile = blockIdx.x;
-    if (ptile >= n_ptiles) {                                     // nothing to do: let the filter loads land and leave
+    const TileWalk walk = tile_walk(n_ptiles, (blockIdx.y + blockIdx.z * gridDim.y) * gridDim.x);
+    int ptile = walk.first;
+    if (ptile >= walk.end) {                                     // nothing to do: let the filter loads land and leave
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         return;
     }
@@ -130,10 +131,10 @@ __global__ __launch_bounds__(256) void conv_taps16_bf16(const ConvArgs* __restri
     // The one wait counter covers loads and stores alike, so the wait sits before this tile's
     // stores are issued: by then the previous tile's stores have had a whole compute phase to
     // complete and do not hold it up.
-    for (int buf = 0; ptile < n_ptiles; ptile += gridDim.x, buf ^= 1) {
-        const bool has_next = ptile + (int)gridDim.x < n_ptiles;
+    for (int buf = 0; ptile < walk.end; ptile += walk.step, buf ^= 1) {
+        const bool has_next = ptile + walk.step < walk.end;
         if (has_next) {
-            make_tables(buf ^ 1, ptile + gridDim.x);
+            make_tables(buf ^ 1, ptile + walk.step);
             __syncthreads();                                     // tables written; the other buffer is free (see the end of the loop)
             issue_window(buf ^ 1);
         }

@@ -45,7 +45,7 @@ __device__ __forceinline__ void wreg_for_each(F&& f, std::integer_sequence<int, 
     (f(std::integral_constant<int, T>{}), ...);
 }
 
-template <int BP, int WPX, int WCG, int TPG>
+template <int BP, int WPX, int WCG>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void conv3x3_wreg_bf16(const ConvArgs* __restrict__ argv, const int nb_, const int hrows) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
@@ -67,57 +67,18 @@ void conv3x3_wreg_bf16(const ConvArgs* __restrict__ argv, const int nb_, const i
     const int c0 = blockIdx.y * BC;
     const int hbytes = hrows * ROWB, nsl = hrows / 32;
 
-    int ptile = blockIdx.x;
-    if (ptile >= n_ptiles) return;
+    const TileWalk walk = tile_walk(n_ptiles, (blockIdx.y + blockIdx.z * gridDim.y) * gridDim.x);
+    int ptile = walk.first;
+    if (ptile >= walk.end) return;
 
     // LDS: window 0 | window 1 | three tables window row -> byte offset of the pixel in x (out of range: no
-    // pixel) | three tables window row -> pixel index (-1: none) | bias of the BC channels
-    unsigned* const tblx = (unsigned*)(lds + 2 * hbytes);
+    // pixel) | three tables window row -> pixel index (-1: none) | bias of the BC channels.  On its way
+    // to the registers the filter passes through the FSTAGE bytes after window 0, which the tables keep
+    // clear of.
+    constexpr int FSTAGE = 5 * BC * 128;
+    unsigned* const tblx = (unsigned*)(lds + (2 * hbytes > hbytes + FSTAGE ? 2 * hbytes : hbytes + FSTAGE));
     int* const tblp = (int*)(tblx + 3 * hrows);
     float* const biasl = (float*)(tblp + 3 * hrows);
-
-    // ---- the filter: fragment (tap, ks) of this wave's 32 channels and 64-channel slice.  A lane's 16
-    //      bytes lie in a different weight row than its neighbour's, so the rows come through LDS
-    //      with coalesced asynchronous loads, TPG taps at a time, and are picked up from there.
-    bf16x8 wreg[9][4];
-    {
-        constexpr int R = BC;                                    // rows per tap: one per channel
-        const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
-            (void*)a.w, 0, (int)((unsigned)a.cout * (unsigned)(9 * a.cin) * 2u), 0x00020000);
-        const int r0 = t >> 3;
-        unsigned wvo[R / 32];                                    // row 32*i + r0, this thread's chunk
-#pragma unroll
-        for (int i = 0; i < R / 32; i++) {
-            const int ch = c0 + 32 * i + r0;
-            wvo[i] = ch < a.cout ? (unsigned)ch * (unsigned)(9 * a.cin) * 2u + (unsigned)(((t & 7) ^ ((r0 >> 1) & 7)) * 16)
-                                 : 0x80000000u;
-        }
-        const int mrow = lane & 31;                              // matrix row; its channel has bits 2 and 3 swapped
-        const int rho = wc0 + ((mrow & 0x13) | ((mrow & 4) << 1) | ((mrow & 8) >> 1));
-        const uint32_t key = (uint32_t)((rho >> 1) & 7), lh = (uint32_t)(lane >> 5);
-#pragma unroll
-        for (int tap0 = 0; tap0 < 9; tap0 += TPG) {
-            if (tap0 > 0) __syncthreads();                       // the previous taps have been picked up
-#pragma unroll
-            for (int j = 0; j < TPG; j++) {
-                if (tap0 + j >= 9) break;
-#pragma unroll
-                for (int i = 0; i < R / 32; i++)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(wres, (lds_ptr_t)(lds + j * R * 128 + i * 4096 + wave * 1024),
-                                                             LDS_LOAD_BYTES, wvo[i], (tap0 + j) * a.cin * 2, 0, 0);
-            }
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-#pragma unroll
-            for (int j = 0; j < TPG; j++) {
-                if (tap0 + j >= 9) break;
-#pragma unroll
-                for (int ks = 0; ks < 4; ks++)
-                    wreg[tap0 + j][ks] = *(const bf16x8*)(lds + j * R * 128 + rho * 128 + (((2 * ks + lh) ^ key) << 4));
-            }
-        }
-        __syncthreads();                                         // LDS is free for the windows
-    }
 
     // ---- window loads.  Offsets past the end of a buffer give zeros in LDS (loads) or are dropped
     //      (stores); 2^31 is past the end of every buffer the launcher admits.
@@ -145,7 +106,7 @@ void conv3x3_wreg_bf16(const ConvArgs* __restrict__ argv, const int nb_, const i
         wi = rem - hi * W1;
         tn = n - 1; thi = hi; twi = wi;
     }
-    const int step_tiles = gridDim.x;
+    const int step_tiles = walk.step;
     const int adv = step_tiles * BP;
     const int adv_n = adv / img, adv_h = (adv - adv_n * img) / W1, adv_w = adv - adv_n * img - adv_h * W1;
     // writes slot `slot` for the tile the thread's position stands at, then moves on to the next tile
@@ -185,6 +146,48 @@ void conv3x3_wreg_bf16(const ConvArgs* __restrict__ argv, const int nb_, const i
     __syncthreads();
     issue_window(0, 0);
 
+    // ---- the filter: fragment (tap, ks) of this wave's 32 channels.  A lane's 16 bytes lie in a
+    //      different weight row than its neighbour's, so the rows come through LDS with coalesced
+    //      asynchronous loads (taps 0..4 next to the first window, which arrives meanwhile, then
+    //      taps 5..8) and are picked up from there.
+    bf16x8 wreg[9][4];
+    {
+        const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
+            (void*)a.w, 0, (int)((unsigned)a.cout * (unsigned)(9 * a.cin) * 2u), 0x00020000);
+        unsigned wvo[BC / 32];                                   // weight row c0 + 32*i + r0, this thread's chunk
+#pragma unroll
+        for (int i = 0; i < BC / 32; i++) {
+            const int ch = c0 + 32 * i + r0;
+            wvo[i] = ch < a.cout ? (unsigned)ch * (unsigned)(9 * a.cin) * 2u + (unsigned)(((t & 7) ^ ((r0 >> 1) & 7)) * 16)
+                                 : OOBV;
+        }
+        const int mrow = lane & 31;                              // matrix row; its channel has bits 2 and 3 swapped
+        const int rho = wc0 + ((mrow & 0x13) | ((mrow & 4) << 1) | ((mrow & 8) >> 1));
+        const uint32_t key = (uint32_t)((rho >> 1) & 7), lh = (uint32_t)(lane >> 5);
+        unsigned char* const fst = lds + hbytes;
+#pragma unroll
+        for (int tap0 = 0; tap0 < 9; tap0 += 5) {
+#pragma unroll
+            for (int j = 0; j < 5; j++) {
+                if (tap0 + j >= 9) break;
+#pragma unroll
+                for (int i = 0; i < BC / 32; i++)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(wres, (lds_ptr_t)(fst + j * BC * 128 + i * 4096 + wave * 1024),
+                                                             LDS_LOAD_BYTES, wvo[i], (tap0 + j) * a.cin * 2, 0, 0);
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < 5; j++) {
+                if (tap0 + j >= 9) break;
+#pragma unroll
+                for (int ks = 0; ks < 4; ks++)
+                    wreg[tap0 + j][ks] = *(const bf16x8*)(fst + j * BC * 128 + rho * 128 + (((2 * ks + lh) ^ key) << 4));
+            }
+            __syncthreads();                                     // picked up: the stage is free for the next taps, then for window 1
+        }
+    }
+
     // ---- fragment side: lane reads position wp0 + (lane & 31) (+32) of the tap, chunk 2*ks + lane/32.
     //      The byte offsets of the nine taps inside a window do not depend on the tile.
     const int lrow = lane & 31, lhalf = lane >> 5;
@@ -214,9 +217,9 @@ void conv3x3_wreg_bf16(const ConvArgs* __restrict__ argv, const int nb_, const i
     // residual, compute, wait for the next window, send the output off.  The one wait counter
     // covers loads and stores alike, so the wait sits before this tile's stores are issued.
     int slot = 0;
-    for (int buf = 0; ptile < n_ptiles; ptile += step_tiles, buf ^= 1) {
+    for (int buf = 0; ptile < walk.end; ptile += step_tiles, buf ^= 1) {
         const int slot1 = slot == 2 ? 0 : slot + 1, slot2 = slot1 == 2 ? 0 : slot1 + 1;
-        if (ptile + step_tiles < n_ptiles) issue_window(buf ^ 1, slot1);
+        if (ptile + step_tiles < walk.end) issue_window(buf ^ 1, slot1);
         // slot2 held the previous tile's table, which every wave has read before that tile's barrier
         make_table(slot2);
         const int* own = tblp + slot * hrows + W1 + 1 + wp0 + lrow;   // the centre tap's rows: this tile's outputs
@@ -341,8 +344,9 @@ static bool wreg_plan(const ConvArgs& a, int nb, int G, WregPlan* pl) {
     const int need = bp + 2 * (a.W + 1) + 2;
     pl->hrows = (need + 31) / 32 * 32;
     if (pl->hrows > 256) return false;                           // one table row per thread
-    pl->bytes = 2 * (size_t)pl->hrows * 128 + 6 * (size_t)pl->hrows * 4 + 64 * 4;
-    if (pl->bytes < (size_t)9 * 64 * 128) pl->bytes = (size_t)9 * 64 * 128;   // the filter passes through LDS on its way to the registers
+    // two windows, or one window and the stage the filter passes through, whichever is larger; tables; bias
+    const size_t hb = (size_t)pl->hrows * 128, fstage = (size_t)5 * 64 * 128;
+    pl->bytes = (2 * hb > hb + fstage ? 2 * hb : hb + fstage) + 6 * (size_t)pl->hrows * 4 + 64 * 4;
     if (2 * pl->bytes > (size_t)WREG_LDS_LIMIT) return false;
     // as many workgroups as the chip holds at once (two per compute unit), and not one more
     const int ctiles = (a.cout + 63) / 64;
@@ -370,7 +374,7 @@ hipError_t launch_conv_wreg(const ConvArgs& a, const ConvArgs* argv, int G, int 
     if (a.res.p && (a.res.stride % 8 || a.res.c0 % 8)) return hipErrorInvalidValue;
     static bool raised = false;                                  // LDS above 64 KB has to be asked for once
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)&conv3x3_wreg_bf16<128, 2, 2, 9>,
+        hipError_t e = hipFuncSetAttribute((const void*)&conv3x3_wreg_bf16<128, 2, 2>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, WREG_LDS_LIMIT);
         if (e != hipSuccess) return e;
         raised = true;
@@ -380,7 +384,7 @@ hipError_t launch_conv_wreg(const ConvArgs& a, const ConvArgs* argv, int G, int 
     if (const char* e = getenv("ENS_CONV_WREG_WGS")) if (atoi(e) > 0) wgs = atoi(e);
 #endif
     const dim3 grid((unsigned)wgs, (unsigned)((a.cout + 63) / 64), G);
-    ENS_LAUNCH((conv3x3_wreg_bf16<128, 2, 2, 9>), grid, dim3(256), pl.bytes, s, argv, nb, pl.hrows);
+    ENS_LAUNCH((conv3x3_wreg_bf16<128, 2, 2>), grid, dim3(256), pl.bytes, s, argv, nb, pl.hrows);
     return hipGetLastError();
 }
 
