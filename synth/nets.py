@@ -4,7 +4,7 @@ A member is a flat list of operations over numbered NHWC tensors plus a list
 of parameter tensors living in one flat fp32 blob.  The description is pure
 data: the CPU oracle and the GPU library each read it and implement every
 operation on their own.  Shapes follow the public architecture papers
-(ResNet, DenseNet, Inception-v3, EfficientNet); only the shapes matter for the
+(ResNet, DenseNet, Inception-v3, EfficientNet, VGG, Xception, MobileNetV2); only the shapes matter for the
 throughput study, the weights are random (see synth.weights).
 
 Operation semantics (tensor = H x W x C, channel slices [c0, c0+n)):
@@ -113,12 +113,12 @@ class Net:
                  off_bn=off_bn, off_pre=off_pre)
         return dt
 
-    def dwconv(self, src, k, stride=1, bn=True, act="silu"):
+    def dwconv(self, src, k, stride=1, bn=True, act="silu", gain=2.0):
         h, w, c = self.tensors[src]
         p = (k - 1) // 2
         ho, wo = self._out(h, k, stride, p, p), self._out(w, k, stride, p, p)
         dt = self.tensor(ho, wo, c)
-        off_w = self._param("conv_w", k * k * c, std=math.sqrt(2.0 / (k * k)))
+        off_w = self._param("conv_w", k * k * c, std=math.sqrt(gain / (k * k)))
         off_b = -1 if bn else self._param("bias", c)
         off_bn = self._bn(c, 1.0) if bn else -1
         self._op(kind=DWCONV, src=src, cin=c, dst=dt, cout=c, kh=k, kw=k, sh=stride, sw=stride,
@@ -454,6 +454,86 @@ def inception_v3(classes=1000, size=299, dtype="bf16"):
 # The five workload configurations
 # ----------------------------------------------------------------------
 
+_VGG = {16: (2, 2, 3, 3, 3), 19: (2, 2, 4, 4, 4)}
+
+
+def vgg(depth=16, classes=1000, size=224, dtype="bf16"):
+    """VGG-16 / VGG-19-shaped member: 3x3 convolutions with bias and no normalisation, five 2x2 max
+    pools, two hidden fully connected layers of 4096.  The first of those is written as a
+    convolution over the whole remaining map (7x7 at 224) and the second as a 1x1 convolution, which
+    is what a fully connected layer over a flattened map is."""
+    n = Net("vgg%d" % depth, size, size, classes, dtype)
+    t, widths = 0, (64, 128, 256, 512, 512)
+    for w, reps in zip(widths, _VGG[depth]):
+        for _ in range(reps):
+            t = n.conv(t, w, 3, bn=False)
+        t = n.maxpool(t, 2, 2)
+    h, w_, _ = n.tensors[t]
+    t = n.conv(t, 4096, (h, w_), pad="valid", bn=False)
+    t = n.conv(t, 4096, 1, bn=False)
+    t = n.gap(t)
+    n.fc(t, classes)
+    return n
+
+
+def xception(classes=1000, size=299, dtype="bf16"):
+    """Xception-shaped member: depthwise-separable convolutions (3x3 depthwise without norm or
+    activation, then 1x1 with norm) in residual blocks; entry flow 128-256-728 with strided max
+    pools and 1x1 stride-2 shortcuts, eight middle blocks at 728, exit flow to 2048.  The ReLU
+    that the architecture puts in front of a separable convolution sits behind the operation that
+    feeds it here (the sum included), which keeps every shape and operation count."""
+    n = Net("xception", size, size, classes, dtype)
+
+    def sep(x, cout, act="relu", res=None, gamma=1.0):
+        d = n.dwconv(x, 3, 1, bn=False, act=None, gain=1.0)
+        return n.conv(d, cout, 1, act=act, res=res, gamma=gamma)
+
+    t = n.conv(0, 32, 3, stride=2, pad="valid")
+    t = n.conv(t, 64, 3, pad="valid")
+    for c in (128, 256, 728):                                   # entry flow
+        u = sep(t, c)
+        u = sep(u, c, act=None, gamma=RES_ALPHA)
+        u = n.maxpool(u, 3, 2, 1)
+        t = n.conv(t, c, 1, stride=2, act="relu", res=u)        # shortcut + pooled branch
+    for _ in range(8):                                           # middle flow
+        u = sep(t, 728)
+        u = sep(u, 728)
+        t = sep(u, 728, act="relu", res=t, gamma=RES_ALPHA)
+    u = sep(t, 728)                                              # exit flow
+    u = sep(u, 1024, act=None, gamma=RES_ALPHA)
+    u = n.maxpool(u, 3, 2, 1)
+    t = n.conv(t, 1024, 1, stride=2, act=None, res=u)
+    t = sep(t, 1536)
+    t = sep(t, 2048)
+    t = n.gap(t)
+    n.fc(t, classes, gain=0.3)
+    return n
+
+
+_MBV2 = ((1, 16, 1, 1), (6, 24, 2, 2), (6, 32, 3, 2), (6, 64, 4, 2), (6, 96, 3, 1), (6, 160, 3, 2), (6, 320, 1, 1))
+
+
+def mobilenet_v2(classes=1000, size=224, dtype="bf16"):
+    """MobileNetV2-shaped member: inverted residuals (1x1 expansion, 3x3 depthwise, linear 1x1
+    projection), widths 16-320, 1280 features.  ReLU stands where the architecture has ReLU6."""
+    n = Net("mobilenet_v2", size, size, classes, dtype)
+    cin = 32
+    t = n.conv(0, cin, 3, stride=2)
+    for (e, c, reps, s) in _MBV2:
+        for i in range(reps):
+            stride = s if i == 0 else 1
+            x = t
+            u = n.conv(x, cin * e, 1, gain=1.0) if e != 1 else x      # the block input is a linear projection: unit gain
+            u = n.dwconv(u, 3, stride, act="relu")
+            skip = x if (stride == 1 and cin == c) else None
+            t = n.conv(u, c, 1, act=None, res=skip, gamma=RES_ALPHA if skip is not None else 1.0)
+            cin = c
+    t = n.conv(t, 1280, 1, gain=1.0)
+    t = n.gap(t)
+    n.fc(t, classes, gain=4.0)
+    return n
+
+
 def config_members(cfg):
     """Members of workload configuration `cfg` (1-5) as a list of Net."""
     if cfg == 1:
@@ -469,7 +549,9 @@ def config_members(cfg):
                 inception_v3(size=224), inception_v3(size=224), inception_v3(size=224)]
     if cfg == 5:
         return [resnet50()]
-    raise ValueError("configuration must be 1..5")
+    if cfg == 6:        # further members of the paper's ImageNet ensembles: VGG, Xception, MobileNetV2 shapes
+        return [vgg(16), vgg(19), xception(size=299), mobilenet_v2()]
+    raise ValueError("configuration must be 1..6")
 
 
-BASE_SIZE = {1: 32, 2: 224, 3: 224, 4: 224, 5: 224}
+BASE_SIZE = {1: 32, 2: 224, 3: 224, 4: 224, 5: 224, 6: 224}

@@ -53,6 +53,9 @@ SMALL = [
     ("efficientnet_b0", lambda: N.efficientnet(0, size=64, classes=200), 64),
     ("efficientnet_b2", lambda: N.efficientnet(2, size=64, classes=200), 64),
     ("inception_v3", lambda: N.inception_v3(size=107, classes=200), 107),
+    ("vgg16", lambda: N.vgg(16, size=64, classes=200), 64),
+    ("xception", lambda: N.xception(size=107, classes=200), 107),
+    ("mobilenet_v2", lambda: N.mobilenet_v2(size=64, classes=200), 64),
 ]
 
 
@@ -89,6 +92,20 @@ def test_config3_heterogeneous_full_size(ens):
     y2 = E.ens_predict(imgs)
     assert np.abs(y2 - y).max() <= 5e-3
     E.close()
+
+
+def test_config6_vgg_xception_mobilenet_full_size(ens):
+    """VGG-16-, Xception- (299, fed by the library's resize) and MobileNetV2-shaped members at their full
+    sizes on a few images: the 7x7x512 -> 4096 layer of VGG (K = 25088), 728-channel separable blocks."""
+    nets = [N.vgg(16), N.xception(size=299), N.mobilenet_v2()]
+    n = 3
+    blobs, imgs = prepared(nets, synth.BASE_SEED + 23, n, 224)
+    E = ens.Ensemble(nets, blobs)
+    E.ens_set_alloc([[2, 2, 2]])
+    y = E.ens_predict(imgs)
+    E.close()
+    y_ref, _ = oracle.ensemble_predict(nets, blobs, imgs, real="f32")
+    check(y, y_ref, "config 6")
 
 
 def test_config4_heavy_ensemble_full_size(ens):

@@ -286,6 +286,12 @@ def test_architecture_work_matches_published_figures():
     assert abs(N.resnet18().n_weights() / 1e6 - 11.7) < 0.1
     assert abs(N.efficientnet(0).macs() / 1e9 - 0.39) < 0.01
     assert abs(N.inception_v3().macs() / 1e9 - 5.7) < 0.05
+    # VGG-16 / VGG-19: 15.5 / 19.6 GMAC, 138.4 / 143.7 M weights; Xception at 299: 8.4 GMAC, 22.9 M;
+    # MobileNetV2: 0.30 GMAC, 3.5 M (the architecture papers' tables)
+    assert abs(N.vgg(16).macs() / 1e9 - 15.47) < 0.02 and abs(N.vgg(16).n_weights() / 1e6 - 138.4) < 0.1
+    assert abs(N.vgg(19).macs() / 1e9 - 19.63) < 0.02 and abs(N.vgg(19).n_weights() / 1e6 - 143.7) < 0.1
+    assert abs(N.xception().macs() / 1e9 - 8.4) < 0.06 and abs(N.xception().n_weights() / 1e6 - 22.9) < 0.1
+    assert abs(N.mobilenet_v2().macs() / 1e9 - 0.30) < 0.01 and abs(N.mobilenet_v2().n_weights() / 1e6 - 3.5) < 0.05
 
 
 def test_bf16_storage_mode_brackets_fp32():
