@@ -63,6 +63,8 @@ static void conv_op(const orc_op* o, const orc_tensor* T, REAL** buf, const floa
     REAL* out = buf[o->dst];
     const float* w = blob + o->off_w;
     REAL* acc = (REAL*)malloc(sizeof(REAL) * o->cout);
+    const int groups = o->r > 1 ? o->r : 1;          /* CONV: r = number of groups (0 or 1: ordinary) */
+    const int ig = o->cin / groups, og = o->cout / groups;
     for (int ho = 0; ho < to.h; ho++)
         for (int wo = 0; wo < to.w; wo++) {
             for (int co = 0; co < o->cout; co++) acc[co] = 0;
@@ -73,15 +75,18 @@ static void conv_op(const orc_op* o, const orc_tensor* T, REAL** buf, const floa
                     int wi = wo * o->sw - o->pl + kw;
                     if (wi < 0 || wi >= ti.w) continue;
                     const REAL* px = in + ((size_t)hi * ti.w + wi) * ti.c + o->src_c0;
-                    const float* wk = w + (size_t)(kh * o->kw + kw) * o->cin * o->cout;
+                    /* groups: output channel co belongs to group co / og and sees only that group's
+                       ig input channels; the weights are [kh][kw][ig][cout] */
+                    const float* wk = w + (size_t)(kh * o->kw + kw) * ig * o->cout;
                     for (int ci = 0; ci < o->cin; ci++) {
                         REAL x = px[ci];
                         if (o->pre) {
                             x = bn_apply(x, blob + o->off_pre, ci, o->cin);
                             x = x > 0 ? x : 0;
                         }
-                        const float* wr = wk + (size_t)ci * o->cout;
-                        for (int co = 0; co < o->cout; co++) acc[co] += x * (REAL)wr[co];
+                        const int g = ci / ig;
+                        const float* wr = wk + (size_t)(ci - g * ig) * o->cout;
+                        for (int co = g * og; co < (g + 1) * og; co++) acc[co] += x * (REAL)wr[co];
                     }
                 }
             }

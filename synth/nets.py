@@ -10,7 +10,8 @@ throughput study, the weights are random (see synth.weights).
 Operation semantics (tensor = H x W x C, channel slices [c0, c0+n)):
 
   CONV     dst[:, :, dst_c0:+cout] = act( bn( conv(pre(src[:, :, src_c0:+cin])) + bias ) + res )
-           weights [kh][kw][cin][cout]; zero padding (pt rows above, pl columns
+           weights [kh][kw][cin][cout]; with r = g > 1 groups output channel co sees the input
+           channels of group co // (cout/g) only and the weights are [kh][kw][cin/g][cout]; zero padding (pt rows above, pl columns
            left; the output size is the dst tensor's H x W); `pre` applies an
            inference batch-norm followed by ReLU to the in-bounds input values.
   DWCONV   depthwise: one kh x kw filter per channel, weights [kh][kw][c].
@@ -80,7 +81,7 @@ class Net:
 
     # ---- operations --------------------------------------------------
     def conv(self, src, cout, k, stride=1, pad="same", bn=True, act="relu", bias=None,
-             res=None, pre=False, gamma=1.0, gain=2.0, dst=None, src_slice=None):
+             res=None, pre=False, gamma=1.0, gain=2.0, dst=None, src_slice=None, groups=1):
         kh, kw = (k, k) if isinstance(k, int) else k
         h, w, c_all = self.tensors[src]
         c0, cin = (0, c_all) if src_slice is None else src_slice
@@ -99,7 +100,8 @@ class Net:
             assert d0 + cout <= self.tensors[dt][2]
         if bias is None:
             bias = not bn
-        fan_in = kh * kw * cin
+        assert cin % groups == 0 and cout % groups == 0
+        fan_in = kh * kw * cin // groups
         off_w = self._param("conv_w", fan_in * cout, std=math.sqrt(gain / fan_in))
         off_b = self._param("bias", cout) if bias else -1
         off_bn = self._bn(cout, gamma) if bn else -1
@@ -109,7 +111,7 @@ class Net:
             assert self.tensors[rt][:2] == (ho, wo) and r0 + cout <= self.tensors[rt][2]
         self._op(kind=CONV, src=src, src_c0=c0, cin=cin, dst=dt, dst_c0=d0, cout=cout,
                  kh=kh, kw=kw, sh=stride, sw=stride, pt=ph, pl=pw, act=_ACT[act],
-                 res=rt, res_c0=r0, pre=int(pre), off_w=off_w, off_b=off_b,
+                 res=rt, res_c0=r0, pre=int(pre), r=groups if groups > 1 else 0, off_w=off_w, off_b=off_b,
                  off_bn=off_bn, off_pre=off_pre)
         return dt
 
@@ -180,7 +182,7 @@ class Net:
         for op in self.ops:
             ho, wo, _ = self.tensors[op["dst"]]
             if op["kind"] == CONV:
-                total += ho * wo * op["cout"] * op["kh"] * op["kw"] * op["cin"]
+                total += ho * wo * op["cout"] * op["kh"] * op["kw"] * op["cin"] // max(1, op["r"])
             elif op["kind"] == DWCONV:
                 total += ho * wo * op["cout"] * op["kh"] * op["kw"]
             elif op["kind"] == FC:
@@ -262,6 +264,28 @@ def resnet_bottleneck(name, blocks, classes=1000, size=224, widths=(64, 128, 256
     # the residual stream's spread grows about 6 % per block; the head is scaled so that the
     # logits keep a spread of about 3 whatever the depth (no saturated softmax)
     n.fc(t, classes, gain=0.25 * 1.126 ** (16 - sum(blocks)))
+    return n
+
+
+def resnext50(classes=1000, size=224, dtype="bf16", groups=32, width=4):
+    """ResNeXt-50 (32x4d)-shaped member: the bottleneck network with a grouped 3x3 convolution of
+    `groups` groups, `width` channels per group in the first stage (doubling per stage)."""
+    n = Net("resnext50", size, size, classes, dtype)
+    t = _resnet_stem(n, 64)
+    cin = 64
+    for si, (w, nb) in enumerate(zip((64, 128, 256, 512), (3, 4, 6, 3))):
+        gw = groups * width * 2 ** si
+        for bi in range(nb):
+            s = 2 if (bi == 0 and si > 0) else 1
+            idt = t
+            if s != 1 or cin != 4 * w:
+                idt = n.conv(t, 4 * w, 1, stride=s, act=None)
+            u = n.conv(t, gw, 1)
+            u = n.conv(u, gw, 3, stride=s, groups=groups)
+            t = n.conv(u, 4 * w, 1, gamma=RES_ALPHA, res=idt)
+            cin = 4 * w
+    t = n.gap(t)
+    n.fc(t, classes, gain=0.25)
     return n
 
 

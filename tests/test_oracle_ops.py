@@ -126,6 +126,7 @@ CONV_CASES = [
     dict(k=5, stride=1), dict(k=5, stride=2), dict(k=7, stride=2), dict(k=(1, 7)), dict(k=(7, 1)),
     dict(k=(1, 3)), dict(k=(3, 1)), dict(k=3, stride=2, pad="valid"), dict(k=3, pad="valid"),
     dict(k=3, act="silu"), dict(k=3, bn=False), dict(k=1, pre=True), dict(k=3, pre=True),
+    dict(k=3, groups=2), dict(k=3, stride=2, groups=2), dict(k=1, groups=2, bn=False),
 ]
 
 
@@ -137,6 +138,32 @@ def test_conv_against_library_conv2d(case):
     got = run_oracle(net, blob, x)
     exp = torch_ref.run(net, blob, x, want=net.out_tensor)
     np.testing.assert_allclose(got, exp, rtol=1e-11, atol=1e-11)
+
+
+def test_grouped_conv_is_independent_convs_on_channel_slices():
+    """A convolution with g groups equals g ordinary convolutions, group j reading input channels
+    [j*cin/g, (j+1)*cin/g) and writing output channels [j*cout/g, (j+1)*cout/g) with columns
+    [j*cout/g, (j+1)*cout/g) of the [kh][kw][cin/g][cout] weights (the definition of groups)."""
+    g, cin, cout = 3, 6, 12
+    a = N.Net("g", 7, 9, 1, dtype="fp32", in_c=cin)
+    a.out_tensor = a.conv(0, cout, 3, bn=False, act=None, bias=True, groups=g)
+    blob = W.make_blob(a, 9, 0)
+    x = RNG.standard_normal((2, 7, 9, cin)).astype(np.float32)
+    got = run_oracle(a, blob, x)
+    w = blob[:9 * (cin // g) * cout].reshape(3, 3, cin // g, cout)
+    bias = blob[9 * (cin // g) * cout:9 * (cin // g) * cout + cout]
+    for j in range(g):
+        b = N.Net("s", 7, 9, 1, dtype="fp32", in_c=cin // g)
+        b.out_tensor = b.conv(0, cout // g, 3, bn=False, act=None, bias=True)
+        bb = np.concatenate([w[..., j * (cout // g):(j + 1) * (cout // g)].ravel(),
+                             bias[j * (cout // g):(j + 1) * (cout // g)]]).astype(np.float32)
+        exp = run_oracle(b, bb, x[..., j * (cin // g):(j + 1) * (cin // g)])
+        np.testing.assert_allclose(got[..., j * (cout // g):(j + 1) * (cout // g)], exp, rtol=1e-12, atol=1e-12)
+    # and a group never sees another group's input
+    x2 = x.copy()
+    x2[..., :cin // g] += 5.0
+    got2 = run_oracle(a, blob, x2)
+    assert np.all(got2[..., cout // g:] == got[..., cout // g:]) and not np.allclose(got2[..., :cout // g], got[..., :cout // g])
 
 
 def test_conv_channel_slices_and_residual():
@@ -258,7 +285,8 @@ def _small_members():
         N.tiny_a(), N.tiny_b(),
         N.resnet18(size=64, classes=17), N.resnet50(size=64, classes=17),
         N.densenet121(size=64, classes=17), N.efficientnet(0, size=64, classes=17),
-        N.inception_v3(size=107, classes=17),
+        N.inception_v3(size=107, classes=17), N.resnext50(size=64, classes=17),
+        N.xception(size=107, classes=17), N.mobilenet_v2(size=64, classes=17), N.vgg(16, size=64, classes=17),
     ]
 
 
@@ -292,6 +320,8 @@ def test_architecture_work_matches_published_figures():
     assert abs(N.vgg(19).macs() / 1e9 - 19.63) < 0.02 and abs(N.vgg(19).n_weights() / 1e6 - 143.7) < 0.1
     assert abs(N.xception().macs() / 1e9 - 8.4) < 0.06 and abs(N.xception().n_weights() / 1e6 - 22.9) < 0.1
     assert abs(N.mobilenet_v2().macs() / 1e9 - 0.30) < 0.01 and abs(N.mobilenet_v2().n_weights() / 1e6 - 3.5) < 0.05
+    # ResNeXt-50 (32x4d): 4.2 GMAC, 25.0 M weights
+    assert abs(N.resnext50().macs() / 1e9 - 4.23) < 0.03 and abs(N.resnext50().n_weights() / 1e6 - 25.0) < 0.1
 
 
 def test_bf16_storage_mode_brackets_fp32():

@@ -46,8 +46,9 @@ def run(net, blob, images, want=None):
                 src = torch.relu(_bn(src, blob[o["off_pre"]:o["off_pre"] + 4 * o["cin"]], o["cin"]))
             kh, kw, cin, cout = o["kh"], o["kw"], o["cin"], o["cout"]
             if k == N.CONV:
-                w = blob[o["off_w"]:o["off_w"] + kh * kw * cin * cout].view(kh, kw, cin, cout).permute(3, 2, 0, 1)
-                groups = 1
+                groups = max(1, o["r"])                          # CONV: r = number of groups
+                ig = cin // groups
+                w = blob[o["off_w"]:o["off_w"] + kh * kw * ig * cout].view(kh, kw, ig, cout).permute(3, 2, 0, 1)
             else:
                 w = blob[o["off_w"]:o["off_w"] + kh * kw * cin].view(kh, kw, 1, cin).permute(3, 2, 0, 1)
                 groups = cin
