@@ -41,7 +41,10 @@ typedef enum {
  *   CONV     dst[.., dst_c0:+cout] = act(bn(conv(pre(src[.., src_c0:+cin])) + bias) + res)
  *            weights [kh][kw][cin][cout] at off_w; zero padding, pt rows above and pl columns
  *            to the left; output size = the dst tensor's H x W; `pre` applies an inference
- *            batch-norm (off_pre) then ReLU to the in-bounds input values;
+ *            batch-norm (off_pre) then ReLU to the in-bounds input values; with r = g > 1 the
+ *            convolution has g groups: output channel co sees the input channels of group
+ *            co / (cout/g) only and the weights are [kh][kw][cin/g][cout] (bf16 members, cout/g a
+ *            divisor or a multiple of 32, no `pre`: otherwise ENS_E_UNSUPPORTED);
  *   DWCONV   depthwise, weights [kh][kw][c];
  *   MAXPOOL / AVGPOOL  over the in-bounds part of the window;
  *   GAP      mean over all pixels (of relu(bn(x)) when pre);

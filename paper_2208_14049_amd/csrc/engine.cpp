@@ -57,7 +57,8 @@ static bool same_network(const Member& a, const Member& b) {
 }
 
 // Fills one member's argument block for operation `pl`; `L` receives kind, class and work.
-static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G, const OpPlan& pl, Launch& L) {
+// `sub`: which of the operation's pl.sub argument blocks (sub-convolutions of a grouped convolution)
+static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G, const OpPlan& pl, Launch& L, int sub = 0) {
     const Member& m = h->members[w.member];
     const int es = m.bf16 ? 2 : 4;
     const ens_op& o = pl.op;
@@ -83,13 +84,22 @@ static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G
                 a.ws = (float*)(w.arena + w.layout.scratch_offset);
                 a.ws_floats = (long long)SPLIT_WS_FLOATS;
             }
-            a.nb = w.batch; a.H = ts.h; a.W = ts.w; a.cin = pl.cin_s; a.Ho = td.h; a.Wo = td.w; a.cout = o.cout;
+            a.nb = w.batch; a.H = ts.h; a.W = ts.w; a.cin = pl.cin_s; a.Ho = td.h; a.Wo = td.w; a.cout = pl.sub_cout;
             a.kh = o.kh; a.kw = o.kw; a.sh = o.sh; a.sw = o.sw; a.pt = o.pt; a.pl = o.pl; a.act = o.act;
             a.inv_hw = 1.0 / ((double)td.h * td.w); a.inv_w = 1.0 / (double)td.w;
-            L.flop = 2.0 * nb * td.h * td.w * o.cout * (pl.alg_k > 0 ? pl.alg_k : o.kh * o.kw * o.cin);
+            L.sub = pl.sub;
+            if (pl.sub > 1) {                                    // this block's slice of channels, weights and bias
+                a.x.c0 += sub * pl.cin_s;
+                a.y.c0 += sub * pl.sub_cout;
+                if (a.res.p) a.res.c0 += sub * pl.sub_cout;
+                a.w = (const char*)a.w + (size_t)sub * pl.sub_cout * o.kh * o.kw * pl.cin_s * es;
+                a.bias += (size_t)sub * pl.sub_cout;
+            }
+            const int groups = o.r > 1 ? o.r : 1;
+            L.flop = 2.0 * nb * td.h * td.w * o.cout * (pl.alg_k > 0 ? pl.alg_k : o.kh * o.kw * o.cin / groups);
             L.bytes = nb * ((double)ts.h * ts.w * o.cin + (double)td.h * td.w * o.cout * (o.res >= 0 ? 2 : 1)) * es +
-                      (double)o.kh * o.kw * o.cin * o.cout * es;
-            L.klass = prof_class(h, m.bf16 ? conv_bf16_variant_name(a, G) : "conv_f32_kernel");
+                      (double)o.kh * o.kw * o.cin / groups * o.cout * es;
+            L.klass = prof_class(h, m.bf16 ? conv_bf16_variant_name(a, G * pl.sub) : "conv_f32_kernel");
             break;
         }
         case ENS_OP_DWCONV:
@@ -163,25 +173,31 @@ static int build_launches(ens_handle* h, Gang& g) {
     const int G = (int)g.workers.size();
     const size_t slot = 512;                                     // bytes reserved per argument block
     static_assert(sizeof(ConvArgs) <= 512 && sizeof(PoolArgs) <= 512 && sizeof(SeArgs) <= 512, "argument block");
-    std::vector<char> host((m.ops.size() + 1) * G * slot, 0);
-    if (!g.d_args) HIP_TRY(hipMalloc((void**)&g.d_args, host.size()));
+    std::vector<size_t> first_blk(m.ops.size() + 1, 0);          // argument blocks: G * sub per operation
+    for (size_t i = 0; i < m.ops.size(); i++) first_blk[i + 1] = first_blk[i] + (size_t)G * (m.ops[i].sub > 1 ? m.ops[i].sub : 1);
+    const size_t n_blk = first_blk[m.ops.size()];
+    std::vector<char> host((n_blk + (size_t)G) * slot, 0);
+    if (g.d_args && g.d_args_bytes < host.size()) { (void)hipFree(g.d_args); g.d_args = nullptr; }
+    if (!g.d_args) { HIP_TRY(hipMalloc((void**)&g.d_args, host.size())); g.d_args_bytes = host.size(); }
     g.launches.clear();
     for (size_t i = 0; i < m.ops.size(); i++) {
         Launch L;
-        for (int k = G - 1; k >= 0; k--) {                       // k == 0 last: L keeps the leader's copy
-            const int rc = fill_args(h, h->workers[g.workers[k]], leader, G, h->members[h->workers[g.workers[k]].member].ops[i], L);
-            if (rc != ENS_OK) return rc;
-            char* dst = host.data() + (i * G + k) * slot;
-            switch (L.kind) {
-                case L_CONV: memcpy(dst, &L.conv, sizeof(ConvArgs)); break;
-                case L_DWCONV:
-                case L_POOL: memcpy(dst, &L.pool, sizeof(PoolArgs)); break;
-                case L_GAP: memcpy(dst, &L.gap, sizeof(GapArgs)); break;
-                case L_FC: memcpy(dst, &L.fc, sizeof(FcArgs)); break;
-                case L_SE: memcpy(dst, &L.se, sizeof(SeArgs)); break;
+        const int nsub = m.ops[i].sub > 1 ? m.ops[i].sub : 1;
+        for (int sub = nsub - 1; sub >= 0; sub--)
+            for (int k = G - 1; k >= 0; k--) {                   // (k, sub) == (0, 0) last: L keeps the leader's first block
+                const int rc = fill_args(h, h->workers[g.workers[k]], leader, G, h->members[h->workers[g.workers[k]].member].ops[i], L, sub);
+                if (rc != ENS_OK) return rc;
+                char* dst = host.data() + (first_blk[i] + (size_t)sub * G + k) * slot;
+                switch (L.kind) {
+                    case L_CONV: memcpy(dst, &L.conv, sizeof(ConvArgs)); break;
+                    case L_DWCONV:
+                    case L_POOL: memcpy(dst, &L.pool, sizeof(PoolArgs)); break;
+                    case L_GAP: memcpy(dst, &L.gap, sizeof(GapArgs)); break;
+                    case L_FC: memcpy(dst, &L.fc, sizeof(FcArgs)); break;
+                    case L_SE: memcpy(dst, &L.se, sizeof(SeArgs)); break;
+                }
             }
-        }
-        L.d_argv = g.d_args + i * G * slot;
+        L.d_argv = g.d_args + first_blk[i] * slot;
         g.launches.push_back(L);
     }
     // The device arrays are indexed by element size, so every block is re-packed densely.
@@ -196,14 +212,15 @@ static int build_launches(ens_handle* h, Gang& g) {
             case L_FC: sz = sizeof(FcArgs); break;
             case L_SE: sz = sizeof(SeArgs); break;
         }
-        char* base = host.data() + i * G * slot;
-        for (int k = 1; k < G; k++) memmove(base + k * sz, base + k * slot, sz);
+        char* base = host.data() + first_blk[i] * slot;
+        const size_t nb_i = first_blk[i + 1] - first_blk[i];
+        for (size_t k = 1; k < nb_i; k++) memmove(base + k * sz, base + k * slot, sz);
     }
     g.stage.src = nullptr;                                       // bound per request
     g.stage.dst = leader.arena + leader.layout.offset[0];
     g.stage.nb = leader.batch; g.stage.sh = h->base_h; g.stage.sw = h->base_w;
     g.stage.dh = m.in_h; g.stage.dw = m.in_w; g.stage.dc = m.tensors[0].cs; g.stage.s2d = m.stem_s2d ? 1 : 0;
-    g.d_stage = (const StageArgs*)(g.d_args + m.ops.size() * G * slot);
+    g.d_stage = (const StageArgs*)(g.d_args + n_blk * slot);
     HIP_TRY(hipMemcpy(g.d_args, host.data(), host.size(), hipMemcpyHostToDevice));
     return ENS_OK;
 }
@@ -329,8 +346,8 @@ static hipEvent_t take_event(ens_handle* h) {
 
 static hipError_t issue(const Launch& L, bool bf16, int G, int nb, long long first, hipStream_t s) {
     switch (L.kind) {
-        case L_CONV: return bf16 ? launch_conv_bf16(L.conv, (const ConvArgs*)L.d_argv, G, nb, s)
-                                 : launch_conv_f32(L.conv, (const ConvArgs*)L.d_argv, G, nb, s);
+        case L_CONV: return bf16 ? launch_conv_bf16(L.conv, (const ConvArgs*)L.d_argv, G * L.sub, nb, s)
+                                 : launch_conv_f32(L.conv, (const ConvArgs*)L.d_argv, G * L.sub, nb, s);
         case L_DWCONV: return launch_dwconv(L.pool, (const PoolArgs*)L.d_argv, G, nb, bf16, s);
         case L_POOL: return launch_pool(L.pool, (const PoolArgs*)L.d_argv, G, nb, L.is_max, bf16, s);
         case L_GAP: return launch_gap(L.gap, (const GapArgs*)L.d_argv, G, nb, bf16, s);

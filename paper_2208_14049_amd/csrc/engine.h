@@ -29,6 +29,10 @@ struct OpPlan {
     int cin_s;       // stored input channels of the convolution's K axis
     int scratch;     // index of the scratch pseudo-tensor (squeeze-excite), -1 otherwise
     int alg_k;       // multiply-adds per output element as the network defines the layer (0: kh*kw*cin of op)
+    // A grouped convolution runs as `sub` dense convolutions on channel slices, sub_cout output channels
+    // each over cin_s input channels, weights [sub][sub_cout][kh*kw][cin_s] (zeros where a pair of
+    // channels belongs to different groups).  Ordinary convolution: sub = 1, sub_cout = cout.
+    int sub, sub_cout;
 };
 
 struct Member {
@@ -75,7 +79,8 @@ struct Launch {
     GapArgs gap;
     FcArgs fc;
     SeArgs se;
-    const void* d_argv = nullptr;  // device: G argument blocks of this operation's kind
+    const void* d_argv = nullptr;  // device: G * sub argument blocks of this operation's kind
+    int sub = 1;                   // argument blocks per member (sub-convolutions of a grouped convolution)
 };
 
 struct Worker {
@@ -100,6 +105,7 @@ struct Gang {
     StageArgs stage;
     const StageArgs* d_stage = nullptr;
     char* d_args = nullptr;        // device block holding every argument array of the gang
+    size_t d_args_bytes = 0;
 };
 
 struct ProfClass {

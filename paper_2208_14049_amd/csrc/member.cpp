@@ -126,6 +126,8 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         pl.cin_s = o.cin;
         pl.scratch = -1;
         pl.alg_k = 0;
+        pl.sub = 1;
+        pl.sub_cout = o.cout;
         TensorInfo& ts = m.tensors[o.src];
         TensorInfo& td = m.tensors[o.dst];
         if (o.cin <= 0 || o.cout <= 0 || o.src_c0 < 0 || o.dst_c0 < 0) return ENS_E_INVALID;
@@ -150,7 +152,18 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         auto aligned8 = [&](int c0, int c) { return c0 % 8 == 0 && c % 8 == 0; };
         switch (o.kind) {
             case ENS_OP_CONV: {
-                const int64_t nw = (int64_t)o.kh * o.kw * o.cin * o.cout;
+                // r > 1: that many groups; output channel co sees the input channels of group co / (cout / r)
+                const int groups = o.r > 1 ? o.r : 1;
+                if (o.cin % groups || o.cout % groups) return ENS_E_INVALID;
+                const int ig = o.cin / groups, og = o.cout / groups;
+                // groups per dense sub-convolution: as many as make 32 output channels (the matrix-core
+                // block), the whole group when it is wider than that
+                const int per_sub = og >= 32 ? 1 : 32 / og;
+                if (groups > 1) {
+                    if (!m.bf16 || o.pre || (og < 32 && 32 % og) || groups % per_sub) return ENS_E_UNSUPPORTED;
+                    if ((per_sub * ig) % 8 || (per_sub * og) % 8) return ENS_E_UNSUPPORTED;
+                }
+                const int64_t nw = (int64_t)o.kh * o.kw * ig * o.cout;
                 if (!in_blob(o.off_w, nw, NP)) return ENS_E_INVALID;
                 if (o.off_b >= 0 && !in_blob(o.off_b, o.cout, NP)) return ENS_E_INVALID;
                 if (o.off_bn >= 0 && !in_blob(o.off_bn, 4 * (int64_t)o.cout, NP)) return ENS_E_INVALID;
@@ -194,6 +207,20 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
                     pl.op.kh = kh2; pl.op.kw = kw2; pl.op.sh = 1; pl.op.sw = 1;
                     pl.op.pt = -ah0; pl.op.pl = -aw0; pl.op.cin = 12;
                     pl.cin_s = 16;
+                } else if (groups > 1) {
+                    // [sub][sub_cout][kh*kw][cin_s]: dense blocks of per_sub groups, zeros between groups
+                    pl.sub = groups / per_sub;
+                    pl.sub_cout = per_sub * og;
+                    pl.cin_s = per_sub * ig;
+                    wf.assign((size_t)o.cout * o.kh * o.kw * pl.cin_s, 0.f);
+                    for (int co = 0; co < o.cout; co++) {
+                        const int g = co / og;
+                        const int ci0 = (g % per_sub) * ig;     // the group's place among its block's input channels
+                        for (int k = 0; k < o.kh * o.kw; k++)
+                            for (int ci = 0; ci < ig; ci++)
+                                wf[((size_t)co * o.kh * o.kw + k) * pl.cin_s + ci0 + ci] =
+                                    w[((size_t)k * ig + ci) * o.cout + co] * scale[co];
+                    }
                 } else {
                     wf.assign((size_t)o.cout * o.kh * o.kw * pl.cin_s, 0.f);
                     for (int co = 0; co < o.cout; co++)

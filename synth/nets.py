@@ -573,8 +573,8 @@ def config_members(cfg):
                 inception_v3(size=224), inception_v3(size=224), inception_v3(size=224)]
     if cfg == 5:
         return [resnet50()]
-    if cfg == 6:        # further members of the paper's ImageNet ensembles: VGG, Xception, MobileNetV2 shapes
-        return [vgg(16), vgg(19), xception(size=299), mobilenet_v2()]
+    if cfg == 6:        # further members of the paper's ImageNet ensembles: VGG, ResNeXt, Xception, MobileNetV2 shapes
+        return [vgg(16), vgg(19), resnext50(), xception(size=299), mobilenet_v2()]
     raise ValueError("configuration must be 1..6")
 
 

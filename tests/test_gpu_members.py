@@ -53,6 +53,7 @@ SMALL = [
     ("efficientnet_b0", lambda: N.efficientnet(0, size=64, classes=200), 64),
     ("efficientnet_b2", lambda: N.efficientnet(2, size=64, classes=200), 64),
     ("inception_v3", lambda: N.inception_v3(size=107, classes=200), 107),
+    ("resnext50", lambda: N.resnext50(size=64, classes=200), 64),
     ("vgg16", lambda: N.vgg(16, size=64, classes=200), 64),
     ("xception", lambda: N.xception(size=107, classes=200), 107),
     ("mobilenet_v2", lambda: N.mobilenet_v2(size=64, classes=200), 64),

@@ -146,6 +146,11 @@ CONV_LAYERS = [
     (24, 40, 64, 96, 3, 1, "same", {"act": None}),             # filter-in-registers kernel: half-empty last channel tile
     (12, 12, 64, 128, 3, 1, "same", {"act": "silu"}),          # ... fewer tiles than workgroups
     (62, 62, 64, 32, 3, 1, "same", {}),                        # ... widest rows it takes, one channel group
+    (28, 28, 128, 128, 3, 1, "same", {"groups": 32}),          # grouped: 4 channels per group, 8 groups per dense block
+    (28, 28, 256, 256, 3, 2, "same", {"groups": 32}),          # ... 8 per group, stride 2
+    (14, 14, 512, 512, 3, 1, "same", {"groups": 32, "res": True}),
+    (7, 7, 1024, 1024, 3, 1, "same", {"groups": 32}),          # ... a group is a whole 32-channel block
+    (14, 14, 128, 256, 3, 1, "same", {"groups": 2}),           # ... groups wider than a block: 64 -> 128 each
     (14, 14, 256, 256, 1, 1, "same", {"res": True}),
     (14, 14, 256, 96, 3, 1, "same", {}),
     (20, 37, 64, 72, 3, 1, "same", {"act": None}),
