@@ -169,3 +169,35 @@ def test_invalid_descriptions_are_rejected():
     with pytest.raises(ens.EnsError) as e:
         ens.ens_spec_bytes(net, 8)
     assert e.value.status == ens.ENS_E_UNSUPPORTED
+
+
+def test_grouped_convolutions_in_descriptions():
+    """The plan accepts the grouped layers of the ResNeXt shape (its weights are the dense 32-channel
+    blocks, so the parameter block grows with the zeros between groups) and rejects group counts that
+    do not divide the channels, groups that do not tile a 32-channel block, and fp32 members."""
+    net = N.resnext50()
+    w, _ = ens.ens_spec_bytes(net, 8)
+    n_w = sum(p["size"] for p in net.params if p["role"] == "conv_w")
+    dense_blocks = sum(9 * op["cout"] * 32 for op in net.ops if op["kind"] == N.CONV and op["r"] > 1)
+    grouped = sum(9 * op["cout"] * op["cin"] // op["r"] for op in net.ops if op["kind"] == N.CONV and op["r"] > 1)
+    assert 2 * (n_w - grouped + dense_blocks) <= w <= 2 * (n_w - grouped + dense_blocks) + 4 * 40000 + 1024 * len(net.ops)
+
+    def one(cin, cout, groups, dtype="bf16"):
+        n = N.Net("g", 16, 16, 10, dtype=dtype)
+        t = n.conv(0, cin, 1)
+        t = n.conv(t, cout, 3, groups=groups)
+        n.fc(n.gap(t), 10)
+        return n
+
+    ens.ens_spec_bytes(one(64, 64, 4), 8)                       # 16 per group: two groups per block
+    ens.ens_spec_bytes(one(128, 256, 2), 8)                     # groups wider than a block
+    for bad, status in ((one(96, 96, 8), ens.ENS_E_UNSUPPORTED),          # 12 per group does not divide 32
+                        (one(64, 64, 4, dtype="fp32"), ens.ENS_E_UNSUPPORTED)):
+        with pytest.raises(ens.EnsError) as e:
+            ens.ens_spec_bytes(bad, 8)
+        assert e.value.status == status
+    bad = one(64, 64, 4)
+    bad.ops[1]["r"] = 5                                          # 5 groups do not divide 64 channels
+    with pytest.raises(ens.EnsError) as e:
+        ens.ens_spec_bytes(bad, 8)
+    assert e.value.status == ens.ENS_E_INVALID
