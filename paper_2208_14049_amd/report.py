@@ -7,7 +7,8 @@ the baseline that only tunes each member's batch size with one worker per member
 alone (worst-fit-decreasing at the default batch size) and Algorithm 1 followed by Algorithm 2 (bounded
 greedy over instances and batch sizes).  Every matrix is then timed again on the same request
 (images resident in HBM) and, for the planned one, with host-resident images (the PCIe-inclusive
-rate).  Prints one JSON object per line.  With --grid (config 5: one ResNet-50) it also times every
+rate), and the latency of single small requests (1 to 128 images) under the planned matrix.  Prints one
+JSON object per line.  With --grid (config 5: one ResNet-50) it also times every
 cell of the instances x batch-size grid.
 """
 import argparse
@@ -98,6 +99,22 @@ def main():
         overhead_share=round(results["greedy"] / ips_fake, 4))
     say(allocation_speedup_vs_bbs=round(results["greedy"] / results["bbs"], 3),
         wfd_vs_bbs=round(results["wfd"] / results["bbs"], 3))
+    # deploy mode on small requests (no request batching in front of the system): latency of one call
+    for small in (1, 8, 32, 128):
+        if small > n:
+            break
+        xs, ys = images[:small], out[:small]
+        E.ens_predict(xs, ys)
+        torch.cuda.synchronize()
+        lat = []
+        for _ in range(7):
+            t0 = time.perf_counter()
+            E.ens_predict(xs, ys)
+            torch.cuda.synchronize()
+            lat.append(time.perf_counter() - t0)
+        lat.sort()
+        say(strategy="greedy", request_images=small, latency_ms=round(1e3 * lat[len(lat) // 2], 3),
+            images_per_s=round(small / lat[len(lat) // 2], 1))
 
     if args.grid:
         best = (0.0, None)
