@@ -188,6 +188,14 @@ hipError_t launch_conv_f32(const ConvArgs& a, const ConvArgs* argv, int G, int n
     return hipGetLastError();
 }
 
+// Windowed kernels (pooling, depthwise) read every input row for several output rows.  Consecutive
+// workgroup ids go to different XCDs, each with its own L2; the ids are regrouped so that an XCD
+// works on one contiguous run of the output and finds the shared input rows in its own L2.
+__device__ __forceinline__ unsigned xcd_block() {
+    const unsigned n = gridDim.x, b = blockIdx.x, per = n / 8;
+    return b < per * 8 ? (b % 8) * per + b / 8 : b;
+}
+
 // ------------------------------------------------------------------ depthwise conv / pooling
 // MODE 0: depthwise convolution (+bias, activation), 1: max pool, 2: average pool over the
 // in-bounds part of the window.  bf16: one lane per (pixel, 8 channels); fp32: per element.
@@ -199,7 +207,7 @@ __global__ void window_kernel(const PoolArgs* __restrict__ argv, const int nb_) 
     a.nb = nb_;
     constexpr int V = BF16 ? 8 : 1;
     const unsigned cv = (unsigned)(a.c / V);
-    const unsigned idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const unsigned idx = xcd_block() * blockDim.x + threadIdx.x;
     const unsigned total = (unsigned)a.nb * (unsigned)(a.Ho * a.Wo) * cv;
     if (idx >= total) return;
     const unsigned pu = idx / cv;
@@ -269,7 +277,7 @@ template <int KH, int KW>
 __global__ void maxpool_bf16_kernel(const PoolArgs* __restrict__ argv, const int nb_) {
     const PoolArgs a = argv[blockIdx.z];
     const unsigned cv = (unsigned)(a.c / 8);
-    const unsigned idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const unsigned idx = xcd_block() * blockDim.x + threadIdx.x;
     const unsigned total = (unsigned)nb_ * (unsigned)(a.Ho * a.Wo) * cv;
     if (idx >= total) return;
     const unsigned pu = idx / cv;
@@ -308,7 +316,7 @@ template <int K>
 __global__ void dwconv_bf16_kernel(const PoolArgs* __restrict__ argv, const int nb_) {
     const PoolArgs a = argv[blockIdx.z];
     const unsigned cv = (unsigned)(a.c / 8);
-    const unsigned idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const unsigned idx = xcd_block() * blockDim.x + threadIdx.x;
     const unsigned total = (unsigned)nb_ * (unsigned)(a.Ho * a.Wo) * cv;
     if (idx >= total) return;
     const unsigned pu = idx / cv;
@@ -365,7 +373,7 @@ template <int K>
 __global__ void avgpool_bf16_kernel(const PoolArgs* __restrict__ argv, const int nb_) {
     const PoolArgs a = argv[blockIdx.z];
     const unsigned cv = (unsigned)(a.c / 8);
-    const unsigned idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const unsigned idx = xcd_block() * blockDim.x + threadIdx.x;
     const unsigned total = (unsigned)nb_ * (unsigned)(a.Ho * a.Wo) * cv;
     if (idx >= total) return;
     const unsigned pu = idx / cv;
