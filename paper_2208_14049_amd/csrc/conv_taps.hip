@@ -40,8 +40,10 @@ __device__ __forceinline__ void for_each_tap(F&& f, std::integer_sequence<int, T
 // The workgroups of one (member, channel tile) are persistent: each takes a share of the position
 // tiles (tile_walk: neighbouring tiles on one XCD).  The filter is loaded once; the window of the next tile arrives in a
 // second buffer while the matrix cores work on the current one and while its output leaves
-// (staged through the window buffer it has just finished with).
-template <int BP, int KH, int KW, int HROWS>
+// straight from the accumulators: the filter rows go to the matrix cores with bits 2 and 3 of the row
+// number swapped, which makes a lane's 16 results of a 32x32 block two runs of 8 consecutive channels
+// (two 16-byte stores); the bias is what the accumulators start from.
+template <int BP, int KH, int KW>
 __global__ __launch_bounds__(256) void conv_taps16_bf16(const ConvArgs* __restrict__ argv, const int nb_,
                                                         const int hrows, const int gh, const int gw) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
@@ -52,7 +54,6 @@ __global__ __launch_bounds__(256) void conv_taps16_bf16(const ConvArgs* __restri
     static_assert(TP == 1 || TP == 2, "32 or 64 positions per wave");
     constexpr int WBYTES = NT * BC * 32;             // the resident filter
     static_assert(WBYTES % 4096 == 0, "whole load instructions");
-    static_assert(HROWS >= 32 && BP % HROWS == 0, "output staging chunk");
 
     const int W1 = a.W + gw, H1 = a.H + gh;
     const int PP = nb_ * H1 * W1;
@@ -63,10 +64,11 @@ __global__ __launch_bounds__(256) void conv_taps16_bf16(const ConvArgs* __restri
     const int c0 = blockIdx.y * BC;
     const int hbytes = hrows * 32, nhl = hrows / 128;            // bytes and load instructions per window
 
-    // LDS: filter | window 0 | window 1 | window tables 0, 1 | output tables 0, 1
+    // LDS: filter | window 0 | window 1 | window tables 0, 1 | output tables 0, 1 | bias of the 64 channels
     unsigned char* const halo = lds + WBYTES;
     int* const tbls = (int*)(halo + 2 * hbytes);     // window row -> input pixel index, -1: no pixel
     int* const owns = tbls + 2 * hrows;              // position of the tile -> output pixel index, -1: none
+    float* const biasl = (float*)(owns + 2 * BP);
     const int origin = a.pt * W1 + a.pl;             // window row 0 is tap (0, 0) of the tile's first position
 
     // ---- loads.  Offsets past the end of a buffer give zeros in LDS; 2^31 is past the end of
@@ -113,16 +115,22 @@ __global__ __launch_bounds__(256) void conv_taps16_bf16(const ConvArgs* __restri
         return;
     }
     make_tables(0, ptile);
+    if (t < BC) biasl[t] = c0 + t < a.cout ? a.bias[c0 + t] : 0.f;
     __syncthreads();
     issue_window(0);
-    TilePrefetch<BP, BC> pf;
-    pf.load(a, owns, c0, false);                                 // bias only: the launcher admits no residual here
 
-    // ---- fragment side: lane reads row (lane & 31) of each 32-row block, half lane / 32
+    // ---- fragment side: lane reads row (lane & 31) of each 32-row block, half lane / 32; of the
+    //      filter the row with bits 2 and 3 swapped
     const int lrow = lane & 31, lhalf = lane >> 5;
+    const int prow = (lrow & 0x13) | ((lrow & 4) << 1) | ((lrow & 8) >> 1);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
-    const uint32_t wa = lds0 + (uint32_t)(lrow * 32 + ((lhalf ^ ((lrow >> 3) & 1)) << 4));
+    const uint32_t wa = lds0 + (uint32_t)(prow * 32 + ((lhalf ^ ((prow >> 3) & 1)) << 4));
     const uint32_t lq = (uint32_t)(wp0 + lrow);
+    // this lane's output channels: cl + 32i + 16k + 0..7; out-of-range offsets drop a store
+    constexpr unsigned OOBS = 0x80000000u;
+    const int cl = c0 + 8 * lhalf;
+    const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)a.y.p, 0, (int)((unsigned)nb_ * (unsigned)(a.Ho * a.Wo) * (unsigned)a.y.stride * 2u), 0x00020000);
 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");             // filter and first window have landed: this wave's part,
     __builtin_amdgcn_s_barrier();                                // and with the barrier everybody's
@@ -139,13 +147,21 @@ __global__ __launch_bounds__(256) void conv_taps16_bf16(const ConvArgs* __restri
             issue_window(buf ^ 1);
         }
 
+        // this tile's output pixels are read before the barrier below: the table is rewritten after it
+        int pout[TP];
+#pragma unroll
+        for (int j = 0; j < TP; j++) pout[j] = owns[buf * BP + wp0 + lrow + 32 * j];
         f32x16 acc[TC][TP];
 #pragma unroll
-        for (int i = 0; i < TC; i++)
+        for (int i = 0; i < TC; i++) {
+            const int cb = 32 * i + 8 * lhalf;
+            const f32x4 bq[4] = {*(const f32x4*)&biasl[cb], *(const f32x4*)&biasl[cb + 4],
+                                 *(const f32x4*)&biasl[cb + 16], *(const f32x4*)&biasl[cb + 20]};
 #pragma unroll
             for (int j = 0; j < TP; j++)
 #pragma unroll
-                for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
+                for (int v = 0; v < 16; v++) acc[i][j][v] = bq[v >> 2][v & 3];
+        }
         const uint32_t halo0 = lds0 + WBYTES + (uint32_t)(buf * hbytes);
         bf16x8 wf[2][TC], xf[2][TP];
         auto read_frags = [&](auto tap_c, int b) {
@@ -179,18 +195,40 @@ __global__ __launch_bounds__(256) void conv_taps16_bf16(const ConvArgs* __restri
         read_frags(std::integral_constant<int, 0>{}, 0);
         for_each_tap(step, std::make_integer_sequence<int, NT>{});
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // the next window has landed (this wave's part)
-        __syncthreads();                                         // everybody's; and this window is free: it becomes the staging area
+        __syncthreads();                                         // everybody's; and this window and its tables are free
 
-        store_tile<BP, BC, TP, TC, HROWS>(a, acc, (float*)(halo + buf * hbytes), owns + buf * BP, pf, wp0, 0, false, 0,
-                                          nb_ * a.Ho * a.Wo);
-        __syncthreads();                                         // staging area and tables of this tile are free again
+        // ---- output: register v of a lane is channel cl + 32i + 16(v/8) + v%8 of its position
+        const bool relu = a.act == ACT_RELU;
+#pragma unroll
+        for (int i = 0; i < TC; i++)
+#pragma unroll
+            for (int j = 0; j < TP; j++)
+#pragma unroll
+                for (int k = 0; k < 2; k++) {
+                    float v[8];
+#pragma unroll
+                    for (int e = 0; e < 8; e++) v[e] = acc[i][j][8 * k + e];
+                    if (!relu) apply_act_n<8>(v, a.act);
+                    uint32_t o[4];
+#pragma unroll
+                    for (int q = 0; q < 4; q++) {
+                        o[q] = pack_bf16x2(v[2 * q], v[2 * q + 1]);
+                        // relu on the rounded pair: a negative bf16 is a negative 16-bit integer
+                        typedef short s16x2 __attribute__((ext_vector_type(2)));
+                        const s16x2 z = {0, 0};
+                        if (relu) o[q] = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2, o[q]), z));
+                    }
+                    const int co = cl + 32 * i + 16 * k;
+                    const unsigned yo = pout[j] >= 0 && co < a.cout ? (unsigned)(pout[j] * a.y.stride + a.y.c0 + co) * 2u : OOBS;
+                    __builtin_amdgcn_raw_buffer_store_b128(u32x4{o[0], o[1], o[2], o[3]}, yres, yo, 0, 0);
+                }
     }
 }
 
 // ---- host side -----------------------------------------------------------------------------
 constexpr int TAPS_LDS_LIMIT = 160 * 1024;
 
-struct TapsPlan { int bp, hrows, gh, gw, stage_rows, wgs; size_t bytes; };
+struct TapsPlan { int bp, hrows, gh, gw, wgs; size_t bytes; };
 constexpr int TAPS_CUS = 256;
 
 // Whether (and how) this layer runs here: 16 stored input channels, stride 1, a 2x2 or 4x4
@@ -202,14 +240,15 @@ static bool taps_plan(const ConvArgs& a, int nb, int G, TapsPlan* pl) {
     if (a.Ho > a.H || a.Wo > a.W) return false;      // output positions are a subset of the input raster
     pl->gh = a.pt > pb ? a.pt : (pb > 0 ? pb : 0);
     pl->gw = a.pl > pr ? a.pl : (pr > 0 ? pr : 0);
+    // 32-bit byte offsets into x and y, with 2^31 standing for 'outside'
     if ((long long)nb * a.H * a.W * a.x.stride * 2 >= 0x7FFFFF00LL) return false;
+    if ((long long)nb * a.Ho * a.Wo * a.y.stride * 2 >= 0x7FFFFF00LL) return false;
     const long long PP = (long long)nb * (a.H + pl->gh) * (a.W + pl->gw);
     if (PP >= (1LL << 24)) return false;
     pl->bp = 256;
     const int need = pl->bp + (a.kh - 1) * (a.W + pl->gw) + a.kw;
     pl->hrows = (need + 127) / 128 * 128;
-    pl->stage_rows = pl->hrows * 32 >= 64 * (64 + 4) * 4 ? 64 : 32;    // the staging area is one window buffer
-    pl->bytes = (size_t)a.kh * a.kw * 64 * 32 + 2 * ((size_t)pl->hrows * 32 + (size_t)pl->hrows * 4 + (size_t)pl->bp * 4);
+    pl->bytes = (size_t)a.kh * a.kw * 64 * 32 + 2 * ((size_t)pl->hrows * 32 + (size_t)pl->hrows * 4 + (size_t)pl->bp * 4) + 64 * 4;
     if (pl->bytes > (size_t)TAPS_LDS_LIMIT) return false;
     // As many workgroups as the chip holds at once, shared by the gang and the channel tiles, and
     // not one more: a workgroup that has to wait for a free slot starts its whole share of the
@@ -233,11 +272,11 @@ bool conv_taps_applicable(const ConvArgs& a, int nb) {
 
 const char* conv_taps_name(const ConvArgs& a) { return a.kh == 4 ? "conv_taps16_bf16<256,4x4>" : "conv_taps16_bf16<256,2x2>"; }
 
-template <int BP, int KH, int KW, int HROWS>
+template <int BP, int KH, int KW>
 static hipError_t launch_taps_variant(const ConvArgs& a, const ConvArgs* argv, int G, int nb, const TapsPlan& pl, hipStream_t s) {
     static bool raised = false;                                  // LDS above 64 KB has to be asked for once
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)&conv_taps16_bf16<BP, KH, KW, HROWS>,
+        hipError_t e = hipFuncSetAttribute((const void*)&conv_taps16_bf16<BP, KH, KW>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, TAPS_LDS_LIMIT);
         if (e != hipSuccess) return e;
         raised = true;
@@ -247,7 +286,7 @@ static hipError_t launch_taps_variant(const ConvArgs& a, const ConvArgs* argv, i
     if (const char* e = getenv("ENS_CONV_TAPS_WGS")) if (atoi(e) > 0) wgs = atoi(e);
 #endif
     const dim3 grid((unsigned)wgs, (unsigned)((a.cout + 63) / 64), G);
-    ENS_LAUNCH((conv_taps16_bf16<BP, KH, KW, HROWS>), grid, dim3(256), pl.bytes, s, argv, nb, pl.hrows, pl.gh, pl.gw);
+    ENS_LAUNCH((conv_taps16_bf16<BP, KH, KW>), grid, dim3(256), pl.bytes, s, argv, nb, pl.hrows, pl.gh, pl.gw);
     return hipGetLastError();
 }
 
@@ -255,12 +294,8 @@ hipError_t launch_conv_taps(const ConvArgs& a, const ConvArgs* argv, int G, int 
     TapsPlan pl;
     if (!taps_plan(a, nb, G, &pl)) return hipErrorInvalidValue;
     if (a.x.stride % 8 || a.x.c0 % 8 || a.y.stride % 8 || a.y.c0 % 8) return hipErrorInvalidValue;
-    if (a.kh == 4) {
-        if (pl.stage_rows == 64) return launch_taps_variant<256, 4, 4, 64>(a, argv, G, nb, pl, s);
-        return launch_taps_variant<256, 4, 4, 32>(a, argv, G, nb, pl, s);
-    }
-    if (pl.stage_rows == 64) return launch_taps_variant<256, 2, 2, 64>(a, argv, G, nb, pl, s);
-    return launch_taps_variant<256, 2, 2, 32>(a, argv, G, nb, pl, s);
+    if (a.kh == 4) return launch_taps_variant<256, 4, 4>(a, argv, G, nb, pl, s);
+    return launch_taps_variant<256, 2, 2>(a, argv, G, nb, pl, s);
 }
 
 }  // namespace ens
