@@ -172,20 +172,29 @@ CONV_LAYERS = [
 ]
 
 
-@pytest.mark.parametrize("case", CONV_LAYERS, ids=lambda c: "%dx%dx%d-%d-k%s-s%d" % (c[0], c[1], c[2], c[3], c[4], c[5]))
-def test_conv_layer_bf16(ens, case):
+# (case, images): the persistent kernels (input stem, 64-channel 3x3) only walk several tiles per
+# workgroup, on the per-XCD runs, when a batch has more tiles than the chip holds workgroups
+MANY_TILES = [
+    ((56, 56, 64, 128, 3, 1, "same", {}), 24),                  # 610 tiles for 256 workgroups per channel tile
+    ((56, 56, 64, 64, 3, 1, "same", {"res": True}), 40),        # 1016 tiles for 512 workgroups, residual
+    ((96, 96, 3, 64, 7, 2, "same", {}), 64),                    # stem: 601 tiles of 256 positions for 512 workgroups
+]
+
+
+@pytest.mark.parametrize("case,nb", [(c, 3) for c in CONV_LAYERS] + MANY_TILES,
+                         ids=lambda c: "%dx%dx%d-%d-k%s-s%d" % (c[0], c[1], c[2], c[3], c[4], c[5]) if isinstance(c, tuple) else "n%d" % c)
+def test_conv_layer_bf16(ens, case, nb):
     h, w, cin, cout, k, stride, pad, extra = case
     extra = dict(extra)
     with_res = extra.pop("res", False)
     net, t = layer_net(h, w, cin, lambda n, s: n.conv(s, cout, k, stride=stride, pad=pad,
                                                       res=s if with_res else None, **extra), "bf16")
-    nb = 3
     blobs, imgs = prepared([net], 11, nb, h, bf16=True)
     imgs = W.round_bf16(W.make_images(4, nb, h, w))
     E = ens.Ensemble([net], blobs)
     E.set_base_size(h, w)
     E.ens_debug_keep_tensors()
-    E.ens_set_alloc([[4]])
+    E.ens_set_alloc([[max(4, nb)]])
     E.ens_predict(imgs)
     got = E.ens_debug_tensor(0, t, net.tensors[t], nb)
     # feed the oracle the bf16 tensor the GPU layer actually read, so only this layer is compared
