@@ -173,8 +173,23 @@ static int build_launches(ens_handle* h, Gang& g) {
     const int G = (int)g.workers.size();
     const size_t slot = 512;                                     // bytes reserved per argument block
     static_assert(sizeof(ConvArgs) <= 512 && sizeof(PoolArgs) <= 512 && sizeof(SeArgs) <= 512, "argument block");
+    // Which pairs of convolutions run as one launch: planned as such, and both on the generic kernel
+    // for this batch size (its workgroups read every field of their own argument block).
+    std::vector<char> fused(m.ops.size(), 0);                    // 1: takes the next operation along, 2: taken along
+    for (size_t i = 0; i + 1 < m.ops.size(); i++) {
+        if (!m.ops[i].fuse_next) continue;
+        Launch a, b;
+        if (fill_args(h, leader, leader, G, m.ops[i], a) != ENS_OK || fill_args(h, leader, leader, G, m.ops[i + 1], b) != ENS_OK) continue;
+        const char* generic = "conv_igemm_bf16";
+        if (strncmp(conv_bf16_variant_name(a.conv, 2 * G), generic, strlen(generic)) == 0 &&
+            strncmp(conv_bf16_variant_name(b.conv, 2 * G), generic, strlen(generic)) == 0) {
+            fused[i] = 1;
+            fused[i + 1] = 2;
+        }
+    }
     std::vector<size_t> first_blk(m.ops.size() + 1, 0);          // argument blocks: G * sub per operation
-    for (size_t i = 0; i < m.ops.size(); i++) first_blk[i + 1] = first_blk[i] + (size_t)G * (m.ops[i].sub > 1 ? m.ops[i].sub : 1);
+    for (size_t i = 0; i < m.ops.size(); i++)
+        first_blk[i + 1] = first_blk[i] + (fused[i] == 2 ? 0 : (size_t)G * (fused[i] == 1 ? 2 : (m.ops[i].sub > 1 ? m.ops[i].sub : 1)));
     const size_t n_blk = first_blk[m.ops.size()];
     std::vector<char> host((n_blk + (size_t)G) * slot, 0);
     if (g.d_args && g.d_args_bytes < host.size()) { (void)hipFree(g.d_args); g.d_args = nullptr; }
@@ -182,11 +197,27 @@ static int build_launches(ens_handle* h, Gang& g) {
     g.launches.clear();
     for (size_t i = 0; i < m.ops.size(); i++) {
         Launch L;
-        const int nsub = m.ops[i].sub > 1 ? m.ops[i].sub : 1;
+        if (fused[i] == 2) {                                     // its argument blocks are in the previous launch
+            L.kind = L_SKIP;
+            g.launches.push_back(L);
+            continue;
+        }
+        const int nsub = fused[i] == 1 ? 2 : (m.ops[i].sub > 1 ? m.ops[i].sub : 1);
+        // the deeper of the two leads: the tile shape is chosen for the first argument block
+        const bool second_leads = fused[i] == 1 &&
+            m.ops[i + 1].op.kh * m.ops[i + 1].op.kw * m.ops[i + 1].cin_s > m.ops[i].op.kh * m.ops[i].op.kw * m.ops[i].cin_s;
+        double flop2 = 0, bytes2 = 0;
         for (int sub = nsub - 1; sub >= 0; sub--)
             for (int k = G - 1; k >= 0; k--) {                   // (k, sub) == (0, 0) last: L keeps the leader's first block
-                const int rc = fill_args(h, h->workers[g.workers[k]], leader, G, h->members[h->workers[g.workers[k]].member].ops[i], L, sub);
+                const Member& mk = h->members[h->workers[g.workers[k]].member];
+                const OpPlan& pl = fused[i] == 1 && (sub == 1) != second_leads ? mk.ops[i + 1] : mk.ops[i];
+                const int rc = fill_args(h, h->workers[g.workers[k]], leader, G, pl, L, fused[i] == 1 ? 0 : sub);
                 if (rc != ENS_OK) return rc;
+                if (fused[i] == 1) {                             // no split of the depth: the two would share one workspace
+                    L.conv.ws = nullptr;
+                    L.conv.ws_floats = 0;
+                    if (sub == 1) { flop2 = L.flop; bytes2 = L.bytes; }
+                }
                 char* dst = host.data() + (first_blk[i] + (size_t)sub * G + k) * slot;
                 switch (L.kind) {
                     case L_CONV: memcpy(dst, &L.conv, sizeof(ConvArgs)); break;
@@ -195,8 +226,15 @@ static int build_launches(ens_handle* h, Gang& g) {
                     case L_GAP: memcpy(dst, &L.gap, sizeof(GapArgs)); break;
                     case L_FC: memcpy(dst, &L.fc, sizeof(FcArgs)); break;
                     case L_SE: memcpy(dst, &L.se, sizeof(SeArgs)); break;
+                    default: break;
                 }
             }
+        if (fused[i] == 1) {
+            L.sub = 2;
+            L.flop += flop2;
+            L.bytes += bytes2;
+            L.klass = prof_class(h, conv_bf16_variant_name(L.conv, 2 * G));
+        }
         L.d_argv = g.d_args + first_blk[i] * slot;
         g.launches.push_back(L);
     }
@@ -211,6 +249,7 @@ static int build_launches(ens_handle* h, Gang& g) {
             case L_GAP: sz = sizeof(GapArgs); break;
             case L_FC: sz = sizeof(FcArgs); break;
             case L_SE: sz = sizeof(SeArgs); break;
+            default: break;
         }
         char* base = host.data() + first_blk[i] * slot;
         const size_t nb_i = first_blk[i + 1] - first_blk[i];
@@ -353,6 +392,7 @@ static hipError_t issue(const Launch& L, bool bf16, int G, int nb, long long fir
         case L_GAP: return launch_gap(L.gap, (const GapArgs*)L.d_argv, G, nb, bf16, s);
         case L_FC: return launch_fc(L.fc, (const FcArgs*)L.d_argv, G, nb, first, bf16, s);
         case L_SE: return launch_se(L.se, (const SeArgs*)L.d_argv, G, nb, bf16, s);
+        case L_SKIP: return hipSuccess;
     }
     return hipErrorInvalidValue;
 }
@@ -384,8 +424,10 @@ static int forward_batch(ens_handle* h, Gang& g, int64_t first, int nb) {
     }
     const double stage_bytes = (double)leader.batch * (h->base_h * h->base_w * 12.0 + (double)m.tensors[0].h * m.tensors[0].w * g.stage.dc * (m.bf16 ? 2 : 4));
     HIP_TRY(timed(h->stage_klass, 0.0, stage_bytes, [&] { return launch_stage(g.stage, g.d_stage, 1, nb, first, m.bf16, g.stream); }));
-    for (const Launch& L : g.launches)
+    for (const Launch& L : g.launches) {
+        if (L.kind == L_SKIP) continue;
         HIP_TRY(timed(L.klass, L.flop * G, L.bytes * G, [&] { return issue(L, m.bf16, G, nb, first, g.stream); }));
+    }
     for (int wi : g.workers) h->workers[wi].last_nb = nb;
     return ENS_OK;
 }

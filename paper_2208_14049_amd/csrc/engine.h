@@ -33,6 +33,10 @@ struct OpPlan {
     // each over cin_s input channels, weights [sub][sub_cout][kh*kw][cin_s] (zeros where a pair of
     // channels belongs to different groups).  Ordinary convolution: sub = 1, sub_cout = cout.
     int sub, sub_cout;
+    // This convolution and the next one read the same input slice and write same-sized outputs (a
+    // residual block's 3x3 / stride-2 branch and its 1x1 shortcut): one launch can run both as further
+    // argument blocks when both go to the generic kernel.  The second output counts as written here.
+    bool fuse_next;
 };
 
 struct Member {
@@ -65,7 +69,7 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out);
 // keep_all gives every tensor its own region (debug read-back of intermediate tensors).
 ArenaLayout plan_arena(const Member& m, int batch, bool keep_all = false);
 
-enum LaunchKind { L_CONV, L_DWCONV, L_POOL, L_GAP, L_FC, L_SE };
+enum LaunchKind { L_CONV, L_DWCONV, L_POOL, L_GAP, L_FC, L_SE, L_SKIP };   // L_SKIP: ran with the previous launch
 
 // One operation of a gang: host copy of the first member's arguments (validation, grid sizing)
 // and the device array holding the arguments of every member of the gang.

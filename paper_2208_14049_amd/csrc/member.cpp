@@ -128,6 +128,7 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         pl.alg_k = 0;
         pl.sub = 1;
         pl.sub_cout = o.cout;
+        pl.fuse_next = false;
         TensorInfo& ts = m.tensors[o.src];
         TensorInfo& td = m.tensors[o.dst];
         if (o.cin <= 0 || o.cout <= 0 || o.src_c0 < 0 || o.dst_c0 < 0) return ENS_E_INVALID;
@@ -140,6 +141,18 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         ts.last = std::max(ts.last, i);
         td.def = std::min(td.def, i);
         td.last = std::max(td.last, i);
+        // Two convolutions in a row over the same input slice with same-sized outputs may run as one launch:
+        // the second output is then written while the first operation runs.
+        if (m.bf16 && i > 0 && o.kind == ENS_OP_CONV && spec.ops[i - 1].kind == ENS_OP_CONV) {
+            const ens_op& q = spec.ops[i - 1];
+            const TensorInfo& tq = m.tensors[q.dst];
+            if (q.src == o.src && q.src_c0 == o.src_c0 && q.cin == o.cin && q.cout == o.cout && q.sh == o.sh && q.sw == o.sw &&
+                tq.h == td.h && tq.w == td.w && q.dst != o.dst && o.src != q.dst && o.res != q.dst && o.src != 0 &&
+                q.r <= 1 && o.r <= 1 && !q.pre && !o.pre && !m.ops[i - 1].fuse_next && (i < 2 || !m.ops[i - 2].fuse_next)) {
+                m.ops[i - 1].fuse_next = true;
+                td.def = std::min(td.def, i - 1);
+            }
+        }
         const bool windowed = o.kind == ENS_OP_CONV || o.kind == ENS_OP_DWCONV || o.kind == ENS_OP_MAXPOOL ||
                               o.kind == ENS_OP_AVGPOOL;
         if (windowed) {

@@ -220,6 +220,41 @@ def test_conv_layer_bf16(ens, case, nb):
     assert err.mean() <= 2.0 ** -8 * scale, (err.mean(), scale, kk)
 
 
+def test_two_convolutions_in_one_launch(ens):
+    """A residual block's strided 3x3 convolution and its 1x1 shortcut read the same tensor and write
+    same-sized outputs: the engine runs them as one launch (argument blocks of both).  Both outputs
+    are read back and compared with the oracle; so is a pair the engine must not put together (the
+    second reads the first)."""
+    n = N.Net("pair", 28, 28, 8, dtype="bf16")
+    t = n.conv(0, 64, 3)
+    a = n.conv(t, 128, 1, stride=2, act=None)                    # shortcut
+    b = n.conv(t, 128, 3, stride=2)                              # branch, same input: one launch with a
+    c = n.conv(b, 128, 3, res=a)
+    d = n.conv(c, 128, 1, act=None)
+    e = n.conv(d, 128, 1)                                        # reads d: not a pair
+    n.fc(n.gap(e), 8)
+    nb = 5
+    blobs, _ = prepared([n], 13, nb, 28, bf16=True)
+    imgs = W.round_bf16(W.make_images(6, nb, 28, 28))
+    E = ens.Ensemble([n], blobs)
+    E.set_base_size(28, 28)
+    E.ens_debug_keep_tensors()
+    E.ens_set_alloc([[8]])
+    E.ens_predict(imgs)
+    got = {x: E.ens_debug_tensor(0, x, n.tensors[x], nb) for x in (a, b, c, e)}
+    E.ens_set_profiling(1)
+    E.ens_predict(imgs)
+    conv_launches = sum(k["launches"] for k in E.ens_profile() if k["name"].startswith("conv"))
+    E.close()
+    assert conv_launches == 5, conv_launches                   # six convolutions, one pair
+    for x in (a, b, c, e):
+        ref = oracle_tensor(n, blobs[0], imgs, x)
+        scale = np.sqrt(np.mean(ref ** 2)) + 1e-6
+        err = np.abs(got[x] - ref)
+        assert err.max() <= 0.05 * scale + 2.0 ** -6 * np.abs(ref).max(), (x, err.max(), scale)
+        assert err.mean() <= 2.0 ** -6 * scale, (x, err.mean(), scale)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 def test_memory_bound_layers(ens, dtype):
     """Depthwise 3x3 / 5x5 (strides 1 and 2), squeeze-excite, max / average pooling into channel
