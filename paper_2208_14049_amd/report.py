@@ -41,7 +41,7 @@ def timed_predict(E, images, out, repeats):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", type=int, default=2, help="configuration 2..5")
+    ap.add_argument("--config", type=int, default=2, help="configuration 2..9 (7, 8, 9: the paper's IMN1, IMN4, IMN12 ensembles as shapes)")
     ap.add_argument("--images", type=int, default=1024)
     ap.add_argument("--slots", type=int, default=2, help="instance slots (rows of the matrix) the greedy search may use")
     ap.add_argument("--max-neighs", type=int, default=32)

@@ -559,7 +559,7 @@ def mobilenet_v2(classes=1000, size=224, dtype="bf16"):
 
 
 def config_members(cfg):
-    """Members of workload configuration `cfg` (1-5) as a list of Net."""
+    """Members of workload configuration `cfg` (1-9) as a list of Net."""
     if cfg == 1:
         return [tiny_a(), tiny_b()]
     if cfg == 2:
@@ -575,7 +575,15 @@ def config_members(cfg):
         return [resnet50()]
     if cfg == 6:        # further members of the paper's ImageNet ensembles: VGG, ResNeXt, Xception, MobileNetV2 shapes
         return [vgg(16), vgg(19), resnext50(), xception(size=299), mobilenet_v2()]
-    raise ValueError("configuration must be 1..6")
+    # the paper's own ImageNet ensembles (section "Experimental settings"), as shapes with synthetic weights
+    if cfg == 7:        # IMN1
+        return [resnet152()]
+    if cfg == 8:        # IMN4
+        return [resnet50(), resnet101(), densenet121(), vgg(19)]
+    if cfg == 9:        # IMN12
+        return [resnet152(), resnet50(), resnet101(), densenet121(), vgg(19), resnet18(), resnet34(), resnext50(),
+                inception_v3(size=299), xception(size=299), vgg(16), mobilenet_v2()]
+    raise ValueError("configuration must be 1..9")
 
 
-BASE_SIZE = {1: 32, 2: 224, 3: 224, 4: 224, 5: 224, 6: 224}
+BASE_SIZE = {1: 32, 2: 224, 3: 224, 4: 224, 5: 224, 6: 224, 7: 224, 8: 224, 9: 224}
