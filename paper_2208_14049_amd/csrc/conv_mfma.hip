@@ -84,6 +84,9 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restric
     const int n_ptiles = (P + BP - 1) / BP, n_ctiles = (a.cout + BC - 1) / BC;
     int ptile, ctile;
     tile_of_block(n_ptiles, n_ctiles, &ptile, &ctile);
+    // a launch may carry argument blocks of a convolution with more output channels than this one
+    // (two operations in one launch): the workgroups past this block's own tiles have nothing to do
+    if (ptile >= n_ptiles) return;
     const int p0 = ptile * BP, c0 = ctile * BC;
 
     if constexpr (PRE) {

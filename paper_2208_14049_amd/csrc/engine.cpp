@@ -203,9 +203,12 @@ static int build_launches(ens_handle* h, Gang& g) {
             continue;
         }
         const int nsub = fused[i] == 1 ? 2 : (m.ops[i].sub > 1 ? m.ops[i].sub : 1);
-        // the deeper of the two leads: the tile shape is chosen for the first argument block
+        // the one with more output channels leads (the grid is sized for the first argument block), the
+        // deeper of two equals (so is the tile shape)
         const bool second_leads = fused[i] == 1 &&
-            m.ops[i + 1].op.kh * m.ops[i + 1].op.kw * m.ops[i + 1].cin_s > m.ops[i].op.kh * m.ops[i].op.kw * m.ops[i].cin_s;
+            (m.ops[i + 1].sub_cout > m.ops[i].sub_cout ||
+             (m.ops[i + 1].sub_cout == m.ops[i].sub_cout &&
+              m.ops[i + 1].op.kh * m.ops[i + 1].op.kw * m.ops[i + 1].cin_s > m.ops[i].op.kh * m.ops[i].op.kw * m.ops[i].cin_s));
         double flop2 = 0, bytes2 = 0;
         for (int sub = nsub - 1; sub >= 0; sub--)
             for (int k = G - 1; k >= 0; k--) {                   // (k, sub) == (0, 0) last: L keeps the leader's first block

@@ -33,9 +33,10 @@ struct OpPlan {
     // each over cin_s input channels, weights [sub][sub_cout][kh*kw][cin_s] (zeros where a pair of
     // channels belongs to different groups).  Ordinary convolution: sub = 1, sub_cout = cout.
     int sub, sub_cout;
-    // This convolution and the next one read the same input slice and write same-sized outputs (a
-    // residual block's 3x3 / stride-2 branch and its 1x1 shortcut): one launch can run both as further
-    // argument blocks when both go to the generic kernel.  The second output counts as written here.
+    // This convolution and the next one read the same input slice and write outputs of the same height
+    // and width (a residual block's 3x3 / stride-2 branch and its 1x1 shortcut, the 1x1 heads of an
+    // inception module's branches): one launch can run both as further argument blocks when both go
+    // to the generic kernel.  The second output counts as written here.
     bool fuse_next;
 };
 

@@ -146,8 +146,9 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         if (m.bf16 && i > 0 && o.kind == ENS_OP_CONV && spec.ops[i - 1].kind == ENS_OP_CONV) {
             const ens_op& q = spec.ops[i - 1];
             const TensorInfo& tq = m.tensors[q.dst];
-            if (q.src == o.src && q.src_c0 == o.src_c0 && q.cin == o.cin && q.cout == o.cout && q.sh == o.sh && q.sw == o.sw &&
-                tq.h == td.h && tq.w == td.w && q.dst != o.dst && o.src != q.dst && o.res != q.dst && o.src != 0 &&
+            if (q.src == o.src && q.src_c0 == o.src_c0 && q.cin == o.cin && q.sh == o.sh && q.sw == o.sw &&
+                tq.h == td.h && tq.w == td.w && o.src != q.dst && o.res != q.dst && o.src != 0 &&
+                (q.dst != o.dst || q.dst_c0 + q.cout <= o.dst_c0 || o.dst_c0 + o.cout <= q.dst_c0) &&   // disjoint outputs
                 q.r <= 1 && o.r <= 1 && !q.pre && !o.pre && !m.ops[i - 1].fuse_next && (i < 2 || !m.ops[i - 2].fuse_next)) {
                 m.ops[i - 1].fuse_next = true;
                 td.def = std::min(td.def, i - 1);

@@ -232,6 +232,10 @@ def test_two_convolutions_in_one_launch(ens):
     c = n.conv(b, 128, 3, res=a)
     d = n.conv(c, 128, 1, act=None)
     e = n.conv(d, 128, 1)                                        # reads d: not a pair
+    cat = n.tensor(14, 14, 64 + 96)                              # two branch heads into slices of one tensor,
+    n.conv(e, 64, 1, dst=(cat, 0))                               # different widths: a pair again
+    n.conv(e, 96, 1, dst=(cat, 64), act=None)
+    e = n.conv(cat, 128, 1)
     n.fc(n.gap(e), 8)
     nb = 5
     blobs, _ = prepared([n], 13, nb, 28, bf16=True)
@@ -241,13 +245,13 @@ def test_two_convolutions_in_one_launch(ens):
     E.ens_debug_keep_tensors()
     E.ens_set_alloc([[8]])
     E.ens_predict(imgs)
-    got = {x: E.ens_debug_tensor(0, x, n.tensors[x], nb) for x in (a, b, c, e)}
+    got = {x: E.ens_debug_tensor(0, x, n.tensors[x], nb) for x in (a, b, c, cat, e)}
     E.ens_set_profiling(1)
     E.ens_predict(imgs)
     conv_launches = sum(k["launches"] for k in E.ens_profile() if k["name"].startswith("conv"))
     E.close()
-    assert conv_launches == 5, conv_launches                   # six convolutions, one pair
-    for x in (a, b, c, e):
+    assert conv_launches == 7, conv_launches                   # nine convolutions, two pairs
+    for x in (a, b, c, cat, e):
         ref = oracle_tensor(n, blobs[0], imgs, x)
         scale = np.sqrt(np.mean(ref ** 2)) + 1e-6
         err = np.abs(got[x] - ref)
