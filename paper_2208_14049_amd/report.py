@@ -8,7 +8,8 @@ alone (worst-fit-decreasing at the default batch size) and Algorithm 1 followed 
 greedy over instances and batch sizes).  Every matrix is then timed again on the same request
 (images resident in HBM) and, for the planned one, with host-resident images (the PCIe-inclusive
 rate), and the latency of single small requests (1 to 128 images) under the planned matrix.  Prints one
-JSON object per line.  With --grid (config 5: one ResNet-50) it also times every
+JSON object per line.  With --member M only that member runs, alone at --batch, and its kernel classes
+are listed.  With --grid (config 5: one ResNet-50) it also times every
 cell of the instances x batch-size grid.
 """
 import argparse
@@ -51,6 +52,9 @@ def main():
     ap.add_argument("--n-calib", type=int, default=512)
     ap.add_argument("--repeats", type=int, default=3)
     ap.add_argument("--grid", action="store_true", help="time every (instances, batch size) cell (single-member configs)")
+    ap.add_argument("--member", type=int, default=-1,
+                    help="run only this member of the configuration, alone, at --batch, and print its per-kernel times")
+    ap.add_argument("--batch", type=int, default=64)
     args = ap.parse_args()
 
     import torch
@@ -61,6 +65,8 @@ def main():
     ens.lib()
 
     nets = N.config_members(args.config)
+    if args.member >= 0:
+        nets = [nets[args.member]]
     blobs = [W.quantise_weights_bf16(n, W.make_blob(n, synth.BASE_SEED, i)) if n.dtype == "bf16"
              else W.make_blob(n, synth.BASE_SEED, i) for i, n in enumerate(nets)]
     E = ens.Ensemble(nets, blobs)
@@ -72,6 +78,20 @@ def main():
     common = dict(n_calib=args.n_calib, repeats=2, verbose=1)
     say = lambda **kw: print(json.dumps(kw), flush=True)
     say(config=args.config, members=[m.name for m in nets], images=n)
+    if args.member >= 0:                                         # one member alone: throughput and kernel classes
+        E.ens_set_alloc([[args.batch]])
+        ips = timed_predict(E, images, out, args.repeats)
+        say(member=nets[0].name, batch=args.batch, images_per_s=round(ips, 1),
+            tflops=round(2.0 * nets[0].macs() * ips / 1e12, 1))
+        E.ens_set_profiling(1)
+        E.ens_predict(images, out)
+        for c in sorted(E.ens_profile(), key=lambda c: -c["ms"]):
+            if c["launches"]:
+                say(kernel=c["name"], ms=round(c["ms"], 3), launches=c["launches"],
+                    us_per_launch=round(1e3 * c["ms"] / c["launches"], 1),
+                    tflops=round(c["flop"] / max(c["ms"], 1e-9) / 1e9, 1), gbs=round(c["bytes"] / max(c["ms"], 1e-9) / 1e6, 1))
+        E.close()
+        return
 
     results = {}
     db = dict(default_batch=args.default_batch) if args.default_batch > 0 else {}
