@@ -235,6 +235,14 @@ bool conv_wreg_applicable(const ConvArgs& a, int nb, int G);
 const char* conv_wreg_name(const ConvArgs& a);
 hipError_t launch_conv_wreg(const ConvArgs& a, const ConvArgs* argv, int G, int nb, hipStream_t s);
 
+// A residual bottleneck (1x1, 3x3, 1x1 with the residual) as one kernel, the two tensors in between
+// held in LDS; defined in conv_bneck.hip.  argv: G blocks of the first convolution, then G of the
+// second, then G of the third.
+bool conv_bneck_applicable(const ConvArgs& a1, const ConvArgs& a2, const ConvArgs& a3, int nb, int G);
+const char* conv_bneck_name(const ConvArgs& a1);
+hipError_t launch_conv_bneck(const ConvArgs& a1, const ConvArgs& a2, const ConvArgs& a3, const ConvArgs* argv, int G, int nb,
+                             hipStream_t s);
+
 // 3x3 stride-1 kernel with the input window resident in LDS; defined in conv_halo.hip.
 // conv_halo_pick returns the variant that runs the layer, or -1 when the generic kernel does.
 int conv_halo_pick(const ConvArgs& a, int nb, int G);

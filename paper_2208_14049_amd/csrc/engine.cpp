@@ -29,6 +29,10 @@ using namespace ens;
 namespace ens {
 
 const char* conv_bf16_variant_name(const ConvArgs& a, int G);
+bool conv_bneck_applicable(const ConvArgs& a1, const ConvArgs& a2, const ConvArgs& a3, int nb, int G);
+const char* conv_bneck_name(const ConvArgs& a1);
+hipError_t launch_conv_bneck(const ConvArgs& a1, const ConvArgs& a2, const ConvArgs& a3, const ConvArgs* argv, int G, int nb,
+                             hipStream_t s);
 
 static int prof_class(ens_handle* h, const std::string& name) {
     for (size_t i = 0; i < h->prof.size(); i++)
@@ -173,11 +177,25 @@ static int build_launches(ens_handle* h, Gang& g) {
     const int G = (int)g.workers.size();
     const size_t slot = 512;                                     // bytes reserved per argument block
     static_assert(sizeof(ConvArgs) <= 512 && sizeof(PoolArgs) <= 512 && sizeof(SeArgs) <= 512, "argument block");
+    // Which bottlenecks run as one kernel: planned as such and within the kernel's shapes at this batch
+    // size.  The tensors in between are then not written (not wanted when they are to be read back).
+    std::vector<char> chain(m.ops.size(), 0);                    // 1: runs the next two operations too, 2: run by it
+    for (size_t i = 0; i + 2 < m.ops.size(); i++) {
+        if (!m.ops[i].fuse_chain || h->keep_tensors) continue;
+        Launch a, b, c;
+        if (fill_args(h, leader, leader, G, m.ops[i], a) != ENS_OK || fill_args(h, leader, leader, G, m.ops[i + 1], b) != ENS_OK ||
+            fill_args(h, leader, leader, G, m.ops[i + 2], c) != ENS_OK)
+            continue;
+        if (conv_bneck_applicable(a.conv, b.conv, c.conv, leader.batch, G)) {
+            chain[i] = 1;
+            chain[i + 1] = chain[i + 2] = 2;
+        }
+    }
     // Which pairs of convolutions run as one launch: planned as such, and both on the generic kernel
     // for this batch size (its workgroups read every field of their own argument block).
     std::vector<char> fused(m.ops.size(), 0);                    // 1: takes the next operation along, 2: taken along
     for (size_t i = 0; i + 1 < m.ops.size(); i++) {
-        if (!m.ops[i].fuse_next) continue;
+        if (!m.ops[i].fuse_next || chain[i] || chain[i + 1]) continue;   // a bottleneck kernel takes precedence
         Launch a, b;
         if (fill_args(h, leader, leader, G, m.ops[i], a) != ENS_OK || fill_args(h, leader, leader, G, m.ops[i + 1], b) != ENS_OK) continue;
         const char* generic = "conv_igemm_bf16";
@@ -189,7 +207,8 @@ static int build_launches(ens_handle* h, Gang& g) {
     }
     std::vector<size_t> first_blk(m.ops.size() + 1, 0);          // argument blocks: G * sub per operation
     for (size_t i = 0; i < m.ops.size(); i++)
-        first_blk[i + 1] = first_blk[i] + (fused[i] == 2 ? 0 : (size_t)G * (fused[i] == 1 ? 2 : (m.ops[i].sub > 1 ? m.ops[i].sub : 1)));
+        first_blk[i + 1] = first_blk[i] + (fused[i] == 2 || chain[i] == 2 ? 0
+                                           : (size_t)G * (chain[i] == 1 ? 3 : fused[i] == 1 ? 2 : (m.ops[i].sub > 1 ? m.ops[i].sub : 1)));
     const size_t n_blk = first_blk[m.ops.size()];
     std::vector<char> host((n_blk + (size_t)G) * slot, 0);
     if (g.d_args && g.d_args_bytes < host.size()) { (void)hipFree(g.d_args); g.d_args = nullptr; }
@@ -197,8 +216,37 @@ static int build_launches(ens_handle* h, Gang& g) {
     g.launches.clear();
     for (size_t i = 0; i < m.ops.size(); i++) {
         Launch L;
-        if (fused[i] == 2) {                                     // its argument blocks are in the previous launch
+        if (fused[i] == 2 || chain[i] == 2) {                    // its argument blocks are in an earlier launch
             L.kind = L_SKIP;
+            g.launches.push_back(L);
+            continue;
+        }
+        if (chain[i] == 1) {                                     // G blocks of each of the three convolutions
+            double flop = 0, wbytes = 0;
+            for (int sub = 2; sub >= 0; sub--)
+                for (int k = G - 1; k >= 0; k--) {
+                    const Member& mk = h->members[h->workers[g.workers[k]].member];
+                    const int rc = fill_args(h, h->workers[g.workers[k]], leader, G, mk.ops[i + sub], L);
+                    if (rc != ENS_OK) return rc;
+                    L.conv.ws = nullptr;
+                    L.conv.ws_floats = 0;
+                    if (k == 0) {
+                        flop += L.flop;
+                        wbytes += 2.0 * L.conv.kh * L.conv.kw * L.conv.cin * L.conv.cout;
+                        if (sub == 2) L.conv3 = L.conv;
+                        if (sub == 1) L.conv2 = L.conv;
+                    }
+                    memcpy(host.data() + (first_blk[i] + (size_t)sub * G + k) * slot, &L.conv, sizeof(ConvArgs));
+                }
+            // algorithmic bytes of the block: input once (it is the residual too, unless that is another tensor), output, weights
+            const double px = (double)leader.batch * L.conv.H * L.conv.W;
+            const bool own_res = L.conv3.res.p && L.conv3.res.p != L.conv.x.p;
+            L.kind = L_BNECK;
+            L.sub = 3;
+            L.flop = flop;
+            L.bytes = px * 2.0 * (L.conv.cin + L.conv3.cout * (own_res ? 2 : 1)) + wbytes;
+            L.klass = prof_class(h, conv_bneck_name(L.conv));
+            L.d_argv = g.d_args + first_blk[i] * slot;
             g.launches.push_back(L);
             continue;
         }
@@ -246,7 +294,8 @@ static int build_launches(ens_handle* h, Gang& g) {
         const Launch& L = g.launches[i];
         size_t sz = 0;
         switch (L.kind) {
-            case L_CONV: sz = sizeof(ConvArgs); break;
+            case L_CONV:
+            case L_BNECK: sz = sizeof(ConvArgs); break;
             case L_DWCONV:
             case L_POOL: sz = sizeof(PoolArgs); break;
             case L_GAP: sz = sizeof(GapArgs); break;
@@ -395,6 +444,7 @@ static hipError_t issue(const Launch& L, bool bf16, int G, int nb, long long fir
         case L_GAP: return launch_gap(L.gap, (const GapArgs*)L.d_argv, G, nb, bf16, s);
         case L_FC: return launch_fc(L.fc, (const FcArgs*)L.d_argv, G, nb, first, bf16, s);
         case L_SE: return launch_se(L.se, (const SeArgs*)L.d_argv, G, nb, bf16, s);
+        case L_BNECK: return launch_conv_bneck(L.conv, L.conv2, L.conv3, (const ConvArgs*)L.d_argv, G, nb, s);
         case L_SKIP: return hipSuccess;
     }
     return hipErrorInvalidValue;

@@ -129,6 +129,7 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         pl.sub = 1;
         pl.sub_cout = o.cout;
         pl.fuse_next = false;
+        pl.fuse_chain = false;
         TensorInfo& ts = m.tensors[o.src];
         TensorInfo& td = m.tensors[o.dst];
         if (o.cin <= 0 || o.cout <= 0 || o.src_c0 < 0 || o.dst_c0 < 0) return ENS_E_INVALID;
@@ -329,6 +330,37 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         m.ops.push_back(pl);
     }
     if (!seen_out) return ENS_E_INVALID;
+    // Residual bottlenecks: 1x1, 3x3 (stride 1, padding 1), 1x1 in a row, each reading what the one
+    // before wrote, with nobody else reading or writing the two tensors in between.  One kernel can
+    // run all three (decided per batch size when the launches are built); the block's output then
+    // counts as written from the first of them on.
+    if (m.bf16) {
+        std::vector<int> uses(m.tensors.size(), 0);              // readers and writers of every tensor
+        for (int i = 0; i < spec.n_ops; i++) {
+            const ens_op& o = spec.ops[i];
+            uses[o.src]++;
+            uses[o.dst]++;
+            if (o.kind == ENS_OP_CONV && o.res >= 0) uses[o.res]++;
+        }
+        auto plain = [](const ens_op& o, int k, int pad) {
+            return o.kind == ENS_OP_CONV && o.kh == k && o.kw == k && o.sh == 1 && o.sw == 1 && o.pt == pad && o.pl == pad &&
+                   o.r <= 1 && !o.pre;
+        };
+        for (int i = 0; i + 2 < spec.n_ops; i++) {
+            const ens_op &p = spec.ops[i], &q = spec.ops[i + 1], &o = spec.ops[i + 2];
+            if (!plain(p, 1, 0) || !plain(q, 3, 1) || !plain(o, 1, 0) || p.res >= 0 || q.res >= 0) continue;
+            if (q.src != p.dst || q.src_c0 != p.dst_c0 || q.cin != p.cout || o.src != q.dst || o.src_c0 != q.dst_c0 || o.cin != q.cout) continue;
+            if (p.cout != q.cout || (p.cout != 64 && p.cout != 128)) continue;
+            if (uses[p.dst] != 2 || uses[q.dst] != 2 || p.dst == q.dst) continue;
+            if (p.src == 0 || o.dst == p.src || o.dst == p.dst || o.dst == q.dst || o.res == p.dst || o.res == q.dst) continue;
+            if (m.tensors[p.dst].c != p.cout || m.tensors[q.dst].c != q.cout) continue;      // whole tensors, not slices
+            if (m.ops[i].fuse_next || m.ops[i + 1].fuse_next || m.ops[i + 2].fuse_next) continue;
+            if (i > 1 && m.ops[i - 2].fuse_chain) continue;      // chains do not overlap
+            if (i > 0 && m.ops[i - 1].fuse_chain) continue;
+            m.ops[i].fuse_chain = true;
+            m.tensors[o.dst].def = std::min(m.tensors[o.dst].def, i);
+        }
+    }
     if (stem_op >= 0) {                                          // tensor 0 as the staging kernel writes it
         m.stem_s2d = true;
         TensorInfo& t0 = m.tensors[0];

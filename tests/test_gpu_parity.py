@@ -259,6 +259,60 @@ def test_two_convolutions_in_one_launch(ens):
         assert err.mean() <= 2.0 ** -6 * scale, (x, err.mean(), scale)
 
 
+# (C, H, W, cin, cout, residual, activation of the last convolution, members in the gang, images, batch)
+BOTTLENECKS = [
+    (64, 24, 24, 256, 256, "input", "relu", 1, 56, 64),        # identity block, short last batch
+    (64, 24, 24, 256, 256, "input", "relu", 2, 28, 28),        # two members in one launch
+    (64, 20, 30, 64, 128, "branch", "relu", 1, 51, 51),        # projection shortcut, non-square, one channel pass
+    (64, 9, 62, 96, 384, None, None, 1, 53, 53),               # widest raster the window holds, no residual, no activation
+    (128, 28, 28, 128, 128, "input", "relu", 1, 40, 40),
+    (128, 30, 30, 64, 256, "branch", "silu", 1, 35, 35),
+    (128, 13, 17, 256, 256, "input", None, 2, 66, 66),
+]
+
+
+@pytest.mark.parametrize("case", BOTTLENECKS, ids=lambda c: "c%d_%dx%d_%d-%d_%s_g%d" % (c[0], c[1], c[2], c[3], c[4], c[5], c[7]))
+def test_bottleneck_in_one_kernel(ens, case):
+    """A residual bottleneck (1x1, 3x3, 1x1 with the residual) runs as one kernel that keeps the two
+    tensors in between on chip.  The block's output is read back and compared with the oracle element
+    by element, for each member of the gang; the profile says that the fused kernel ran."""
+    C, H, Wd, cin, cout, res, act3, G, n_img, batch = case
+    nets = []
+    for g in range(G):
+        n = N.Net("bneck%d" % g, H, Wd, 8, dtype="bf16")
+        x = n.conv(0, cin, 3)
+        idt = None
+        if res == "input":
+            idt = x
+        elif res == "branch":
+            idt = n.conv(x, cout, 1, act=None)
+            x = n.conv(x, cin, 1)                                # keeps the shortcut and the block's head apart
+        u = n.conv(x, C, 1)
+        u = n.conv(u, C, 3)
+        y = n.conv(u, cout, 1, res=idt, act=act3)
+        n.fc(n.gap(y), 8)
+        nets.append(n)
+    blobs = [W.quantise_weights_bf16(n, W.make_blob(n, 31, i)) for i, n in enumerate(nets)]
+    imgs = W.round_bf16(W.make_images(32, n_img, H, Wd))
+    E = ens.Ensemble(nets, blobs)
+    E.set_base_size(H, Wd)
+    E.ens_set_alloc([[batch] * G])
+    E.ens_set_profiling(1)
+    E.ens_predict(imgs)
+    ran = {k["name"]: k["launches"] for k in E.ens_profile() if k["launches"]}
+    # the block's output is alive until the pooling that ends the network: still there after the pass
+    got = [E.ens_debug_tensor(g, y, nets[g].tensors[y], n_img) for g in range(G)]
+    E.close()
+    assert ran.get("bottleneck_bf16<c%d>" % C) == 1, ran
+    for g in range(G):
+        ref = oracle_tensor(nets[g], blobs[g], imgs, y)
+        scale = np.sqrt(np.mean(ref ** 2)) + 1e-6
+        err = np.abs(got[g] - ref)
+        # three bf16 layers in a row: roundings of the two middle tensors carry into the third
+        assert err.max() <= 0.05 * scale + 2.0 ** -6 * np.abs(ref).max(), (g, err.max(), scale)
+        assert err.mean() <= 2.0 ** -6 * scale, (g, err.mean(), scale)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 def test_memory_bound_layers(ens, dtype):
     """Depthwise 3x3 / 5x5 (strides 1 and 2), squeeze-excite, max / average pooling into channel
