@@ -7,19 +7,23 @@
 // Pixels are numbered in the padded raster of conv_halo.hip (one extra column per row, one extra
 // row per image, treated as zeros), so that tap (dh, dw) of any position lies dh * (W + 1) + dw
 // positions further on.  A workgroup of four wavefronts owns 128 consecutive positions and works
-// in three phases, all fed through one two-stage ring of weight tiles (8 KB each) that runs on
-// across the phase boundaries:
+// in three phases:
 //   1. t1 = act(W1 x + b1) for the R positions the 3x3 taps of the tile reach (the tile and W + 2
-//      positions either side), 32 input channels at a time through a two-stage ring of input
-//      chunks; the result goes to LDS as bf16 in the layout the 3x3 kernel reads its window in,
-//      with zeros at the positions that hold no pixel (the 3x3 padding is zero in t1, not act(b1));
+//      positions either side), 32 input channels at a time through a three-deep ring of input
+//      chunks filled by asynchronous global-to-LDS loads; the result goes to LDS as bf16 in the
+//      layout the 3x3 kernel reads its window in, with zeros at the positions that hold no pixel
+//      (the 3x3 padding is zero in t1, not act(b1));
 //   2. t2 = act(W2 * t1 + b2), nine taps over the window in LDS; the result replaces t1 in LDS;
 //   3. y = act(W3 t2 + b3 + residual), 128 output channels at a time, stored from the accumulators.
+// The weights do not pass through LDS: the member keeps a second copy of them in the order of the
+// matrix-core operands (blocks of 32 rows x 16 columns, 16 bytes per lane), so a wavefront fetches
+// a fragment as 1 KB in a row straight into registers, several steps ahead of its use.  Phases 2
+// and 3 therefore run without a barrier; their only LDS traffic is the pixel fragments.
 // The weight rows are handed to the matrix cores with bits 2 and 3 of the row number swapped, so
 // that a lane of a 32x32 result block holds two runs of 8 consecutive channels of one position:
 // 16-byte LDS writes in phases 1 and 2, 16-byte global stores in phase 3.  The price of the fusion
 // is phase 1 on the R - 128 extra positions; the gain is the traffic of t1 and t2 and the second
-// pass over x (the residual is re-read while its lines are still in L2).
+// pass over x (the residual is re-read while its lines are still in a cache).
 #include "conv_common.h"
 
 #include <cstdlib>
@@ -46,41 +50,6 @@ __device__ __forceinline__ void bn_static_for(F&& f, std::integer_sequence<int, 
 template <int N, class F>
 __device__ __forceinline__ void bn_unroll(F&& f) { bn_static_for(f, std::make_integer_sequence<int, N>{}); }
 
-// The KS matrix-core steps of one weight stage: TC blocks of 32 weight rows (WBLK bytes apart)
-// against TP blocks of 32 positions (XBLK bytes apart).  ws / xs: this lane's 16-byte chunk of
-// step 0 in its first row; step ks lies at the address with bits 5.. xor ks (swizzled chunks).
-// The next step's reads are issued first; LDS returns in order, so once no more than those are
-// outstanding this step's fragments are complete.
-template <int TC, int TP, int KS, int WBLK, int XBLK>
-__device__ __forceinline__ void bn_mma_stage(f32x16 (&acc)[TC][TP], const uint32_t ws, const uint32_t xs) {
-    bf16x8 wf[2][TC], xf[2][TP];
-    auto read_frags = [&](auto ks_c, auto b_c) {
-        constexpr int ks = decltype(ks_c)::value, b = decltype(b_c)::value;
-        const uint32_t wa = ws ^ (uint32_t)(ks << 5), xa = xs ^ (uint32_t)(ks << 5);
-        bn_unroll<TC>([&](auto i) { wf[b][decltype(i)::value] = bn_lds_read<decltype(i)::value * WBLK>(wa); });
-        bn_unroll<TP>([&](auto j) { xf[b][decltype(j)::value] = bn_lds_read<decltype(j)::value * XBLK>(xa); });
-    };
-    read_frags(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-    bn_unroll<KS>([&](auto ks_c) {
-        constexpr int ks = decltype(ks_c)::value, b = ks & 1;
-        if constexpr (ks + 1 < KS) {
-            read_frags(std::integral_constant<int, ks + 1>{}, std::integral_constant<int, b ^ 1>{});
-            asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(TC + TP) : "memory");
-        } else {
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        }
-#pragma unroll
-        for (int i = 0; i < TC; i++) bn_tie(wf[b][i]);
-#pragma unroll
-        for (int j = 0; j < TP; j++) bn_tie(xf[b][j]);
-#pragma unroll
-        for (int i = 0; i < TC; i++)
-#pragma unroll
-            for (int j = 0; j < TP; j++)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[b][i], xf[b][j], acc[i][j], 0, 0, 0);
-    });
-}
-
 // matrix row -> weight row within a block of 32: bits 2 and 3 swapped
 __device__ __forceinline__ int bn_perm(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
@@ -105,32 +74,40 @@ __device__ __forceinline__ u32x4 bn_pack(const f32x16& acc, int k, int act) {
     return u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
 }
 
+// One operand fragment of the packed weights: 16 bytes per lane, 1 KB in a row per wavefront.
+__device__ __forceinline__ bf16x8 bn_wload(const __amdgpu_buffer_rsrc_t& r, unsigned vo, int so) {
+    return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(r, vo, so, 0));
+}
+
+template <int N>
+__device__ __forceinline__ void bn_wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
 constexpr int bn_max3(int a, int b, int c) { return a > b ? (a > c ? a : c) : (b > c ? b : c); }
 
 constexpr int BN_BP = 128;           // positions per workgroup
-constexpr int BN_WST = 8192;         // bytes per stage of the weight ring
 constexpr int BN_NCH = 128;          // output channels per pass of phase 3
+constexpr int BN_NXB = 3;            // input chunks in flight or in use
 template <int C, int R>
-constexpr int bn_big() { return bn_max3(2 * R * 64, (C / 64) * R * 128, (C / 64) * BN_BP * 128); }
+constexpr int bn_big() { return bn_max3(BN_NXB * R * 64, (C / 64) * R * 128, (C / 64) * BN_BP * 128); }
 
 // argv: the argument blocks of the three convolutions, gridDim.z of each (one per member of the gang)
 template <int C, int R>
-__global__ __launch_bounds__(256) void bottleneck_bf16(const ConvArgs* __restrict__ argv, const int nb_) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void bottleneck_bf16(const ConvArgs* __restrict__ argv, const int nb_) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int G = gridDim.z;
     const ConvArgs a1 = argv[blockIdx.z], a2 = argv[G + blockIdx.z], a3 = argv[2 * G + blockIdx.z];
     static_assert(C == 64 || C == 128, "64 or 128 channels between the convolutions");
-    constexpr int BP = BN_BP, WST = BN_WST, NCH = BN_NCH;
-    // phase 1: wavefronts WR1 along the window rows, WC1 along the channels
-    constexpr int WR1 = C == 64 ? 4 : 2, WC1 = 4 / WR1;
+    constexpr int BP = BN_BP, NCH = BN_NCH;
+    // phase 1: wavefronts WR1 along the window rows, WC1 along the channels (a weight fragment is then
+    // fetched by two wavefronts, not by all four)
+    constexpr int WR1 = 2, WC1 = 4 / WR1;
     constexpr int TP1 = R / (32 * WR1), TC1 = C / (32 * WC1);
     static_assert(TP1 * 32 * WR1 == R && TC1 * 32 * WC1 == C && R % 64 == 0, "window rows split evenly");
-    // phase 2: 2 x 2 wavefronts; a stage of the 3x3 filter is C rows of K2 input channels of one tap
-    constexpr int CH2 = C == 64 ? 8 : 4, K2 = CH2 * 8, KS2 = K2 / 16, ROWB2 = K2 * 2, NK2 = C / K2;
-    constexpr int TP2 = 2, TC2 = C / 64;
-    // phase 3: 2 x 2 wavefronts over 128 positions x 128 channels; a stage is 128 rows of 32 input channels
-    constexpr int KC3 = C / 32;
-    static_assert(C * 64 <= WST && C * ROWB2 <= WST && NCH * 64 <= WST, "weight stages fit the ring");
+    constexpr int XO = R / 64, WO = 2 * TC1;         // loads per thread and chunk: input rows, weight fragments
+    // phases 2 and 3: 2 x 2 wavefronts, 64 positions each
+    constexpr int TC2 = C / 64;
+    constexpr int KK = C / 16;                       // matrix-core steps over C channels
+    constexpr int PW = 8 / TC2;                      // steps the weight fragments are asked for ahead in phase 2
     constexpr int XS = R * 64;                       // bytes of an input chunk: R rows of 32 channels
     constexpr int T1B = R * 128, T2B = BP * 128;     // bytes of a 64-channel block of t1 / t2
     constexpr int BIG = bn_big<C, R>();
@@ -145,12 +122,26 @@ __global__ __launch_bounds__(256) void bottleneck_bf16(const ConvArgs* __restric
     const int pp0 = ptile * BP;
     const int cin1 = a1.cin, cout3 = a3.cout;
 
-    // LDS: weight ring | x chunks, then t1, then t2 | window row -> pixel index (-1: none) | biases
-    unsigned char* const big = lds + 2 * WST;
+    // LDS: x chunks, then t1, then t2 | window row -> pixel index (-1: none) | biases
+    unsigned char* const big = lds;
     int* const tbl = (int*)(big + BIG);
     float* const b1l = (float*)(tbl + R);
     float* const b2l = b1l + C;
     float* const b3l = b2l + C;
+    // the weights of the first two input chunks are asked for before anything else
+    const __amdgpu_buffer_rsrc_t w1res = __builtin_amdgcn_make_buffer_rsrc((void*)a1.wpk, 0, (int)((unsigned)C * (unsigned)cin1 * 2u), 0x00020000);
+    const int row0 = (wave % WR1) * (TP1 * 32), ch0 = (wave / WR1) * (TC1 * 32);   // phase 1: this wave's window rows and channels
+    const int NS1 = cin1 / 16, nk1 = cin1 / 32;                  // steps per block of 32 weight rows; input chunks
+    const unsigned wv1 = (unsigned)((ch0 / 32) * NS1 * 1024 + lane * 16);
+    bf16x8 w0[2][TC1], w1[2][TC1], w2[2][TC1];                   // weights of this chunk, the next, the one after
+    auto load_w = [&](bf16x8 (&w)[2][TC1], int kc) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ks++)
+#pragma unroll
+            for (int i = 0; i < TC1; i++) w[ks][i] = bn_wload(w1res, wv1, (i * NS1 + kc * 2 + ks) * 1024);
+    };
+    load_w(w0, 0);
+    if (nk1 > 1) load_w(w1, 1);
     raster_table(tbl, R, pp0 - (W1 + 1), PP, H1, W1, a1.H, a1.W);
     for (int i = t; i < C; i += 256) {
         b1l[i] = a1.bias[i];
@@ -164,83 +155,97 @@ __global__ __launch_bounds__(256) void bottleneck_bf16(const ConvArgs* __restric
     constexpr unsigned OOBV = 0x80000000u;
     const unsigned npix = (unsigned)nb_ * (unsigned)(a1.H * a1.W);
     const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc((void*)a1.x.p, 0, (int)(npix * (unsigned)a1.x.stride * 2u), 0x00020000);
-    const __amdgpu_buffer_rsrc_t w1res = __builtin_amdgcn_make_buffer_rsrc((void*)a1.w, 0, (int)((unsigned)C * (unsigned)cin1 * 2u), 0x00020000);
-    const __amdgpu_buffer_rsrc_t w2res = __builtin_amdgcn_make_buffer_rsrc((void*)a2.w, 0, (int)(9u * C * C * 2u), 0x00020000);
-    const __amdgpu_buffer_rsrc_t w3res = __builtin_amdgcn_make_buffer_rsrc((void*)a3.w, 0, (int)((unsigned)cout3 * (unsigned)C * 2u), 0x00020000);
-    // thread roles in a load instruction of the workgroup (4 KB): row and swizzled chunk for rows of
-    // 64 bytes (4 chunks, 64 rows per instruction) and of 128 bytes (8 chunks, 32 rows)
+    const __amdgpu_buffer_rsrc_t w2res = __builtin_amdgcn_make_buffer_rsrc((void*)a2.wpk, 0, (int)(9u * C * C * 2u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t w3res = __builtin_amdgcn_make_buffer_rsrc((void*)a3.wpk, 0, (int)((unsigned)cout3 * (unsigned)C * 2u), 0x00020000);
+    // thread roles in a load instruction of the workgroup (4 KB of 64-byte rows): row and swizzled chunk
     const int r4 = t >> 2, c4 = (t & 3) ^ ((r4 >> 2) & 3);
-    const int r8 = t >> 3, c8 = (t & 7) ^ ((r8 >> 1) & 7);
-    unsigned xvo[R / 64];
+    unsigned xvo[XO];
 #pragma unroll
-    for (int s = 0; s < R / 64; s++) {
+    for (int s = 0; s < XO; s++) {
         const int p = tbl[r4 + 64 * s];
         xvo[s] = p >= 0 ? (unsigned)(p * a1.x.stride * 2) + (unsigned)(a1.x.c0 * 2 + c4 * 16) : OOBV;
-    }
-    unsigned w1vo[C / 64], w2vo[2], w3vo[2];
-#pragma unroll
-    for (int i = 0; i < C / 64; i++) w1vo[i] = (unsigned)bn_perm(r4 + 64 * i) * (unsigned)(cin1 * 2) + (unsigned)(c4 * 16);
-#pragma unroll
-    for (int i = 0; i < 2; i++) {
-        w2vo[i] = CH2 == 8 ? (unsigned)bn_perm(r8 + 32 * i) * (unsigned)(9 * C * 2) + (unsigned)(c8 * 16)
-                           : (unsigned)bn_perm(r4 + 64 * i) * (unsigned)(9 * C * 2) + (unsigned)(c4 * 16);
-        w3vo[i] = (unsigned)bn_perm(r4 + 64 * i) * (unsigned)(C * 2) + (unsigned)(c4 * 16);
     }
     unsigned char* const mine = lds + wave * 1024;               // this wave's quarter of a 4 KB load
     auto issue_x = [&](int buf, int kc) {
 #pragma unroll
-        for (int s = 0; s < R / 64; s++)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (lds_ptr_t)(mine + 2 * WST + buf * XS + s * 4096), LDS_LOAD_BYTES, xvo[s], kc * 64, 0, 0);
-    };
-    auto issue_w1 = [&](int stage, int kc) {
-#pragma unroll
-        for (int i = 0; i < C / 64; i++)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(w1res, (lds_ptr_t)(mine + stage * WST + i * 4096), LDS_LOAD_BYTES, w1vo[i], kc * 64, 0, 0);
-    };
-    auto issue_w2 = [&](int stage, int st) {                     // stage st: K2 channels further on in the row [tap][C]
-#pragma unroll
-        for (int i = 0; i < 2; i++)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(w2res, (lds_ptr_t)(mine + stage * WST + i * 4096), LDS_LOAD_BYTES, w2vo[i], st * ROWB2, 0, 0);
-    };
-    auto issue_w3 = [&](int stage, int nc, int kc) {
-#pragma unroll
-        for (int i = 0; i < 2; i++)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(w3res, (lds_ptr_t)(mine + stage * WST + i * 4096), LDS_LOAD_BYTES, w3vo[i],
-                                                     nc * (NCH * C * 2) + kc * 64, 0, 0);
+        for (int s = 0; s < XO; s++)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (lds_ptr_t)(mine + buf * XS + s * 4096), LDS_LOAD_BYTES, xvo[s], kc * 64, 0, 0);
     };
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
-    const uint32_t big0 = lds0 + 2 * WST;
-    int stage = 0;
+    // phases 2 and 3: this wave's 64 positions and its half of the channels; the first weight fragments
+    // of a phase are asked for before the phase before it has written its result to LDS
+    const int wp0 = (wave & 1) * 64, wcg = wave >> 1;
+    constexpr int NST = 9 * KK, PW3 = 4;
+    static_assert(KK % PW3 == 0, "a step of phase 3 keeps its slot from pass to pass");
+    const int wc2 = wcg * (32 * TC2), wc3 = wcg * 64;
+    const unsigned wv2 = (unsigned)((wc2 / 32) * NST * 1024 + lane * 16);
+    const unsigned wv3 = (unsigned)((wc3 / 32) * KK * 1024 + lane * 16);
+    bf16x8 wq2[PW][TC2], wq3[PW3][2];
+    // block i, step kk of pass nc of phase 3 lies at ((4 nc + wc3 / 32 + i) KK + kk) KB
+    auto load_w3 = [&](bf16x8 (&w)[2], int nc, int kk) {
+#pragma unroll
+        for (int i = 0; i < 2; i++) w[i] = bn_wload(w3res, wv3, ((nc * (NCH / 32) + i) * KK + kk) * 1024);
+    };
 
-    // ---- phase 1: t1 over the window
+    // ---- phase 1: t1 over the window.  Chunk kc + 2 of the input and the weights of chunk kc + 2 are
+    //      asked for while chunk kc is used.  Loads complete in the order they were issued, so the
+    //      wait before a chunk is used counts what was issued after it and may still be on its way.
     {
-        const int row0 = (wave % WR1) * (TP1 * 32), ch0 = (wave / WR1) * (TC1 * 32);
-        const int xr = row0 + lrow, wr = ch0 + lrow;
-        const uint32_t xs1 = big0 + (uint32_t)(xr * 64 + ((lhalf ^ ((xr >> 2) & 3)) << 4));
-        const uint32_t ws1 = lds0 + (uint32_t)(wr * 64 + ((lhalf ^ ((wr >> 2) & 3)) << 4));
+        const int xr = row0 + lrow;
+        const uint32_t xs1 = lds0 + (uint32_t)(xr * 64 + ((lhalf ^ ((xr >> 2) & 3)) << 4));
         f32x16 acc[TC1][TP1];
 #pragma unroll
         for (int i = 0; i < TC1; i++)
 #pragma unroll
             for (int j = 0; j < TP1; j++) bn_init(acc[i][j], b1l + ch0 + 32 * i + 8 * lhalf);
         issue_x(0, 0);
-        issue_w1(0, 0);
-        const int nk1 = cin1 / 32;
+        if (nk1 > 1) issue_x(1, 1);
+        int buf = 0;
         for (int kc = 0; kc < nk1; kc++) {
-            // this step's chunk and weights have landed; the barrier extends that to the other waves'
-            // loads and says that nobody still reads what is refilled next
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            if (kc + 1 < nk1) {
-                issue_x((kc + 1) & 1, kc + 1);
-                issue_w1(stage ^ 1, kc + 1);
+            // chunk kc has landed (this wave's part; with the barrier everybody's), and nobody still reads
+            // the buffer that chunk kc + 2 goes to
+            if (kc == 0) {
+                if (nk1 > 1) bn_wait_vm<XO>(); else bn_wait_vm<0>();
             } else {
-                issue_w2(stage ^ 1, 0);
+                if (kc + 1 < nk1) bn_wait_vm<WO + XO>(); else bn_wait_vm<0>();
             }
-            bn_mma_stage<TC1, TP1, 2, 2048, 2048>(acc, ws1 + (uint32_t)(stage * WST), xs1 + (uint32_t)((kc & 1) * XS));
-            stage ^= 1;
+            __builtin_amdgcn_s_barrier();
+            if (kc + 2 < nk1) {
+                load_w(w2, kc + 2);
+                issue_x(buf >= 1 ? buf - 1 : 2, kc + 2);         // (buf + 2) % 3
+            }
+            const uint32_t xs = xs1 + (uint32_t)(buf * XS);
+            bf16x8 xf[2][TP1];
+            bn_unroll<TP1>([&](auto j) { xf[0][decltype(j)::value] = bn_lds_read<decltype(j)::value * 2048>(xs); });
+            bn_unroll<TP1>([&](auto j) { xf[1][decltype(j)::value] = bn_lds_read<decltype(j)::value * 2048>(xs ^ 32u); });
+            asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(TP1) : "memory");
+#pragma unroll
+            for (int j = 0; j < TP1; j++) bn_tie(xf[0][j]);
+#pragma unroll
+            for (int i = 0; i < TC1; i++)
+#pragma unroll
+                for (int j = 0; j < TP1; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0[0][i], xf[0][j], acc[i][j], 0, 0, 0);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int j = 0; j < TP1; j++) bn_tie(xf[1][j]);
+#pragma unroll
+            for (int i = 0; i < TC1; i++)
+#pragma unroll
+                for (int j = 0; j < TP1; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0[1][i], xf[1][j], acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int ks = 0; ks < 2; ks++)
+#pragma unroll
+                for (int i = 0; i < TC1; i++) {
+                    w0[ks][i] = w1[ks][i];
+                    w1[ks][i] = w2[ks][i];
+                }
+            buf = buf == 2 ? 0 : buf + 1;
         }
+        bn_unroll<PW>([&](auto s) {
+#pragma unroll
+            for (int i = 0; i < TC2; i++) wq2[decltype(s)::value][i] = bn_wload(w2res, wv2, (i * NST + decltype(s)::value) * 1024);
+        });
         __syncthreads();                                         // everybody is done with the input chunks
 #pragma unroll
         for (int j = 0; j < TP1; j++) {
@@ -256,42 +261,86 @@ __global__ __launch_bounds__(256) void bottleneck_bf16(const ConvArgs* __restric
                         live ? o : u32x4{0u, 0u, 0u, 0u};
                 }
         }
-        __syncthreads();
     }
 
-    const int wp0 = (wave & 1) * 64;                             // phases 2 and 3: this wave's 64 positions
-    // ---- phase 2: t2 = 3x3 over t1
+    // What phase 3 needs from memory per pass, the residual of this lane's 2 x 2 x 2 runs of 8 channels,
+    // is asked for a pass ahead; the first pass's now, before phase 2.
+    const bool has_res = a3.res.p != nullptr;
+    const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc((void*)a3.y.p, 0, (int)(npix * (unsigned)a3.y.stride * 2u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rres = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(has_res ? a3.res.p : a3.y.p), 0, (int)(npix * (unsigned)(has_res ? a3.res.stride : a3.y.stride) * 2u), 0x00020000);
+    unsigned yo[2], ro[2];
     {
-        const int wc2 = (wave >> 1) * (32 * TC2);
-        const int wr = wc2 + lrow;
-        const uint32_t ws2 = lds0 + (uint32_t)(wr * ROWB2 + ((lhalf ^ (CH2 == 8 ? (wr >> 1) & 7 : (wr >> 2) & 3)) << 4));
-        const uint32_t lq = (uint32_t)(wp0 + lrow);
-        f32x16 acc[TC2][TP2];
+        const int* own = tbl + W1 + 1 + wp0 + lrow;              // the centre tap's rows: this tile's outputs
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            const int pout = own[32 * j];
+            yo[j] = pout >= 0 ? (unsigned)(pout * a3.y.stride * 2) + (unsigned)((a3.y.c0 + wc3 + 8 * lhalf) * 2) : OOBV;
+            ro[j] = pout >= 0 ? (unsigned)(pout * a3.res.stride * 2) + (unsigned)((a3.res.c0 + wc3 + 8 * lhalf) * 2) : OOBV;
+        }
+    }
+    u32x4 resn[2][2][2];
+    auto load_res = [&](int nc) {
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+#pragma unroll
+            for (int i = 0; i < 2; i++)
+#pragma unroll
+                for (int k = 0; k < 2; k++)
+                    resn[j][i][k] = __builtin_amdgcn_raw_buffer_load_b128(rres, ro[j], (nc * NCH + 32 * i + 16 * k) * 2, 0);
+    };
+    if (has_res) load_res(0);
+    // ---- phase 2: t2 = 3x3 over t1.  No barrier and no LDS traffic but the pixel fragments: the
+    //      weights come PW steps ahead from memory into registers.
+    {
+        f32x16 acc[TC2][2];
 #pragma unroll
         for (int i = 0; i < TC2; i++)
 #pragma unroll
-            for (int j = 0; j < TP2; j++) bn_init(acc[i][j], b2l + wc2 + 32 * i + 8 * lhalf);
+            for (int j = 0; j < 2; j++) bn_init(acc[i][j], b2l + wc2 + 32 * i + 8 * lhalf);
+        uint32_t xoff[9];                                        // tap (dh, dw): dh rows of the padded raster down, dw positions right
 #pragma unroll
         for (int tap = 0; tap < 9; tap++) {
-            // tap (dh, dw): dh rows of the padded raster down, dw positions to the right
-            const uint32_t q = lq + (uint32_t)((tap / 3) * W1 + tap % 3);
-            const uint32_t xq = big0 + q * 128 + ((((uint32_t)lhalf) ^ ((q >> 1) & 7)) << 4);
-#pragma unroll
-            for (int kq = 0; kq < NK2; kq++) {
-                const int st = tap * NK2 + kq;
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                __builtin_amdgcn_s_barrier();
-                if (st + 1 < 9 * NK2) issue_w2(stage ^ 1, st + 1);
-                else issue_w3(stage ^ 1, 0, 0);
-                // 32-channel stages: block kq / 2 of t1, upper or lower half of its row
-                const uint32_t xs = CH2 == 8 ? xq : (xq + (uint32_t)((kq >> 1) * T1B)) ^ (uint32_t)((kq & 1) << 6);
-                bn_mma_stage<TC2, TP2, KS2, 32 * ROWB2, 4096>(acc, ws2 + (uint32_t)(stage * WST), xs);
-                stage ^= 1;
-            }
+            const uint32_t q = (uint32_t)(wp0 + lrow + (tap / 3) * W1 + tap % 3);
+            xoff[tap] = lds0 + q * 128 + ((((uint32_t)lhalf) ^ ((q >> 1) & 7)) << 4);
         }
+        __syncthreads();                                         // t1 is complete
+        bf16x8 xf[2][2];
+        auto read_frags = [&](auto st_c, auto b_c) {
+            constexpr int st = decltype(st_c)::value, b = decltype(b_c)::value;
+            constexpr int tap = st / KK, kk = st % KK;           // step kk of the tap: block kk / 4 of t1, chunks 2 (kk % 4) and + 1
+            const uint32_t xa = (xoff[tap] + (uint32_t)((kk / 4) * T1B)) ^ (uint32_t)((kk % 4) << 5);
+            xf[b][0] = bn_lds_read<0>(xa);
+            xf[b][1] = bn_lds_read<4096>(xa);
+        };
+        read_frags(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        bn_unroll<NST>([&](auto st_c) {
+            constexpr int st = decltype(st_c)::value, b = st & 1, slot = st % PW;
+            if constexpr (st + 1 < NST) {
+                read_frags(std::integral_constant<int, st + 1>{}, std::integral_constant<int, b ^ 1>{});
+                asm volatile("s_waitcnt lgkmcnt(2)" ::: "memory");
+            } else {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            }
+            bn_tie(xf[b][0]);
+            bn_tie(xf[b][1]);
+            bf16x8 wc[TC2];
+#pragma unroll
+            for (int i = 0; i < TC2; i++) wc[i] = wq2[slot][i];
+            if constexpr (st + PW < NST) {
+#pragma unroll
+                for (int i = 0; i < TC2; i++) wq2[slot][i] = bn_wload(w2res, wv2, (i * NST + st + PW) * 1024);
+            }
+#pragma unroll
+            for (int i = 0; i < TC2; i++)
+#pragma unroll
+                for (int j = 0; j < 2; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[i], xf[b][j], acc[i][j], 0, 0, 0);
+        });
+#pragma unroll
+        for (int kk = 0; kk < PW3; kk++) load_w3(wq3[kk], 0, kk);
         __syncthreads();                                         // everybody is done with t1
 #pragma unroll
-        for (int j = 0; j < TP2; j++) {
+        for (int j = 0; j < 2; j++) {
             const int row = wp0 + 32 * j + lrow;
 #pragma unroll
             for (int i = 0; i < TC2; i++)
@@ -302,57 +351,62 @@ __global__ __launch_bounds__(256) void bottleneck_bf16(const ConvArgs* __restric
                         bn_pack(acc[i][j], k, a2.act);
                 }
         }
-        __syncthreads();
     }
 
     // ---- phase 3: y = W3 t2 + residual, 128 channels per pass.  Register v of a lane is channel
     //      16(v/8) + 8(lane/32) + v%8 of its block and position; stores to positions without a pixel
     //      carry the out-of-range offset and are dropped by the hardware.
     {
-        const int wc3 = (wave >> 1) * 64;
-        const bool has_res = a3.res.p != nullptr;
-        const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc((void*)a3.y.p, 0, (int)(npix * (unsigned)a3.y.stride * 2u), 0x00020000);
-        const __amdgpu_buffer_rsrc_t rres = __builtin_amdgcn_make_buffer_rsrc(
-            (void*)(has_res ? a3.res.p : a3.y.p), 0, (int)(npix * (unsigned)(has_res ? a3.res.stride : a3.y.stride) * 2u), 0x00020000);
-        const int* own = tbl + W1 + 1 + wp0 + lrow;              // the centre tap's rows: this tile's outputs
-        unsigned yo[2], ro[2];
-#pragma unroll
-        for (int j = 0; j < 2; j++) {
-            const int pout = own[32 * j];
-            yo[j] = pout >= 0 ? (unsigned)(pout * a3.y.stride * 2) + (unsigned)((a3.y.c0 + wc3 + 8 * lhalf) * 2) : OOBV;
-            ro[j] = pout >= 0 ? (unsigned)(pout * a3.res.stride * 2) + (unsigned)((a3.res.c0 + wc3 + 8 * lhalf) * 2) : OOBV;
-        }
-        const int xr = wp0 + lrow, wr = wc3 + lrow;
-        const uint32_t xs3 = big0 + (uint32_t)(xr * 128 + ((lhalf ^ ((xr >> 1) & 7)) << 4));
-        const uint32_t ws3 = lds0 + (uint32_t)(wr * 64 + ((lhalf ^ ((wr >> 2) & 3)) << 4));
+        const int xr = wp0 + lrow;
+        const uint32_t xs3 = lds0 + (uint32_t)(xr * 128 + ((lhalf ^ ((xr >> 1) & 7)) << 4));
         const int nch = cout3 / NCH;
         const bool relu = a3.act == ACT_RELU;
+        // weight fragments PW3 steps ahead, on into the next pass
+        __syncthreads();                                         // t2 is complete
         for (int nc = 0; nc < nch; nc++) {
             u32x4 res[2][2][2];
+#pragma unroll
+            for (int j = 0; j < 2; j++)
+#pragma unroll
+                for (int i = 0; i < 2; i++)
+#pragma unroll
+                    for (int k = 0; k < 2; k++) res[j][i][k] = resn[j][i][k];
+            if (has_res && nc + 1 < nch) load_res(nc + 1);
             f32x16 acc[2][2];
 #pragma unroll
             for (int i = 0; i < 2; i++)
 #pragma unroll
                 for (int j = 0; j < 2; j++) bn_init(acc[i][j], b3l + nc * NCH + wc3 + 32 * i + 8 * lhalf);
-#pragma unroll
-            for (int kc = 0; kc < KC3; kc++) {
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                __builtin_amdgcn_s_barrier();
-                if (kc + 1 < KC3) issue_w3(stage ^ 1, nc, kc + 1);
-                else if (nc + 1 < nch) issue_w3(stage ^ 1, nc + 1, 0);
-                if (kc == 0 && has_res) {                        // lands while this pass computes
-#pragma unroll
-                    for (int j = 0; j < 2; j++)
-#pragma unroll
-                        for (int i = 0; i < 2; i++)
-#pragma unroll
-                            for (int k = 0; k < 2; k++)
-                                res[j][i][k] = __builtin_amdgcn_raw_buffer_load_b128(rres, ro[j], (nc * NCH + 32 * i + 16 * k) * 2, 0);
+            bf16x8 xf[2][2];
+            auto read_frags = [&](auto kk_c, auto b_c) {
+                constexpr int kk = decltype(kk_c)::value, b = decltype(b_c)::value;
+                const uint32_t xa = (xs3 + (uint32_t)((kk / 4) * T2B)) ^ (uint32_t)((kk % 4) << 5);
+                xf[b][0] = bn_lds_read<0>(xa);
+                xf[b][1] = bn_lds_read<4096>(xa);
+            };
+            read_frags(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+            bn_unroll<KK>([&](auto kk_c) {
+                constexpr int kk = decltype(kk_c)::value, b = kk & 1;
+                if constexpr (kk + 1 < KK) {
+                    read_frags(std::integral_constant<int, kk + 1>{}, std::integral_constant<int, b ^ 1>{});
+                    asm volatile("s_waitcnt lgkmcnt(2)" ::: "memory");
+                } else {
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 }
-                const uint32_t xs = (xs3 + (uint32_t)((kc >> 1) * T2B)) ^ (uint32_t)((kc & 1) << 6);
-                bn_mma_stage<2, 2, 2, 2048, 4096>(acc, ws3 + (uint32_t)(stage * WST), xs);
-                stage ^= 1;
-            }
+                bn_tie(xf[b][0]);
+                bn_tie(xf[b][1]);
+                constexpr int slot = kk % PW3;
+                bf16x8 wc[2] = {wq3[slot][0], wq3[slot][1]};
+                if constexpr (kk + PW3 < KK) {
+                    load_w3(wq3[slot], nc, kk + PW3);
+                } else {
+                    if (nc + 1 < nch) load_w3(wq3[slot], nc + 1, kk + PW3 - KK);
+                }
+#pragma unroll
+                for (int i = 0; i < 2; i++)
+#pragma unroll
+                    for (int j = 0; j < 2; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[i], xf[b][j], acc[i][j], 0, 0, 0);
+            });
 #pragma unroll
             for (int j = 0; j < 2; j++)
 #pragma unroll
@@ -389,7 +443,7 @@ __global__ __launch_bounds__(256) void bottleneck_bf16(const ConvArgs* __restric
 
 // ---- host side -----------------------------------------------------------------------------
 constexpr int BNECK_LDS_LIMIT = 160 * 1024;
-constexpr int BNECK_CUS = 256;
+constexpr int BNECK_MIN_TILES = 24;
 
 struct BneckPlan { int c, rows; size_t bytes; int tiles; };
 
@@ -402,7 +456,7 @@ static bool bneck_plan(const ConvArgs& a1, const ConvArgs& a2, const ConvArgs& a
     if (a2.H != a1.H || a2.W != a1.W || a2.Ho != a1.H || a2.Wo != a1.W || a3.H != a1.H || a3.W != a1.W) return false;
     const int c = a1.cout;
     if ((c != 64 && c != 128) || a2.cin != c || a2.cout != c || a3.cin != c) return false;
-    if (a1.cin % 32 || a3.cout % BN_NCH || a3.cout > 2048) return false;
+    if (a1.cin % 32 || a3.cout % BN_NCH || a3.cout > 2048 || !a1.wpk || !a2.wpk || !a3.wpk) return false;
     // the middle tensors are skipped: the 3x3 reads what the first convolution writes, and so on
     if (a2.x.p != a1.y.p || a2.x.c0 != a1.y.c0 || a3.x.p != a2.y.p || a3.x.c0 != a2.y.c0) return false;
     if (a3.y.p == a1.x.p) return false;
@@ -418,7 +472,7 @@ static bool bneck_plan(const ConvArgs& a1, const ConvArgs& a2, const ConvArgs& a
     pl->rows = c == 64 ? 256 : 192;
     if (BN_BP + 2 * (a1.W + 1) + 2 > pl->rows) return false;
     const int big = c == 64 ? bn_big<64, 256>() : bn_big<128, 192>();
-    pl->bytes = (size_t)2 * BN_WST + big + (size_t)pl->rows * 4 + (size_t)(2 * c + a3.cout) * 4;
+    pl->bytes = (size_t)big + (size_t)pl->rows * 4 + (size_t)(2 * c + a3.cout) * 4;
     pl->tiles = (int)((PP + BN_BP - 1) / BN_BP);
     return pl->bytes <= (size_t)BNECK_LDS_LIMIT;
 }
@@ -429,9 +483,14 @@ bool conv_bneck_applicable(const ConvArgs& a1, const ConvArgs& a2, const ConvArg
     if (const char* e = getenv("ENS_CONV_BNECK")) if (atoi(e) == 0) return false;
 #endif
     if (!bneck_plan(a1, a2, a3, nb, &pl)) return false;
-    // a workgroup runs its tile's three layers one after the other: with fewer tiles than compute
-    // units the separate kernels, which also split the channels, fill the chip better
-    return (long long)pl.tiles * G >= BNECK_CUS;
+    // A workgroup runs its tile's three layers one after the other, so a handful of tiles leaves the
+    // chip to a handful of workgroups; the separate kernels split the channels too.  Measured on a
+    // ResNet-50-shaped member the one kernel wins from about two dozen tiles on (batch 4 at 28x28).
+    long long least = BNECK_MIN_TILES;
+#ifdef ENS_CONV_TUNING
+    if (const char* e = getenv("ENS_CONV_BNECK_MIN")) least = atoll(e);
+#endif
+    return (long long)pl.tiles * G >= least;
 }
 
 const char* conv_bneck_name(const ConvArgs& a1) { return a1.cout == 64 ? "bottleneck_bf16<c64>" : "bottleneck_bf16<c128>"; }

@@ -84,6 +84,7 @@ static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G
             a.pre_shift = pl.pre_shift != SIZE_MAX ? (const float*)(P + pl.pre_shift) : nullptr;
             a.ws = nullptr; a.ws_floats = 0;
             a.zeros = P + m.zeros_off;
+            a.wpk = pl.w_packed != SIZE_MAX ? P + pl.w_packed : nullptr;
             if (w.layout.scratch_offset != SIZE_MAX) {
                 a.ws = (float*)(w.arena + w.layout.scratch_offset);
                 a.ws_floats = (long long)SPLIT_WS_FLOATS;

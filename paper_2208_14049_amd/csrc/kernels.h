@@ -35,6 +35,7 @@ struct ConvArgs {
     float* ws;
     long long ws_floats;
     const void* zeros;         // at least 16 bytes of zeros in device memory (padding source of the register-staged kernel)
+    const void* wpk;           // the weights in matrix-core operand order (fused bottleneck kernel), or null
     double inv_hw, inv_w;      // 1 / (Ho * Wo) and 1 / Wo, for the pixel index decomposition
     int nb, H, W, cin, Ho, Wo, cout;
     int kh, kw, sh, sw, pt, pl;

@@ -122,7 +122,7 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         const ens_op& o = spec.ops[i];
         OpPlan pl;
         pl.op = o;
-        pl.w = pl.b = pl.pre_scale = pl.pre_shift = pl.w2 = pl.b2 = SIZE_MAX;
+        pl.w = pl.b = pl.pre_scale = pl.pre_shift = pl.w2 = pl.b2 = pl.w_packed = SIZE_MAX;
         pl.cin_s = o.cin;
         pl.scratch = -1;
         pl.alg_k = 0;
@@ -357,8 +357,29 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
             if (m.ops[i].fuse_next || m.ops[i + 1].fuse_next || m.ops[i + 2].fuse_next) continue;
             if (i > 1 && m.ops[i - 2].fuse_chain) continue;      // chains do not overlap
             if (i > 0 && m.ops[i - 1].fuse_chain) continue;
+            if (p.cin % 32 || o.cout % 32) continue;
             m.ops[i].fuse_chain = true;
             m.tensors[o.dst].def = std::min(m.tensors[o.dst].def, i);
+            // The fused kernel takes each wavefront's weights straight from memory: a second copy in the order
+            // of the matrix-core operands, so that a wavefront's load is 1 KB in a row.  Rows in blocks of 32,
+            // the K axis (taps x channels) in steps of 16: [block][step][lane][8], lane (r, h) holding row
+            // 32 block + r', columns 16 step + 8 h .. + 7, r' = r with bits 2 and 3 swapped.
+            for (int j = 0; j < 3; j++) {
+                OpPlan& pl = m.ops[i + j];
+                const int rows = pl.op.cout, K = pl.op.kh * pl.op.kw * pl.cin_s;
+                const size_t off = bw.reserve((size_t)rows * K * 2);
+                const uint16_t* src = (const uint16_t*)(m.host_params.data() + pl.w);
+                uint16_t* dst = (uint16_t*)(m.host_params.data() + off);
+                const int NS = K / 16;
+                for (int rb = 0; rb < rows / 32; rb++)
+                    for (int st = 0; st < NS; st++)
+                        for (int lane = 0; lane < 64; lane++) {
+                            const int r = lane & 31, h = lane >> 5;
+                            const int row = 32 * rb + ((r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1));
+                            memcpy(dst + (((size_t)rb * NS + st) * 64 + lane) * 8, src + (size_t)row * K + 16 * st + 8 * h, 16);
+                        }
+                pl.w_packed = off;
+            }
         }
     }
     if (stem_op >= 0) {                                          // tensor 0 as the staging kernel writes it
