@@ -201,3 +201,39 @@ def test_grouped_convolutions_in_descriptions():
     with pytest.raises(ens.EnsError) as e:
         ens.ens_spec_bytes(bad, 8)
     assert e.value.status == ens.ENS_E_INVALID
+
+
+def test_bottleneck_chains_in_descriptions():
+    """The plan recognises residual bottlenecks that one kernel can run (1x1, 3x3 stride 1, 1x1, with 64 or
+    128 channels in between and nobody else touching the two middle tensors) and keeps a second copy
+    of their weights in matrix-core operand order: the parameter block grows by exactly those copies.
+    The same layers with a stride on the 3x3, another width in the middle, a second reader of a middle
+    tensor or fp32 parameters get no copy."""
+    def block(c, cin, cout, stride=1, tap_t1=False, dtype="bf16"):
+        n = N.Net("b", 16, 16, 10, dtype=dtype)
+        x = n.conv(0, cin, 3)
+        t1 = n.conv(x, c, 1)
+        t2 = n.conv(t1, c, 3, stride=stride)
+        y = n.conv(t2, cout, 1)
+        g = n.gap(y)
+        if tap_t1:
+            n.conv(t1, 8, 1)                                     # someone else reads the first middle tensor
+        n.fc(g, 10)
+        return n
+
+    def copies(c, cin, cout):
+        up = lambda b: (b + 255) // 256 * 256
+        return up(2 * c * cin) + up(2 * 9 * c * c) + up(2 * c * cout)
+
+    for c, cin, cout in ((64, 256, 256), (128, 64, 512), (64, 32, 128)):
+        fused, _ = ens.ens_spec_bytes(block(c, cin, cout), 8)
+        plain, _ = ens.ens_spec_bytes(block(c, cin, cout, stride=2), 8)
+        assert fused - plain == copies(c, cin, cout), (c, cin, cout, fused - plain)
+    plain, _ = ens.ens_spec_bytes(block(96, 256, 256, stride=2), 8)
+    assert ens.ens_spec_bytes(block(96, 256, 256), 8)[0] == plain            # 96 channels in the middle
+    w_tap, _ = ens.ens_spec_bytes(block(64, 256, 256, tap_t1=True), 8)
+    w_tap2, _ = ens.ens_spec_bytes(block(64, 256, 256, stride=2, tap_t1=True), 8)
+    assert w_tap == w_tap2                                                    # a second reader of t1
+    assert ens.ens_spec_bytes(block(64, 256, 256, dtype="fp32"), 8)[0] == ens.ens_spec_bytes(block(64, 256, 256, stride=2, dtype="fp32"), 8)[0]
+    assert ens.ens_spec_bytes(block(64, 48, 256), 8)[0] == ens.ens_spec_bytes(block(64, 48, 256, stride=2), 8)[0]   # input not in 32s
+
