@@ -24,63 +24,11 @@
 // 16-byte LDS writes in phases 1 and 2, 16-byte global stores in phase 3.  The price of the fusion
 // is phase 1 on the R - 128 extra positions; the gain is the traffic of t1 and t2 and the second
 // pass over x (the residual is re-read while its lines are still in a cache).
-#include "conv_common.h"
+#include "conv_direct.h"
 
 #include <cstdlib>
-#include <type_traits>
-#include <utility>
 
 namespace ens {
-
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
-
-template <int OFFSET>
-__device__ __forceinline__ bf16x8 bn_lds_read(uint32_t addr) {
-    bf16x8 v;
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET));
-    return v;
-}
-// keeps the matrix-core instructions that use v behind the wait that precedes this statement
-__device__ __forceinline__ void bn_tie(bf16x8& v) { asm volatile("" : "+v"(v)); }
-
-template <class F, int... T>
-__device__ __forceinline__ void bn_static_for(F&& f, std::integer_sequence<int, T...>) {
-    (f(std::integral_constant<int, T>{}), ...);
-}
-template <int N, class F>
-__device__ __forceinline__ void bn_unroll(F&& f) { bn_static_for(f, std::make_integer_sequence<int, N>{}); }
-
-// matrix row -> weight row within a block of 32: bits 2 and 3 swapped
-__device__ __forceinline__ int bn_perm(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
-
-// accumulators of a lane start from the bias of its channels b[0..7] and b[16..23]
-__device__ __forceinline__ void bn_init(f32x16& acc, const float* b) {
-    const f32x4 q0 = *(const f32x4*)b, q1 = *(const f32x4*)(b + 4), q2 = *(const f32x4*)(b + 16), q3 = *(const f32x4*)(b + 20);
-#pragma unroll
-    for (int e = 0; e < 4; e++) {
-        acc[e] = q0[e];
-        acc[4 + e] = q1[e];
-        acc[8 + e] = q2[e];
-        acc[12 + e] = q3[e];
-    }
-}
-
-// registers 8k .. 8k+7 of a result block with the activation, as 8 bf16
-__device__ __forceinline__ u32x4 bn_pack(const f32x16& acc, int k, int act) {
-    float v[8];
-#pragma unroll
-    for (int e = 0; e < 8; e++) v[e] = acc[8 * k + e];
-    apply_act_n<8>(v, act);
-    return u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
-}
-
-// One operand fragment of the packed weights: 16 bytes per lane, 1 KB in a row per wavefront.
-__device__ __forceinline__ bf16x8 bn_wload(const __amdgpu_buffer_rsrc_t& r, unsigned vo, int so) {
-    return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(r, vo, so, 0));
-}
-
-template <int N>
-__device__ __forceinline__ void bn_wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 constexpr int bn_max3(int a, int b, int c) { return a > b ? (a > c ? a : c) : (b > c ? b : c); }
 

@@ -243,6 +243,12 @@ const char* conv_bneck_name(const ConvArgs& a1);
 hipError_t launch_conv_bneck(const ConvArgs& a1, const ConvArgs& a2, const ConvArgs& a3, const ConvArgs* argv, int G, int nb,
                              hipStream_t s);
 
+// 1x1 stride-1 kernel that takes its weights straight from memory in matrix-core operand order (a.wpk);
+// defined in conv_pw.hip.
+bool conv_pw_applicable(const ConvArgs& a, int nb, int G);
+const char* conv_pw_name(const ConvArgs& a, int G);
+hipError_t launch_conv_pw(const ConvArgs& a, const ConvArgs* argv, int G, int nb, hipStream_t s);
+
 // 3x3 stride-1 kernel with the input window resident in LDS; defined in conv_halo.hip.
 // conv_halo_pick returns the variant that runs the layer, or -1 when the generic kernel does.
 int conv_halo_pick(const ConvArgs& a, int nb, int G);

@@ -461,6 +461,7 @@ static bool pre_in_dma_kernel(const ConvArgs& a) {
 const char* conv_bf16_variant_name(const ConvArgs& a, int G) {
     const long long P = (long long)a.nb * a.Ho * a.Wo;
     if (a.pre_scale && !pre_in_dma_kernel(a)) return conv_regstage_name(a, (int)P);
+    if (conv_pw_applicable(a, a.nb, G)) return conv_pw_name(a, G);
     if (conv_taps_applicable(a, a.nb)) return conv_taps_name(a);
     if (conv_wreg_applicable(a, a.nb, G)) return conv_wreg_name(a);
     if (const int hv = conv_halo_pick(a, a.nb, G); hv >= 0) return conv_halo_name(hv);
@@ -493,6 +494,7 @@ hipError_t launch_conv_bf16(const ConvArgs& a, const ConvArgs* argv, int G, int 
     if (P64 <= 0 || P64 >= (1LL << 31) || K64 >= (1LL << 31)) return hipErrorInvalidValue;
     const int P = (int)P64;
     if (a.pre_scale && !pre_in_dma_kernel(a)) return launch_conv_regstage(a, argv, G, nb, P, s);
+    if (conv_pw_applicable(a, nb, G)) return launch_conv_pw(a, argv, G, nb, s);
     if (conv_taps_applicable(a, nb)) return launch_conv_taps(a, argv, G, nb, s);
     if (conv_wreg_applicable(a, nb, G)) return launch_conv_wreg(a, argv, G, nb, s);
     if (const int hv = conv_halo_pick(a, nb, G); hv >= 0) return launch_conv_halo(a, argv, G, nb, hv, s);

@@ -1,0 +1,228 @@
+// 1x1, stride-1 convolution on the CDNA4 matrix cores with the weights taken straight from memory
+// in matrix-core operand order (conv_direct.h), for layers whose input channels come in 64s and
+// output channels in 32s: the 1x1 layers of residual bottlenecks that do not run inside the fused
+// bottleneck kernel.
+//
+// GEMM view: rows = pixels, columns = output channels, K = input channels.  A workgroup of four
+// wavefronts owns 128 pixels x BC channels.  The pixels' input arrives 64 channels at a time
+// through a three-deep ring of LDS buffers filled by asynchronous global-to-LDS loads, two chunks
+// ahead of its use, with counted waits (loads complete in the order they were issued, so the wait
+// before a chunk is used names the number of loads issued after it).  A wavefront's weight
+// fragments, 1 KB in a row each, go from memory to registers two chunks ahead as well; nothing but
+// the pixel fragments is read from LDS, and the one barrier per chunk covers 16 or 8 matrix-core
+// instructions per wavefront where the generic kernel's covers 4 to 8 and also waits for its
+// weights.  The output leaves from the accumulators as 16-byte runs of 8 channels; bias is what the
+// accumulators start from; the residual is asked for before the loop.
+//
+// Wavefront roles: WPX along the pixels, 4 / WPX along blocks of 32 channels.  WPX = 1: a wavefront
+// has all 128 pixels of 32 channels (a weight fragment serves four matrix-core instructions and is
+// fetched by one wavefront only), BC = 128; WPX = 2 for layers with 64 output channels or fewer.
+#include "conv_direct.h"
+
+#include <cstdlib>
+
+namespace ens {
+
+constexpr int PW_BP = 128, PW_NXB = 3, PW_XS = PW_BP * 128;
+
+template <int WPX>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void conv1x1_direct_bf16(const ConvArgs* __restrict__ argv,
+                                                                                                     const int nb_) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    const ConvArgs a = argv[blockIdx.z];
+    static_assert(WPX == 1 || WPX == 2, "one or two wavefronts along the pixels");
+    constexpr int BP = PW_BP, WCG = 4 / WPX, TP = BP / (32 * WPX), BC = 32 * WCG, XS = PW_XS;
+    constexpr int XO = BP / 32, WO = 4;              // loads per thread and chunk: input rows, weight fragments
+    const int P = nb_ * a.H * a.W;
+    const int t = threadIdx.x, lane = t & 63, lrow = lane & 31, lhalf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int n_ptiles = (P + BP - 1) / BP, n_ctiles = (a.cout + BC - 1) / BC;
+    int ptile, ctile;
+    tile_of_block(n_ptiles, n_ctiles, &ptile, &ctile);
+    if (ptile >= n_ptiles) return;
+    const int p0 = ptile * BP, c0 = ctile * BC;
+    const int wp0 = (wave % WPX) * (TP * 32);
+    const int wc = c0 + (wave / WPX) * 32;           // this wave's 32 channels (the launcher admits multiples of 32 only)
+    const bool wave_ok = wc < a.cout;
+    const int NS = a.cin / 16, nk = a.cin / 64;      // matrix-core steps per block of weight rows; input chunks
+
+    // Offsets past the end of a buffer give zeros (loads) or are dropped (stores); 2^31 is past the
+    // end of every buffer the launcher admits.
+    constexpr unsigned OOBV = 0x80000000u;
+    const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc((void*)a.wpk, 0, (int)((unsigned)a.cout * (unsigned)a.cin * 2u), 0x00020000);
+    const unsigned wv = wave_ok ? (unsigned)((wc / 32) * NS * 1024 + lane * 16) : OOBV;
+    bf16x8 w0[4], w1[4], w2[4];                      // weights of this chunk, the next, the one after
+    auto load_w = [&](bf16x8 (&w)[4], int kc) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) w[ks] = bn_wload(wres, wv, (kc * 4 + ks) * 1024);
+    };
+    load_w(w0, 0);
+    if (nk > 1) load_w(w1, 1);
+
+    // ---- what the epilogue needs from memory: asked for now, older than every input chunk
+    const unsigned npix = (unsigned)P;
+    const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc((void*)a.y.p, 0, (int)(npix * (unsigned)a.y.stride * 2u), 0x00020000);
+    const bool has_res = a.res.p != nullptr;
+    const __amdgpu_buffer_rsrc_t rres = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(has_res ? a.res.p : a.y.p), 0, (int)(npix * (unsigned)(has_res ? a.res.stride : a.y.stride) * 2u), 0x00020000);
+    unsigned yo[TP], ro[TP];
+#pragma unroll
+    for (int j = 0; j < TP; j++) {
+        const int p = p0 + wp0 + 32 * j + lrow;
+        const bool ok = p < P && wave_ok;
+        yo[j] = ok ? (unsigned)(p * a.y.stride * 2) + (unsigned)((a.y.c0 + wc + 8 * lhalf) * 2) : OOBV;
+        ro[j] = ok ? (unsigned)(p * a.res.stride * 2) + (unsigned)((a.res.c0 + wc + 8 * lhalf) * 2) : OOBV;
+    }
+    u32x4 res[TP][2];
+    if (has_res) {
+#pragma unroll
+        for (int j = 0; j < TP; j++) {
+            res[j][0] = __builtin_amdgcn_raw_buffer_load_b128(rres, ro[j], 0, 0);
+            res[j][1] = __builtin_amdgcn_raw_buffer_load_b128(rres, ro[j], 32, 0);
+        }
+    }
+    f32x16 acc[TP];
+    {
+        const float* b = a.bias + (wave_ok ? wc : 0) + 8 * lhalf;   // this lane's channels: b[0..7] and b[16..23]
+        const f32x4 q0 = *ENS_GLOBAL(f32x4, b), q1 = *ENS_GLOBAL(f32x4, b + 4), q2 = *ENS_GLOBAL(f32x4, b + 16), q3 = *ENS_GLOBAL(f32x4, b + 20);
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            acc[0][e] = q0[e];
+            acc[0][4 + e] = q1[e];
+            acc[0][8 + e] = q2[e];
+            acc[0][12 + e] = q3[e];
+        }
+#pragma unroll
+        for (int j = 1; j < TP; j++) acc[j] = acc[0];
+    }
+
+    // ---- input chunks: thread t fills chunk slot t % 8 of rows t / 8 + 32 s with the swizzled chunk
+    const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc((void*)a.x.p, 0, (int)(npix * (unsigned)a.x.stride * 2u), 0x00020000);
+    const int r8 = t >> 3, c8 = (t & 7) ^ ((r8 >> 1) & 7);
+    unsigned xvo[XO];
+#pragma unroll
+    for (int s = 0; s < XO; s++) {
+        const int p = p0 + r8 + 32 * s;
+        xvo[s] = p < P ? (unsigned)(p * a.x.stride * 2) + (unsigned)(a.x.c0 * 2 + c8 * 16) : OOBV;
+    }
+    unsigned char* const mine = lds + wave * 1024;               // this wave's quarter of a 4 KB load
+    auto issue_x = [&](int buf, int kc) {
+#pragma unroll
+        for (int s = 0; s < XO; s++)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (lds_ptr_t)(mine + buf * XS + s * 4096), LDS_LOAD_BYTES, xvo[s], kc * 128, 0, 0);
+    };
+    issue_x(0, 0);
+    if (nk > 1) issue_x(1, 1);
+
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
+    const int xr = wp0 + lrow;
+    const uint32_t xs0 = lds0 + (uint32_t)(xr * 128 + ((lhalf ^ ((xr >> 1) & 7)) << 4));
+    int buf = 0;
+    for (int kc = 0; kc < nk; kc++) {
+        // chunk kc has landed (this wave's part; with the barrier everybody's), and nobody still reads
+        // the buffer that chunk kc + 2 goes to.  Issued after chunk kc: the weights and the input of
+        // chunk kc + 1 (chunk 0: only the input of chunk 1, the weights went first).
+        if (kc == 0) {
+            if (nk > 1) bn_wait_vm<XO>(); else bn_wait_vm<0>();
+        } else {
+            if (kc + 1 < nk) bn_wait_vm<WO + XO>(); else bn_wait_vm<0>();
+        }
+        __builtin_amdgcn_s_barrier();
+        if (kc + 2 < nk) {
+            load_w(w2, kc + 2);
+            issue_x(buf >= 1 ? buf - 1 : 2, kc + 2);             // (buf + 2) % 3
+        }
+        const uint32_t xs = xs0 + (uint32_t)(buf * XS);
+        bf16x8 xf[2][TP];
+        auto read_frags = [&](auto ks_c, auto b_c) {
+            constexpr int ks = decltype(ks_c)::value, b = decltype(b_c)::value;
+            const uint32_t xa = xs ^ (uint32_t)(ks << 5);
+            bn_unroll<TP>([&](auto j) { xf[b][decltype(j)::value] = bn_lds_read<decltype(j)::value * 4096>(xa); });
+        };
+        read_frags(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        bn_unroll<4>([&](auto ks_c) {
+            constexpr int ks = decltype(ks_c)::value, b = ks & 1;
+            // the next step's reads are issued first; LDS returns in order, so once no more than those
+            // are outstanding this step's fragments are complete
+            if constexpr (ks + 1 < 4) {
+                read_frags(std::integral_constant<int, ks + 1>{}, std::integral_constant<int, b ^ 1>{});
+                asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(TP) : "memory");
+            } else {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            }
+#pragma unroll
+            for (int j = 0; j < TP; j++) bn_tie(xf[b][j]);
+#pragma unroll
+            for (int j = 0; j < TP; j++) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0[ks], xf[b][j], acc[j], 0, 0, 0);
+        });
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) {
+            w0[ks] = w1[ks];
+            w1[ks] = w2[ks];
+        }
+        buf = buf == 2 ? 0 : buf + 1;
+    }
+
+    // ---- output: register v of a lane is channel wc + 16(v/8) + 8(lane/32) + v%8 of its pixel.  Stores
+    //      to rows past the last pixel carry the out-of-range offset and are dropped by the hardware.
+#pragma unroll
+    for (int j = 0; j < TP; j++)
+#pragma unroll
+        for (int k = 0; k < 2; k++) {
+            const u32x4 o = has_res ? bn_pack_res<true>(acc[j], k, res[j][k], a.act) : bn_pack_res<false>(acc[j], k, res[j][k], a.act);
+            __builtin_amdgcn_raw_buffer_store_b128(o, yres, yo[j], 32 * k, 0);
+        }
+}
+
+// ---- host side -----------------------------------------------------------------------------
+static bool pw_shape_ok(const ConvArgs& a, int nb) {
+    if (a.kh != 1 || a.kw != 1 || a.sh != 1 || a.sw != 1 || a.pt != 0 || a.pl != 0 || a.Ho != a.H || a.Wo != a.W) return false;
+    if (a.pre_scale || !a.wpk || a.cin % 64 || a.cout % 32) return false;
+    // 32-bit byte offsets with 2^31 standing for 'outside'
+    const long long P = (long long)nb * a.H * a.W;
+    if (P * a.x.stride * 2 >= 0x7FFFFF00LL || P * a.y.stride * 2 >= 0x7FFFFF00LL) return false;
+    if (a.res.p && P * a.res.stride * 2 >= 0x7FFFFF00LL) return false;
+    if ((long long)a.cout * a.cin * 2 >= 0x7FFFFF00LL) return false;
+    if (a.x.stride % 8 || a.x.c0 % 8 || a.y.stride % 8 || a.y.c0 % 8) return false;
+    if (a.res.p && (a.res.stride % 8 || a.res.c0 % 8)) return false;
+    return true;
+}
+
+bool conv_pw_applicable(const ConvArgs& a, int nb, int G) {
+#ifdef ENS_CONV_TUNING
+    if (const char* e = getenv("ENS_CONV_PW")) if (atoi(e) == 0) return false;
+#endif
+    return pw_shape_ok(a, nb);
+}
+
+
+
+template <int WPX>
+static hipError_t launch_pw_variant(const ConvArgs& a, const ConvArgs* argv, int G, int nb, hipStream_t s) {
+    constexpr int BC = 32 * (4 / WPX);
+    const long long P = (long long)nb * a.H * a.W;
+    const dim3 grid((unsigned)(((P + PW_BP - 1) / PW_BP) * ((a.cout + BC - 1) / BC)), 1, G);
+    ENS_LAUNCH((conv1x1_direct_bf16<WPX>), grid, dim3(256), (size_t)PW_NXB * PW_XS, s, argv, nb);
+    return hipGetLastError();
+}
+
+// 128 x 128 tiles unless the layer has 64 output channels or fewer, or so few pixels that those tiles
+// number fewer than the compute units (measured over the 1x1 layers of a ResNet-50 at batches of 16 to
+// 128: with 196 tiles or fewer the 128 x 64 tile is faster or equal, with 392 or more the larger one)
+static int pw_wpx(const ConvArgs& a, int nb, int G) {
+    const long long tiles = (((long long)nb * a.H * a.W + PW_BP - 1) / PW_BP) * ((a.cout + 127) / 128) * G;
+    int wpx = a.cout <= 64 || tiles < 256 ? 2 : 1;
+#ifdef ENS_CONV_TUNING
+    if (const char* e = getenv("ENS_CONV_PW_WPX")) if (atoi(e) == 1 || atoi(e) == 2) wpx = atoi(e);
+#endif
+    return wpx;
+}
+
+const char* conv_pw_name(const ConvArgs& a, int G) { return pw_wpx(a, a.nb, G) == 2 ? "conv1x1_direct_bf16<128x64>" : "conv1x1_direct_bf16<128x128>"; }
+
+hipError_t launch_conv_pw(const ConvArgs& a, const ConvArgs* argv, int G, int nb, hipStream_t s) {
+    if (!pw_shape_ok(a, nb)) return hipErrorInvalidValue;
+    return pw_wpx(a, nb, G) == 2 ? launch_pw_variant<2>(a, argv, G, nb, s) : launch_pw_variant<1>(a, argv, G, nb, s);
+}
+
+}  // namespace ens

@@ -199,6 +199,7 @@ static int build_launches(ens_handle* h, Gang& g) {
         if (!m.ops[i].fuse_next || chain[i] || chain[i + 1]) continue;   // a bottleneck kernel takes precedence
         Launch a, b;
         if (fill_args(h, leader, leader, G, m.ops[i], a) != ENS_OK || fill_args(h, leader, leader, G, m.ops[i + 1], b) != ENS_OK) continue;
+        a.conv.wpk = b.conv.wpk = nullptr;                       // a pair runs on the generic kernel
         const char* generic = "conv_igemm_bf16";
         if (strncmp(conv_bf16_variant_name(a.conv, 2 * G), generic, strlen(generic)) == 0 &&
             strncmp(conv_bf16_variant_name(b.conv, 2 * G), generic, strlen(generic)) == 0) {
@@ -266,6 +267,7 @@ static int build_launches(ens_handle* h, Gang& g) {
                 const int rc = fill_args(h, h->workers[g.workers[k]], leader, G, pl, L, fused[i] == 1 ? 0 : sub);
                 if (rc != ENS_OK) return rc;
                 if (fused[i] == 1) {                             // no split of the depth: the two would share one workspace
+                    L.conv.wpk = nullptr;                        // the generic kernel runs both
                     L.conv.ws = nullptr;
                     L.conv.ws_floats = 0;
                     if (sub == 1) { flop2 = L.flop; bytes2 = L.bytes; }

@@ -334,6 +334,35 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
     // before wrote, with nobody else reading or writing the two tensors in between.  One kernel can
     // run all three (decided per batch size when the launches are built); the block's output then
     // counts as written from the first of them on.
+    // Kernels that take each wavefront's weights straight from memory read a second copy of them in the
+    // order of the matrix-core operands, so that a wavefront's load is 1 KB in a row.  Rows in blocks of
+    // 32, the K axis (taps x channels) in steps of 16: [block][step][lane][8], lane (r, h) holding row
+    // 32 block + r', columns 16 step + 8 h .. + 7, r' = r with bits 2 and 3 swapped.
+    auto pack_operand_order = [&](OpPlan& pl) {
+        if (pl.w_packed != SIZE_MAX) return;
+        const int rows = pl.op.cout, K = pl.op.kh * pl.op.kw * pl.cin_s;
+        const size_t off = bw.reserve((size_t)rows * K * 2);
+        const uint16_t* src = (const uint16_t*)(m.host_params.data() + pl.w);
+        uint16_t* dst = (uint16_t*)(m.host_params.data() + off);
+        const int NS = K / 16;
+        for (int rb = 0; rb < rows / 32; rb++)
+            for (int st = 0; st < NS; st++)
+                for (int lane = 0; lane < 64; lane++) {
+                    const int r = lane & 31, h = lane >> 5;
+                    const int row = 32 * rb + ((r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1));
+                    memcpy(dst + (((size_t)rb * NS + st) * 64 + lane) * 8, src + (size_t)row * K + 16 * st + 8 * h, 16);
+                }
+        pl.w_packed = off;
+    };
+    // 1x1 stride-1 layers whose channels come in 64s (in) and 32s (out): the kernel of conv_pw.hip
+    if (m.bf16) {
+        for (int i = 0; i < spec.n_ops; i++) {
+            const ens_op& o = spec.ops[i];
+            if (o.kind == ENS_OP_CONV && o.kh == 1 && o.kw == 1 && o.sh == 1 && o.sw == 1 && o.pt == 0 && o.pl == 0 && o.r <= 1 &&
+                !o.pre && o.cin % 64 == 0 && o.cout % 32 == 0 && m.ops[i].cin_s == o.cin)
+                pack_operand_order(m.ops[i]);
+        }
+    }
     if (m.bf16) {
         std::vector<int> uses(m.tensors.size(), 0);              // readers and writers of every tensor
         for (int i = 0; i < spec.n_ops; i++) {
@@ -360,26 +389,7 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
             if (p.cin % 32 || o.cout % 32) continue;
             m.ops[i].fuse_chain = true;
             m.tensors[o.dst].def = std::min(m.tensors[o.dst].def, i);
-            // The fused kernel takes each wavefront's weights straight from memory: a second copy in the order
-            // of the matrix-core operands, so that a wavefront's load is 1 KB in a row.  Rows in blocks of 32,
-            // the K axis (taps x channels) in steps of 16: [block][step][lane][8], lane (r, h) holding row
-            // 32 block + r', columns 16 step + 8 h .. + 7, r' = r with bits 2 and 3 swapped.
-            for (int j = 0; j < 3; j++) {
-                OpPlan& pl = m.ops[i + j];
-                const int rows = pl.op.cout, K = pl.op.kh * pl.op.kw * pl.cin_s;
-                const size_t off = bw.reserve((size_t)rows * K * 2);
-                const uint16_t* src = (const uint16_t*)(m.host_params.data() + pl.w);
-                uint16_t* dst = (uint16_t*)(m.host_params.data() + off);
-                const int NS = K / 16;
-                for (int rb = 0; rb < rows / 32; rb++)
-                    for (int st = 0; st < NS; st++)
-                        for (int lane = 0; lane < 64; lane++) {
-                            const int r = lane & 31, h = lane >> 5;
-                            const int row = 32 * rb + ((r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1));
-                            memcpy(dst + (((size_t)rb * NS + st) * 64 + lane) * 8, src + (size_t)row * K + 16 * st + 8 * h, 16);
-                        }
-                pl.w_packed = off;
-            }
+            for (int j = 0; j < 3; j++) pack_operand_order(m.ops[i + j]);
         }
     }
     if (stem_op >= 0) {                                          // tensor 0 as the staging kernel writes it

@@ -169,6 +169,8 @@ CONV_LAYERS = [
     (7, 7, 512, 512, 3, 1, "same", {}),
     (7, 7, 2048, 512, 1, 1, "same", {}),
     (9, 9, 24, 1000, 1, 1, "same", {}),
+    (13, 13, 192, 96, 1, 1, "same", {"act": "silu"}),          # weights-from-memory 1x1 kernel: three input chunks, half-empty channel tile
+    (10, 10, 64, 32, 1, 1, "same", {"act": None}),             # ... one chunk, one block of channels
 ]
 
 
@@ -178,6 +180,8 @@ MANY_TILES = [
     ((56, 56, 64, 128, 3, 1, "same", {}), 24),                  # 610 tiles for 256 workgroups per channel tile
     ((56, 56, 64, 64, 3, 1, "same", {"res": True}), 40),        # 1016 tiles for 512 workgroups, residual
     ((96, 96, 3, 64, 7, 2, "same", {}), 64),                    # stem: 601 tiles of 256 positions for 512 workgroups
+    ((56, 56, 64, 160, 1, 1, "same", {}), 6),                   # 1x1 from operand-ordered weights, 128x128 tiles, 32 channels in the last
+    ((28, 28, 128, 128, 1, 1, "same", {"res": True}), 48),      # ... with the residual
 ]
 
 
