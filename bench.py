@@ -25,7 +25,7 @@ TRAFFIC = {
     "kernel": "conv3x3_halo_bf16<128,64,c64>",
     "bytes_per_launch": 80.4e6,
     "sources": ("conv_halo.hip", "conv_common.h", "kernels.h"),
-    "sha256": "7138c7409b7c71bfaac0215463636e564634e77b95043eff0bb83857ed57375e",
+    "sha256": "4c78a285f36902f3fcec5f9b15c63a10e0b3cac99aba0bd07050e84f26cebdf5",
 }
 
 
