@@ -263,6 +263,40 @@ def test_two_convolutions_in_one_launch(ens):
         assert err.mean() <= 2.0 ** -6 * scale, (x, err.mean(), scale)
 
 
+def test_pointwise_layers_of_a_gang(ens):
+    """Two members of the same shape run every layer as one launch with two argument blocks; their 1x1
+    layers (64 -> 128 with 128-channel tiles, 128 -> 64 with 64-channel tiles and a residual) go to the
+    kernel that reads operand-ordered weights.  Each member's tensors are compared with the oracle."""
+    nets = []
+    for g in range(2):
+        n = N.Net("pw%d" % g, 20, 20, 8, dtype="bf16")
+        x = n.conv(0, 64, 3)
+        a = n.conv(x, 128, 1, act="silu")
+        b = n.conv(a, 64, 1, res=x)
+        n.fc(n.gap(b), 8)
+        nets.append(n)
+    nb = 7
+    blobs = [W.quantise_weights_bf16(n, W.make_blob(n, 41, i)) for i, n in enumerate(nets)]
+    imgs = W.round_bf16(W.make_images(42, nb, 20, 20))
+    E = ens.Ensemble(nets, blobs)
+    E.set_base_size(20, 20)
+    E.ens_debug_keep_tensors()
+    E.ens_set_alloc([[8, 8]])
+    E.ens_set_profiling(1)
+    E.ens_predict(imgs)
+    ran = {k["name"]: k["launches"] for k in E.ens_profile() if k["launches"]}
+    got = [[E.ens_debug_tensor(g, t, nets[g].tensors[t], nb) for t in (a, b)] for g in range(2)]
+    E.close()
+    assert ran.get("conv1x1_direct_bf16<128x64>") == 2, ran        # both layers: 22 tiles of 128 x 128 are fewer than the compute units
+    for g in range(2):
+        for t, y in zip((a, b), got[g]):
+            ref = oracle_tensor(nets[g], blobs[g], imgs, t)
+            scale = np.sqrt(np.mean(ref ** 2)) + 1e-6
+            err = np.abs(y - ref)
+            assert err.max() <= 0.05 * scale + 2.0 ** -6 * np.abs(ref).max(), (g, t, err.max(), scale)
+            assert err.mean() <= 2.0 ** -6 * scale, (g, t, err.mean(), scale)
+
+
 # (C, H, W, cin, cout, residual, activation of the last convolution, members in the gang, images, batch)
 BOTTLENECKS = [
     (64, 24, 24, 256, 256, "input", "relu", 1, 56, 64),        # identity block, short last batch
