@@ -77,9 +77,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     float* const b2l = b1l + C;
     float* const b3l = b2l + C;
     // the weights of the first two input chunks are asked for before anything else
-    const __amdgpu_buffer_rsrc_t w1res = __builtin_amdgcn_make_buffer_rsrc((void*)a1.wpk, 0, (int)((unsigned)C * (unsigned)cin1 * 2u), 0x00020000);
+    const int NS1 = (cin1 + 63) / 64 * 4, nk1 = cin1 / 32;       // steps per block of 32 weight rows (columns padded to 64s); input chunks
+    const __amdgpu_buffer_rsrc_t w1res = __builtin_amdgcn_make_buffer_rsrc((void*)a1.wpk, 0, (int)((unsigned)C * (unsigned)(NS1 * 16) * 2u), 0x00020000);
     const int row0 = (wave % WR1) * (TP1 * 32), ch0 = (wave / WR1) * (TC1 * 32);   // phase 1: this wave's window rows and channels
-    const int NS1 = cin1 / 16, nk1 = cin1 / 32;                  // steps per block of 32 weight rows; input chunks
     const unsigned wv1 = (unsigned)((ch0 / 32) * NS1 * 1024 + lane * 16);
     bf16x8 w0[2][TC1], w1[2][TC1], w2[2][TC1];                   // weights of this chunk, the next, the one after
     auto load_w = [&](bf16x8 (&w)[2][TC1], int kc) {

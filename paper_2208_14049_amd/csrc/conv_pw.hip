@@ -1,7 +1,8 @@
 // 1x1, stride-1 convolution on the CDNA4 matrix cores with the weights taken straight from memory
-// in matrix-core operand order (conv_direct.h), for layers whose input channels come in 64s and
-// output channels in 32s: the 1x1 layers of residual bottlenecks that do not run inside the fused
-// bottleneck kernel.
+// in matrix-core operand order (conv_direct.h): the 1x1 layers of residual bottlenecks that do not
+// run inside the fused bottleneck kernel, the expansion and projection layers of inverted-residual
+// blocks, the pointwise halves of separable convolutions.  Channel counts are multiples of 8; the
+// operand-ordered copy of the weights is padded with zeros to 32 rows and 64 columns.
 //
 // GEMM view: rows = pixels, columns = output channels, K = input channels.  A workgroup of four
 // wavefronts owns 128 pixels x BC channels.  The pixels' input arrives 64 channels at a time
@@ -42,14 +43,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     if (ptile >= n_ptiles) return;
     const int p0 = ptile * BP, c0 = ctile * BC;
     const int wp0 = (wave % WPX) * (TP * 32);
-    const int wc = c0 + (wave / WPX) * 32;           // this wave's 32 channels (the launcher admits multiples of 32 only)
+    const int wc = c0 + (wave / WPX) * 32;           // this wave's 32 channels; the last block of a layer may hold fewer
     const bool wave_ok = wc < a.cout;
-    const int NS = a.cin / 16, nk = a.cin / 64;      // matrix-core steps per block of weight rows; input chunks
+    const int nk = (a.cin + 63) / 64, NS = nk * 4;   // input chunks; matrix-core steps per block of weight rows
 
     // Offsets past the end of a buffer give zeros (loads) or are dropped (stores); 2^31 is past the
     // end of every buffer the launcher admits.
     constexpr unsigned OOBV = 0x80000000u;
-    const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc((void*)a.wpk, 0, (int)((unsigned)a.cout * (unsigned)a.cin * 2u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)a.wpk, 0, (int)((unsigned)((a.cout + 31) / 32 * 32) * (unsigned)(nk * 64) * 2u), 0x00020000);
     const unsigned wv = wave_ok ? (unsigned)((wc / 32) * NS * 1024 + lane * 16) : OOBV;
     bf16x8 w0[4], w1[4], w2[4];                      // weights of this chunk, the next, the one after
     auto load_w = [&](bf16x8 (&w)[4], int kc) {
@@ -65,26 +67,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const bool has_res = a.res.p != nullptr;
     const __amdgpu_buffer_rsrc_t rres = __builtin_amdgcn_make_buffer_rsrc(
         (void*)(has_res ? a.res.p : a.y.p), 0, (int)(npix * (unsigned)(has_res ? a.res.stride : a.y.stride) * 2u), 0x00020000);
-    unsigned yo[TP], ro[TP];
+    // this lane's two runs of 8 channels, wc + 8 (lane / 32) + 16 k: each exists as a whole or not at all
+    const int ch0 = wc + 8 * lhalf;
+    const bool run_ok[2] = {ch0 < a.cout, ch0 + 16 < a.cout};
+    unsigned yo[TP][2], ro[TP][2];
 #pragma unroll
     for (int j = 0; j < TP; j++) {
         const int p = p0 + wp0 + 32 * j + lrow;
-        const bool ok = p < P && wave_ok;
-        yo[j] = ok ? (unsigned)(p * a.y.stride * 2) + (unsigned)((a.y.c0 + wc + 8 * lhalf) * 2) : OOBV;
-        ro[j] = ok ? (unsigned)(p * a.res.stride * 2) + (unsigned)((a.res.c0 + wc + 8 * lhalf) * 2) : OOBV;
+#pragma unroll
+        for (int k = 0; k < 2; k++) {
+            const bool ok = p < P && run_ok[k];
+            yo[j][k] = ok ? (unsigned)(p * a.y.stride * 2) + (unsigned)((a.y.c0 + ch0) * 2) : OOBV;
+            ro[j][k] = ok ? (unsigned)(p * a.res.stride * 2) + (unsigned)((a.res.c0 + ch0) * 2) : OOBV;
+        }
     }
     u32x4 res[TP][2];
     if (has_res) {
 #pragma unroll
         for (int j = 0; j < TP; j++) {
-            res[j][0] = __builtin_amdgcn_raw_buffer_load_b128(rres, ro[j], 0, 0);
-            res[j][1] = __builtin_amdgcn_raw_buffer_load_b128(rres, ro[j], 32, 0);
+            res[j][0] = __builtin_amdgcn_raw_buffer_load_b128(rres, ro[j][0], 0, 0);
+            res[j][1] = __builtin_amdgcn_raw_buffer_load_b128(rres, ro[j][1], 32, 0);
         }
     }
     f32x16 acc[TP];
     {
-        const float* b = a.bias + (wave_ok ? wc : 0) + 8 * lhalf;   // this lane's channels: b[0..7] and b[16..23]
-        const f32x4 q0 = *ENS_GLOBAL(f32x4, b), q1 = *ENS_GLOBAL(f32x4, b + 4), q2 = *ENS_GLOBAL(f32x4, b + 16), q3 = *ENS_GLOBAL(f32x4, b + 20);
+        // bias of channels ch0 + 0..7 and ch0 + 16..23 (zeros past the last channel)
+        const __amdgpu_buffer_rsrc_t bres = __builtin_amdgcn_make_buffer_rsrc((void*)a.bias, 0, (int)((unsigned)a.cout * 4u), 0x00020000);
+        const unsigned bo = (unsigned)ch0 * 4u;
+        const f32x4 q0 = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(bres, bo, 0, 0));
+        const f32x4 q1 = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(bres, bo, 16, 0));
+        const f32x4 q2 = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(bres, bo, 64, 0));
+        const f32x4 q3 = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(bres, bo, 80, 0));
 #pragma unroll
         for (int e = 0; e < 4; e++) {
             acc[0][e] = q0[e];
@@ -105,11 +118,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         const int p = p0 + r8 + 32 * s;
         xvo[s] = p < P ? (unsigned)(p * a.x.stride * 2) + (unsigned)(a.x.c0 * 2 + c8 * 16) : OOBV;
     }
+    // in the last chunk of a layer whose input channels are not a multiple of 64 this thread's 8 channels
+    // may lie past the last one: zeros then (what follows them in memory belongs to the next pixel)
+    const bool tail_ok = (nk - 1) * 64 + c8 * 8 < a.cin;
     unsigned char* const mine = lds + wave * 1024;               // this wave's quarter of a 4 KB load
     auto issue_x = [&](int buf, int kc) {
+        const bool live = kc + 1 < nk || tail_ok;
 #pragma unroll
         for (int s = 0; s < XO; s++)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (lds_ptr_t)(mine + buf * XS + s * 4096), LDS_LOAD_BYTES, xvo[s], kc * 128, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (lds_ptr_t)(mine + buf * XS + s * 4096), LDS_LOAD_BYTES, live ? xvo[s] : OOBV,
+                                                     kc * 128, 0, 0);
     };
     issue_x(0, 0);
     if (nk > 1) issue_x(1, 1);
@@ -170,19 +188,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int k = 0; k < 2; k++) {
             const u32x4 o = has_res ? bn_pack_res<true>(acc[j], k, res[j][k], a.act) : bn_pack_res<false>(acc[j], k, res[j][k], a.act);
-            __builtin_amdgcn_raw_buffer_store_b128(o, yres, yo[j], 32 * k, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(o, yres, yo[j][k], 32 * k, 0);
         }
 }
 
 // ---- host side -----------------------------------------------------------------------------
 static bool pw_shape_ok(const ConvArgs& a, int nb) {
     if (a.kh != 1 || a.kw != 1 || a.sh != 1 || a.sw != 1 || a.pt != 0 || a.pl != 0 || a.Ho != a.H || a.Wo != a.W) return false;
-    if (a.pre_scale || !a.wpk || a.cin % 64 || a.cout % 32) return false;
+    if (a.pre_scale || !a.wpk || a.cin % 8 || a.cout % 8) return false;
     // 32-bit byte offsets with 2^31 standing for 'outside'
     const long long P = (long long)nb * a.H * a.W;
     if (P * a.x.stride * 2 >= 0x7FFFFF00LL || P * a.y.stride * 2 >= 0x7FFFFF00LL) return false;
     if (a.res.p && P * a.res.stride * 2 >= 0x7FFFFF00LL) return false;
-    if ((long long)a.cout * a.cin * 2 >= 0x7FFFFF00LL) return false;
+    if ((long long)(a.cout + 31) * (a.cin + 63) * 2 >= 0x7FFFFF00LL) return false;
     if (a.x.stride % 8 || a.x.c0 % 8 || a.y.stride % 8 || a.y.c0 % 8) return false;
     if (a.res.p && (a.res.stride % 8 || a.res.c0 % 8)) return false;
     return true;

@@ -337,29 +337,31 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
     // Kernels that take each wavefront's weights straight from memory read a second copy of them in the
     // order of the matrix-core operands, so that a wavefront's load is 1 KB in a row.  Rows in blocks of
     // 32, the K axis (taps x channels) in steps of 16: [block][step][lane][8], lane (r, h) holding row
-    // 32 block + r', columns 16 step + 8 h .. + 7, r' = r with bits 2 and 3 swapped.
+    // 32 block + r', columns 16 step + 8 h .. + 7, r' = r with bits 2 and 3 swapped.  Rows are padded with
+    // zeros to a multiple of 32, columns to a multiple of 64.
     auto pack_operand_order = [&](OpPlan& pl) {
         if (pl.w_packed != SIZE_MAX) return;
-        const int rows = pl.op.cout, K = pl.op.kh * pl.op.kw * pl.cin_s;
-        const size_t off = bw.reserve((size_t)rows * K * 2);
+        const int rows = pl.op.cout, K = pl.op.kh * pl.op.kw * pl.cin_s;       // K in 8s: a lane's 16 bytes are real or padding as a whole
+        const int rows_p = (rows + 31) / 32 * 32, K_p = (K + 63) / 64 * 64;
+        const size_t off = bw.reserve((size_t)rows_p * K_p * 2);
         const uint16_t* src = (const uint16_t*)(m.host_params.data() + pl.w);
         uint16_t* dst = (uint16_t*)(m.host_params.data() + off);
-        const int NS = K / 16;
-        for (int rb = 0; rb < rows / 32; rb++)
+        const int NS = K_p / 16;
+        for (int rb = 0; rb < rows_p / 32; rb++)
             for (int st = 0; st < NS; st++)
                 for (int lane = 0; lane < 64; lane++) {
                     const int r = lane & 31, h = lane >> 5;
-                    const int row = 32 * rb + ((r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1));
-                    memcpy(dst + (((size_t)rb * NS + st) * 64 + lane) * 8, src + (size_t)row * K + 16 * st + 8 * h, 16);
+                    const int row = 32 * rb + ((r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1)), col = 16 * st + 8 * h;
+                    if (row < rows && col < K) memcpy(dst + (((size_t)rb * NS + st) * 64 + lane) * 8, src + (size_t)row * K + col, 16);
                 }
         pl.w_packed = off;
     };
-    // 1x1 stride-1 layers whose channels come in 64s (in) and 32s (out): the kernel of conv_pw.hip
+    // 1x1 stride-1 layers without pre-activation: the kernel of conv_pw.hip
     if (m.bf16) {
         for (int i = 0; i < spec.n_ops; i++) {
             const ens_op& o = spec.ops[i];
             if (o.kind == ENS_OP_CONV && o.kh == 1 && o.kw == 1 && o.sh == 1 && o.sw == 1 && o.pt == 0 && o.pl == 0 && o.r <= 1 &&
-                !o.pre && o.cin % 64 == 0 && o.cout % 32 == 0 && m.ops[i].cin_s == o.cin)
+                !o.pre && o.cin % 8 == 0 && o.cout % 8 == 0 && m.ops[i].cin_s == o.cin)
                 pack_operand_order(m.ops[i]);
         }
     }

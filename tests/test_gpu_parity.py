@@ -171,6 +171,8 @@ CONV_LAYERS = [
     (9, 9, 24, 1000, 1, 1, "same", {}),
     (13, 13, 192, 96, 1, 1, "same", {"act": "silu"}),          # weights-from-memory 1x1 kernel: three input chunks, half-empty channel tile
     (10, 10, 64, 32, 1, 1, "same", {"act": None}),             # ... one chunk, one block of channels
+    (14, 14, 80, 80, 1, 1, "same", {"res": True, "act": None}),    # ... channels in 8s: half-empty last chunk and last block, residual
+    (19, 19, 728, 728, 1, 1, "same", {}),                      # ... the pointwise half of a 728-channel separable layer
 ]
 
 

@@ -181,9 +181,8 @@ def test_grouped_convolutions_in_descriptions():
     dense_blocks = sum(9 * op["cout"] * 32 for op in net.ops if op["kind"] == N.CONV and op["r"] > 1)
     grouped = sum(9 * op["cout"] * op["cin"] // op["r"] for op in net.ops if op["kind"] == N.CONV and op["r"] > 1)
     # plus the second, operand-ordered copy of the 1x1 stride-1 layers that a kernel fetches straight from memory
-    copies = sum(op["cin"] * op["cout"] for op in net.ops
-                 if op["kind"] == N.CONV and op["kh"] == 1 and op["kw"] == 1 and op["sh"] == 1 and op["r"] <= 1
-                 and op["cin"] % 64 == 0 and op["cout"] % 32 == 0)
+    copies = sum(-(-op["cin"] // 64) * 64 * -(-op["cout"] // 32) * 32 for op in net.ops
+                 if op["kind"] == N.CONV and op["kh"] == 1 and op["kw"] == 1 and op["sh"] == 1 and op["r"] <= 1)
     assert copies > 0
     expected = 2 * (n_w - grouped + dense_blocks + copies)
     assert expected <= w <= expected + 4 * 40000 + 1024 * len(net.ops)
@@ -210,13 +209,13 @@ def test_grouped_convolutions_in_descriptions():
 
 
 def test_bottleneck_chains_in_descriptions():
-    """The plan keeps a second copy, in matrix-core operand order, of the weights of layers that kernels
-    fetch straight from memory: every 1x1 stride-1 convolution whose input channels come in 64s and
-    output channels in 32s, and all three layers of a residual bottleneck that one kernel can run (1x1,
-    3x3 stride 1, 1x1, with 64 or 128 channels in between and nobody else touching the two middle
+    """The plan keeps a second copy, in matrix-core operand order (rows padded to 32, columns to 64), of
+    the weights of layers that kernels fetch straight from memory: every 1x1 stride-1 convolution
+    without pre-activation, and the 3x3 layer of a residual bottleneck that one kernel can run (1x1, 3x3
+    stride 1, 1x1, with 64 or 128 channels in between and nobody else touching the two middle
     tensors).  The parameter block grows by exactly those copies: the same layers with a stride on the
     3x3, another width in the middle, a second reader of a middle tensor or fp32 parameters get no
-    copy of the 3x3 filter (nor of a 1x1 filter that only the chain qualifies)."""
+    copy of the 3x3 filter."""
     def block(c, cin, cout, stride=1, tap_t1=False, dtype="bf16"):
         n = N.Net("b", 16, 16, 10, dtype=dtype)
         x = n.conv(0, cin, 3)
@@ -230,20 +229,17 @@ def test_bottleneck_chains_in_descriptions():
         return n
 
     up = lambda b: (b + 255) // 256 * 256
-    pointwise = lambda cin, cout: up(2 * cin * cout) if cin % 64 == 0 and cout % 32 == 0 else 0
+    pointwise = lambda cin, cout: up(2 * (-(-cin // 64) * 64) * (-(-cout // 32) * 32))
 
     for c, cin, cout in ((64, 256, 256), (128, 64, 512), (64, 32, 128)):
         fused, _ = ens.ens_spec_bytes(block(c, cin, cout), 8)
         plain, _ = ens.ens_spec_bytes(block(c, cin, cout, stride=2), 8)
-        chain_only = up(2 * 9 * c * c) + (up(2 * c * cin) - pointwise(cin, c)) + (up(2 * c * cout) - pointwise(c, cout))
-        assert fused - plain == chain_only, (c, cin, cout, fused - plain)
-    # the 1x1 layers alone: 256 -> 64 and 64 -> 256 qualify, 96 -> 256 qualifies and 256 -> 96 too, 48 -> 64 does not
-    n1 = N.Net("p", 16, 16, 10, dtype="bf16"); n1.fc(n1.gap(n1.conv(n1.conv(0, 256, 3), 64, 1)), 10)
-    n2 = N.Net("p", 16, 16, 10, dtype="bf16"); n2.fc(n2.gap(n2.conv(n2.conv(0, 256, 3), 64, 1, stride=2)), 10)
-    assert ens.ens_spec_bytes(n1, 8)[0] - ens.ens_spec_bytes(n2, 8)[0] == up(2 * 256 * 64)
-    n3 = N.Net("p", 16, 16, 10, dtype="bf16"); n3.fc(n3.gap(n3.conv(n3.conv(0, 48, 3), 64, 1)), 10)
-    n4 = N.Net("p", 16, 16, 10, dtype="bf16"); n4.fc(n4.gap(n4.conv(n4.conv(0, 48, 3), 64, 1, stride=2)), 10)
-    assert ens.ens_spec_bytes(n3, 8)[0] == ens.ens_spec_bytes(n4, 8)[0]
+        assert fused - plain == up(2 * 9 * c * c), (c, cin, cout, fused - plain)
+    # the 1x1 layers alone: a stride-1 layer gets the padded copy (256 -> 64 as it is; 40 -> 24 as 64 -> 32), a stride-2 layer none
+    for cin, cout in ((256, 64), (40, 24)):
+        n1 = N.Net("p", 16, 16, 10, dtype="bf16"); n1.fc(n1.gap(n1.conv(n1.conv(0, cin, 3), cout, 1)), 10)
+        n2 = N.Net("p", 16, 16, 10, dtype="bf16"); n2.fc(n2.gap(n2.conv(n2.conv(0, cin, 3), cout, 1, stride=2)), 10)
+        assert ens.ens_spec_bytes(n1, 8)[0] - ens.ens_spec_bytes(n2, 8)[0] == pointwise(cin, cout)
     plain, _ = ens.ens_spec_bytes(block(96, 256, 256, stride=2), 8)
     assert ens.ens_spec_bytes(block(96, 256, 256), 8)[0] == plain            # 96 channels in the middle
     w_tap, _ = ens.ens_spec_bytes(block(64, 256, 256, tap_t1=True), 8)
@@ -251,3 +247,4 @@ def test_bottleneck_chains_in_descriptions():
     assert w_tap == w_tap2                                                    # a second reader of t1
     assert ens.ens_spec_bytes(block(64, 256, 256, dtype="fp32"), 8)[0] == ens.ens_spec_bytes(block(64, 256, 256, stride=2, dtype="fp32"), 8)[0]
     assert ens.ens_spec_bytes(block(64, 48, 256), 8)[0] == ens.ens_spec_bytes(block(64, 48, 256, stride=2), 8)[0]   # input not in 32s
+    assert pointwise(48, 64) == up(2 * 64 * 64)
