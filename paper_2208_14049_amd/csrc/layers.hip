@@ -366,6 +366,88 @@ __global__ void dwconv_bf16_kernel(const PoolArgs* __restrict__ argv, const int 
     *(uint4*)((uint16_t*)a.y.p + (long long)pu * a.y.stride + a.y.c0 + c) = pack8(acc);
 }
 
+// Depthwise K x K convolution with stride S (the same both ways), bf16, one lane per (NW consecutive
+// output columns, 8 channels).  With one output per lane every input value is fetched K x K times
+// and the filter once per output, 2 K^2 loads of 16 bytes per 16 bytes stored, and the kernel is
+// bound by the compute unit's 64 bytes per clock from L1, not by HBM.  Here a filter row costs
+// (NW - 1) S + K input loads and K weight loads for NW outputs (K = 3, S = 1, NW = 4: 6.75 loads
+// per output instead of 18).  Taps are loaded from positions clamped into the image and zeroed
+// by a select when they lie outside; the filter rows stay a loop.
+template <int K, int S, int NW>
+__global__ __launch_bounds__(256) void dwconv_row_bf16_kernel(const PoolArgs* __restrict__ argv, const int nb_) {
+    const PoolArgs a = argv[blockIdx.z];
+    constexpr int NCOL = (NW - 1) * S + K;
+    const unsigned cv = (unsigned)(a.c / 8);
+    const unsigned wgroups = (unsigned)(a.Wo + NW - 1) / NW;     // lanes' runs of NW columns per output row
+    const unsigned idx = xcd_block() * blockDim.x + threadIdx.x;
+    const unsigned total = (unsigned)nb_ * (unsigned)a.Ho * wgroups * cv;
+    if (idx >= total) return;
+    const unsigned gu = idx / cv;
+    const int c = (int)(idx - gu * cv) * 8;
+    const unsigned row = gu / wgroups;                           // n * Ho + ho
+    const int wo0 = (int)(gu - row * wgroups) * NW;
+    const unsigned nu = row / (unsigned)a.Ho;
+    const int ho = (int)(row - nu * (unsigned)a.Ho);
+    const uint16_t* __restrict__ x = (const uint16_t*)a.x.p + (long long)nu * a.H * a.W * a.x.stride + a.x.c0 + c;
+    const uint16_t* __restrict__ w = (const uint16_t*)a.w + c;
+    float acc[NW][8];
+    {
+        const float4 b0 = *(const float4*)(a.bias + c), b1 = *(const float4*)(a.bias + c + 4);
+#pragma unroll
+        for (int o = 0; o < NW; o++) {
+            acc[o][0] = b0.x; acc[o][1] = b0.y; acc[o][2] = b0.z; acc[o][3] = b0.w;
+            acc[o][4] = b1.x; acc[o][5] = b1.y; acc[o][6] = b1.z; acc[o][7] = b1.w;
+        }
+    }
+    const int wi0 = wo0 * S - a.pl;
+#pragma unroll 1
+    for (int kh = 0; kh < K; kh++) {
+        const int hi = ho * S - a.pt + kh;
+        const bool hok = (unsigned)hi < (unsigned)a.H;
+        const int hic = min(max(hi, 0), a.H - 1);
+        uint4 xv[NCOL], wv[K];
+#pragma unroll
+        for (int j = 0; j < NCOL; j++) {
+            const int wic = min(max(wi0 + j, 0), a.W - 1);
+            xv[j] = *(const uint4*)(x + (long long)(hic * a.W + wic) * a.x.stride);
+        }
+#pragma unroll
+        for (int kw = 0; kw < K; kw++) wv[kw] = *(const uint4*)(w + (kh * K + kw) * a.c);
+        float wf[K][8];
+#pragma unroll
+        for (int kw = 0; kw < K; kw++) unpack8(wv[kw], wf[kw]);
+#pragma unroll
+        for (int j = 0; j < NCOL; j++) {
+            const bool ok = hok && (unsigned)(wi0 + j) < (unsigned)a.W;
+            if (!ok) xv[j] = make_uint4(0u, 0u, 0u, 0u);
+            float xf[8];
+            unpack8(xv[j], xf);
+            // input column j is tap kw = j - o S of output o
+#pragma unroll
+            for (int o = 0; o < NW; o++) {
+                const int kw = j - o * S;
+                if (kw >= 0 && kw < K) {
+#pragma unroll
+                    for (int e = 0; e < 8; e++) acc[o][e] = fmaf(xf[e], wf[kw][e], acc[o][e]);
+                }
+            }
+        }
+    }
+    uint16_t* __restrict__ y = (uint16_t*)a.y.p + ((long long)row * a.Wo + wo0) * a.y.stride + a.y.c0 + c;
+#pragma unroll
+    for (int o = 0; o < NW; o++) {
+        if (wo0 + o >= a.Wo) break;
+        if (a.act == ACT_SILU) {
+#pragma unroll
+            for (int e = 0; e < 8; e++) acc[o][e] = acc[o][e] / (1.f + __expf(-acc[o][e]));
+        } else if (a.act == ACT_RELU) {
+#pragma unroll
+            for (int e = 0; e < 8; e++) acc[o][e] = fmaxf(acc[o][e], 0.f);
+        }
+        *(uint4*)(y + (long long)o * a.y.stride) = pack8(acc[o]);
+    }
+}
+
 // Average pooling over the in-bounds part of a K x K window, bf16, one lane per (pixel, 8
 // channels): loads from clamped positions, taps outside the image zeroed by a select and left out
 // of the divisor.
@@ -425,6 +507,17 @@ hipError_t launch_dwconv(const PoolArgs& a, const PoolArgs* argv, int G, int nb,
     const long long total = (long long)nb * a.Ho * a.Wo * (a.c / (bf16 ? 8 : 1));
     if (total >= (1LL << 31) - 256) return hipErrorInvalidValue;   // 32-bit work item index in the kernel
     const dim3 g(blocks_for(total, 256), 1, G);
+    // 3x3 and 5x5 at strides 1 and 2: four output columns per lane (eight were measured too: no faster)
+    const int st = a.sh == a.sw ? a.sh : 0;
+    if (bf16 && a.kh == a.kw && (a.kh == 3 || a.kh == 5) && (st == 1 || st == 2)) {
+        constexpr int NW = 4;
+        const dim3 gw(blocks_for((long long)nb * a.Ho * ((a.Wo + NW - 1) / NW) * (a.c / 8), 256), 1, G);
+        if (a.kh == 3 && st == 1) ENS_LAUNCH((dwconv_row_bf16_kernel<3, 1, NW>), gw, dim3(256), 0, s, argv, nb);
+        else if (a.kh == 3) ENS_LAUNCH((dwconv_row_bf16_kernel<3, 2, NW>), gw, dim3(256), 0, s, argv, nb);
+        else if (st == 1) ENS_LAUNCH((dwconv_row_bf16_kernel<5, 1, NW>), gw, dim3(256), 0, s, argv, nb);
+        else ENS_LAUNCH((dwconv_row_bf16_kernel<5, 2, NW>), gw, dim3(256), 0, s, argv, nb);
+        return hipGetLastError();
+    }
     if (bf16 && a.kh == 3 && a.kw == 3) ENS_LAUNCH((dwconv_bf16_kernel<3>), g, dim3(256), 0, s, argv, nb);
     else if (bf16 && a.kh == 5 && a.kw == 5) ENS_LAUNCH((dwconv_bf16_kernel<5>), g, dim3(256), 0, s, argv, nb);
     else if (bf16) ENS_LAUNCH((window_kernel<0, true>), g, dim3(256), 0, s, argv, nb);
