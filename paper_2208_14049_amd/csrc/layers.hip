@@ -681,8 +681,14 @@ hipError_t launch_fc(const FcArgs& a, const FcArgs* argv, int G, int nb, long lo
 // and the rows are added through LDS.  (2) Gate: one workgroup per image adds the partial sums,
 // then the two small FC layers (SiLU, sigmoid) with all 256 threads on the first one.  (3) The
 // channel-wise rescale of the activation tensor.
-static inline int se_splits(int HW) {
-    const int s = (HW + 511) / 512;
+// Workgroups that share an image's pixels in the channel sums: one per 512 pixels, more when the
+// launch would otherwise have fewer than about 2048 workgroups (small maps, small batches), never
+// fewer than 8 pixels each.
+static inline int se_splits(int HW, int images) {
+    int s = (HW + 511) / 512;
+    const int fill = (2048 + images - 1) / (images > 0 ? images : 1);
+    if (s < fill) s = fill;
+    if (s > HW / 8) s = HW / 8;
     return s < 1 ? 1 : (s > SE_MAX_SPLITS ? SE_MAX_SPLITS : s);
 }
 
@@ -706,13 +712,22 @@ __global__ __launch_bounds__(256) void se_sum_kernel(const SeArgs* __restrict__ 
         for (int e = 0; e < V; e++) acc[e] = 0.f;
         if (g < cv && row < rows) {
             const long long base = (long long)n * a.HW * a.x.stride + a.x.c0 + g * V;
-            for (int p = p0 + row; p < p1; p += rows) {
-                const long long off = base + (long long)p * a.x.stride;
-                float v[V];
-                if (BF16) unpack8(*(const uint4*)((const uint16_t*)a.x.p + off), v);
-                else v[0] = ((const float*)a.x.p)[off];
+            // four loads in flight per lane; the sums keep the order of the pixels
+            for (int p = p0 + row; p < p1; p += 4 * rows) {
+                float v[4][V];
 #pragma unroll
-                for (int e = 0; e < V; e++) acc[e] += v[e];
+                for (int u = 0; u < 4; u++) {
+                    const int pu = min(p + u * rows, p1 - 1);
+                    const long long off = base + (long long)pu * a.x.stride;
+                    if (BF16) unpack8(*(const uint4*)((const uint16_t*)a.x.p + off), v[u]);
+                    else v[u][0] = ((const float*)a.x.p)[off];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; u++)
+                    if (p + u * rows < p1) {
+#pragma unroll
+                        for (int e = 0; e < V; e++) acc[e] += v[u][e];
+                    }
             }
         }
 #pragma unroll
@@ -807,7 +822,7 @@ hipError_t launch_se(const SeArgs& a, const SeArgs* argv, int G, int nb, bool bf
     if (bf16 && (a.c % 8 || a.x.stride % 8 || a.x.c0 % 8 || a.y.stride % 8 || a.y.c0 % 8)) return hipErrorInvalidValue;
     const long long tot = (long long)nb * a.HW * (a.c / (bf16 ? 8 : 1));
     if (tot >= (1LL << 31) - 256) return hipErrorInvalidValue;
-    const int splits = se_splits(a.HW);
+    const int splits = se_splits(a.HW, nb * G);
     if (bf16) ENS_LAUNCH_FIRST(se_sum_kernel<true>, dim3(splits, nb, G), dim3(256), 0, s, argv, nb);
     else ENS_LAUNCH_FIRST(se_sum_kernel<false>, dim3(splits, nb, G), dim3(256), 0, s, argv, nb);
     ENS_LAUNCH_MIDDLE(se_gate_kernel, dim3(nb, 1, G), dim3(SE_GATE_THREADS), 0, s, argv, nb, splits);
