@@ -33,6 +33,9 @@ bool conv_bneck_applicable(const ConvArgs& a1, const ConvArgs& a2, const ConvArg
 const char* conv_bneck_name(const ConvArgs& a1);
 hipError_t launch_conv_bneck(const ConvArgs& a1, const ConvArgs& a2, const ConvArgs& a3, const ConvArgs* argv, int G, int nb,
                              hipStream_t s);
+bool conv_dense_applicable(const ConvArgs& a1, const ConvArgs& a2, int nb, int G);
+const char* conv_dense_name();
+hipError_t launch_conv_dense(const ConvArgs& a1, const ConvArgs& a2, const ConvArgs* argv, int G, int nb, hipStream_t s);
 
 static int prof_class(ens_handle* h, const std::string& name) {
     for (size_t i = 0; i < h->prof.size(); i++)
@@ -192,6 +195,16 @@ static int build_launches(ens_handle* h, Gang& g) {
             chain[i + 1] = chain[i + 2] = 2;
         }
     }
+    // Which layers of dense blocks run as one kernel: chain[] 3 marks the head (two operations), 2 the one it runs
+    for (size_t i = 0; i + 1 < m.ops.size(); i++) {
+        if (!m.ops[i].fuse_dense || h->keep_tensors || chain[i] || chain[i + 1]) continue;
+        Launch a, b;
+        if (fill_args(h, leader, leader, G, m.ops[i], a) != ENS_OK || fill_args(h, leader, leader, G, m.ops[i + 1], b) != ENS_OK) continue;
+        if (conv_dense_applicable(a.conv, b.conv, leader.batch, G)) {
+            chain[i] = 3;
+            chain[i + 1] = 2;
+        }
+    }
     // Which pairs of convolutions run as one launch: planned as such, and both on the generic kernel
     // for this batch size (its workgroups read every field of their own argument block).
     std::vector<char> fused(m.ops.size(), 0);                    // 1: takes the next operation along, 2: taken along
@@ -210,7 +223,7 @@ static int build_launches(ens_handle* h, Gang& g) {
     std::vector<size_t> first_blk(m.ops.size() + 1, 0);          // argument blocks: G * sub per operation
     for (size_t i = 0; i < m.ops.size(); i++)
         first_blk[i + 1] = first_blk[i] + (fused[i] == 2 || chain[i] == 2 ? 0
-                                           : (size_t)G * (chain[i] == 1 ? 3 : fused[i] == 1 ? 2 : (m.ops[i].sub > 1 ? m.ops[i].sub : 1)));
+                                           : (size_t)G * (chain[i] == 1 ? 3 : chain[i] == 3 || fused[i] == 1 ? 2 : (m.ops[i].sub > 1 ? m.ops[i].sub : 1)));
     const size_t n_blk = first_blk[m.ops.size()];
     std::vector<char> host((n_blk + (size_t)G) * slot, 0);
     if (g.d_args && g.d_args_bytes < host.size()) { (void)hipFree(g.d_args); g.d_args = nullptr; }
@@ -220,6 +233,35 @@ static int build_launches(ens_handle* h, Gang& g) {
         Launch L;
         if (fused[i] == 2 || chain[i] == 2) {                    // its argument blocks are in an earlier launch
             L.kind = L_SKIP;
+            g.launches.push_back(L);
+            continue;
+        }
+        if (chain[i] == 3) {                                     // a layer of a dense block: G blocks of each of its two convolutions
+            double flop = 0, bytes = 0;
+            for (int sub = 1; sub >= 0; sub--)
+                for (int k = G - 1; k >= 0; k--) {
+                    const Member& mk = h->members[h->workers[g.workers[k]].member];
+                    const int rc = fill_args(h, h->workers[g.workers[k]], leader, G, mk.ops[i + sub], L);
+                    if (rc != ENS_OK) return rc;
+                    L.conv.ws = nullptr;
+                    L.conv.ws_floats = 0;
+                    if (k == 0) {
+                        flop += L.flop;
+                        if (sub == 1) {                          // algorithmic bytes: the block's input and weights, the appended channels
+                            L.conv2 = L.conv;
+                            bytes += (double)leader.batch * L.conv.H * L.conv.W * L.conv.cout * 2.0 + 2.0 * 9 * L.conv.cin * L.conv.cout;
+                        } else {
+                            bytes += (double)leader.batch * L.conv.H * L.conv.W * L.conv.cin * 2.0 + 2.0 * L.conv.cin * L.conv.cout;
+                        }
+                    }
+                    memcpy(host.data() + (first_blk[i] + (size_t)sub * G + k) * slot, &L.conv, sizeof(ConvArgs));
+                }
+            L.kind = L_DENSE;
+            L.sub = 2;
+            L.flop = flop;
+            L.bytes = bytes;
+            L.klass = prof_class(h, conv_dense_name());
+            L.d_argv = g.d_args + first_blk[i] * slot;
             g.launches.push_back(L);
             continue;
         }
@@ -298,7 +340,8 @@ static int build_launches(ens_handle* h, Gang& g) {
         size_t sz = 0;
         switch (L.kind) {
             case L_CONV:
-            case L_BNECK: sz = sizeof(ConvArgs); break;
+            case L_BNECK:
+            case L_DENSE: sz = sizeof(ConvArgs); break;
             case L_DWCONV:
             case L_POOL: sz = sizeof(PoolArgs); break;
             case L_GAP: sz = sizeof(GapArgs); break;
@@ -448,6 +491,7 @@ static hipError_t issue(const Launch& L, bool bf16, int G, int nb, long long fir
         case L_FC: return launch_fc(L.fc, (const FcArgs*)L.d_argv, G, nb, first, bf16, s);
         case L_SE: return launch_se(L.se, (const SeArgs*)L.d_argv, G, nb, bf16, s);
         case L_BNECK: return launch_conv_bneck(L.conv, L.conv2, L.conv3, (const ConvArgs*)L.d_argv, G, nb, s);
+        case L_DENSE: return launch_conv_dense(L.conv, L.conv2, (const ConvArgs*)L.d_argv, G, nb, s);
         case L_SKIP: return hipSuccess;
     }
     return hipErrorInvalidValue;

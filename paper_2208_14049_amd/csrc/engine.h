@@ -42,6 +42,9 @@ struct OpPlan {
     // This 1x1 convolution, the 3x3 after it and the 1x1 after that form a residual bottleneck whose two
     // middle tensors nobody else touches: one kernel can run the three without writing them.
     bool fuse_chain;
+    // This pre-activated 1x1 convolution (to 128 channels) and the 3x3 after it (to 32 channels) are a layer
+    // of a dense block whose middle tensor nobody else touches: one kernel can run both.
+    bool fuse_dense;
 };
 
 struct Member {
@@ -74,7 +77,7 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out);
 // keep_all gives every tensor its own region (debug read-back of intermediate tensors).
 ArenaLayout plan_arena(const Member& m, int batch, bool keep_all = false);
 
-enum LaunchKind { L_CONV, L_DWCONV, L_POOL, L_GAP, L_FC, L_SE, L_BNECK, L_SKIP };   // L_SKIP: ran with an earlier launch
+enum LaunchKind { L_CONV, L_DWCONV, L_POOL, L_GAP, L_FC, L_SE, L_BNECK, L_DENSE, L_SKIP };   // L_SKIP: ran with an earlier launch
 
 // One operation of a gang: host copy of the first member's arguments (validation, grid sizing)
 // and the device array holding the arguments of every member of the gang.
@@ -84,7 +87,7 @@ struct Launch {
     int klass = 0;                 // profile class
     double flop = 0, bytes = 0;    // algorithmic work of one member's full-batch launch
     ConvArgs conv;
-    ConvArgs conv2, conv3;         // L_BNECK: the second and third convolution of the chain
+    ConvArgs conv2, conv3;         // L_BNECK: the second and third convolution of the chain; L_DENSE: conv2 is the 3x3
     PoolArgs pool;
     GapArgs gap;
     FcArgs fc;

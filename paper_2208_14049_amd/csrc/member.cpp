@@ -130,6 +130,7 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         pl.sub_cout = o.cout;
         pl.fuse_next = false;
         pl.fuse_chain = false;
+        pl.fuse_dense = false;
         TensorInfo& ts = m.tensors[o.src];
         TensorInfo& td = m.tensors[o.dst];
         if (o.cin <= 0 || o.cout <= 0 || o.src_c0 < 0 || o.dst_c0 < 0) return ENS_E_INVALID;
@@ -392,6 +393,32 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
             m.ops[i].fuse_chain = true;
             m.tensors[o.dst].def = std::min(m.tensors[o.dst].def, i);
             for (int j = 0; j < 3; j++) pack_operand_order(m.ops[i + j]);
+        }
+    }
+    // Layers of dense blocks: pre-activated 1x1 to 128 channels, then 3x3 (stride 1, padding 1) to 32 channels,
+    // the tensor in between read by nobody else.  One kernel can run both (decided per batch size).
+    if (m.bf16) {
+        std::vector<int> uses(m.tensors.size(), 0);
+        for (int i = 0; i < spec.n_ops; i++) {
+            const ens_op& o = spec.ops[i];
+            uses[o.src]++;
+            uses[o.dst]++;
+            if (o.kind == ENS_OP_CONV && o.res >= 0) uses[o.res]++;
+        }
+        for (int i = 0; i + 1 < spec.n_ops; i++) {
+            const ens_op &p = spec.ops[i], &q = spec.ops[i + 1];
+            if (p.kind != ENS_OP_CONV || q.kind != ENS_OP_CONV || !p.pre || q.pre || p.r > 1 || q.r > 1 || p.res >= 0 || q.res >= 0) continue;
+            if (p.kh != 1 || p.kw != 1 || p.sh != 1 || p.sw != 1 || p.pt != 0 || p.pl != 0) continue;
+            if (q.kh != 3 || q.kw != 3 || q.sh != 1 || q.sw != 1 || q.pt != 1 || q.pl != 1) continue;
+            if (p.cout != 128 || q.cin != 128 || q.cout != 32 || p.cin % 32 || p.cin > 2048 || m.ops[i].cin_s != p.cin) continue;
+            if (q.src != p.dst || q.src_c0 != p.dst_c0 || uses[p.dst] != 2 || m.tensors[p.dst].c != p.cout || p.src == 0) continue;
+            if (q.dst == p.dst || (q.dst == p.src && q.dst_c0 < p.src_c0 + p.cin)) continue;
+            if (m.ops[i].fuse_next || m.ops[i + 1].fuse_next || m.ops[i].fuse_chain || (i > 0 && m.ops[i - 1].fuse_chain) ||
+                (i > 1 && m.ops[i - 2].fuse_chain) || m.ops[i + 1].fuse_chain)
+                continue;
+            m.ops[i].fuse_dense = true;
+            pack_operand_order(m.ops[i]);
+            pack_operand_order(m.ops[i + 1]);
         }
     }
     if (stem_op >= 0) {                                          // tensor 0 as the staging kernel writes it

@@ -353,6 +353,43 @@ def test_bottleneck_in_one_kernel(ens, case):
         assert err.mean() <= 2.0 ** -6 * scale, (g, err.mean(), scale)
 
 
+@pytest.mark.parametrize("h,w,c0,layers,G,nb", [(14, 14, 64, 3, 1, 16), (10, 40, 96, 2, 2, 5), (7, 7, 256, 2, 1, 50)],
+                         ids=["14x14", "10x40_gang2", "7x7_256"])
+def test_dense_block_layers_in_one_kernel(ens, h, w, c0, layers, G, nb):
+    """A layer of a dense block (pre-activated 1x1 to 128 channels, then 3x3 to 32 channels appended to the
+    block's tensor) runs as one kernel with the 128-channel tensor in LDS.  The block's tensor is read
+    back after the pass and compared with the oracle element by element, for each member of the gang."""
+    nets = []
+    for g in range(G):
+        n = N.Net("dense%d" % g, h, w, 8, dtype="bf16")
+        blk = n.tensor(h, w, c0 + 32 * layers)
+        n.conv(0, c0, 3, dst=(blk, 0))
+        c = c0
+        for _ in range(layers):
+            u = n.conv(blk, 128, 1, pre=True, src_slice=(0, c))
+            n.conv(u, 32, 3, bn=False, act=None, bias=False, dst=(blk, c))
+            c += 32
+        n.fc(n.gap(blk, pre=True), 8)
+        nets.append(n)
+    blobs = [W.quantise_weights_bf16(n, W.make_blob(n, 51, i)) for i, n in enumerate(nets)]
+    imgs = W.round_bf16(W.make_images(52, nb, h, w))
+    E = ens.Ensemble(nets, blobs)
+    E.set_base_size(h, w)
+    E.ens_set_alloc([[nb] * G])
+    E.ens_set_profiling(1)
+    E.ens_predict(imgs)
+    ran = {k["name"]: k["launches"] for k in E.ens_profile() if k["launches"]}
+    got = [E.ens_debug_tensor(g, blk, nets[g].tensors[blk], nb) for g in range(G)]   # alive until the pooling that ends the network
+    E.close()
+    assert ran.get("dense_layer_bf16") == layers, ran
+    for g in range(G):
+        ref = oracle_tensor(nets[g], blobs[g], imgs, blk)
+        scale = np.sqrt(np.mean(ref ** 2)) + 1e-6
+        err = np.abs(got[g] - ref)
+        assert err.max() <= 0.05 * scale + 2.0 ** -6 * np.abs(ref).max(), (g, err.max(), scale)
+        assert err.mean() <= 2.0 ** -6 * scale, (g, err.mean(), scale)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 def test_memory_bound_layers(ens, dtype):
     """Depthwise 3x3 / 5x5 (strides 1 and 2), squeeze-excite, max / average pooling into channel
