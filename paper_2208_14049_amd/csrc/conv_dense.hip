@@ -13,7 +13,9 @@
 // the pixel fragments between LDS and the matrix cores (its scale and shift wait in LDS); the
 // result goes to LDS as bf16 in the window layout of the 3x3 kernels, zeros where the raster holds
 // no pixel.  Phase 2 is the nine taps, each wavefront 32 positions x 32 channels, stored from the
-// accumulators.  Weights come straight from memory in matrix-core operand order (conv_direct.h).
+// accumulators.  On small maps a workgroup owns 64 or 32 positions instead (phase 2 then occupies two
+// wavefronts or one): a 14x14 map at batch 64 has 113 tiles of 128 positions for 256 compute units,
+// and a workgroup's time is the chain of its input chunks, not the chip's throughput.  Weights come straight from memory in matrix-core operand order (conv_direct.h).
 // The input and the output may be channel slices of one tensor (they are in a dense block): a
 // workgroup reads channels below the slice it writes, and so does every other workgroup.
 #include "conv_direct.h"
@@ -22,17 +24,18 @@
 
 namespace ens {
 
-constexpr int DN_BP = 128, DN_C = 128, DN_CO = 32, DN_MAXCIN = 2048;
+constexpr int DN_C = 128, DN_CO = 32, DN_MAXCIN = 2048;
 template <int R>
 constexpr int dn_big() { return 3 * R * 64 > 2 * R * 128 ? 3 * R * 64 : 2 * R * 128; }
 
 // argv: the argument blocks of the two convolutions, gridDim.z of each (one per member of the gang)
-template <int R>
+template <int BP, int R>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void dense_layer_bf16(const ConvArgs* __restrict__ argv, const int nb_) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int G = gridDim.z;
     const ConvArgs a1 = argv[blockIdx.z], a2 = argv[G + blockIdx.z];
-    constexpr int BP = DN_BP, C = DN_C;
+    constexpr int C = DN_C;
+    static_assert(BP == 32 || BP == 64 || BP == 128, "one to four wavefronts of 32 positions in phase 2");
     // phase 1: wavefronts 2 along the window rows, 2 along the channels
     constexpr int WR1 = 2, TP1 = R / (32 * WR1), TC1 = 2;
     static_assert(TP1 * 32 * WR1 == R && R % 64 == 0, "window rows split evenly");
@@ -195,7 +198,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
 
     // ---- phase 2: the nine taps over the middle tensor, 32 output channels; no barrier, weights PW steps ahead
-    {
+    __syncthreads();                                             // the middle tensor is complete
+    if (wave < BP / 32) {
         const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc((void*)a2.y.p, 0, (int)(npix * (unsigned)a2.y.stride * 2u), 0x00020000);
         const int pout = tbl[W1 + 1 + wp0 + lrow];               // the centre tap's rows: this tile's outputs
         const unsigned yo = pout >= 0 ? (unsigned)(pout * a2.y.stride * 2) + (unsigned)((a2.y.c0 + 8 * lhalf) * 2) : OOBV;
@@ -207,7 +211,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             const uint32_t q = (uint32_t)(wp0 + lrow + (tap / 3) * W1 + tap % 3);
             xoff[tap] = lds0 + q * 128 + ((((uint32_t)lhalf) ^ ((q >> 1) & 7)) << 4);
         }
-        __syncthreads();                                         // the middle tensor is complete
         bf16x8 xf[2];
         auto read_frag = [&](auto st_c, auto b_c) {
             constexpr int st = decltype(st_c)::value, b = decltype(b_c)::value;
@@ -239,9 +242,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 constexpr int DENSE_LDS_LIMIT = 160 * 1024;
 constexpr int DENSE_MIN_TILES = 1;   // measured on a DenseNet-121-shaped member: the one kernel is faster at every batch size, 1 to 128
 
-struct DensePlan { int rows; size_t bytes; int tiles; };
+struct DensePlan { int bp, rows; size_t bytes; int tiles; };
+constexpr int DENSE_CUS = 256;
 
-static bool dense_plan(const ConvArgs& a1, const ConvArgs& a2, int nb, DensePlan* pl) {
+static bool dense_plan(const ConvArgs& a1, const ConvArgs& a2, int nb, int G, DensePlan* pl) {
     if (a1.kh != 1 || a1.kw != 1 || a1.sh != 1 || a1.sw != 1 || a1.pt != 0 || a1.pl != 0 || a1.Ho != a1.H || a1.Wo != a1.W) return false;
     if (!a1.pre_scale || !a1.pre_shift || a1.res.p || a2.res.p || a2.pre_scale) return false;
     if (a2.kh != 3 || a2.kw != 3 || a2.sh != 1 || a2.sw != 1 || a2.pt != 1 || a2.pl != 1) return false;
@@ -257,12 +261,24 @@ static bool dense_plan(const ConvArgs& a1, const ConvArgs& a2, int nb, DensePlan
     const long long PP = (long long)nb * (a1.H + 1) * (a1.W + 1);
     if (PP >= (1LL << 24)) return false;
     if (a1.x.stride % 8 || a1.x.c0 % 8 || a2.y.stride % 8 || a2.y.c0 % 8) return false;
-    const int need = DN_BP + 2 * (a1.W + 1) + 2;
-    pl->rows = need <= 192 ? 192 : 256;
+    // positions per workgroup: 128, or fewer while that does not give every compute unit a workgroup
+    // and the window of the smaller tile fits the next smaller number of rows
+    const int reach = 2 * (a1.W + 1) + 2;
+    pl->bp = 128;
+    if (G * ((PP + 127) / 128) < DENSE_CUS && 64 + reach <= 128) pl->bp = 64;
+    if (G * ((PP + 63) / 64) < DENSE_CUS && 32 + reach <= 64) pl->bp = 32;
+#ifdef ENS_CONV_TUNING
+    if (const char* e = getenv("ENS_CONV_DENSE_BP")) {
+        const int bp = atoi(e);
+        if ((bp == 128 || bp == 64 || bp == 32) && bp + reach <= 2 * bp) pl->bp = bp;
+    }
+#endif
+    const int need = pl->bp + reach;
+    pl->rows = pl->bp == 32 ? 64 : pl->bp == 64 ? 128 : need <= 192 ? 192 : 256;
     if (need > pl->rows) return false;
-    const int big = pl->rows == 192 ? dn_big<192>() : dn_big<256>();
+    const int big = pl->rows == 64 ? dn_big<64>() : pl->rows == 128 ? dn_big<128>() : pl->rows == 192 ? dn_big<192>() : dn_big<256>();
     pl->bytes = (size_t)big + (size_t)pl->rows * 4 + (size_t)(DN_C + DN_CO + 2 * a1.cin) * 4;
-    pl->tiles = (int)((PP + DN_BP - 1) / DN_BP);
+    pl->tiles = (int)((PP + pl->bp - 1) / pl->bp);
     return 2 * pl->bytes <= (size_t)DENSE_LDS_LIMIT;
 }
 
@@ -271,7 +287,7 @@ bool conv_dense_applicable(const ConvArgs& a1, const ConvArgs& a2, int nb, int G
 #ifdef ENS_CONV_TUNING
     if (const char* e = getenv("ENS_CONV_DENSE")) if (atoi(e) == 0) return false;
 #endif
-    if (!dense_plan(a1, a2, nb, &pl)) return false;
+    if (!dense_plan(a1, a2, nb, G, &pl)) return false;
     long long least = DENSE_MIN_TILES;
 #ifdef ENS_CONV_TUNING
     if (const char* e = getenv("ENS_CONV_DENSE_MIN")) least = atoll(e);
@@ -281,22 +297,24 @@ bool conv_dense_applicable(const ConvArgs& a1, const ConvArgs& a2, int nb, int G
 
 const char* conv_dense_name() { return "dense_layer_bf16"; }
 
-template <int R>
+template <int BP, int R>
 static hipError_t launch_dense_variant(const ConvArgs* argv, int G, int nb, const DensePlan& pl, hipStream_t s) {
     static bool raised = false;                                  // LDS above 64 KB has to be asked for once
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)&dense_layer_bf16<R>, hipFuncAttributeMaxDynamicSharedMemorySize, DENSE_LDS_LIMIT);
+        hipError_t e = hipFuncSetAttribute((const void*)&dense_layer_bf16<BP, R>, hipFuncAttributeMaxDynamicSharedMemorySize, DENSE_LDS_LIMIT);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    ENS_LAUNCH((dense_layer_bf16<R>), dim3((unsigned)pl.tiles, 1, G), dim3(256), pl.bytes, s, argv, nb);
+    ENS_LAUNCH((dense_layer_bf16<BP, R>), dim3((unsigned)pl.tiles, 1, G), dim3(256), pl.bytes, s, argv, nb);
     return hipGetLastError();
 }
 
 hipError_t launch_conv_dense(const ConvArgs& a1, const ConvArgs& a2, const ConvArgs* argv, int G, int nb, hipStream_t s) {
     DensePlan pl;
-    if (!dense_plan(a1, a2, nb, &pl)) return hipErrorInvalidValue;
-    return pl.rows == 192 ? launch_dense_variant<192>(argv, G, nb, pl, s) : launch_dense_variant<256>(argv, G, nb, pl, s);
+    if (!dense_plan(a1, a2, nb, G, &pl)) return hipErrorInvalidValue;
+    if (pl.bp == 32) return launch_dense_variant<32, 64>(argv, G, nb, pl, s);
+    if (pl.bp == 64) return launch_dense_variant<64, 128>(argv, G, nb, pl, s);
+    return pl.rows == 192 ? launch_dense_variant<128, 192>(argv, G, nb, pl, s) : launch_dense_variant<128, 256>(argv, G, nb, pl, s);
 }
 
 }  // namespace ens

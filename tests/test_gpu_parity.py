@@ -353,12 +353,15 @@ def test_bottleneck_in_one_kernel(ens, case):
         assert err.mean() <= 2.0 ** -6 * scale, (g, err.mean(), scale)
 
 
-@pytest.mark.parametrize("h,w,c0,layers,G,nb", [(14, 14, 64, 3, 1, 16), (10, 40, 96, 2, 2, 5), (7, 7, 256, 2, 1, 50)],
-                         ids=["14x14", "10x40_gang2", "7x7_256"])
+@pytest.mark.parametrize("h,w,c0,layers,G,nb", [(14, 14, 64, 3, 1, 16), (10, 40, 96, 2, 2, 5), (7, 7, 256, 2, 1, 50),
+                                                (20, 20, 64, 2, 1, 6), (14, 14, 32, 1, 1, 150)],
+                         ids=["14x14", "10x40_gang2", "7x7_256", "20x20_tiles_of_64", "14x14_many_tiles"])
 def test_dense_block_layers_in_one_kernel(ens, h, w, c0, layers, G, nb):
     """A layer of a dense block (pre-activated 1x1 to 128 channels, then 3x3 to 32 channels appended to the
     block's tensor) runs as one kernel with the 128-channel tensor in LDS.  The block's tensor is read
-    back after the pass and compared with the oracle element by element, for each member of the gang."""
+    back after the pass and compared with the oracle element by element, for each member of the gang.
+    The cases cover the kernel's tiles of 32 positions (14x14, 7x7), 64 (20x20) and 128 (window of 256
+    rows: 10x40; of 192 rows: 14x14 with enough tiles for every compute unit)."""
     nets = []
     for g in range(G):
         n = N.Net("dense%d" % g, h, w, 8, dtype="bf16")
