@@ -28,6 +28,14 @@ constexpr int DN_C = 128, DN_CO = 32, DN_MAXCIN = 2048;
 template <int R>
 constexpr int dn_big() { return 3 * R * 64 > 2 * R * 128 ? 3 * R * 64 : 2 * R * 128; }
 
+template <int OFFSET>
+__device__ __forceinline__ f32x4 dn_lds_read_f4(uint32_t addr) {
+    f32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET));
+    return v;
+}
+__device__ __forceinline__ void dn_tie(f32x4& v) { asm volatile("" : "+v"(v)); }
+
 // argv: the argument blocks of the two convolutions, gridDim.z of each (one per member of the gang)
 template <int BP, int R>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void dense_layer_bf16(const ConvArgs* __restrict__ argv, const int nb_) {
@@ -40,7 +48,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     constexpr int WR1 = 2, TP1 = R / (32 * WR1), TC1 = 2;
     static_assert(TP1 * 32 * WR1 == R && R % 64 == 0, "window rows split evenly");
     constexpr int XO = R / 64, WO = 2 * TC1;         // loads per thread and chunk: input rows, weight fragments
-    constexpr int KK = C / 16, NST = 9 * KK, PW = 8; // phase 2: steps per tap, steps, steps the weights run ahead
+    constexpr int KK = C / 16, NST = 9 * KK, PW = R == 256 ? 6 : 8;   // phase 2: steps per tap, steps, steps the weights run ahead (registers)
     constexpr int XS = R * 64;                       // bytes of an input chunk: R rows of 32 channels
     constexpr int T1B = R * 128;                     // bytes of a 64-channel block of the middle tensor
     constexpr int BIG = dn_big<R>();
@@ -116,6 +124,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     //      the wait before a chunk is used counts what was issued after it and may still be on its way.
     {
         const int xr = row0 + lrow;
+        const uint32_t psl0 = (uint32_t)(uintptr_t)(lds_ptr_t)psl;
         const uint32_t xs1 = lds0 + (uint32_t)(xr * 64 + ((lhalf ^ ((xr >> 2) & 3)) << 4));
         f32x16 acc[TC1][TP1];
 #pragma unroll
@@ -124,8 +133,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             for (int j = 0; j < TP1; j++) bn_init(acc[i][j], b1l + ch0 + 32 * i + 8 * lhalf);
         issue_x(0, 0);
         if (nk1 > 1) issue_x(1, 1);
-        int buf = 0;
-        for (int kc = 0; kc < nk1; kc++) {
+        // One chunk: `wc` holds its weights, `wl` receives those of chunk kc + 2, BUF is its place in the
+        // ring.  The three roles rotate with period three, so the loop below is written out three chunks
+        // at a time: a rotation through register copies would have to wait for the loads just issued.
+        auto chunk = [&](auto buf_c, bf16x8 (&wc)[2][TC1], bf16x8 (&wl)[2][TC1], const int kc) {
+            constexpr int buf = decltype(buf_c)::value;
             if (kc == 0) {
                 if (nk1 > 1) bn_wait_vm<XO>(); else bn_wait_vm<0>();
             } else {
@@ -133,22 +145,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             }
             __builtin_amdgcn_s_barrier();
             if (kc + 2 < nk1) {
-                load_w(w2, kc + 2);
-                issue_x(buf >= 1 ? buf - 1 : 2, kc + 2);         // (buf + 2) % 3
+                load_w(wl, kc + 2);
+                issue_x((buf + 2) % 3, kc + 2);
             }
             // scale and shift of this lane's 8 channels in each of the chunk's two steps
+            // (read with the fragments, behind the barrier: read any earlier they would only occupy registers)
             f32x4 ps[2][2], ph[2][2];
-#pragma unroll
-            for (int ks = 0; ks < 2; ks++) {
-                const int kb = kc * 32 + ks * 16 + 8 * lhalf;
-                ps[ks][0] = *(const f32x4*)&psl[kb]; ps[ks][1] = *(const f32x4*)&psl[kb + 4];
-                ph[ks][0] = *(const f32x4*)&phl[kb]; ph[ks][1] = *(const f32x4*)&phl[kb + 4];
-            }
+            const uint32_t pa = psl0 + (uint32_t)((kc * 32 + 8 * lhalf) * 4), ha = pa + (uint32_t)(cin1 * 4);
+            ps[0][0] = dn_lds_read_f4<0>(pa); ps[0][1] = dn_lds_read_f4<16>(pa);
+            ps[1][0] = dn_lds_read_f4<64>(pa); ps[1][1] = dn_lds_read_f4<80>(pa);
+            ph[0][0] = dn_lds_read_f4<0>(ha); ph[0][1] = dn_lds_read_f4<16>(ha);
+            ph[1][0] = dn_lds_read_f4<64>(ha); ph[1][1] = dn_lds_read_f4<80>(ha);
             const uint32_t xs = xs1 + (uint32_t)(buf * XS);
             bf16x8 xf[2][TP1];
             bn_unroll<TP1>([&](auto j) { xf[0][decltype(j)::value] = bn_lds_read<decltype(j)::value * 2048>(xs); });
             bn_unroll<TP1>([&](auto j) { xf[1][decltype(j)::value] = bn_lds_read<decltype(j)::value * 2048>(xs ^ 32u); });
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int ks = 0; ks < 2; ks++)
+#pragma unroll
+                for (int q = 0; q < 2; q++) {
+                    dn_tie(ps[ks][q]);
+                    dn_tie(ph[ks][q]);
+                }
 #pragma unroll
             for (int ks = 0; ks < 2; ks++) {
 #pragma unroll
@@ -167,17 +186,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
                 for (int i = 0; i < TC1; i++)
 #pragma unroll
-                    for (int j = 0; j < TP1; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0[ks][i], xf[ks][j], acc[i][j], 0, 0, 0);
+                    for (int j = 0; j < TP1; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[ks][i], xf[ks][j], acc[i][j], 0, 0, 0);
             }
-#pragma unroll
-            for (int ks = 0; ks < 2; ks++)
-#pragma unroll
-                for (int i = 0; i < TC1; i++) {
-                    w0[ks][i] = w1[ks][i];
-                    w1[ks][i] = w2[ks][i];
-                }
-            buf = buf == 2 ? 0 : buf + 1;
+        };
+        int kc = 0;
+        for (; kc + 2 < nk1; kc += 3) {
+            chunk(std::integral_constant<int, 0>{}, w0, w2, kc);
+            chunk(std::integral_constant<int, 1>{}, w1, w0, kc + 1);
+            chunk(std::integral_constant<int, 2>{}, w2, w1, kc + 2);
         }
+        if (kc < nk1) chunk(std::integral_constant<int, 0>{}, w0, w2, kc);
+        if (kc + 1 < nk1) chunk(std::integral_constant<int, 1>{}, w1, w0, kc + 1);
 #pragma unroll
         for (int s = 0; s < PW; s++) wq2[s] = bn_wload(w2res, wv2, s * 1024);
         __syncthreads();                                         // everybody is done with the input chunks
