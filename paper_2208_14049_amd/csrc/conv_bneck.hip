@@ -149,8 +149,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             for (int j = 0; j < TP1; j++) bn_init(acc[i][j], b1l + ch0 + 32 * i + 8 * lhalf);
         issue_x(0, 0);
         if (nk1 > 1) issue_x(1, 1);
-        int buf = 0;
-        for (int kc = 0; kc < nk1; kc++) {
+        // One chunk: `wc` holds its weights, `wl` receives those of chunk kc + 2, BUF is its place in the
+        // ring.  The three roles rotate with period three, so the loop below is written out three chunks
+        // at a time: a rotation through register copies would have to wait for the loads just issued.
+        auto chunk = [&](auto buf_c, bf16x8 (&wc)[2][TC1], bf16x8 (&wl)[2][TC1], const int kc) {
+            constexpr int buf = decltype(buf_c)::value;
             // chunk kc has landed (this wave's part; with the barrier everybody's), and nobody still reads
             // the buffer that chunk kc + 2 goes to
             if (kc == 0) {
@@ -160,8 +163,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             }
             __builtin_amdgcn_s_barrier();
             if (kc + 2 < nk1) {
-                load_w(w2, kc + 2);
-                issue_x(buf >= 1 ? buf - 1 : 2, kc + 2);         // (buf + 2) % 3
+                load_w(wl, kc + 2);
+                issue_x((buf + 2) % 3, kc + 2);
             }
             const uint32_t xs = xs1 + (uint32_t)(buf * XS);
             bf16x8 xf[2][TP1];
@@ -173,23 +176,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
             for (int i = 0; i < TC1; i++)
 #pragma unroll
-                for (int j = 0; j < TP1; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0[0][i], xf[0][j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < TP1; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[0][i], xf[0][j], acc[i][j], 0, 0, 0);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
             for (int j = 0; j < TP1; j++) bn_tie(xf[1][j]);
 #pragma unroll
             for (int i = 0; i < TC1; i++)
 #pragma unroll
-                for (int j = 0; j < TP1; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0[1][i], xf[1][j], acc[i][j], 0, 0, 0);
-#pragma unroll
-            for (int ks = 0; ks < 2; ks++)
-#pragma unroll
-                for (int i = 0; i < TC1; i++) {
-                    w0[ks][i] = w1[ks][i];
-                    w1[ks][i] = w2[ks][i];
-                }
-            buf = buf == 2 ? 0 : buf + 1;
+                for (int j = 0; j < TP1; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[1][i], xf[1][j], acc[i][j], 0, 0, 0);
+        };
+        int kc = 0;
+        for (; kc + 2 < nk1; kc += 3) {
+            chunk(std::integral_constant<int, 0>{}, w0, w2, kc);
+            chunk(std::integral_constant<int, 1>{}, w1, w0, kc + 1);
+            chunk(std::integral_constant<int, 2>{}, w2, w1, kc + 2);
         }
+        if (kc < nk1) chunk(std::integral_constant<int, 0>{}, w0, w2, kc);
+        if (kc + 1 < nk1) chunk(std::integral_constant<int, 1>{}, w1, w0, kc + 1);
         bn_unroll<PW>([&](auto s) {
 #pragma unroll
             for (int i = 0; i < TC2; i++) wq2[decltype(s)::value][i] = bn_wload(w2res, wv2, (i * NST + decltype(s)::value) * 1024);

@@ -135,8 +135,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
     const int xr = wp0 + lrow;
     const uint32_t xs0 = lds0 + (uint32_t)(xr * 128 + ((lhalf ^ ((xr >> 1) & 7)) << 4));
-    int buf = 0;
-    for (int kc = 0; kc < nk; kc++) {
+    // One chunk: `wc` holds its weights, `wl` receives those of chunk kc + 2, BUF is its place in the
+    // ring.  The three roles rotate with period three, so the loop below is written out three chunks at
+    // a time: a rotation through register copies would have to wait for the loads just issued.
+    auto chunk = [&](auto buf_c, bf16x8 (&wc_)[4], bf16x8 (&wl)[4], const int kc) {
+        constexpr int buf = decltype(buf_c)::value;
         // chunk kc has landed (this wave's part; with the barrier everybody's), and nobody still reads
         // the buffer that chunk kc + 2 goes to.  Issued after chunk kc: the weights and the input of
         // chunk kc + 1 (chunk 0: only the input of chunk 1, the weights went first).
@@ -147,8 +150,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
         __builtin_amdgcn_s_barrier();
         if (kc + 2 < nk) {
-            load_w(w2, kc + 2);
-            issue_x(buf >= 1 ? buf - 1 : 2, kc + 2);             // (buf + 2) % 3
+            load_w(wl, kc + 2);
+            issue_x((buf + 2) % 3, kc + 2);
         }
         const uint32_t xs = xs0 + (uint32_t)(buf * XS);
         bf16x8 xf[2][TP];
@@ -171,15 +174,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
             for (int j = 0; j < TP; j++) bn_tie(xf[b][j]);
 #pragma unroll
-            for (int j = 0; j < TP; j++) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0[ks], xf[b][j], acc[j], 0, 0, 0);
+            for (int j = 0; j < TP; j++) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc_[ks], xf[b][j], acc[j], 0, 0, 0);
         });
-#pragma unroll
-        for (int ks = 0; ks < 4; ks++) {
-            w0[ks] = w1[ks];
-            w1[ks] = w2[ks];
-        }
-        buf = buf == 2 ? 0 : buf + 1;
+    };
+    int kc = 0;
+    for (; kc + 2 < nk; kc += 3) {
+        chunk(std::integral_constant<int, 0>{}, w0, w2, kc);
+        chunk(std::integral_constant<int, 1>{}, w1, w0, kc + 1);
+        chunk(std::integral_constant<int, 2>{}, w2, w1, kc + 2);
     }
+    if (kc < nk) chunk(std::integral_constant<int, 0>{}, w0, w2, kc);
+    if (kc + 1 < nk) chunk(std::integral_constant<int, 1>{}, w1, w0, kc + 1);
 
     // ---- output: register v of a lane is channel wc + 16(v/8) + 8(lane/32) + v%8 of its pixel.  Stores
     //      to rows past the last pixel carry the out-of-range offset and are dropped by the hardware.
