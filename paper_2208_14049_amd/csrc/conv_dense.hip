@@ -197,8 +197,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
         if (kc < nk1) chunk(std::integral_constant<int, 0>{}, w0, w2, kc);
         if (kc + 1 < nk1) chunk(std::integral_constant<int, 1>{}, w1, w0, kc + 1);
+        if (wave < BP / 32) {                                    // the wavefronts that take part in phase 2
 #pragma unroll
-        for (int s = 0; s < PW; s++) wq2[s] = bn_wload(w2res, wv2, s * 1024);
+            for (int s = 0; s < PW; s++) wq2[s] = bn_wload(w2res, wv2, s * 1024);
+        }
         __syncthreads();                                         // everybody is done with the input chunks
 #pragma unroll
         for (int j = 0; j < TP1; j++) {
