@@ -547,9 +547,12 @@ hipError_t launch_pool(const PoolArgs& a, const PoolArgs* argv, int G, int nb, b
 }
 
 // ------------------------------------------------------------------ global average pool
-// One workgroup per image.  Lanes run along the channels (16-byte groups of 8 for bf16) so that
-// every pixel row is read in whole lines; the pixels are dealt round-robin to the thread rows
-// and the partial sums are added through LDS.
+// A workgroup owns one image and 32 channel groups (16-byte groups of 8 channels for bf16): lanes
+// run along the channels so that every pixel row is read in whole lines, the pixels are dealt
+// round-robin to 8 thread rows (a 7x7 map: six or seven independent loads per thread, where one
+// workgroup per image walked 49 pixels one after the other) and the partial sums are added
+// through LDS in a fixed order.
+constexpr int GAP_COLS = 32, GAP_ROWS = 8;
 template <bool BF16>
 __global__ __launch_bounds__(256) void gap_kernel(const GapArgs* __restrict__ argv, const int nb_) {
     GapArgs a = argv[blockIdx.z];
@@ -558,52 +561,52 @@ __global__ __launch_bounds__(256) void gap_kernel(const GapArgs* __restrict__ ar
     __shared__ float part[256 * V];
     const int n = blockIdx.x;
     const int cv = (a.c + V - 1) / V;                 // channel groups
-    const int cols = min(cv, 256);                    // groups handled side by side
-    const int rows = 256 / cols;                      // pixel phases
-    const int col = threadIdx.x % cols, row = threadIdx.x / cols;
+    // 32 channel groups side by side, 8 pixel phases: a thread's loads are few and independent
+    const int col = threadIdx.x % GAP_COLS, row = threadIdx.x / GAP_COLS;
+    const int g = blockIdx.y * GAP_COLS + col;
     const bool pre = a.pre_scale != nullptr;
-    for (int g0 = 0; g0 < cv; g0 += cols) {
-        const int g = g0 + col;
-        float acc[V];
+    float acc[V];
 #pragma unroll
-        for (int e = 0; e < V; e++) acc[e] = 0.f;
-        if (g < cv && row < rows) {
-            const int c = g * V;
-            float sc[V], sf[V];
+    for (int e = 0; e < V; e++) acc[e] = 0.f;
+    if (g < cv) {
+        const int c = g * V;
+        float sc[V], sf[V];
 #pragma unroll
-            for (int e = 0; e < V; e++) {
-                sc[e] = pre && c + e < a.c ? a.pre_scale[c + e] : 1.f;
-                sf[e] = pre && c + e < a.c ? a.pre_shift[c + e] : 0.f;
-            }
-            for (int p = row; p < a.HW; p += rows) {
-                const long long off = ((long long)n * a.HW + p) * a.x.stride + a.x.c0 + c;
-                float v[V];
-                if (BF16) unpack8(*(const uint4*)((const uint16_t*)a.x.p + off), v);
-                else v[0] = ((const float*)a.x.p)[off];
-#pragma unroll
-                for (int e = 0; e < V; e++) acc[e] += pre ? fmaxf(v[e] * sc[e] + sf[e], 0.f) : v[e];
-            }
+        for (int e = 0; e < V; e++) {
+            sc[e] = pre && c + e < a.c ? a.pre_scale[c + e] : 1.f;
+            sf[e] = pre && c + e < a.c ? a.pre_shift[c + e] : 0.f;
         }
+#pragma unroll 4
+        for (int p = row; p < a.HW; p += GAP_ROWS) {
+            const long long off = ((long long)n * a.HW + p) * a.x.stride + a.x.c0 + c;
+            float v[V];
+            if (BF16) unpack8(*(const uint4*)((const uint16_t*)a.x.p + off), v);
+            else v[0] = ((const float*)a.x.p)[off];
 #pragma unroll
-        for (int e = 0; e < V; e++) part[threadIdx.x * V + e] = acc[e];
-        __syncthreads();
-        if (row == 0 && g < cv) {
-#pragma unroll
-            for (int e = 0; e < V; e++) {
-                float s = 0.f;
-                for (int r = 0; r < rows; r++) s += part[(r * cols + col) * V + e];
-                if (g * V + e < a.c) a.y[(long long)n * a.c + g * V + e] = s / (float)a.HW;
-            }
+            for (int e = 0; e < V; e++) acc[e] += pre ? fmaxf(v[e] * sc[e] + sf[e], 0.f) : v[e];
         }
-        __syncthreads();
+    }
+#pragma unroll
+    for (int e = 0; e < V; e++) part[threadIdx.x * V + e] = acc[e];
+    __syncthreads();
+    if (row == 0 && g < cv) {
+#pragma unroll
+        for (int e = 0; e < V; e++) {
+            float s = 0.f;
+#pragma unroll
+            for (int r = 0; r < GAP_ROWS; r++) s += part[(r * GAP_COLS + col) * V + e];
+            if (g * V + e < a.c) a.y[(long long)n * a.c + g * V + e] = s / (float)a.HW;
+        }
     }
 }
 
 hipError_t launch_gap(const GapArgs& a, const GapArgs* argv, int G, int nb, bool bf16, hipStream_t s) {
     if (nb <= 0 || a.c <= 0 || a.HW <= 0 || G <= 0 || !argv) return hipErrorInvalidValue;
     if (bf16 && (a.c % 8 || a.x.stride % 8 || a.x.c0 % 8)) return hipErrorInvalidValue;
-    if (bf16) ENS_LAUNCH(gap_kernel<true>, dim3(nb, 1, G), dim3(256), 0, s, argv, nb);
-    else ENS_LAUNCH(gap_kernel<false>, dim3(nb, 1, G), dim3(256), 0, s, argv, nb);
+    const int cv = bf16 ? (a.c + 7) / 8 : a.c;
+    const dim3 grid(nb, (cv + GAP_COLS - 1) / GAP_COLS, G);
+    if (bf16) ENS_LAUNCH(gap_kernel<true>, grid, dim3(256), 0, s, argv, nb);
+    else ENS_LAUNCH(gap_kernel<false>, grid, dim3(256), 0, s, argv, nb);
     return hipGetLastError();
 }
 
