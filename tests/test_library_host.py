@@ -208,6 +208,31 @@ def test_grouped_convolutions_in_descriptions():
     assert e.value.status == ens.ENS_E_INVALID
 
 
+def test_dense_block_layers_in_descriptions():
+    """A layer of a dense block that one kernel can run (pre-activated 1x1 to 128 channels, 3x3 to 32
+    channels appended to the block's tensor, nobody else reading the tensor in between) gets operand-
+    ordered copies of both filters; with a second reader of the middle tensor it gets none.  The two
+    networks below hold the same layers with the same parameter sizes and differ only in what the
+    extra 1x1 layer reads."""
+    def net(tap_middle):
+        n = N.Net("d", 12, 12, 8, dtype="bf16")
+        blk = n.tensor(12, 12, 128 + 32)
+        n.conv(0, 128, 3, dst=(blk, 0))
+        u = n.conv(blk, 128, 1, pre=True, src_slice=(0, 128))
+        n.conv(u, 32, 3, bn=False, act=None, bias=False, dst=(blk, 128))
+        if tap_middle:
+            t = n.conv(u, 8, 1)
+        else:
+            t = n.conv(blk, 8, 1, src_slice=(0, 128))
+        n.fc(n.gap(t), 8)
+        return n
+
+    up = lambda b: (b + 255) // 256 * 256
+    fused, _ = ens.ens_spec_bytes(net(False), 8)
+    plain, _ = ens.ens_spec_bytes(net(True), 8)
+    assert fused - plain == up(2 * 128 * 128) + up(2 * 9 * 128 * 32), fused - plain
+
+
 def test_bottleneck_chains_in_descriptions():
     """The plan keeps a second copy, in matrix-core operand order (rows padded to 32, columns to 64), of
     the weights of layers that kernels fetch straight from memory: every 1x1 stride-1 convolution
