@@ -678,12 +678,11 @@ hipError_t launch_fc(const FcArgs& a, const FcArgs* argv, int G, int nb, long lo
 }
 
 // ------------------------------------------------------------------ squeeze-excite
-// Three kernels on the worker's stream.  (1) Channel sums: workgroup (split, image) adds its share
+// Two kernels on the worker's stream.  (1) Channel sums: workgroup (split, image) adds its share
 // of the image's pixels; lanes run along the channels (16-byte groups of 8 for bf16) so that every
 // pixel is read in whole lines, the pixels of the share are dealt round-robin to the thread rows
-// and the rows are added through LDS.  (2) Gate: one workgroup per image adds the partial sums,
-// then the two small FC layers (SiLU, sigmoid) with all 256 threads on the first one.  (3) The
-// channel-wise rescale of the activation tensor.
+// and the rows are added through LDS.  (2) Gate and rescale: a workgroup adds the partial sums of
+// its image, runs the two small FC layers (SiLU, sigmoid) and rescales its share of the image.
 // Workgroups that share an image's pixels in the channel sums: one per 512 pixels, more when the
 // launch would otherwise have fewer than about 2048 workgroups (small maps, small batches), never
 // fewer than 8 pixels each.
@@ -749,16 +748,14 @@ __global__ __launch_bounds__(256) void se_sum_kernel(const SeArgs* __restrict__ 
 }
 
 constexpr int SE_GATE_THREADS = 1024;   // the gate is a chain of dependent memory latencies: many threads, few steps each
-constexpr int SE_GATE_MAXC = 4096;      // channels the gate kernel holds in LDS
+constexpr int SE_GATE_MAXC = 4096;      // channels the gate holds in LDS
+constexpr int SE_SCALE_BYTES = 32768;   // about what a workgroup of the last kernel rescales
 
-__global__ __launch_bounds__(SE_GATE_THREADS) void se_gate_kernel(const SeArgs* __restrict__ argv, const int nb_, const int splits) {
-    const SeArgs a = argv[blockIdx.z];
-    const int n = blockIdx.x, t = threadIdx.x;
+// The gate of image n into LDS (`gate`): the partial sums added in a fixed order, then the two
+// small FC layers (SiLU, sigmoid) with all threads on the first one.
+__device__ __forceinline__ void se_gate(const SeArgs& a, const int n, const int splits, float* mean, float* red, float* z, float* gate) {
+    const int t = threadIdx.x;
     const float* part = a.scratch + (long long)n * se_scratch_floats(a.c, a.r);   // partial sums of the image
-    float* g = a.scratch + (long long)n * se_scratch_floats(a.c, a.r) + (long long)SE_MAX_SPLITS * a.c + a.r;
-    __shared__ float mean[SE_GATE_MAXC];
-    __shared__ float red[SE_GATE_THREADS];
-    __shared__ float z[256];
     const float inv = 1.f / (float)a.HW;
     for (int c = t; c < a.c; c += SE_GATE_THREADS) {
         float m = 0.f;
@@ -790,32 +787,42 @@ __global__ __launch_bounds__(SE_GATE_THREADS) void se_gate_kernel(const SeArgs* 
         float acc = a.b2[c];
 #pragma unroll 8
         for (int r = 0; r < a.r; r++) acc = fmaf(z[r], a.w2[(long long)r * a.c + c], acc);
-        g[c] = 1.f / (1.f + __expf(-acc));
+        gate[c] = 1.f / (1.f + __expf(-acc));
     }
+    __syncthreads();
 }
 
-// The launcher admits fewer than 2^31 work items: 32-bit index arithmetic.
+// Gate and rescale in one kernel: workgroup (share, image) works out the image's gate (every share of
+// an image does, from the same sums in the same order: the two FC layers are a few ten thousand
+// multiply-adds, a launch of their own cost 13 us) and rescales its share of the image's pixels.
 template <bool BF16>
-__global__ void se_scale_kernel(const SeArgs* __restrict__ argv, const int nb_) {
+__global__ __launch_bounds__(SE_GATE_THREADS) void se_gate_scale_kernel(const SeArgs* __restrict__ argv, const int nb_, const int splits) {
     const SeArgs a = argv[blockIdx.z];
+    __shared__ float mean[SE_GATE_MAXC];
+    __shared__ __attribute__((aligned(16))) float gate[SE_GATE_MAXC];
+    __shared__ float red[SE_GATE_THREADS];
+    __shared__ float z[256];
+    const int n = blockIdx.y;
+    se_gate(a, n, splits, mean, red, z, gate);
     constexpr int V = BF16 ? 8 : 1;
-    const unsigned cv = (unsigned)(a.c / V);
-    const unsigned idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (unsigned)nb_ * (unsigned)a.HW * cv) return;
-    const unsigned p = idx / cv;
-    const int c = (int)(idx - p * cv) * V;
-    const unsigned n = p / (unsigned)a.HW;
-    const float* g = a.scratch + (long long)n * se_scratch_floats(a.c, a.r) + (long long)SE_MAX_SPLITS * a.c + a.r + c;
-    const long long xo = (long long)p * a.x.stride + a.x.c0 + c, yo = (long long)p * a.y.stride + a.y.c0 + c;
-    if (BF16) {
-        float f[8];
-        unpack8(*(const uint4*)((const uint16_t*)a.x.p + xo), f);
-        const float4 g0 = *(const float4*)g, g1 = *(const float4*)(g + 4);
-        f[0] *= g0.x; f[1] *= g0.y; f[2] *= g0.z; f[3] *= g0.w;
-        f[4] *= g1.x; f[5] *= g1.y; f[6] *= g1.z; f[7] *= g1.w;
-        *(uint4*)((uint16_t*)a.y.p + yo) = pack8(f);
-    } else {
-        ((float*)a.y.p)[yo] = ((const float*)a.x.p)[xo] * g[0];
+    const int cv = a.c / V;
+    const int per = (a.HW + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int p0 = blockIdx.x * per, p1 = min(a.HW, p0 + per);
+    const int items = p1 > p0 ? (p1 - p0) * cv : 0;
+    for (int i = threadIdx.x; i < items; i += SE_GATE_THREADS) {
+        const int q = i / cv, c = (i - q * cv) * V;
+        const long long pix = (long long)n * a.HW + p0 + q;
+        const long long xo = pix * a.x.stride + a.x.c0 + c, yo = pix * a.y.stride + a.y.c0 + c;
+        if (BF16) {
+            float f[8];
+            unpack8(*(const uint4*)((const uint16_t*)a.x.p + xo), f);
+            const float4 g0 = *(const float4*)&gate[c], g1 = *(const float4*)&gate[c + 4];
+            f[0] *= g0.x; f[1] *= g0.y; f[2] *= g0.z; f[3] *= g0.w;
+            f[4] *= g1.x; f[5] *= g1.y; f[6] *= g1.z; f[7] *= g1.w;
+            *(uint4*)((uint16_t*)a.y.p + yo) = pack8(f);
+        } else {
+            ((float*)a.y.p)[yo] = ((const float*)a.x.p)[xo] * gate[c];
+        }
     }
 }
 
@@ -823,14 +830,20 @@ hipError_t launch_se(const SeArgs& a, const SeArgs* argv, int G, int nb, bool bf
     if (nb <= 0 || a.c <= 0 || a.r <= 0 || a.HW <= 0 || !a.scratch || G <= 0 || !argv) return hipErrorInvalidValue;
     if (a.c > SE_GATE_MAXC || a.r > 256) return hipErrorInvalidValue;   // what the gate kernel holds in LDS
     if (bf16 && (a.c % 8 || a.x.stride % 8 || a.x.c0 % 8 || a.y.stride % 8 || a.y.c0 % 8)) return hipErrorInvalidValue;
-    const long long tot = (long long)nb * a.HW * (a.c / (bf16 ? 8 : 1));
-    if (tot >= (1LL << 31) - 256) return hipErrorInvalidValue;
+    if ((long long)nb * a.HW >= (1LL << 31) / 8) return hipErrorInvalidValue;
     const int splits = se_splits(a.HW, nb * G);
     if (bf16) ENS_LAUNCH_FIRST(se_sum_kernel<true>, dim3(splits, nb, G), dim3(256), 0, s, argv, nb);
     else ENS_LAUNCH_FIRST(se_sum_kernel<false>, dim3(splits, nb, G), dim3(256), 0, s, argv, nb);
-    ENS_LAUNCH_MIDDLE(se_gate_kernel, dim3(nb, 1, G), dim3(SE_GATE_THREADS), 0, s, argv, nb, splits);
-    if (bf16) ENS_LAUNCH_LAST(se_scale_kernel<true>, dim3(blocks_for(tot, 256), 1, G), dim3(256), 0, s, argv, nb);
-    else ENS_LAUNCH_LAST(se_scale_kernel<false>, dim3(blocks_for(tot, 256), 1, G), dim3(256), 0, s, argv, nb);
+    // shares of an image in the second kernel: about SE_SCALE_BYTES of the tensor each
+    long long shares = ((long long)a.HW * a.c * (bf16 ? 2 : 4) + SE_SCALE_BYTES - 1) / SE_SCALE_BYTES;
+    // and no more workgroups than the chip holds at once (two of 1024 threads per compute unit): every
+    // workgroup starts with the gate's chain of memory latencies, which a second round would pay again
+    const long long room = 512 / ((long long)nb * G);
+    if (shares > room) shares = room;
+    if (shares > a.HW) shares = a.HW;
+    if (shares < 1) shares = 1;
+    if (bf16) ENS_LAUNCH_LAST(se_gate_scale_kernel<true>, dim3((unsigned)shares, nb, G), dim3(SE_GATE_THREADS), 0, s, argv, nb, splits);
+    else ENS_LAUNCH_LAST(se_gate_scale_kernel<false>, dim3((unsigned)shares, nb, G), dim3(SE_GATE_THREADS), 0, s, argv, nb, splits);
     return hipGetLastError();
 }
 
