@@ -429,6 +429,33 @@ def test_memory_bound_layers(ens, dtype):
     E.close()
 
 
+@pytest.mark.parametrize("dtype,h,c,pre", [("bf16", 7, 2048, False), ("bf16", 1, 328, True), ("fp32", 5, 100, True), ("bf16", 13, 40, False)],
+                         ids=["bf16_7x7x2048", "bf16_1x1x328_pre", "fp32_5x5x100_pre", "bf16_13x13x40"])
+def test_global_pool_shapes(ens, dtype, h, c, pre):
+    """Global average pooling over the shapes its grid distinguishes: several channel tiles per image
+    (2048 channels), a last tile that is partly empty (328 and 40 channels in groups of 8; 100 fp32
+    channels), fewer pixels than thread rows (1x1) and more (13x13), with and without pre-activation.
+    The pooled vector is read back and compared with the oracle element by element."""
+    bf = dtype == "bf16"
+    n = N.Net("gp", h, h, 8, dtype=dtype)
+    t = n.conv(0, c, 1)
+    g = n.gap(t, pre=pre)
+    n.fc(g, 8)
+    nb = 6
+    blobs, imgs = prepared([n], 61, nb, h, bf16=bf)
+    E = ens.Ensemble([n], blobs)
+    E.ens_debug_keep_tensors()
+    E.ens_set_alloc([[8]])
+    E.ens_predict(imgs)
+    got = E.ens_debug_tensor(0, g, n.tensors[g], nb)
+    E.close()
+    ref = oracle_tensor(n, blobs[0], imgs, g)
+    scale = np.sqrt(np.mean(ref ** 2)) + 1e-6
+    # the inputs of the pooling are the same bf16 (or fp32) values on both sides: only the order of the sum differs
+    tol = 2.0 ** -7 if bf else 2e-5
+    assert np.abs(got - ref).max() <= tol * (scale + np.abs(ref).max()), (np.abs(got - ref).max(), scale)
+
+
 def test_resize_staging(ens):
     """A member at 45 x 45 fed from 32 x 32 requests: bilinear resize inside the library."""
     for dtype in ("fp32", "bf16"):
