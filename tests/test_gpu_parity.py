@@ -456,6 +456,31 @@ def test_global_pool_shapes(ens, dtype, h, c, pre):
     assert np.abs(got - ref).max() <= tol * (scale + np.abs(ref).max()), (np.abs(got - ref).max(), scale)
 
 
+@pytest.mark.parametrize("dtype,h,c,r,nb", [("bf16", 28, 96, 4, 3), ("bf16", 7, 1152, 48, 6), ("bf16", 2, 16, 4, 600), ("fp32", 9, 40, 10, 4)],
+                         ids=["bf16_28x28x96", "bf16_7x7x1152", "bf16_2x2x16_600_images", "fp32_9x9x40"])
+def test_squeeze_excite_shapes(ens, dtype, h, c, r, nb):
+    """Squeeze-excite over the shapes its two kernels distinguish: several workgroups share an image in
+    the channel sums and in the rescale (28x28x96, 7x7x1152), one workgroup per image in the rescale
+    when the batch alone fills the chip (600 images), fp32 with a channel count that is no multiple of
+    8.  The rescaled tensor is read back and compared with the oracle element by element."""
+    bf = dtype == "bf16"
+    n = N.Net("se", h, h, 8, dtype=dtype)
+    t = n.conv(0, c, 1, act="silu")
+    u = n.se(t, r)
+    n.fc(n.gap(u), 8)
+    blobs, imgs = prepared([n], 71, nb, h, bf16=bf)
+    E = ens.Ensemble([n], blobs)
+    E.ens_debug_keep_tensors()
+    E.ens_set_alloc([[nb]])
+    E.ens_predict(imgs)
+    got = E.ens_debug_tensor(0, u, n.tensors[u], nb)
+    E.close()
+    ref = oracle_tensor(n, blobs[0], imgs, u)
+    scale = np.sqrt(np.mean(ref ** 2)) + 1e-6
+    tol = 2.0 ** -7 if bf else 2e-5
+    assert np.abs(got - ref).max() <= tol * (scale + np.abs(ref).max()) * (4 if bf else 1), (np.abs(got - ref).max(), scale)
+
+
 def test_resize_staging(ens):
     """A member at 45 x 45 fed from 32 x 32 requests: bilinear resize inside the library."""
     for dtype in ("fp32", "bf16"):
