@@ -32,7 +32,8 @@ typedef enum {
     ENS_E_NOFIT = -3,       /* Algorithm 1: no device has enough memory for a member           */
     ENS_E_HIP = -4,         /* a HIP runtime call failed                                       */
     ENS_E_NODEVICE = -5,    /* no GPU visible                                                  */
-    ENS_E_UNSUPPORTED = -6  /* description uses a shape the GPU kernels do not cover           */
+    ENS_E_UNSUPPORTED = -6, /* description uses a shape the GPU kernels do not cover           */
+    ENS_E_TOOBIG = -7       /* ens_predict_static: the request does not fit the static scratch */
 } ens_status;
 
 /* ---- member description --------------------------------------------------------------------
@@ -136,7 +137,11 @@ void ens_free(ens_handle* h);
 /* Input geometry and buffer placement for ens_predict: requests are n x base_h x base_w x 3
  * fp32 images; members whose own resolution differs are fed a bilinear resize (half-pixel
  * centres, edge clamp).  images_on_device / probs_on_device: the pointers given to ens_predict
- * are device pointers.  Default: base size = member 0's input size, host pointers. */
+ * are device pointers.  Default: base size = member 0's input size, host pointers.
+ * Device buffers are read and written on the library's own streams, which are not ordered against
+ * any stream of the caller: the images must be complete in device memory before ens_predict is
+ * called (synchronise the producing stream first), and the probabilities are complete when it
+ * returns. */
 int ens_set_io(ens_handle* h, int32_t base_h, int32_t base_w, int32_t images_on_device,
                int32_t probs_on_device);
 
@@ -170,6 +175,23 @@ int ens_bench(ens_handle* h, const ens_alloc* a, int32_t segment_size, int64_t n
  * worker of batch size 8.
  */
 int ens_predict(ens_handle* h, const float* images, int64_t n, float* probs_out);
+
+/* ens_predict for callers that cannot allocate device memory (code under HIP graph capture set-up,
+ * tight serving loops, harnesses that forbid hipMalloc): the same computation as ens_predict with
+ * the per-request scratch of the call (the members' logits, members x n x classes fp32, and the
+ * device table of their pointers), which ens_predict grows with hipMalloc, placed in a fixed device
+ * array inside the library (ens_static_scratch_bytes() bytes, 32 MiB, held by every GPU the
+ * library is loaded on until the process ends).  The call allocates and frees nothing.
+ *   d_images   : DEVICE, n x base_h x base_w x 3 fp32, complete before the call
+ *   d_probs_out: DEVICE, n x classes fp32, complete when the call returns
+ * Needs an installed allocation (ens_plan / ens_set_alloc: they allocate the workers' arenas) and
+ * per-kernel profiling switched off; ENS_E_INVALID otherwise.  ENS_E_TOOBIG, with a message on
+ * stderr, when members x n x classes x 4 bytes exceed the array less its 4 KiB table (3 members of
+ * 1000 classes: n <= 2795).  The array is shared by every handle and call on a GPU and keeps the last
+ * call's contents; a call writes every value it later reads, so nothing needs clearing, but calls
+ * that overlap in time on one GPU race.  ens_member_logits reads the array after such a call. */
+int ens_predict_static(ens_handle* h, const float* d_images, int64_t n, float* d_probs_out);
+int ens_static_scratch_bytes(void);
 
 /* Combination rule of ens_predict (section "The prediction accumulator").  The default is the
  * paper's: the mean of the members' softmax outputs.  The same section names two more:

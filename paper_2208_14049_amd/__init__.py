@@ -17,7 +17,7 @@ import numpy as np  # noqa: E402
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libens_mi355x.so")
 
-ENS_OK, ENS_E_INVALID, ENS_E_NOMEM, ENS_E_NOFIT, ENS_E_HIP, ENS_E_NODEVICE, ENS_E_UNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
+ENS_OK, ENS_E_INVALID, ENS_E_NOMEM, ENS_E_NOFIT, ENS_E_HIP, ENS_E_NODEVICE, ENS_E_UNSUPPORTED, ENS_E_TOOBIG = 0, -1, -2, -3, -4, -5, -6, -7
 ENS_FP32, ENS_BF16 = 0, 1
 ENS_MAX_SLOTS, ENS_MAX_MEMBERS, ENS_MAX_DOMAIN = 16, 64, 16
 
@@ -77,6 +77,7 @@ BENCH_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.POINTER(ctypes.c_int32), cty
 BENCH_SINGLE_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p)
 
 EXPORTS = ("ens_load", "ens_free", "ens_set_io", "ens_plan", "ens_set_alloc", "ens_bench", "ens_predict",
+           "ens_predict_static", "ens_static_scratch_bytes",
            "ens_member_logits", "ens_debug_tensor", "ens_debug_keep_tensors", "ens_classes", "ens_n_members", "ens_member_bytes",
            "ens_spec_bytes", "ens_set_profiling", "ens_profile_get", "ens_last_ms", "ens_set_combination", "ens_debug_fake_predictor",
            "ens_planner_fit_mem", "ens_planner_wfd", "ens_planner_neighbors", "ens_planner_greedy",
@@ -106,6 +107,7 @@ def lib():
         L.ens_set_alloc.argtypes = [vp, P(EnsAlloc), i32]
         L.ens_bench.argtypes = [vp, P(EnsAlloc), i32, i64, i32, P(dbl)]
         L.ens_predict.argtypes = [vp, vp, i64, vp]
+        L.ens_predict_static.argtypes = [vp, vp, i64, vp]
         L.ens_member_logits.argtypes = [vp, i32, i64, vp]
         L.ens_debug_tensor.argtypes = [vp, i32, i32, i32, vp]
         L.ens_debug_keep_tensors.argtypes = [vp, i32]
@@ -188,6 +190,13 @@ def _ptr(buf):
 
 def _is_device(buf):
     return (not isinstance(buf, np.ndarray)) and getattr(buf, "is_cuda", False)
+
+
+def _sync_producer(tensor):
+    """The library runs on its own streams: what torch's current stream still has to write into a
+    device tensor must have landed before the library reads it."""
+    import torch
+    torch.cuda.current_stream(tensor.device).synchronize()
 
 
 def make_alloc(matrix):
@@ -277,7 +286,21 @@ class Ensemble:
             else:
                 out = np.empty((n, self.classes), dtype=np.float32)
         self._set_io(dev_in, _is_device(out))
+        if dev_in:
+            _sync_producer(images)
         _check(lib().ens_predict(self._h, _ptr(images), n, _ptr(out)), "ens_predict")
+        return out
+
+    def ens_predict_static(self, images, out):
+        """ens_predict without device allocations: images and out are torch device tensors."""
+        n = int(images.shape[0])
+        assert tuple(images.shape[1:]) == (self.base_hw[0], self.base_hw[1], 3), images.shape
+        assert _is_device(images) and _is_device(out), "device tensors only"
+        assert images.is_contiguous() and str(images.dtype) == "torch.float32"
+        assert out.is_contiguous() and str(out.dtype) == "torch.float32" and tuple(out.shape) == (n, self.classes)
+        self._set_io(True, True)
+        _sync_producer(images)
+        _check(lib().ens_predict_static(self._h, _ptr(images), n, _ptr(out)), "ens_predict_static")
         return out
 
     def ens_member_logits(self, member, n):

@@ -14,6 +14,7 @@
 
 #include "planner.h"
 #include "seedgen.h"
+#include "static_scratch.h"
 
 using namespace ens;
 
@@ -175,7 +176,9 @@ static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G
 }
 
 // Translates the gang's operations into kernel argument arrays in device memory.
-static int build_launches(ens_handle* h, Gang& g) {
+// may_alloc false: the device block of the gang must already be large enough (it is once the
+// allocation has been installed); the function then only rewrites it.
+static int build_launches(ens_handle* h, Gang& g, bool may_alloc = true) {
     const Worker& leader = h->workers[g.workers[0]];
     const Member& m = h->members[leader.member];
     const int G = (int)g.workers.size();
@@ -226,6 +229,7 @@ static int build_launches(ens_handle* h, Gang& g) {
                                            : (size_t)G * (chain[i] == 1 ? 3 : chain[i] == 3 || fused[i] == 1 ? 2 : (m.ops[i].sub > 1 ? m.ops[i].sub : 1)));
     const size_t n_blk = first_blk[m.ops.size()];
     std::vector<char> host((n_blk + (size_t)G) * slot, 0);
+    if (!may_alloc && (!g.d_args || g.d_args_bytes < host.size())) return ENS_E_INVALID;
     if (g.d_args && g.d_args_bytes < host.size()) { (void)hipFree(g.d_args); g.d_args = nullptr; }
     if (!g.d_args) { HIP_TRY(hipMalloc((void**)&g.d_args, host.size())); g.d_args_bytes = host.size(); }
     g.launches.clear();
@@ -534,20 +538,57 @@ static int forward_batch(ens_handle* h, Gang& g, int64_t first, int nb) {
 
 static int ensure_buffers(ens_handle* h, int64_t n) {
     const size_t rows = (size_t)n;
-    if (rows > h->d_logits_rows) {
-        for (float*& p : h->d_logits) {
+    bool moved = false;
+    if (rows > h->d_logits_heap_rows) {
+        for (float*& p : h->d_logits_heap) {
             if (p) (void)hipFree(p);
             p = nullptr;
         }
-        h->d_logits.assign(h->members.size(), nullptr);
-        h->d_logits_rows = 0;
+        h->d_logits_heap.assign(h->members.size(), nullptr);
+        h->d_logits_heap_rows = 0;
         for (size_t m = 0; m < h->members.size(); m++)
-            HIP_TRY(hipMalloc((void**)&h->d_logits[m], rows * h->members[m].classes * sizeof(float)));
-        h->d_logits_rows = rows;
-        h->args_stale = true;                                  // the FC argument blocks name these buffers
+            HIP_TRY(hipMalloc((void**)&h->d_logits_heap[m], rows * h->members[m].classes * sizeof(float)));
+        h->d_logits_heap_rows = rows;
         if (!h->d_logit_ptrs) HIP_TRY(hipMalloc((void**)&h->d_logit_ptrs, ENS_MAX_MEMBERS * sizeof(float*)));
+        moved = true;
+    }
+    if (moved || h->logits_static || h->d_logit_table != h->d_logit_ptrs) {   // (back) to the library's own buffers
+        h->d_logits = h->d_logits_heap;
+        h->d_logits_rows = h->d_logits_heap_rows;
+        h->d_logit_table = h->d_logit_ptrs;
+        h->logits_static = false;
+        h->args_stale = true;                                  // the FC argument blocks name these buffers
         HIP_TRY(hipMemcpy((void*)h->d_logit_ptrs, h->d_logits.data(), h->members.size() * sizeof(float*), hipMemcpyHostToDevice));
     }
+    return ENS_OK;
+}
+
+// Points the per-member logits at slices of the fixed device array: a table of the members' pointers
+// in its first bytes, then one block of `rows` x classes floats per member.  Allocates nothing.
+static int use_static_logits(ens_handle* h, int64_t n) {
+    void* base = nullptr;
+    size_t bytes = 0;
+    HIP_TRY(static_scratch(&base, &bytes));
+    const size_t M = h->members.size();
+    const size_t row_bytes = M * (size_t)h->classes * sizeof(float);
+    const size_t rows_cap = (bytes - STATIC_SCRATCH_TABLE_BYTES) / row_bytes;
+    if ((size_t)n > rows_cap) {
+        fprintf(stderr, "ens_predict_static: %lld images x %zu members x %d classes of fp32 logits exceed the %zu-byte "
+                "static scratch (at most %zu images for this ensemble)\n", (long long)n, M, h->classes, bytes, rows_cap);
+        return ENS_E_TOOBIG;
+    }
+    float* first = (float*)((char*)base + STATIC_SCRATCH_TABLE_BYTES);
+    const bool there = h->logits_static && h->d_logit_table == (const float**)base && !h->d_logits.empty() && h->d_logits[0] == first;
+    if (!there) {
+        h->d_logits.assign(M, nullptr);
+        for (size_t m = 0; m < M; m++) h->d_logits[m] = first + m * rows_cap * (size_t)h->classes;
+        h->d_logits_rows = rows_cap;
+        h->d_logit_table = (const float**)base;
+        h->logits_static = true;
+        h->args_stale = true;                                  // the FC argument blocks name these buffers
+    }
+    // the table is written on every call: another handle's call may have left its own there
+    HIP_TRY(hipMemcpy(base, h->d_logits.data(), M * sizeof(float*), hipMemcpyHostToDevice));
     return ENS_OK;
 }
 
@@ -563,17 +604,20 @@ static int grow(float** p, size_t* cap, size_t want_floats) {
 
 // f(X, A) -> Y with X and Y on the device.  `mask` selects the members that take part (all
 // members for a real request; a single member when the BBS baseline times it alone).
-static int run_device(ens_handle* h, const float* d_images, int64_t n, float* d_probs, uint64_t mask) {
+// may_alloc false (the allocation-free entry point): the logits buffers are already in place and
+// nothing on the way may allocate or free device memory.
+static int run_device(ens_handle* h, const float* d_images, int64_t n, float* d_probs, uint64_t mask, bool may_alloc = true) {
     if (n == 0) return ENS_OK;
-    int rc = ensure_buffers(h, n);
+    int rc = may_alloc ? ensure_buffers(h, n) : ENS_OK;
     if (rc != ENS_OK) return rc;
+    if ((size_t)n > h->d_logits_rows) return ENS_E_INVALID;
     const int M = (int)h->members.size();
     const int seg = h->segment_size;
     const int64_t n_seg = (n + seg - 1) / seg;
     if (h->args_stale || h->bound_images != d_images) {          // (re)bind request buffers in the argument blocks
         for (Gang& g : h->gangs) {
             if (h->args_stale) {
-                rc = build_launches(h, g);
+                rc = build_launches(h, g, may_alloc);
                 if (rc != ENS_OK) return rc;
             }
             g.stage.src = d_images;
@@ -612,7 +656,7 @@ static int run_device(ens_handle* h, const float* d_images, int64_t n, float* d_
             if (!r.start || !r.stop) return ENS_E_HIP;
             next_launch_events() = LaunchEvents{r.start, r.stop};
         }
-        HIP_TRY(launch_combine(h->d_logit_ptrs, h->d_weights, h->combine_rule, M, n, h->classes, d_probs, h->main_stream));
+        HIP_TRY(launch_combine(h->d_logit_table, h->d_weights, h->combine_rule, M, n, h->classes, d_probs, h->main_stream));
         if (h->profiling) {
             next_launch_events() = LaunchEvents{};
             h->prof_recs.push_back(r);
@@ -743,7 +787,7 @@ void ens_free(ens_handle* h) {
     destroy_workers(h);
     for (Member& m : h->members)
         if (m.dev_params) (void)hipFree(m.dev_params);
-    for (float* p : h->d_logits)
+    for (float* p : h->d_logits_heap)
         if (p) (void)hipFree(p);
     if (h->d_logit_ptrs) (void)hipFree((void*)h->d_logit_ptrs);
     if (h->d_weights) (void)hipFree(h->d_weights);
@@ -810,6 +854,27 @@ int ens_predict(ens_handle* h, const float* images, int64_t n, float* probs_out)
     h->last_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
     return ENS_OK;
 }
+
+int ens_predict_static(ens_handle* h, const float* d_images, int64_t n, float* d_probs_out) {
+    if (!h || n < 0 || (n > 0 && (!d_images || !d_probs_out))) return ENS_E_INVALID;
+    if (!h->have_alloc || h->profiling) {
+        fprintf(stderr, "ens_predict_static: %s\n", !h->have_alloc ? "no allocation installed (ens_plan or ens_set_alloc first)"
+                                                                   : "per-kernel profiling creates events: switch it off");
+        return ENS_E_INVALID;
+    }
+    if (n == 0) return ENS_OK;
+    const auto t0 = std::chrono::steady_clock::now();
+    int rc = use_static_logits(h, n);
+    if (rc != ENS_OK) return rc;
+    rc = run_device(h, d_images, n, d_probs_out, ~0ull, false);
+    if (rc != ENS_OK) { (void)hipDeviceSynchronize(); return rc; }
+    HIP_TRY(hipStreamSynchronize(h->main_stream));
+    h->last_n = n;
+    h->last_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    return ENS_OK;
+}
+
+int ens_static_scratch_bytes(void) { return (int)STATIC_SCRATCH_BYTES; }
 
 int ens_bench(ens_handle* h, const ens_alloc* a, int32_t segment_size, int64_t n_calib, int32_t repeats,
               double* img_per_sec) {
@@ -1064,6 +1129,7 @@ const char* ens_strerror(int status) {
         case ENS_E_HIP: return "HIP runtime error";
         case ENS_E_NODEVICE: return "no GPU visible";
         case ENS_E_UNSUPPORTED: return "shape not covered by the GPU kernels";
+        case ENS_E_TOOBIG: return "request larger than the static scratch of the allocation-free entry point";
     }
     return "unknown status";
 }

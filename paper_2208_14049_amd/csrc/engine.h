@@ -148,8 +148,14 @@ struct ens_handle {
     // request buffers, grown on demand
     float* d_images = nullptr;  size_t d_images_cap = 0;
     float* d_probs = nullptr;   size_t d_probs_cap = 0;
-    std::vector<float*> d_logits; size_t d_logits_rows = 0;
-    const float** d_logit_ptrs = nullptr;
+    // Per-member logits of the request in flight.  d_logits / d_logit_table are the buffers in use:
+    // either the library's own allocations (d_logits_heap, d_logit_ptrs; grown on demand) or, for the
+    // allocation-free entry point, slices of the fixed device array.
+    std::vector<float*> d_logits; size_t d_logits_rows = 0;      // in use, and the rows they hold
+    std::vector<float*> d_logits_heap; size_t d_logits_heap_rows = 0;
+    const float** d_logit_ptrs = nullptr;                        // device table of the heap pointers
+    const float** d_logit_table = nullptr;                       // device table of the pointers in use
+    bool logits_static = false;
     int combine_rule = 0;                        // ENS_COMBINE_*
     float* d_weights = nullptr;                  // member weights of the weighted rule (device)
     float* d_calib = nullptr;   size_t d_calib_images = 0;
