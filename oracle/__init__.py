@@ -6,7 +6,7 @@ benchmark's CPU-baseline leg only.  Shares no code with the GPU library.
 """
 from .forward import forward_logits                      # noqa: F401
 from .combine import (softmax, combine_mean, combine_weighted, combine_vote, segments, batches,   # noqa: F401
-                      broadcast, accumulate_messages, top1, resize_bilinear)
+                      broadcast, accumulate_messages, top1, resize_bilinear, fifo_hand_out)
 from . import planner                                      # noqa: F401
 
 

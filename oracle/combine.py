@@ -70,6 +70,24 @@ def broadcast(nb_images, seg, n_models):
     return {m: list(ids) for m in range(n_models)}
 
 
+def fifo_hand_out(nb_images, seg, worker_batches, launch_cost, image_cost):
+    """Which worker of one DNN predicts which segment when all of them take segment ids from the same
+    FIFO queue (section "Data-parallelism"), in a model of time where a worker with batch size b
+    needs ceil(L / b) * launch_cost + L * image_cost for a segment of L samples.  Event simulation: a
+    heap of (time the worker becomes idle, worker); the idle worker with the earliest time (lowest
+    index among equals) pops the next id.  Returns the owner of every segment."""
+    import heapq
+    idle = [(0.0, k) for k in range(len(worker_batches))]
+    heapq.heapify(idle)
+    owners = []
+    for (a, b) in segments(nb_images, seg):
+        t, k = heapq.heappop(idle)
+        duration = len(batches(a, b, worker_batches[k])) * launch_cost + (b - a) * image_cost
+        heapq.heappush(idle, (t + duration, k))
+        owners.append(k)
+    return owners
+
+
 def accumulate_messages(messages, nb_images, n_classes, n_models, seg, dtype=np.float64):
     """The accumulator as the paper runs it: a zeroed Y updated by each arriving
     triplet (s, m, P) in whatever order the messages come."""

@@ -39,6 +39,35 @@ def test_segments_cover_request_exactly_once(n, seg):
             assert all(y - x == bs for x, y in bt[:-1]) and 0 < bt[-1][1] - bt[-1][0] <= bs
 
 
+def test_fifo_hand_out_pins():
+    """Workers of one DNN sharing a FIFO queue of segment ids (section "Data-parallelism"): every segment has
+    exactly one owner; equal workers alternate; with no per-batch cost the batch size does not matter; a
+    worker whose segments take half the time ends up with two thirds of them; the makespan is within one
+    segment of the best possible split (the list-scheduling bound)."""
+    assert oracle.fifo_hand_out(0, 128, [8, 8], 1.0, 1.0) == []
+    assert oracle.fifo_hand_out(300, 128, [8], 1.0, 1.0) == [0, 0, 0]
+    assert oracle.fifo_hand_out(128 * 7, 128, [32, 32, 32], 1e-3, 1e-5) == [0, 1, 2, 0, 1, 2, 0]
+    assert oracle.fifo_hand_out(128 * 6, 128, [8, 128], 0.0, 1e-5) == [0, 1, 0, 1, 0, 1]
+    # batch 64: 2 batches per segment, batch 128: 1; per-batch cost only -> worker 1 is twice as fast
+    own = oracle.fifo_hand_out(128 * 300, 128, [64, 128], 1.0, 0.0)
+    assert len(own) == 300 and abs(own.count(1) - 200) <= 1
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        k = int(rng.integers(1, 5))
+        b = [int(v) for v in rng.choice([1, 4, 8, 16, 32, 64, 128], k)]
+        n, seg = int(rng.integers(1, 3000)), int(rng.choice([16, 64, 128]))
+        lc, ic = float(rng.uniform(0, 1e-3)), float(rng.uniform(1e-6, 1e-4))
+        own = oracle.fifo_hand_out(n, seg, b, lc, ic)
+        segs = oracle.segments(n, seg)
+        assert len(own) == len(segs) and all(0 <= o < k for o in own)
+        cost = lambda w, a, e: len(oracle.batches(a, e, b[w])) * lc + (e - a) * ic      # noqa: E731
+        load = [sum(cost(w, a, e) for o, (a, e) in zip(own, segs) if o == w) for w in range(k)]
+        # the ideal split gives every worker the same finishing time T with sum_w T / cost_w(full segment) = #segments
+        full = [cost(w, 0, seg) for w in range(k)]
+        t_ideal = len(segs) / sum(1.0 / f for f in full)
+        assert max(load) <= t_ideal + max(full) + 1e-12
+
+
 def test_softmax_properties():
     z = RNG.standard_normal((5, 1000)) * 4
     p = oracle.softmax(z)
