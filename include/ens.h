@@ -111,7 +111,8 @@ typedef struct {
     int32_t default_batch;      /* Algorithm 1 places every member at this size, default 8     */
     int32_t segment_size;       /* default 128; raised to the largest batch size if smaller    */
     int32_t max_neighs;         /* default 100                                                 */
-    int32_t max_iter;           /* default 10                                                  */
+    int32_t max_iter;           /* moves of Algorithm 2, default 10; raised to (slots - members) when
+                                   that is larger (section "Offline benchmark settings")       */
     int32_t slots;              /* instance slots (rows) on the GPU, default 1                 */
     int32_t strategy;           /* 0 = Algorithm 1 then Algorithm 2; 1 = Algorithm 1 only;
                                    2 = BBS baseline (each member's batch size tuned alone)     */
@@ -153,8 +154,8 @@ int ens_set_io(ens_handle* h, int32_t base_h, int32_t base_w, int32_t images_on_
  */
 int ens_plan(ens_handle* h, uint64_t mem_budget_bytes, const ens_plan_opts* opts, ens_alloc* out);
 
-/* Installs a caller-made or cached matrix (section "The allocation optimizer": "the best matrix
- * is cached").  ENS_E_INVALID for a zero column or a non-positive size, ENS_E_NOMEM when the
+/* Installs a caller-made matrix, or one kept from an earlier ens_plan (section "The allocation
+ * optimizer" keeps the best matrix for reuse).  ENS_E_INVALID for a zero column or a non-positive size, ENS_E_NOMEM when the
  * workers do not fit.  Builds one stream and one activation arena per non-zero cell. */
 int ens_set_alloc(ens_handle* h, const ens_alloc* a, int32_t segment_size);
 
@@ -256,7 +257,7 @@ typedef struct {
     const int32_t* row_pool;      /* n_rows: pool of each row                                  */
     const int32_t* row_is_gpu;    /* n_rows: 1 = GPU, 0 = CPU (Algorithm 1 prefers GPUs)       */
     const int64_t* pool_cap;      /* n_pools                                                   */
-    int32_t max_iter, max_neighs;
+    int32_t max_iter, max_neighs;   /* max_iter is raised to n_rows - n_models when that is larger */
     uint64_t seed;
 } ens_plan_problem;
 
@@ -274,6 +275,15 @@ int ens_planner_bbs(const ens_plan_problem* p, ens_bench_single_fn bench, void* 
 /* Segment / batch partition of a request: writes up to max_out (start, end) pairs. */
 int ens_partition(int64_t nb_images, int32_t segment_size, int32_t batch, int64_t* starts,
                   int64_t* ends, int32_t max_out, int32_t* n_out);
+
+/* Hand-out of a member's segments among its n_workers workers (section "Data-parallelism": the
+ * workers of one DNN take segment ids from the same FIFO queue, so each gets segments in proportion to
+ * its speed).  The queue is run in estimated time on the host: a worker of batch size b needs
+ * ceil(L / b) * launch_cost + L * image_cost for a segment of L images, and each segment, in order,
+ * goes to the worker that becomes free first (lowest index on ties).  Writes the owner of each of the
+ * first max_out segments, *n_out = number of segments. */
+int ens_hand_out(int64_t nb_images, int32_t segment_size, const int32_t* batch, int32_t n_workers,
+                 double launch_cost, double image_cost, int32_t* owner_out, int32_t max_out, int32_t* n_out);
 
 const char* ens_strerror(int status);
 const char* ens_version(void);

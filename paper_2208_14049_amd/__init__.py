@@ -81,7 +81,7 @@ EXPORTS = ("ens_load", "ens_free", "ens_set_io", "ens_plan", "ens_set_alloc", "e
            "ens_member_logits", "ens_debug_tensor", "ens_debug_keep_tensors", "ens_classes", "ens_n_members", "ens_member_bytes",
            "ens_spec_bytes", "ens_set_profiling", "ens_profile_get", "ens_last_ms", "ens_set_combination", "ens_debug_fake_predictor",
            "ens_planner_fit_mem", "ens_planner_wfd", "ens_planner_neighbors", "ens_planner_greedy",
-           "ens_planner_bbs", "ens_partition", "ens_strerror", "ens_version")
+           "ens_planner_bbs", "ens_partition", "ens_hand_out", "ens_strerror", "ens_version")
 
 _lib = None
 
@@ -127,6 +127,7 @@ def lib():
         L.ens_planner_greedy.argtypes = [P(EnsPlanProblem), P(i32), BENCH_FN, vp, P(dbl), P(i32)]
         L.ens_planner_bbs.argtypes = [P(EnsPlanProblem), BENCH_SINGLE_FN, vp, P(i32), P(i32)]
         L.ens_partition.argtypes = [i64, i32, i32, P(i64), P(i64), i32, P(i32)]
+        L.ens_hand_out.argtypes = [i64, i32, P(i32), i32, dbl, dbl, P(i32), i32, P(i32)]
         L.ens_strerror.argtypes = [ctypes.c_int]
         L.ens_strerror.restype = ctypes.c_char_p
         L.ens_version.restype = ctypes.c_char_p
@@ -367,6 +368,16 @@ def ens_partition(nb_images, segment_size, batch):
     en = (ctypes.c_int64 * max(1, n.value))()
     _check(lib().ens_partition(nb_images, segment_size, batch, st, en, n.value, ctypes.byref(n)), "ens_partition")
     return [(st[i], en[i]) for i in range(n.value)]
+
+
+def ens_hand_out(nb_images, segment_size, batches, launch_cost, image_cost):
+    """Owner (worker index) of every segment of one member's request."""
+    b = (ctypes.c_int32 * len(batches))(*[int(v) for v in batches])
+    n = ctypes.c_int32()
+    _check(lib().ens_hand_out(nb_images, segment_size, b, len(batches), launch_cost, image_cost, None, 0, ctypes.byref(n)), "ens_hand_out")
+    out = (ctypes.c_int32 * max(1, n.value))()
+    _check(lib().ens_hand_out(nb_images, segment_size, b, len(batches), launch_cost, image_cost, out, n.value, ctypes.byref(n)), "ens_hand_out")
+    return [out[i] for i in range(n.value)]
 
 
 class PlanProblem:

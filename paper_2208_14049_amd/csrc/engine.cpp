@@ -431,13 +431,18 @@ static int install_alloc(ens_handle* h, const ens_alloc& a, int segment_size) {
             return e == hipErrorOutOfMemory ? ENS_E_NOMEM : ENS_E_HIP;
         }
     }
-    // gangs: same row, same batch size, same share of the segments, same network shape
+    // gangs: same row, same network shape and the same column of the matrix (hence the same batch size
+    // here, the same fellow workers and so the same share of the segments)
+    auto same_column = [&](int c1, int c2) {
+        for (int r = 0; r < a.rows; r++)
+            if (a.batch[r][c1] != a.batch[r][c2]) return false;
+        return true;
+    };
     for (size_t i = 0; i < h->workers.size(); i++) {
         Worker& w = h->workers[i];
         for (size_t gi = 0; gi < h->gangs.size() && w.gang < 0 && h->gangs_enabled; gi++) {
             const Worker& l = h->workers[h->gangs[gi].workers[0]];
-            if (l.slot == w.slot && l.batch == w.batch && l.rank == w.rank && l.of == w.of &&
-                same_network(h->members[l.member], h->members[w.member])) {
+            if (l.slot == w.slot && same_column(l.member, w.member) && same_network(h->members[l.member], h->members[w.member])) {
                 w.gang = (int)gi;
                 h->gangs[gi].workers.push_back((int)i);
             }
@@ -630,11 +635,32 @@ static int run_device(ens_handle* h, const float* d_images, int64_t n, float* d_
     // the workers start once the request images are in place on the main stream
     HIP_TRY(hipEventRecord(h->input_ready, h->main_stream));
     for (Gang& g : h->gangs) HIP_TRY(hipStreamWaitEvent(g.stream, h->input_ready, 0));
-    // every segment id goes once to every member; a member's workers take its segments in turn
+    // every segment id goes once to every member; a member's workers share its segments as they
+    // would by taking them from one queue, the faster worker more of them (planner.cpp, hand_out)
+    std::vector<std::vector<int32_t>> owner(M);
+    for (int c = 0; c < M; c++) {
+        std::vector<int32_t> batches;
+        const Gang* first = nullptr;
+        for (const Worker& w : h->workers)                       // in slot order = rank order
+            if (w.member == c) {
+                batches.push_back(w.batch);
+                if (w.rank == 0) first = &h->gangs[w.gang];
+            }
+        if (batches.size() <= 1 || !first) continue;
+        double flop = 0;
+        int launches = 1;
+        for (const Launch& L : first->launches)
+            if (L.kind != L_SKIP) { flop += L.flop; launches++; }
+        const double launch_cost = launches * 8e-6;              // a kernel of a small batch lasts about this long whatever it does
+        const double image_cost = flop / batches[0] / (h->members[c].bf16 ? 4e14 : 2e13);
+        rc = hand_out(n, seg, batches.data(), (int)batches.size(), launch_cost, image_cost, &owner[c]);
+        if (rc != ENS_OK) return rc;
+    }
     for (int64_t s = 0; s < n_seg; s++) {
         const int64_t start = s * seg, end = std::min<int64_t>((s + 1) * seg, n);
         for (Gang& g : h->gangs) {
-            if ((int)(s % g.of) != g.rank) continue;
+            const int member0 = h->workers[g.workers[0]].member;
+            if (g.of > 1 && owner[member0][s] != g.rank) continue;
             bool wanted = false;
             for (int wi : g.workers) wanted = wanted || ((mask >> h->workers[wi].member) & 1);
             if (!wanted) continue;
@@ -882,7 +908,7 @@ int ens_bench(ens_handle* h, const ens_alloc* a, int32_t segment_size, int64_t n
     if (repeats <= 0) repeats = 3;
     *img_per_sec = 0.0;
     int rc = install_alloc(h, *a, segment_size);
-    if (rc == ENS_E_NOMEM) return ENS_OK;                        // "0 if a DNN instance does not fit in memory"
+    if (rc == ENS_E_NOMEM) return ENS_OK;                        // a matrix that does not fit scores zero (Algorithm 2, definition of bench)
     if (rc != ENS_OK) return rc;
     if (h->profiling) reset_profile(h);
     return time_installed(h, n_calib, repeats, ~0ull, img_per_sec);

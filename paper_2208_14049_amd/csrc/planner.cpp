@@ -128,45 +128,52 @@ struct SplitMix {
     }
 };
 
+// The fastest of up to max_neighs one-cell neighbours of A (all of them, or a seeded draw without
+// replacement by a partial Fisher-Yates shuffle); the first in enumeration order wins ties.
+// Returns false when A has no neighbour.
+static bool fastest_neighbour(const ens_plan_problem& p, const int32_t* A, SplitMix& rng,
+                              const std::function<double(const int32_t*)>& bench, int* benches, Move* move, double* speed) {
+    std::vector<Move> cand = neighborhood(p, A);
+    if ((int)cand.size() > p.max_neighs) {
+        const size_t n = cand.size();
+        for (int i = 0; i < p.max_neighs; i++) {
+            const size_t j = i + (size_t)(rng.next() % (uint64_t)(n - i));
+            std::swap(cand[i], cand[j]);
+        }
+        cand.resize(p.max_neighs);
+    }
+    const size_t cells = (size_t)p.n_rows * p.n_models;
+    std::vector<int32_t> trial(A, A + cells);
+    bool found = false;
+    for (const Move& mv : cand) {
+        const int32_t keep = trial[mv.cell];
+        trial[mv.cell] = mv.value;
+        const double s = bench(trial.data());
+        trial[mv.cell] = keep;
+        ++*benches;
+        if (!found || s > *speed) { found = true; *move = mv; *speed = s; }
+    }
+    return found;
+}
+
+// Algorithm 2: hill climbing from A, one cell per move, each move to the fastest benchmarked
+// neighbour, only while that is strictly faster than the matrix held; at most `moves_allowed`
+// moves.  Section "Offline benchmark settings" raises that bound to (rows - models) when there are
+// more rows than the bound lets the search fill, and so does this function.
 int greedy(const ens_plan_problem& p, int32_t* A, const std::function<double(const int32_t*)>& bench,
            double* score, int32_t* n_bench) {
-    int max_iter = p.max_iter;
-    if (p.n_rows - p.n_models > max_iter) max_iter = p.n_rows - p.n_models;
+    const int moves_allowed = std::max(p.max_iter, p.n_rows - p.n_models);
     SplitMix rng{p.seed};
-    const size_t cells = (size_t)p.n_rows * p.n_models;
-    std::vector<int32_t> trial(cells);
-    double a_speed = bench(A);
+    double held = bench(A);
     int benches = 1;
-    int iter = 0;
-    while (iter < max_iter) {
-        std::vector<Move> neighs = neighborhood(p, A);
-        if ((int)neighs.size() > p.max_neighs) {            // partial Fisher-Yates draw
-            const size_t n = neighs.size();
-            for (int i = 0; i < p.max_neighs; i++) {
-                const size_t j = i + (size_t)(rng.next() % (uint64_t)(n - i));
-                std::swap(neighs[i], neighs[j]);
-            }
-            neighs.resize(p.max_neighs);
-        }
-        bool have = false;
-        Move best_move{0, 0};
-        double best_speed = 0;
-        for (const Move& mv : neighs) {
-            std::copy(A, A + cells, trial.begin());
-            trial[mv.cell] = mv.value;
-            const double s = bench(trial.data());
-            benches++;
-            if (!have || s > best_speed) { have = true; best_move = mv; best_speed = s; }
-        }
-        if (have && best_speed > a_speed) {
-            A[best_move.cell] = best_move.value;
-            a_speed = best_speed;
-            iter++;
-        } else {
-            iter = max_iter;                                 // local maximum or plateau
-        }
+    for (int moves = 0; moves < moves_allowed; moves++) {
+        Move mv{0, 0};
+        double s = 0;
+        if (!fastest_neighbour(p, A, rng, bench, &benches, &mv, &s) || !(s > held)) break;   // local maximum or plateau
+        A[mv.cell] = mv.value;
+        held = s;
     }
-    if (score) *score = a_speed;
+    if (score) *score = held;
     if (n_bench) *n_bench = benches;
     return ENS_OK;
 }
@@ -195,6 +202,32 @@ int partition(int64_t nb_images, int seg, int batch, std::vector<std::pair<int64
     for (int64_t s = 0; s * seg < nb_images; s++) {
         const int64_t start = s * seg, end = std::min<int64_t>((s + 1) * seg, nb_images);
         for (int64_t a = start; a < end; a += batch) out->push_back({a, std::min<int64_t>(a + batch, end)});
+    }
+    return ENS_OK;
+}
+
+// Which of a member's workers takes which segment.  In the paper the workers of one DNN take
+// segment ids from the same FIFO queue (section "Data-parallelism"): whoever is free takes the next
+// one, so a worker gets segments in proportion to its speed.  Here the hand-out is decided on the
+// host before anything is launched, by running that queue in estimated time: a worker with batch
+// size b needs ceil(L / b) * launch_cost + L * image_cost for a segment of L images (a batch costs a
+// fixed amount for its kernel launches plus an amount per image), and every segment, in order, goes
+// to the worker that becomes free first (lowest index on ties).  Deterministic; with equal batch
+// sizes it is round-robin.
+int hand_out(int64_t nb_images, int seg, const int32_t* batch, int n_workers, double launch_cost, double image_cost,
+             std::vector<int32_t>* owner) {
+    if (nb_images < 0 || seg <= 0 || n_workers <= 0 || !batch || launch_cost < 0 || image_cost < 0) return ENS_E_INVALID;
+    for (int k = 0; k < n_workers; k++)
+        if (batch[k] <= 0) return ENS_E_INVALID;
+    owner->clear();
+    std::vector<double> free_at(n_workers, 0.0);
+    for (int64_t s = 0; s * seg < nb_images; s++) {
+        const int64_t len = std::min<int64_t>((s + 1) * seg, nb_images) - s * seg;
+        int pick = 0;
+        for (int k = 1; k < n_workers; k++)
+            if (free_at[k] < free_at[pick]) pick = k;
+        free_at[pick] += (double)((len + batch[pick] - 1) / batch[pick]) * launch_cost + (double)len * image_cost;
+        owner->push_back(pick);
     }
     return ENS_OK;
 }
@@ -253,6 +286,16 @@ int ens_partition(int64_t nb_images, int32_t segment_size, int32_t batch, int64_
         starts[i] = v[i].first;
         ends[i] = v[i].second;
     }
+    return ENS_OK;
+}
+
+int ens_hand_out(int64_t nb_images, int32_t segment_size, const int32_t* batch, int32_t n_workers, double launch_cost,
+                 double image_cost, int32_t* owner_out, int32_t max_out, int32_t* n_out) {
+    std::vector<int32_t> v;
+    const int rc = hand_out(nb_images, segment_size, batch, n_workers, launch_cost, image_cost, &v);
+    if (rc != ENS_OK || !n_out) return ENS_E_INVALID;
+    *n_out = (int32_t)v.size();
+    for (size_t i = 0; i < v.size() && (int32_t)i < max_out && owner_out; i++) owner_out[i] = v[i];
     return ENS_OK;
 }
 

@@ -21,5 +21,7 @@ int greedy(const ens_plan_problem& p, int32_t* A, const std::function<double(con
 int bbs(const ens_plan_problem& p, const std::function<double(int, int)>& bench_single, int32_t* batch_out,
         int32_t* n_bench);
 int partition(int64_t nb_images, int seg, int batch, std::vector<std::pair<int64_t, int64_t>>* out);
+int hand_out(int64_t nb_images, int seg, const int32_t* batch, int n_workers, double launch_cost, double image_cost,
+             std::vector<int32_t>* owner);
 
 }  // namespace ens

@@ -128,6 +128,19 @@ def test_partition_matches_oracle(n, seg, b):
     assert ens.ens_partition(n, seg, b) == exp
 
 
+def test_hand_out_matches_oracle_queue_simulation():
+    """The library decides on the host which worker of a member takes which segment; the oracle runs the
+    shared FIFO queue of section "Data-parallelism" as an event simulation in the same model of time."""
+    rnd = random.Random(11)
+    for _ in range(200):
+        k = rnd.randint(1, 6)
+        b = [rnd.choice([1, 4, 8, 16, 32, 64, 128, 256]) for _ in range(k)]
+        n, seg = rnd.randint(0, 5000), rnd.choice([16, 64, 128, 256])
+        lc, ic = rnd.choice([0.0, 1e-4, 4e-4]), rnd.choice([0.0, 1e-5, 5e-5])
+        assert ens.ens_hand_out(n, seg, b, lc, ic) == oracle.fifo_hand_out(n, seg, b, lc, ic), (n, seg, b, lc, ic)
+    assert ens.ens_hand_out(128 * 5, 128, [32, 32], 3e-4, 2e-5) == [0, 1, 0, 1, 0]
+
+
 def test_memory_model_from_description():
     net = N.resnet18()
     w, a8 = ens.ens_spec_bytes(net, 8)
