@@ -26,7 +26,6 @@
 // pass over x (the residual is re-read while its lines are still in a cache).
 #include "conv_direct.h"
 
-#include <cstdlib>
 
 namespace ens {
 
@@ -70,12 +69,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int pp0 = ptile * BP;
     const int cin1 = a1.cin, cout3 = a3.cout;
 
-    // LDS: x chunks, then t1, then t2 | window row -> pixel index (-1: none) | biases
+    // LDS: x chunks, then t1, then t2 | window row -> pixel index (-1: none) | biases of the three layers | their scales
     unsigned char* const big = lds;
     int* const tbl = (int*)(big + BIG);
     float* const b1l = (float*)(tbl + R);
     float* const b2l = b1l + C;
     float* const b3l = b2l + C;
+    const int SBS = 2 * C + cout3;                               // from a channel's bias to its scale
     // the weights of the first two input chunks are asked for before anything else
     const int NS1 = (cin1 + 63) / 64 * 4, nk1 = cin1 / 32;       // steps per block of 32 weight rows (columns padded to 64s); input chunks
     const __amdgpu_buffer_rsrc_t w1res = __builtin_amdgcn_make_buffer_rsrc((void*)a1.wpk, 0, (int)((unsigned)C * (unsigned)(NS1 * 16) * 2u), 0x00020000);
@@ -94,8 +94,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int i = t; i < C; i += 256) {
         b1l[i] = a1.bias[i];
         b2l[i] = a2.bias[i];
+        b1l[SBS + i] = a1.scale[i];
+        b2l[SBS + i] = a2.scale[i];
     }
-    for (int i = t; i < cout3; i += 256) b3l[i] = a3.bias[i];
+    for (int i = t; i < cout3; i += 256) {
+        b3l[i] = a3.bias[i];
+        b3l[SBS + i] = a3.scale[i];
+    }
     __syncthreads();
 
     // ---- load side.  Offsets past the end of a buffer give zeros in LDS (loads) or are dropped
@@ -146,7 +151,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int i = 0; i < TC1; i++)
 #pragma unroll
-            for (int j = 0; j < TP1; j++) bn_init(acc[i][j], b1l + ch0 + 32 * i + 8 * lhalf);
+            for (int j = 0; j < TP1; j++) bn_zero(acc[i][j]);
         issue_x(0, 0);
         if (nk1 > 1) issue_x(1, 1);
         // One chunk: `wc` holds its weights, `wl` receives those of chunk kc + 2, BUF is its place in the
@@ -207,7 +212,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
                 for (int k = 0; k < 2; k++) {
                     const int ch = ch0 + 32 * i + 16 * k + 8 * lhalf;
-                    const u32x4 o = bn_pack(acc[i][j], k, a1.act);
+                    const u32x4 o = bn_pack(acc[i][j], k, a1.act, b1l + ch0 + 32 * i + 8 * lhalf, SBS);
                     *(u32x4*)(big + (ch >> 6) * T1B + row * 128 + ((((ch & 63) >> 3) ^ ((row >> 1) & 7)) << 4)) =
                         live ? o : u32x4{0u, 0u, 0u, 0u};
                 }
@@ -248,7 +253,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int i = 0; i < TC2; i++)
 #pragma unroll
-            for (int j = 0; j < 2; j++) bn_init(acc[i][j], b2l + wc2 + 32 * i + 8 * lhalf);
+            for (int j = 0; j < 2; j++) bn_zero(acc[i][j]);
         uint32_t xoff[9];                                        // tap (dh, dw): dh rows of the padded raster down, dw positions right
 #pragma unroll
         for (int tap = 0; tap < 9; tap++) {
@@ -299,7 +304,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 for (int k = 0; k < 2; k++) {
                     const int ch = wc2 + 32 * i + 16 * k + 8 * lhalf;
                     *(u32x4*)(big + (ch >> 6) * T2B + row * 128 + ((((ch & 63) >> 3) ^ ((row >> 1) & 7)) << 4)) =
-                        bn_pack(acc[i][j], k, a2.act);
+                        bn_pack(acc[i][j], k, a2.act, b2l + wc2 + 32 * i + 8 * lhalf, SBS);
                 }
         }
     }
@@ -327,7 +332,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
             for (int i = 0; i < 2; i++)
 #pragma unroll
-                for (int j = 0; j < 2; j++) bn_init(acc[i][j], b3l + nc * NCH + wc3 + 32 * i + 8 * lhalf);
+                for (int j = 0; j < 2; j++) bn_zero(acc[i][j]);
             bf16x8 xf[2][2];
             auto read_frags = [&](auto kk_c, auto b_c) {
                 constexpr int kk = decltype(kk_c)::value, b = decltype(b_c)::value;
@@ -365,8 +370,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
                     for (int k = 0; k < 2; k++) {
                         float v[8];
-#pragma unroll
-                        for (int e = 0; e < 8; e++) v[e] = acc[i][j][8 * k + e];
+                        bn_affine8(v, acc[i][j], k, b3l + nc * NCH + wc3 + 32 * i + 8 * lhalf, SBS);
                         if (has_res) {
                             const uint32_t rr[4] = {res[j][i][k].x, res[j][i][k].y, res[j][i][k].z, res[j][i][k].w};
 #pragma unroll
@@ -423,24 +427,18 @@ static bool bneck_plan(const ConvArgs& a1, const ConvArgs& a2, const ConvArgs& a
     pl->rows = c == 64 ? 256 : 192;
     if (BN_BP + 2 * (a1.W + 1) + 2 > pl->rows) return false;
     const int big = c == 64 ? bn_big<64, 256>() : bn_big<128, 192>();
-    pl->bytes = (size_t)big + (size_t)pl->rows * 4 + (size_t)(2 * c + a3.cout) * 4;
+    pl->bytes = (size_t)big + (size_t)pl->rows * 4 + (size_t)(2 * c + a3.cout) * 8;
     pl->tiles = (int)((PP + BN_BP - 1) / BN_BP);
     return pl->bytes <= (size_t)BNECK_LDS_LIMIT;
 }
 
 bool conv_bneck_applicable(const ConvArgs& a1, const ConvArgs& a2, const ConvArgs& a3, int nb, int G) {
     BneckPlan pl;
-#ifdef ENS_CONV_TUNING
-    if (const char* e = getenv("ENS_CONV_BNECK")) if (atoi(e) == 0) return false;
-#endif
     if (!bneck_plan(a1, a2, a3, nb, &pl)) return false;
     // A workgroup runs its tile's three layers one after the other, so a handful of tiles leaves the
     // chip to a handful of workgroups; the separate kernels split the channels too.  Measured on a
     // ResNet-50-shaped member the one kernel wins from about two dozen tiles on (batch 4 at 28x28).
     long long least = BNECK_MIN_TILES;
-#ifdef ENS_CONV_TUNING
-    if (const char* e = getenv("ENS_CONV_BNECK_MIN")) least = atoll(e);
-#endif
     return (long long)pl.tiles * G >= least;
 }
 

@@ -117,14 +117,14 @@ __device__ __forceinline__ void raster_table(int* tbl, int rows, int first, int 
     }
 }
 
-// What the epilogue of a BP x BC tile needs from memory, asked for before the main loop: the bias
-// of this thread's 8 channels and the residual values of its BP * BC / 2048 output groups.
+// What the epilogue of a BP x BC tile needs from memory, asked for before the main loop: scale and
+// bias of this thread's 8 channels and the residual values of its BP * BC / 2048 output groups.
 template <int BP, int BC>
 struct TilePrefetch {
     static constexpr int G = BC / 8;                 // 8-channel groups per output row
     static constexpr int RPI = 256 / G;              // output rows the workgroup stores per pass
     static constexpr int NI = BP / RPI;              // 16-byte output groups per thread
-    f32x4 bias0, bias1;
+    f32x4 bias0, bias1, scale0, scale1;
     u32x4 res[NI];
     int co;                                          // first of this thread's 8 channels
     bool cok, has_res;
@@ -135,9 +135,13 @@ struct TilePrefetch {
         cok = co < a.cout;
         bias0 = f32x4{0.f, 0.f, 0.f, 0.f};
         bias1 = bias0;
+        scale0 = f32x4{1.f, 1.f, 1.f, 1.f};
+        scale1 = scale0;
         if (cok && !partial) {
             bias0 = *ENS_GLOBAL(f32x4, a.bias + co);
             bias1 = *ENS_GLOBAL(f32x4, a.bias + co + 4);
+            scale0 = *ENS_GLOBAL(f32x4, a.scale + co);
+            scale1 = *ENS_GLOBAL(f32x4, a.scale + co + 4);
         }
         const uint16_t* rg = partial ? nullptr : (const uint16_t*)a.res.p;
         has_res = rg != nullptr;
@@ -155,8 +159,8 @@ struct TilePrefetch {
 
 // Epilogue of a BP x BC tile held in the accumulators of 4 waves (wave tile TP x TC blocks of
 // 32 x 32 at rows wp0, channels wc0): the tile is turned round in LDS (fp32, HROWS rows at a time,
-// rows padded by 16 bytes) and leaves as 16-byte groups of 8 channels with bias, residual and
-// activation applied, or, when `partial` (a share of the K range), as fp32 sums into slice
+// rows padded by 16 bytes) and leaves as 16-byte groups of 8 channels with scale, bias, residual
+// and activation applied, or, when `partial` (a share of the K range), as fp32 sums into slice
 // `slice` of the workspace.  Rows whose table entry is negative are dropped.  The caller has
 // made sure that nobody still uses the LDS behind otile.
 template <int BP, int BC, int TP, int TC, int HROWS>
@@ -197,8 +201,10 @@ __device__ __forceinline__ void store_tile(const ConvArgs& a, f32x16 (&acc)[TC][
                 *ENS_GLOBAL_W(f32x4, d + 4) = f32x4{hi.x, hi.y, hi.z, hi.w};
                 continue;
             }
-            float v[8] = {lo.x + pf.bias0.x, lo.y + pf.bias0.y, lo.z + pf.bias0.z, lo.w + pf.bias0.w,
-                          hi.x + pf.bias1.x, hi.y + pf.bias1.y, hi.z + pf.bias1.z, hi.w + pf.bias1.w};
+            float v[8] = {fmaf(lo.x, pf.scale0.x, pf.bias0.x), fmaf(lo.y, pf.scale0.y, pf.bias0.y),
+                          fmaf(lo.z, pf.scale0.z, pf.bias0.z), fmaf(lo.w, pf.scale0.w, pf.bias0.w),
+                          fmaf(hi.x, pf.scale1.x, pf.bias1.x), fmaf(hi.y, pf.scale1.y, pf.bias1.y),
+                          fmaf(hi.z, pf.scale1.z, pf.bias1.z), fmaf(hi.w, pf.scale1.w, pf.bias1.w)};
             if (pf.has_res) {
                 const uint32_t rr[4] = {pf.res[item].x, pf.res[item].y, pf.res[item].z, pf.res[item].w};
 #pragma unroll

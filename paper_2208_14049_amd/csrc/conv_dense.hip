@@ -20,7 +20,6 @@
 // workgroup reads channels below the slice it writes, and so does every other workgroup.
 #include "conv_direct.h"
 
-#include <cstdlib>
 
 namespace ens {
 
@@ -63,12 +62,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int pp0 = ptile * BP;
     const int cin1 = a1.cin;
 
-    // LDS: x chunks, then the middle tensor | window row -> pixel index (-1: none) | biases | pre-activation
+    // LDS: x chunks, then the middle tensor | window row -> pixel index (-1: none) | biases | scales | pre-activation
     unsigned char* const big = lds;
     int* const tbl = (int*)(big + BIG);
     float* const b1l = (float*)(tbl + R);
     float* const b2l = b1l + C;
-    float* const psl = b2l + DN_CO;                  // scale of the cin input channels
+    constexpr int SBS = C + DN_CO;                   // from a channel's bias to its scale
+    float* const psl = b2l + DN_CO + SBS;            // pre-activation scale of the cin input channels
     float* const phl = psl + cin1;                   // shift
     // the weights of the first two input chunks are asked for before anything else
     const int NS1 = (cin1 + 63) / 64 * 4, nk1 = cin1 / 32;       // steps per block of 32 weight rows (columns padded to 64s); input chunks
@@ -85,8 +85,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     load_w(w0, 0);
     if (nk1 > 1) load_w(w1, 1);
     raster_table(tbl, R, pp0 - (W1 + 1), PP, H1, W1, a1.H, a1.W);
-    for (int i = t; i < C; i += 256) b1l[i] = a1.bias[i];
-    if (t < DN_CO) b2l[t] = a2.bias[t];
+    for (int i = t; i < C; i += 256) {
+        b1l[i] = a1.bias[i];
+        b1l[SBS + i] = a1.scale[i];
+    }
+    if (t < DN_CO) {
+        b2l[t] = a2.bias[t];
+        b2l[SBS + t] = a2.scale[t];
+    }
     for (int i = t; i < cin1; i += 256) {
         psl[i] = a1.pre_scale[i];
         phl[i] = a1.pre_shift[i];
@@ -130,7 +136,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int i = 0; i < TC1; i++)
 #pragma unroll
-            for (int j = 0; j < TP1; j++) bn_init(acc[i][j], b1l + ch0 + 32 * i + 8 * lhalf);
+            for (int j = 0; j < TP1; j++) bn_zero(acc[i][j]);
         issue_x(0, 0);
         if (nk1 > 1) issue_x(1, 1);
         // One chunk: `wc` holds its weights, `wl` receives those of chunk kc + 2, BUF is its place in the
@@ -211,7 +217,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
                 for (int k = 0; k < 2; k++) {
                     const int ch = ch0 + 32 * i + 16 * k + 8 * lhalf;
-                    const u32x4 o = bn_pack(acc[i][j], k, a1.act);
+                    const u32x4 o = bn_pack(acc[i][j], k, a1.act, b1l + ch0 + 32 * i + 8 * lhalf, SBS);
                     *(u32x4*)(big + (ch >> 6) * T1B + row * 128 + ((((ch & 63) >> 3) ^ ((row >> 1) & 7)) << 4)) =
                         live ? o : u32x4{0u, 0u, 0u, 0u};
                 }
@@ -225,7 +231,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         const int pout = tbl[W1 + 1 + wp0 + lrow];               // the centre tap's rows: this tile's outputs
         const unsigned yo = pout >= 0 ? (unsigned)(pout * a2.y.stride * 2) + (unsigned)((a2.y.c0 + 8 * lhalf) * 2) : OOBV;
         f32x16 acc;
-        bn_init(acc, b2l + 8 * lhalf);
+        bn_zero(acc);
         uint32_t xoff[9];                                        // tap (dh, dw): dh rows of the padded raster down, dw positions right
 #pragma unroll
         for (int tap = 0; tap < 9; tap++) {
@@ -255,7 +261,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         // register v of a lane is channel 16(v/8) + 8(lane/32) + v%8 of its position; stores to positions
         // without a pixel carry the out-of-range offset and are dropped by the hardware
 #pragma unroll
-        for (int k = 0; k < 2; k++) __builtin_amdgcn_raw_buffer_store_b128(bn_pack(acc, k, a2.act), yres, yo, 32 * k, 0);
+        for (int k = 0; k < 2; k++) __builtin_amdgcn_raw_buffer_store_b128(bn_pack(acc, k, a2.act, b2l + 8 * lhalf, SBS), yres, yo, 32 * k, 0);
     }
 }
 
@@ -288,31 +294,19 @@ static bool dense_plan(const ConvArgs& a1, const ConvArgs& a2, int nb, int G, De
     pl->bp = 128;
     if (G * ((PP + 127) / 128) < DENSE_CUS && 64 + reach <= 128) pl->bp = 64;
     if (G * ((PP + 63) / 64) < DENSE_CUS && 32 + reach <= 64) pl->bp = 32;
-#ifdef ENS_CONV_TUNING
-    if (const char* e = getenv("ENS_CONV_DENSE_BP")) {
-        const int bp = atoi(e);
-        if ((bp == 128 || bp == 64 || bp == 32) && bp + reach <= 2 * bp) pl->bp = bp;
-    }
-#endif
     const int need = pl->bp + reach;
     pl->rows = pl->bp == 32 ? 64 : pl->bp == 64 ? 128 : need <= 192 ? 192 : 256;
     if (need > pl->rows) return false;
     const int big = pl->rows == 64 ? dn_big<64>() : pl->rows == 128 ? dn_big<128>() : pl->rows == 192 ? dn_big<192>() : dn_big<256>();
-    pl->bytes = (size_t)big + (size_t)pl->rows * 4 + (size_t)(DN_C + DN_CO + 2 * a1.cin) * 4;
+    pl->bytes = (size_t)big + (size_t)pl->rows * 4 + (size_t)(2 * (DN_C + DN_CO) + 2 * a1.cin) * 4;
     pl->tiles = (int)((PP + pl->bp - 1) / pl->bp);
     return 2 * pl->bytes <= (size_t)DENSE_LDS_LIMIT;
 }
 
 bool conv_dense_applicable(const ConvArgs& a1, const ConvArgs& a2, int nb, int G) {
     DensePlan pl;
-#ifdef ENS_CONV_TUNING
-    if (const char* e = getenv("ENS_CONV_DENSE")) if (atoi(e) == 0) return false;
-#endif
     if (!dense_plan(a1, a2, nb, G, &pl)) return false;
     long long least = DENSE_MIN_TILES;
-#ifdef ENS_CONV_TUNING
-    if (const char* e = getenv("ENS_CONV_DENSE_MIN")) least = atoll(e);
-#endif
     return (long long)pl.tiles * G >= least;
 }
 

@@ -32,33 +32,38 @@ __device__ __forceinline__ void bn_static_for(F&& f, std::integer_sequence<int, 
 template <int N, class F>
 __device__ __forceinline__ void bn_unroll(F&& f) { bn_static_for(f, std::make_integer_sequence<int, N>{}); }
 
-// accumulators of a lane start from the bias of its channels b[0..7] and b[16..23]
-__device__ __forceinline__ void bn_init(f32x16& acc, const float* b) {
-    const f32x4 q0 = *(const f32x4*)b, q1 = *(const f32x4*)(b + 4), q2 = *(const f32x4*)(b + 16), q3 = *(const f32x4*)(b + 20);
+__device__ __forceinline__ void bn_zero(f32x16& acc) {
+#pragma unroll
+    for (int e = 0; e < 16; e++) acc[e] = 0.f;
+}
+
+// Scale and bias of a lane's two runs of 8 channels: sb points at the lane's first channel in a table
+// (LDS) that holds the bias of the tile's channels and, `stride` floats further on, their scale.
+// Registers 8k .. 8k+7 of a result block are the channels sb[16k .. 16k+7].
+__device__ __forceinline__ void bn_affine8(float* v, const f32x16& acc, int k, const float* sb, int stride) {
+    const f32x4 b0 = *(const f32x4*)(sb + 16 * k), b1 = *(const f32x4*)(sb + 16 * k + 4);
+    const f32x4 s0 = *(const f32x4*)(sb + stride + 16 * k), s1 = *(const f32x4*)(sb + stride + 16 * k + 4);
 #pragma unroll
     for (int e = 0; e < 4; e++) {
-        acc[e] = q0[e];
-        acc[4 + e] = q1[e];
-        acc[8 + e] = q2[e];
-        acc[12 + e] = q3[e];
+        v[e] = fmaf(acc[8 * k + e], s0[e], b0[e]);
+        v[4 + e] = fmaf(acc[8 * k + 4 + e], s1[e], b1[e]);
     }
 }
 
-// registers 8k .. 8k+7 of a result block with the activation, as 8 bf16
-__device__ __forceinline__ u32x4 bn_pack(const f32x16& acc, int k, int act) {
+// registers 8k .. 8k+7 of a result block, scaled and biased per channel, with the activation, as 8 bf16
+__device__ __forceinline__ u32x4 bn_pack(const f32x16& acc, int k, int act, const float* sb, int stride) {
     float v[8];
-#pragma unroll
-    for (int e = 0; e < 8; e++) v[e] = acc[8 * k + e];
+    bn_affine8(v, acc, k, sb, stride);
     apply_act_n<8>(v, act);
     return u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
 }
 
-// registers 8k .. 8k+7 of a result block plus 8 bf16 of residual, activation applied, as 8 bf16
+// registers 8k .. 8k+7 of a result block, scaled and biased per channel, plus 8 bf16 of residual,
+// activation applied, as 8 bf16
 template <bool RES>
-__device__ __forceinline__ u32x4 bn_pack_res(const f32x16& acc, int k, const u32x4& res, int act) {
+__device__ __forceinline__ u32x4 bn_pack_res(const f32x16& acc, int k, const u32x4& res, int act, const float* sb, int stride) {
     float v[8];
-#pragma unroll
-    for (int e = 0; e < 8; e++) v[e] = acc[8 * k + e];
+    bn_affine8(v, acc, k, sb, stride);
     if constexpr (RES) {
         const uint32_t rr[4] = {res.x, res.y, res.z, res.w};
 #pragma unroll

@@ -21,7 +21,6 @@
 // is the scalar offset), so the loop body is address-free apart from the fragment reads.
 #include "conv_common.h"
 
-#include <cstdlib>
 
 namespace ens {
 
@@ -310,9 +309,6 @@ int conv_halo_pick(const ConvArgs& a, int nb, int G) {
     } else if (a.cin >= 96) {
         choice = 4;                                              // multiples of 32 only: 32-channel blocks
     }
-#ifdef ENS_CONV_TUNING   // variant override for kernel experiments only (out of range: generic kernel)
-    if (const char* e = getenv("ENS_CONV_HALO")) choice = atoi(e);
-#endif
     if (choice < 0 || choice >= N_HALO_VARIANTS) return -1;
     int hrows, nbuf;
     size_t bytes;
@@ -348,15 +344,6 @@ hipError_t launch_conv_halo(const ConvArgs& a, const ConvArgs* argv, int G, int 
     int hrows, nbuf;
     size_t bytes;
     int splits = halo_splits(a, HALO_VARIANTS[variant], nb, G);
-#ifdef ENS_CONV_TUNING
-    if (const char* e = getenv("ENS_CONV_HALO_SPLITS")) {
-        splits = atoi(e);
-        const int ncb = a.cin / HALO_VARIANTS[variant].cb;
-        if (splits < 1 || splits > ncb || !a.ws || (long long)splits * nb * a.H * a.W * a.cout > a.ws_floats) splits = 1;
-        const int per = (ncb + splits - 1) / splits;
-        splits = (ncb + per - 1) / per;
-    }
-#endif
     if (!halo_layout(a, HALO_VARIANTS[variant], splits, &hrows, &nbuf, &bytes)) return hipErrorInvalidValue;
     switch (variant) {
         case 0: return launch_halo_variant<128, 64, 2, 2, 64, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);

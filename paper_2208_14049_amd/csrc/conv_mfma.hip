@@ -29,7 +29,6 @@
 // workspace, and a second small kernel sums the slices and applies the epilogue.
 #include "conv_common.h"
 
-#include <cstdlib>
 
 namespace ens {
 
@@ -342,7 +341,9 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restric
                 continue;
             }
             const f32x4 b0 = *ENS_GLOBAL(f32x4, a.bias + co), b1 = *ENS_GLOBAL(f32x4, a.bias + co + 4);
-            float v[8] = {lo.x + b0.x, lo.y + b0.y, lo.z + b0.z, lo.w + b0.w, hi.x + b1.x, hi.y + b1.y, hi.z + b1.z, hi.w + b1.w};
+            const f32x4 s0 = *ENS_GLOBAL(f32x4, a.scale + co), s1 = *ENS_GLOBAL(f32x4, a.scale + co + 4);
+            float v[8] = {fmaf(lo.x, s0.x, b0.x), fmaf(lo.y, s0.y, b0.y), fmaf(lo.z, s0.z, b0.z), fmaf(lo.w, s0.w, b0.w),
+                          fmaf(hi.x, s1.x, b1.x), fmaf(hi.y, s1.y, b1.y), fmaf(hi.z, s1.z, b1.z), fmaf(hi.w, s1.w, b1.w)};
             if (rg) {
                 const u32x4 r = *ENS_GLOBAL(u32x4, rg + (size_t)p * a.res.stride + a.res.c0 + co);
                 const uint32_t rr[4] = {r.x, r.y, r.z, r.w};
@@ -377,8 +378,8 @@ __global__ void conv_splitk_epilogue(const ConvArgs* __restrict__ argv, const in
         const float4 v = *(const float4*)(a.ws + sp * slice + (size_t)p * a.cout + co);
         s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
-    const float4 b = *(const float4*)(a.bias + co);
-    float v[4] = {s.x + b.x, s.y + b.y, s.z + b.z, s.w + b.w};
+    const float4 b = *(const float4*)(a.bias + co), m = *(const float4*)(a.scale + co);
+    float v[4] = {fmaf(s.x, m.x, b.x), fmaf(s.y, m.y, b.y), fmaf(s.z, m.z, b.z), fmaf(s.w, m.w, b.w)};
     if (a.res.p) {
         const uint2 r = *(const uint2*)((const uint16_t*)a.res.p + (size_t)p * a.res.stride + a.res.c0 + co);
         v[0] += bf16_to_f32((uint16_t)(r.x & 0xFFFF));
@@ -415,11 +416,6 @@ static const Variant VARIANTS[] = {
     {64, 64, 32, "conv_igemm_bf16<64,64,k32>"},      // small grids, shallow K
     {128, 64, 64, "conv_igemm_bf16<128,64,k64>"},    // grids that fill the chip, deep K
     {128, 64, 32, "conv_igemm_bf16<128,64,k32>"},    // grids that fill the chip, shallow K
-#ifdef ENS_CONV_TUNING
-    {128, 128, 64, "t5"}, {256, 128, 64, "t6"}, {128, 128, 32, "t7"}, {256, 64, 64, "t8"}, {128, 128, 32, "t9"},
-    {128, 64, 32, "t10"}, {128, 64, 32, "t11"}, {128, 128, 32, "t12"}, {64, 64, 32, "t13"},
-    {64, 64, 64, "t14"}, {64, 64, 64, "t15"}, {128, 64, 32, "t16"}, {64, 64, 32, "t17"},
-#endif
 };
 constexpr int CUS = 256;
 
@@ -452,9 +448,6 @@ static int pick_splits(const ConvArgs& a, long long P, long long K, int variant,
 // the LDS table.  Others go to the register-staged kernel.
 static bool pre_in_dma_kernel(const ConvArgs& a) {
     bool ok = a.kh == 1 && a.kw == 1 && a.sh == 1 && a.sw == 1 && a.pt == 0 && a.pl == 0 && a.cin <= PRE_MAXK;
-#ifdef ENS_CONV_TUNING
-    if (const char* e = getenv("ENS_CONV_PRE_DMA")) ok = ok && atoi(e) != 0;
-#endif
     return ok;
 }
 
@@ -487,7 +480,7 @@ hipError_t launch_conv_bf16(const ConvArgs& a, const ConvArgs* argv, int G, int 
     if (a.cin % 8 || a.x.stride % 8 || a.x.c0 % 8) return hipErrorInvalidValue;
     if (a.cout % 8 || a.y.stride % 8 || a.y.c0 % 8) return hipErrorInvalidValue;
     if (a.res.p && (a.res.stride % 8 || a.res.c0 % 8)) return hipErrorInvalidValue;
-    if (nb <= 0 || a.cin <= 0 || a.cout <= 0 || !a.bias || G <= 0 || !argv) return hipErrorInvalidValue;
+    if (nb <= 0 || a.cin <= 0 || a.cout <= 0 || !a.bias || !a.scale || G <= 0 || !argv) return hipErrorInvalidValue;
     if ((a.pre_scale == nullptr) != (a.pre_shift == nullptr)) return hipErrorInvalidValue;
     const long long P64 = (long long)nb * a.Ho * a.Wo;
     const long long K64 = (long long)a.kh * a.kw * a.cin;
@@ -502,30 +495,11 @@ hipError_t launch_conv_bf16(const ConvArgs& a, const ConvArgs* argv, int G, int 
     if ((long long)nb * a.H * a.W * a.x.stride >= 0x7FFFFF00LL || (long long)a.cout * K64 >= 0x70000000LL || a.kh > 16 || a.kw > 16) return hipErrorInvalidValue;
     int variant = pick_variant(a, P64, K64, G);
     int splits = a.pre_scale ? 1 : pick_splits(a, P64, K64, variant, G);
-#ifdef ENS_CONV_TUNING   // tile / split override for kernel experiments only
-    if (const char* e = getenv("ENS_CONV_VARIANT")) { if (a.cout > 32 || atoi(e) == 0) variant = atoi(e); splits = pick_splits(a, P64, K64, variant, G); }
-    if (const char* e = getenv("ENS_CONV_SPLITS")) { splits = atoi(e); if (splits > 1 && (!a.ws || (long long)splits * P64 * a.cout > a.ws_floats)) splits = 1; }
-#endif
     switch (variant) {
         case 0: return launch_variant<128, 32, 4, 1, 2, 64>(a, argv, G, nb, P, splits, s);
         case 2: return launch_variant<64, 64, 2, 2, 2, 32>(a, argv, G, nb, P, splits, s);
         case 3: return launch_variant<128, 64, 2, 2, 2, 64>(a, argv, G, nb, P, splits, s);
         case 4: return launch_variant<128, 64, 2, 2, 2, 32>(a, argv, G, nb, P, splits, s);
-#ifdef ENS_CONV_TUNING
-        case 5: return launch_variant<128, 128, 2, 2, 2, 64>(a, argv, G, nb, P, splits, s);
-        case 6: return launch_variant<256, 128, 2, 2, 2, 64>(a, argv, G, nb, P, splits, s);
-        case 7: return launch_variant<128, 128, 2, 2, 3, 32>(a, argv, G, nb, P, splits, s);
-        case 8: return launch_variant<256, 64, 4, 1, 2, 64>(a, argv, G, nb, P, splits, s);
-        case 9: return launch_variant<128, 128, 2, 2, 2, 32>(a, argv, G, nb, P, splits, s);
-        case 10: return launch_variant<128, 64, 2, 2, 2, 32>(a, argv, G, nb, P, splits, s);
-        case 11: return launch_variant<128, 64, 2, 2, 3, 32>(a, argv, G, nb, P, splits, s);
-        case 12: return launch_variant<128, 128, 2, 2, 4, 32>(a, argv, G, nb, P, splits, s);
-        case 13: return launch_variant<64, 64, 2, 2, 3, 32>(a, argv, G, nb, P, splits, s);
-        case 14: return launch_variant<64, 64, 2, 2, 4, 64>(a, argv, G, nb, P, splits, s);
-        case 15: return launch_variant<64, 64, 2, 2, 3, 64>(a, argv, G, nb, P, splits, s);
-        case 16: return launch_variant<128, 64, 2, 2, 4, 32>(a, argv, G, nb, P, splits, s);
-        case 17: return launch_variant<64, 64, 2, 2, 4, 32>(a, argv, G, nb, P, splits, s);
-#endif
         default: return launch_variant<64, 64, 2, 2, 2, 64>(a, argv, G, nb, P, splits, s);
     }
 }

@@ -12,15 +12,14 @@
 // fragments, 1 KB in a row each, go from memory to registers two chunks ahead as well; nothing but
 // the pixel fragments is read from LDS, and the one barrier per chunk covers 16 or 8 matrix-core
 // instructions per wavefront where the generic kernel's covers 4 to 8 and also waits for its
-// weights.  The output leaves from the accumulators as 16-byte runs of 8 channels; bias is what the
-// accumulators start from; the residual is asked for before the loop.
+// weights.  The output leaves from the accumulators as 16-byte runs of 8 channels after the
+// per-channel scale and bias (which wait in LDS); the residual is asked for before the loop.
 //
 // Wavefront roles: WPX along the pixels, 4 / WPX along blocks of 32 channels.  WPX = 1: a wavefront
 // has all 128 pixels of 32 channels (a weight fragment serves four matrix-core instructions and is
 // fetched by one wavefront only), BC = 128; WPX = 2 for layers with 64 output channels or fewer.
 #include "conv_direct.h"
 
-#include <cstdlib>
 
 namespace ens {
 
@@ -90,23 +89,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
     }
     f32x16 acc[TP];
-    {
-        // bias of channels ch0 + 0..7 and ch0 + 16..23 (zeros past the last channel)
-        const __amdgpu_buffer_rsrc_t bres = __builtin_amdgcn_make_buffer_rsrc((void*)a.bias, 0, (int)((unsigned)a.cout * 4u), 0x00020000);
-        const unsigned bo = (unsigned)ch0 * 4u;
-        const f32x4 q0 = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(bres, bo, 0, 0));
-        const f32x4 q1 = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(bres, bo, 16, 0));
-        const f32x4 q2 = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(bres, bo, 64, 0));
-        const f32x4 q3 = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(bres, bo, 80, 0));
 #pragma unroll
-        for (int e = 0; e < 4; e++) {
-            acc[0][e] = q0[e];
-            acc[0][4 + e] = q1[e];
-            acc[0][8 + e] = q2[e];
-            acc[0][12 + e] = q3[e];
-        }
-#pragma unroll
-        for (int j = 1; j < TP; j++) acc[j] = acc[0];
+    for (int j = 0; j < TP; j++) bn_zero(acc[j]);
+    // bias and scale of the tile's BC channels wait in LDS behind the ring (zeros and ones past the last
+    // channel); the first barrier of the chunk loop comes between this write and the epilogue's reads
+    float* const sbl = (float*)(lds + PW_NXB * XS);
+    if (t < BC) {
+        const bool ok = c0 + t < a.cout;
+        sbl[t] = ok ? a.bias[c0 + t] : 0.f;
+        sbl[BC + t] = ok ? a.scale[c0 + t] : 1.f;
     }
 
     // ---- input chunks: thread t fills chunk slot t % 8 of rows t / 8 + 32 s with the swizzled chunk
@@ -192,7 +183,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int j = 0; j < TP; j++)
 #pragma unroll
         for (int k = 0; k < 2; k++) {
-            const u32x4 o = has_res ? bn_pack_res<true>(acc[j], k, res[j][k], a.act) : bn_pack_res<false>(acc[j], k, res[j][k], a.act);
+            const float* sb = sbl + (ch0 - c0);
+            const u32x4 o = has_res ? bn_pack_res<true>(acc[j], k, res[j][k], a.act, sb, BC) : bn_pack_res<false>(acc[j], k, res[j][k], a.act, sb, BC);
             __builtin_amdgcn_raw_buffer_store_b128(o, yres, yo[j][k], 32 * k, 0);
         }
 }
@@ -212,9 +204,6 @@ static bool pw_shape_ok(const ConvArgs& a, int nb) {
 }
 
 bool conv_pw_applicable(const ConvArgs& a, int nb, int G) {
-#ifdef ENS_CONV_TUNING
-    if (const char* e = getenv("ENS_CONV_PW")) if (atoi(e) == 0) return false;
-#endif
     return pw_shape_ok(a, nb);
 }
 
@@ -225,7 +214,7 @@ static hipError_t launch_pw_variant(const ConvArgs& a, const ConvArgs* argv, int
     constexpr int BC = 32 * (4 / WPX);
     const long long P = (long long)nb * a.H * a.W;
     const dim3 grid((unsigned)(((P + PW_BP - 1) / PW_BP) * ((a.cout + BC - 1) / BC)), 1, G);
-    ENS_LAUNCH((conv1x1_direct_bf16<WPX>), grid, dim3(256), (size_t)PW_NXB * PW_XS, s, argv, nb);
+    ENS_LAUNCH((conv1x1_direct_bf16<WPX>), grid, dim3(256), (size_t)PW_NXB * PW_XS + 2 * 128 * sizeof(float), s, argv, nb);
     return hipGetLastError();
 }
 
@@ -235,9 +224,6 @@ static hipError_t launch_pw_variant(const ConvArgs& a, const ConvArgs* argv, int
 static int pw_wpx(const ConvArgs& a, int nb, int G) {
     const long long tiles = (((long long)nb * a.H * a.W + PW_BP - 1) / PW_BP) * ((a.cout + 127) / 128) * G;
     int wpx = a.cout <= 64 || tiles < 256 ? 2 : 1;
-#ifdef ENS_CONV_TUNING
-    if (const char* e = getenv("ENS_CONV_PW_WPX")) if (atoi(e) == 1 || atoi(e) == 2) wpx = atoi(e);
-#endif
     return wpx;
 }
 

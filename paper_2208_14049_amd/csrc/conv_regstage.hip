@@ -192,8 +192,8 @@ __global__ __launch_bounds__(256) void conv_regstage_bf16(const ConvArgs* __rest
                 if (co >= a.cout) continue;
                 float v0 = acc[i][j][g * 4 + 0], v1 = acc[i][j][g * 4 + 1];
                 float v2 = acc[i][j][g * 4 + 2], v3 = acc[i][j][g * 4 + 3];
-                const float4 b = *(const float4*)(a.bias + co);
-                v0 += b.x; v1 += b.y; v2 += b.z; v3 += b.w;
+                const float4 b = *(const float4*)(a.bias + co), m = *(const float4*)(a.scale + co);
+                v0 = fmaf(v0, m.x, b.x); v1 = fmaf(v1, m.y, b.y); v2 = fmaf(v2, m.z, b.z); v3 = fmaf(v3, m.w, b.w);
                 if (rg) {
                     const uint2 r = *(const uint2*)(rg + (size_t)p * a.res.stride + a.res.c0 + co);
                     v0 += bf16_to_f32((uint16_t)(r.x & 0xFFFF));

@@ -17,7 +17,6 @@
 // cover all 64 banks.
 #include "conv_common.h"
 
-#include <cstdlib>
 #include <type_traits>
 #include <utility>
 
@@ -42,7 +41,7 @@ __device__ __forceinline__ void for_each_tap(F&& f, std::integer_sequence<int, T
 // second buffer while the matrix cores work on the current one and while its output leaves
 // straight from the accumulators: the filter rows go to the matrix cores with bits 2 and 3 of the row
 // number swapped, which makes a lane's 16 results of a 32x32 block two runs of 8 consecutive channels
-// (two 16-byte stores); the bias is what the accumulators start from.
+// (two 16-byte stores) after the per-channel scale and bias.
 template <int BP, int KH, int KW>
 __global__ __launch_bounds__(256) void conv_taps16_bf16(const ConvArgs* __restrict__ argv, const int nb_,
                                                         const int hrows, const int gh, const int gw) {
@@ -64,11 +63,12 @@ __global__ __launch_bounds__(256) void conv_taps16_bf16(const ConvArgs* __restri
     const int c0 = blockIdx.y * BC;
     const int hbytes = hrows * 32, nhl = hrows / 128;            // bytes and load instructions per window
 
-    // LDS: filter | window 0 | window 1 | window tables 0, 1 | output tables 0, 1 | bias of the 64 channels
+    // LDS: filter | window 0 | window 1 | window tables 0, 1 | output tables 0, 1 | bias, then scale, of the 64 channels
     unsigned char* const halo = lds + WBYTES;
     int* const tbls = (int*)(halo + 2 * hbytes);     // window row -> input pixel index, -1: no pixel
     int* const owns = tbls + 2 * hrows;              // position of the tile -> output pixel index, -1: none
     float* const biasl = (float*)(owns + 2 * BP);
+    float* const scalel = biasl + BC;
     const int origin = a.pt * W1 + a.pl;             // window row 0 is tap (0, 0) of the tile's first position
 
     // ---- loads.  Offsets past the end of a buffer give zeros in LDS; 2^31 is past the end of
@@ -115,7 +115,10 @@ __global__ __launch_bounds__(256) void conv_taps16_bf16(const ConvArgs* __restri
         return;
     }
     make_tables(0, ptile);
-    if (t < BC) biasl[t] = c0 + t < a.cout ? a.bias[c0 + t] : 0.f;
+    if (t < BC) {
+        biasl[t] = c0 + t < a.cout ? a.bias[c0 + t] : 0.f;
+        scalel[t] = c0 + t < a.cout ? a.scale[c0 + t] : 1.f;
+    }
     __syncthreads();
     issue_window(0);
 
@@ -153,15 +156,11 @@ __global__ __launch_bounds__(256) void conv_taps16_bf16(const ConvArgs* __restri
         for (int j = 0; j < TP; j++) pout[j] = owns[buf * BP + wp0 + lrow + 32 * j];
         f32x16 acc[TC][TP];
 #pragma unroll
-        for (int i = 0; i < TC; i++) {
-            const int cb = 32 * i + 8 * lhalf;
-            const f32x4 bq[4] = {*(const f32x4*)&biasl[cb], *(const f32x4*)&biasl[cb + 4],
-                                 *(const f32x4*)&biasl[cb + 16], *(const f32x4*)&biasl[cb + 20]};
+        for (int i = 0; i < TC; i++)
 #pragma unroll
             for (int j = 0; j < TP; j++)
 #pragma unroll
-                for (int v = 0; v < 16; v++) acc[i][j][v] = bq[v >> 2][v & 3];
-        }
+                for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
         const uint32_t halo0 = lds0 + WBYTES + (uint32_t)(buf * hbytes);
         bf16x8 wf[2][TC], xf[2][TP];
         auto read_frags = [&](auto tap_c, int b) {
@@ -197,17 +196,21 @@ __global__ __launch_bounds__(256) void conv_taps16_bf16(const ConvArgs* __restri
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // the next window has landed (this wave's part)
         __syncthreads();                                         // everybody's; and this window and its tables are free
 
-        // ---- output: register v of a lane is channel cl + 32i + 16(v/8) + v%8 of its position
+        // ---- output: register v of a lane is channel cl + 32i + 16(v/8) + v%8 of its position, scaled
+        //      and biased per channel
         const bool relu = a.act == ACT_RELU;
 #pragma unroll
         for (int i = 0; i < TC; i++)
 #pragma unroll
-            for (int j = 0; j < TP; j++)
+            for (int k = 0; k < 2; k++) {
+                const int cb = 32 * i + 16 * k + 8 * lhalf;
+                const f32x4 sq[2] = {*(const f32x4*)&scalel[cb], *(const f32x4*)&scalel[cb + 4]};
+                const f32x4 bq[2] = {*(const f32x4*)&biasl[cb], *(const f32x4*)&biasl[cb + 4]};
 #pragma unroll
-                for (int k = 0; k < 2; k++) {
+                for (int j = 0; j < TP; j++) {
                     float v[8];
 #pragma unroll
-                    for (int e = 0; e < 8; e++) v[e] = acc[i][j][8 * k + e];
+                    for (int e = 0; e < 8; e++) v[e] = fmaf(acc[i][j][8 * k + e], sq[e >> 2][e & 3], bq[e >> 2][e & 3]);
                     if (!relu) apply_act_n<8>(v, a.act);
                     uint32_t o[4];
 #pragma unroll
@@ -222,6 +225,7 @@ __global__ __launch_bounds__(256) void conv_taps16_bf16(const ConvArgs* __restri
                     const unsigned yo = pout[j] >= 0 && co < a.cout ? (unsigned)(pout[j] * a.y.stride + a.y.c0 + co) * 2u : OOBS;
                     __builtin_amdgcn_raw_buffer_store_b128(u32x4{o[0], o[1], o[2], o[3]}, yres, yo, 0, 0);
                 }
+            }
     }
 }
 
@@ -248,7 +252,7 @@ static bool taps_plan(const ConvArgs& a, int nb, int G, TapsPlan* pl) {
     pl->bp = 256;
     const int need = pl->bp + (a.kh - 1) * (a.W + pl->gw) + a.kw;
     pl->hrows = (need + 127) / 128 * 128;
-    pl->bytes = (size_t)a.kh * a.kw * 64 * 32 + 2 * ((size_t)pl->hrows * 32 + (size_t)pl->hrows * 4 + (size_t)pl->bp * 4) + 64 * 4;
+    pl->bytes = (size_t)a.kh * a.kw * 64 * 32 + 2 * ((size_t)pl->hrows * 32 + (size_t)pl->hrows * 4 + (size_t)pl->bp * 4) + 2 * 64 * 4;
     if (pl->bytes > (size_t)TAPS_LDS_LIMIT) return false;
     // As many workgroups as the chip holds at once, shared by the gang and the channel tiles, and
     // not one more: a workgroup that has to wait for a free slot starts its whole share of the
@@ -264,9 +268,6 @@ static bool taps_plan(const ConvArgs& a, int nb, int G, TapsPlan* pl) {
 
 bool conv_taps_applicable(const ConvArgs& a, int nb) {
     TapsPlan pl;
-#ifdef ENS_CONV_TUNING
-    if (const char* e = getenv("ENS_CONV_TAPS")) if (atoi(e) == 0) return false;
-#endif
     return taps_plan(a, nb, 1, &pl);
 }
 
@@ -282,9 +283,6 @@ static hipError_t launch_taps_variant(const ConvArgs& a, const ConvArgs* argv, i
         raised = true;
     }
     int wgs = pl.wgs;
-#ifdef ENS_CONV_TUNING
-    if (const char* e = getenv("ENS_CONV_TAPS_WGS")) if (atoi(e) > 0) wgs = atoi(e);
-#endif
     const dim3 grid((unsigned)wgs, (unsigned)((a.cout + 63) / 64), G);
     ENS_LAUNCH((conv_taps16_bf16<BP, KH, KW>), grid, dim3(256), pl.bytes, s, argv, nb, pl.hrows, pl.gh, pl.gw);
     return hipGetLastError();

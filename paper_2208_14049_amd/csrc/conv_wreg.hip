@@ -20,12 +20,11 @@
 // position and the matrix rows 8g + 4h + e (g = 0..3, e = 0..3, h = lane / 32); the weight rows
 // are handed to the matrix cores with bits 2 and 3 of the row number swapped, so that those rows
 // are the channels 16(g/2) + 8h + 4(g%2) + e: two runs of 8 consecutive channels, two 16-byte
-// stores per lane, 32 contiguous bytes per position and instruction.  The bias is what the
-// accumulators start from.  A tile therefore costs one barrier: the one that says that the next
+// stores per lane, 32 contiguous bytes per position and instruction, after the per-channel scale
+// and bias (both wait in LDS).  A tile therefore costs one barrier: the one that says that the next
 // window has landed and the current one is free.
 #include "conv_common.h"
 
-#include <cstdlib>
 #include <type_traits>
 #include <utility>
 
@@ -72,13 +71,14 @@ void conv3x3_wreg_bf16(const ConvArgs* __restrict__ argv, const int nb_, const i
     if (ptile >= walk.end) return;
 
     // LDS: window 0 | window 1 | three tables window row -> byte offset of the pixel in x (out of range: no
-    // pixel) | three tables window row -> pixel index (-1: none) | bias of the BC channels.  On its way
+    // pixel) | three tables window row -> pixel index (-1: none) | bias, then scale, of the BC channels.  On its way
     // to the registers the filter passes through the FSTAGE bytes after window 0, which the tables keep
     // clear of.
     constexpr int FSTAGE = 5 * BC * 128;
     unsigned* const tblx = (unsigned*)(lds + (2 * hbytes > hbytes + FSTAGE ? 2 * hbytes : hbytes + FSTAGE));
     int* const tblp = (int*)(tblx + 3 * hrows);
     float* const biasl = (float*)(tblp + 3 * hrows);
+    float* const scalel = biasl + BC;
 
     // ---- window loads.  Offsets past the end of a buffer give zeros in LDS (loads) or are dropped
     //      (stores); 2^31 is past the end of every buffer the launcher admits.
@@ -142,7 +142,10 @@ void conv3x3_wreg_bf16(const ConvArgs* __restrict__ argv, const int nb_, const i
     };
     make_table(0);
     make_table(1);                                               // (of a tile past the end when there is only one: never used)
-    if (t < BC) biasl[t] = c0 + t < a.cout ? a.bias[c0 + t] : 0.f;
+    if (t < BC) {
+        biasl[t] = c0 + t < a.cout ? a.bias[c0 + t] : 0.f;
+        scalel[t] = c0 + t < a.cout ? a.scale[c0 + t] : 1.f;
+    }
     __syncthreads();
     issue_window(0, 0);
 
@@ -230,11 +233,6 @@ void conv3x3_wreg_bf16(const ConvArgs* __restrict__ argv, const int nb_, const i
             yo[j] = pout >= 0 && wave_ok ? (unsigned)(pout * a.y.stride * 2) + ylane : OOBV;
             ro[j] = pout >= 0 && wave_ok ? (unsigned)(pout * a.res.stride * 2) + rlane : OOBV;
         }
-        f32x4 bq[4];                                             // bias of channels cl + 0..7 and cl + 16..23
-        bq[0] = *(const f32x4*)&biasl[cl];
-        bq[1] = *(const f32x4*)&biasl[cl + 4];
-        bq[2] = *(const f32x4*)&biasl[cl + 16];
-        bq[3] = *(const f32x4*)&biasl[cl + 20];
         u32x4 res[TP][2];
         if (has_res) {
 #pragma unroll
@@ -248,7 +246,7 @@ void conv3x3_wreg_bf16(const ConvArgs* __restrict__ argv, const int nb_, const i
 #pragma unroll
         for (int j = 0; j < TP; j++)
 #pragma unroll
-            for (int v = 0; v < 16; v++) acc[j][v] = bq[v >> 2][v & 3];
+            for (int v = 0; v < 16; v++) acc[j][v] = 0.f;
         const uint32_t wbase = lds0 + (uint32_t)(buf * hbytes);
         bf16x8 xf[2][TP];
         auto read_frags = [&](auto step_c, int b) {
@@ -280,17 +278,20 @@ void conv3x3_wreg_bf16(const ConvArgs* __restrict__ argv, const int nb_, const i
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // the next window has landed (this wave's part)
         __syncthreads();                                         // everybody's; and this window is free for the one after
 
-        // ---- output: register v of a lane is channel cl + 16(v/8) + v%8 of its position.  Stores to
-        //      positions without a pixel carry the out-of-range offset and are dropped by the hardware.
+        // ---- output: register v of a lane is channel cl + 16(v/8) + v%8 of its position, scaled and
+        //      biased per channel.  Stores to positions without a pixel carry the out-of-range offset
+        //      and are dropped by the hardware.
         auto emit = [&](auto res_c, auto relu_c) {
             constexpr bool RES = decltype(res_c)::value, RELU = decltype(relu_c)::value;
 #pragma unroll
-            for (int j = 0; j < TP; j++)
+            for (int k = 0; k < 2; k++) {
+                const f32x4 sq[2] = {*(const f32x4*)&scalel[cl + 16 * k], *(const f32x4*)&scalel[cl + 16 * k + 4]};
+                const f32x4 bq[2] = {*(const f32x4*)&biasl[cl + 16 * k], *(const f32x4*)&biasl[cl + 16 * k + 4]};
 #pragma unroll
-                for (int k = 0; k < 2; k++) {
+                for (int j = 0; j < TP; j++) {
                     float v[8];
 #pragma unroll
-                    for (int e = 0; e < 8; e++) v[e] = acc[j][8 * k + e];
+                    for (int e = 0; e < 8; e++) v[e] = fmaf(acc[j][8 * k + e], sq[e >> 2][e & 3], bq[e >> 2][e & 3]);
                     if constexpr (RES) {
                         const uint32_t rr[4] = {res[j][k].x, res[j][k].y, res[j][k].z, res[j][k].w};
 #pragma unroll
@@ -313,6 +314,7 @@ void conv3x3_wreg_bf16(const ConvArgs* __restrict__ argv, const int nb_, const i
                     }
                     __builtin_amdgcn_raw_buffer_store_b128(u32x4{o[0], o[1], o[2], o[3]}, yres, yo[j], 32 * k, 0);
                 }
+            }
         };
         if (a.act == ACT_RELU) {
             if (has_res) emit(std::true_type{}, std::true_type{});
@@ -344,9 +346,9 @@ static bool wreg_plan(const ConvArgs& a, int nb, int G, WregPlan* pl) {
     const int need = bp + 2 * (a.W + 1) + 2;
     pl->hrows = (need + 31) / 32 * 32;
     if (pl->hrows > 256) return false;                           // one table row per thread
-    // two windows, or one window and the stage the filter passes through, whichever is larger; tables; bias
+    // two windows, or one window and the stage the filter passes through, whichever is larger; tables; bias and scale
     const size_t hb = (size_t)pl->hrows * 128, fstage = (size_t)5 * 64 * 128;
-    pl->bytes = (2 * hb > hb + fstage ? 2 * hb : hb + fstage) + 6 * (size_t)pl->hrows * 4 + 64 * 4;
+    pl->bytes = (2 * hb > hb + fstage ? 2 * hb : hb + fstage) + 6 * (size_t)pl->hrows * 4 + 2 * 64 * 4;
     if (2 * pl->bytes > (size_t)WREG_LDS_LIMIT) return false;
     // as many workgroups as the chip holds at once (two per compute unit), and not one more
     const int ctiles = (a.cout + 63) / 64;
@@ -359,9 +361,6 @@ static bool wreg_plan(const ConvArgs& a, int nb, int G, WregPlan* pl) {
 
 bool conv_wreg_applicable(const ConvArgs& a, int nb, int G) {
     WregPlan pl;
-#ifdef ENS_CONV_TUNING
-    if (const char* e = getenv("ENS_CONV_WREG")) if (atoi(e) == 0) return false;
-#endif
     return wreg_plan(a, nb, G, &pl);
 }
 
@@ -380,9 +379,6 @@ hipError_t launch_conv_wreg(const ConvArgs& a, const ConvArgs* argv, int G, int 
         raised = true;
     }
     int wgs = pl.wgs;
-#ifdef ENS_CONV_TUNING
-    if (const char* e = getenv("ENS_CONV_WREG_WGS")) if (atoi(e) > 0) wgs = atoi(e);
-#endif
     const dim3 grid((unsigned)wgs, (unsigned)((a.cout + 63) / 64), G);
     ENS_LAUNCH((conv3x3_wreg_bf16<128, 2, 2>), grid, dim3(256), pl.bytes, s, argv, nb, pl.hrows);
     return hipGetLastError();

@@ -84,6 +84,7 @@ static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G
             if (o.res >= 0) a.res = view_of(w, leader, m, o.res, o.res_c0);
             a.w = P + pl.w;
             a.bias = (const float*)(P + pl.b);
+            a.scale = (const float*)(P + pl.scale);
             a.pre_scale = pl.pre_scale != SIZE_MAX ? (const float*)(P + pl.pre_scale) : nullptr;
             a.pre_shift = pl.pre_shift != SIZE_MAX ? (const float*)(P + pl.pre_shift) : nullptr;
             a.ws = nullptr; a.ws_floats = 0;
@@ -103,6 +104,7 @@ static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G
                 if (a.res.p) a.res.c0 += sub * pl.sub_cout;
                 a.w = (const char*)a.w + (size_t)sub * pl.sub_cout * o.kh * o.kw * pl.cin_s * es;
                 a.bias += (size_t)sub * pl.sub_cout;
+                a.scale += (size_t)sub * pl.sub_cout;
             }
             const int groups = o.r > 1 ? o.r : 1;
             L.flop = 2.0 * nb * td.h * td.w * o.cout * (pl.alg_k > 0 ? pl.alg_k : o.kh * o.kw * o.cin / groups);
@@ -121,6 +123,7 @@ static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G
             a.y = view_of(w, leader, m, o.dst, o.dst_c0);
             a.w = o.kind == ENS_OP_DWCONV ? P + pl.w : nullptr;
             a.bias = o.kind == ENS_OP_DWCONV ? (const float*)(P + pl.b) : nullptr;
+            a.scale = o.kind == ENS_OP_DWCONV ? (const float*)(P + pl.scale) : nullptr;
             a.nb = w.batch; a.H = ts.h; a.W = ts.w; a.c = o.cin; a.Ho = td.h; a.Wo = td.w;
             a.kh = o.kh; a.kw = o.kw; a.sh = o.sh; a.sw = o.sw; a.pt = o.pt; a.pl = o.pl; a.act = o.act;
             L.flop = o.kind == ENS_OP_DWCONV ? 2.0 * nb * td.h * td.w * o.cin * o.kh * o.kw : 0.0;

@@ -25,7 +25,7 @@ struct TensorInfo {
 struct OpPlan {
     ens_op op;
     // byte offsets into the member's device parameter block (SIZE_MAX: absent)
-    size_t w, b, pre_scale, pre_shift, w2, b2;
+    size_t w, b, scale, pre_scale, pre_shift, w2, b2;
     size_t w_packed; // the convolution's weights once more in matrix-core operand order (members of a fused chain)
     int cin_s;       // stored input channels of the convolution's K axis
     int scratch;     // index of the scratch pseudo-tensor (squeeze-excite), -1 otherwise

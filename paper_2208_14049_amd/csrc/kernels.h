@@ -20,15 +20,20 @@ struct View {
 };
 
 // Convolution (and its fused epilogue) over a batch of `nb` images.
-//   y[n, ho, wo, co] = act( sum_{kh,kw,ci} pre(x[n, ho*sh-pt+kh, wo*sw-pl+kw, ci]) * w[co][kh][kw][ci]
+//   y[n, ho, wo, co] = act( scale[co] * sum_{kh,kw,ci} pre(x[n, ho*sh-pt+kh, wo*sw-pl+kw, ci]) * w[co][kh][kw][ci]
 //                           + bias[co] + res[n, ho, wo, co] )
-// Weights are stored [cout][kh][kw][cin] (K contiguous per output channel) with the batch-norm
-// folded in; bias is fp32.  pre_scale / pre_shift (fp32, per input channel) apply
-// relu(x * scale + shift) to in-bounds inputs when non-null.
+// Weights are stored [cout][kh][kw][cin] (K contiguous per output channel).  The batch-norm that
+// follows the convolution is scale (gamma / sqrt(var + eps)) and bias (beta - mean * scale + the
+// layer's own bias * scale), both fp32 and applied to the fp32 sum: bf16 members keep the weights
+// exactly as given (folding the scale into them would round every weight a second time, an error
+// that is the same for all pixels of a channel and does not average out); fp32 members have the
+// scale folded into the weights and a scale of ones.  pre_scale / pre_shift (fp32, per input
+// channel) apply relu(x * scale + shift) to in-bounds inputs when non-null.
 struct ConvArgs {
     View x, y, res;            // res.p == nullptr: no residual
     const void* w;
     const float* bias;         // never null (zeros when the layer has none)
+    const float* scale;        // never null (ones when there is nothing to scale by)
     const float* pre_scale;
     const float* pre_shift;
     // split-K scratch of the worker (may be null: no splitting): room for ws_floats partial sums
@@ -44,8 +49,9 @@ struct ConvArgs {
 
 struct PoolArgs {              // max / average pooling, depthwise convolution
     View x, y;
-    const void* w;             // depthwise: [kh][kw][c] in the member's dtype, folded
+    const void* w;             // depthwise: [kh][kw][c] in the member's dtype
     const float* bias;         // depthwise only
+    const float* scale;        // depthwise only: y = act(scale[c] * sum + bias[c]), as for ConvArgs
     int nb, H, W, c, Ho, Wo;
     int kh, kw, sh, sw, pt, pl;
     int act;

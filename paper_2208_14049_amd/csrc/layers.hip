@@ -27,6 +27,14 @@ __device__ __forceinline__ void unpack8(const uint4 v, float* f) {
         f[2 * e + 1] = bf2f((uint16_t)(u[e] >> 16));
     }
 }
+// f[e] = f[e] * scale[e] + bias[e] for 8 consecutive channels (16-byte aligned fp32 vectors)
+__device__ __forceinline__ void scale_bias8(float* f, const float* scale, const float* bias) {
+    const float4 s0 = *(const float4*)scale, s1 = *(const float4*)(scale + 4);
+    const float4 b0 = *(const float4*)bias, b1 = *(const float4*)(bias + 4);
+    f[0] = fmaf(f[0], s0.x, b0.x); f[1] = fmaf(f[1], s0.y, b0.y); f[2] = fmaf(f[2], s0.z, b0.z); f[3] = fmaf(f[3], s0.w, b0.w);
+    f[4] = fmaf(f[4], s1.x, b1.x); f[5] = fmaf(f[5], s1.y, b1.y); f[6] = fmaf(f[6], s1.z, b1.z); f[7] = fmaf(f[7], s1.w, b1.w);
+}
+
 __device__ __forceinline__ uint4 pack8(const float* f) {
     typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
     typedef float f32x2_t __attribute__((ext_vector_type(2)));
@@ -175,7 +183,7 @@ __global__ void conv_f32_kernel(const ConvArgs* __restrict__ argv, const int nb_
             }
         }
     }
-    acc += a.bias[co];
+    acc = fmaf(acc, a.scale[co], a.bias[co]);        // fp32 members: the scale is in the weights and this one is 1
     if (a.res.p) acc += ((const float*)a.res.p)[p * a.res.stride + a.res.c0 + co];
     ((float*)a.y.p)[p * a.y.stride + a.y.c0 + co] = act_f(acc, a.act);
 }
@@ -248,7 +256,7 @@ __global__ void window_kernel(const PoolArgs* __restrict__ argv, const int nb_) 
     if (MODE == 0) {
         // one uniform branch for the launch's activation instead of a chain per value
 #pragma unroll
-        for (int e = 0; e < V; e++) acc[e] += a.bias[c + e];
+        for (int e = 0; e < V; e++) acc[e] = fmaf(acc[e], a.scale[c + e], a.bias[c + e]);
         if (a.act == ACT_SILU) {
 #pragma unroll
             for (int e = 0; e < V; e++) acc[e] = acc[e] / (1.f + __expf(-acc[e]));
@@ -327,12 +335,7 @@ __global__ void dwconv_bf16_kernel(const PoolArgs* __restrict__ argv, const int 
     const int ho = (int)(row - nu * (unsigned)a.Ho);
     const uint16_t* __restrict__ x = (const uint16_t*)a.x.p + (long long)nu * a.H * a.W * a.x.stride + a.x.c0 + c;
     const uint16_t* __restrict__ w = (const uint16_t*)a.w + c;
-    float acc[8];
-    {
-        const float4 b0 = *(const float4*)(a.bias + c), b1 = *(const float4*)(a.bias + c + 4);
-        acc[0] = b0.x; acc[1] = b0.y; acc[2] = b0.z; acc[3] = b0.w;
-        acc[4] = b1.x; acc[5] = b1.y; acc[6] = b1.z; acc[7] = b1.w;
-    }
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll 1
     for (int kh = 0; kh < K; kh++) {
         const int hi = ho * a.sh - a.pt + kh;
@@ -356,6 +359,7 @@ __global__ void dwconv_bf16_kernel(const PoolArgs* __restrict__ argv, const int 
             for (int e = 0; e < 8; e++) acc[e] = fmaf(xf[e], wf[e], acc[e]);
         }
     }
+    scale_bias8(acc, a.scale + c, a.bias + c);
     if (a.act == ACT_SILU) {
 #pragma unroll
         for (int e = 0; e < 8; e++) acc[e] = acc[e] / (1.f + __expf(-acc[e]));
@@ -391,14 +395,10 @@ __global__ __launch_bounds__(256) void dwconv_row_bf16_kernel(const PoolArgs* __
     const uint16_t* __restrict__ x = (const uint16_t*)a.x.p + (long long)nu * a.H * a.W * a.x.stride + a.x.c0 + c;
     const uint16_t* __restrict__ w = (const uint16_t*)a.w + c;
     float acc[NW][8];
-    {
-        const float4 b0 = *(const float4*)(a.bias + c), b1 = *(const float4*)(a.bias + c + 4);
 #pragma unroll
-        for (int o = 0; o < NW; o++) {
-            acc[o][0] = b0.x; acc[o][1] = b0.y; acc[o][2] = b0.z; acc[o][3] = b0.w;
-            acc[o][4] = b1.x; acc[o][5] = b1.y; acc[o][6] = b1.z; acc[o][7] = b1.w;
-        }
-    }
+    for (int o = 0; o < NW; o++)
+#pragma unroll
+        for (int e = 0; e < 8; e++) acc[o][e] = 0.f;
     const int wi0 = wo0 * S - a.pl;
 #pragma unroll 1
     for (int kh = 0; kh < K; kh++) {
@@ -437,6 +437,7 @@ __global__ __launch_bounds__(256) void dwconv_row_bf16_kernel(const PoolArgs* __
 #pragma unroll
     for (int o = 0; o < NW; o++) {
         if (wo0 + o >= a.Wo) break;
+        scale_bias8(acc[o], a.scale + c, a.bias + c);
         if (a.act == ACT_SILU) {
 #pragma unroll
             for (int e = 0; e < 8; e++) acc[o][e] = acc[o][e] / (1.f + __expf(-acc[o][e]));
@@ -503,7 +504,7 @@ static hipError_t check_window(const PoolArgs& a, bool bf16) {
 }
 
 hipError_t launch_dwconv(const PoolArgs& a, const PoolArgs* argv, int G, int nb, bool bf16, hipStream_t s) {
-    if (check_window(a, bf16) != hipSuccess || !a.w || !a.bias || nb <= 0 || G <= 0 || !argv) return hipErrorInvalidValue;
+    if (check_window(a, bf16) != hipSuccess || !a.w || !a.bias || !a.scale || nb <= 0 || G <= 0 || !argv) return hipErrorInvalidValue;
     const long long total = (long long)nb * a.Ho * a.Wo * (a.c / (bf16 ? 8 : 1));
     if (total >= (1LL << 31) - 256) return hipErrorInvalidValue;   // 32-bit work item index in the kernel
     const dim3 g(blocks_for(total, 256), 1, G);

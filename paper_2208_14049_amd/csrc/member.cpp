@@ -122,7 +122,7 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         const ens_op& o = spec.ops[i];
         OpPlan pl;
         pl.op = o;
-        pl.w = pl.b = pl.pre_scale = pl.pre_shift = pl.w2 = pl.b2 = pl.w_packed = SIZE_MAX;
+        pl.w = pl.b = pl.scale = pl.pre_scale = pl.pre_shift = pl.w2 = pl.b2 = pl.w_packed = SIZE_MAX;
         pl.cin_s = o.cin;
         pl.scratch = -1;
         pl.alg_k = 0;
@@ -202,6 +202,10 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
                 }
                 std::vector<float> scale(o.cout, 1.f), shift(o.cout, 0.f);
                 if (o.off_bn >= 0) bn_affine(params + o.off_bn, o.cout, &scale, &shift);
+                // bf16 members: the weights stay as given and the kernels multiply the fp32 sum by the scale;
+                // fp32 members: the scale goes into the weights (wscale) and the kernels see ones
+                std::vector<float> wscale(o.cout, 1.f);
+                if (!m.bf16) { wscale = scale; }
                 const float* w = params + o.off_w;               // [kh][kw][cin][cout]
                 std::vector<float> wf;
                 if (i == stem_op) {
@@ -217,7 +221,7 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
                                 const int aw = floor2(kw - o.pl), bw2 = kw - o.pl - 2 * aw;
                                 for (int ci = 0; ci < 3; ci++)
                                     wf[(((size_t)co * kh2 + (ah - ah0)) * kw2 + (aw - aw0)) * 16 + (bh * 2 + bw2) * 3 + ci] =
-                                        w[((size_t)(kh * o.kw + kw) * 3 + ci) * o.cout + co] * scale[co];
+                                        w[((size_t)(kh * o.kw + kw) * 3 + ci) * o.cout + co] * wscale[co];
                             }
                     pl.alg_k = o.kh * o.kw * o.cin;
                     pl.op.kh = kh2; pl.op.kw = kw2; pl.op.sh = 1; pl.op.sw = 1;
@@ -235,7 +239,7 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
                         for (int k = 0; k < o.kh * o.kw; k++)
                             for (int ci = 0; ci < ig; ci++)
                                 wf[((size_t)co * o.kh * o.kw + k) * pl.cin_s + ci0 + ci] =
-                                    w[((size_t)k * ig + ci) * o.cout + co] * scale[co];
+                                    w[((size_t)k * ig + ci) * o.cout + co] * wscale[co];
                     }
                 } else {
                     wf.assign((size_t)o.cout * o.kh * o.kw * pl.cin_s, 0.f);
@@ -243,13 +247,14 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
                         for (int k = 0; k < o.kh * o.kw; k++)
                             for (int ci = 0; ci < o.cin; ci++)
                                 wf[((size_t)co * o.kh * o.kw + k) * pl.cin_s + ci] =
-                                    w[((size_t)k * o.cin + ci) * o.cout + co] * scale[co];
+                                    w[((size_t)k * o.cin + ci) * o.cout + co] * wscale[co];
                 }
                 std::vector<float> bias(o.cout);
                 for (int co = 0; co < o.cout; co++)
                     bias[co] = (o.off_b >= 0 ? params[o.off_b + co] * scale[co] : 0.f) + shift[co];
                 pl.w = bw.put(wf, m.bf16);
                 pl.b = bw.put_f32(bias);
+                pl.scale = bw.put_f32(m.bf16 ? scale : std::vector<float>(o.cout, 1.f));
                 if (o.pre) {
                     std::vector<float> ps, ph;
                     bn_affine(params + o.off_pre, o.cin, &ps, &ph);
@@ -272,11 +277,12 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
                 if (o.off_bn >= 0) bn_affine(params + o.off_bn, o.cout, &scale, &shift);
                 std::vector<float> wf((size_t)nw), bias(o.cout);
                 for (int k = 0; k < o.kh * o.kw; k++)
-                    for (int c = 0; c < o.cin; c++) wf[(size_t)k * o.cin + c] = params[o.off_w + (size_t)k * o.cin + c] * scale[c];
+                    for (int c = 0; c < o.cin; c++) wf[(size_t)k * o.cin + c] = params[o.off_w + (size_t)k * o.cin + c] * (m.bf16 ? 1.f : scale[c]);
                 for (int c = 0; c < o.cout; c++)
                     bias[c] = (o.off_b >= 0 ? params[o.off_b + c] * scale[c] : 0.f) + shift[c];
                 pl.w = bw.put(wf, m.bf16);
                 pl.b = bw.put_f32(bias);
+                pl.scale = bw.put_f32(m.bf16 ? scale : std::vector<float>(o.cout, 1.f));
                 break;
             }
             case ENS_OP_MAXPOOL:
