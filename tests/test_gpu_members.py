@@ -34,15 +34,21 @@ def prepared(nets, seed, n, size):
 
 
 def check(y, y_ref, label):
+    """Probabilities within 2e-2; top-1 agreement >= 99.5 % up to ties inside that tolerance (the GPU's
+    arg-max has an oracle probability within 2e-2 of the oracle's maximum), and strictly: a request of
+    fewer than 200 images may hold one image whose arg-max differs (one of 256 is what the full-size
+    requests of tests/test_gpu_full_size.py show for bf16 members: 99.6 %)."""
     err = float(np.abs(y - y_ref).max())
     a = np.argmax(y, 1)
-    strict = float((a == np.argmax(y_ref, 1)).mean())
+    agree = a == np.argmax(y_ref, 1)
+    strict = float(agree.mean())
     near = float((y_ref[np.arange(len(a)), a] >= y_ref.max(1) - TOL_BF16).mean())
     print("%s: max-abs prob err %.3e, top-1 strict %.4f, in tolerance band %.4f" % (label, err, strict, near))
     assert np.isfinite(y).all()
     np.testing.assert_allclose(y.sum(1), 1.0, atol=1e-4)
     assert err <= TOL_BF16, (label, err)
     assert near >= TOP1, (label, near)
+    assert strict >= TOP1 or int((~agree).sum()) <= 1, (label, strict)
     return err, strict
 
 

@@ -525,7 +525,7 @@ def test_config2_resnet18_ensemble_bf16(ens, config2):
     assert err <= TOL_BF16
     # Several arg-maxes are correct when the oracle's top classes lie closer together than the
     # probability tolerance: agreement is counted up to such ties; the strict rate is reported.
-    assert near >= TOP1 and strict >= 0.95
+    assert near >= TOP1 and (strict >= TOP1 or int(round((1.0 - strict) * len(y))) <= 1)    # at most one of the 64 images
     for m in range(3):
         z = E.ens_member_logits(m, 8)
         rel = np.abs(z - z_ref[m]).max() / z_ref[m].std()
