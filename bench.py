@@ -2,31 +2,40 @@
 
 A step is one pass of the whole hot path (input staging, every member's forward pass on its
 worker streams, fused softmax-and-mean) over one request of n synthetic images resident in HBM.
-Prints one JSON line: images per second, the roofline figures of the dominant kernel (measured
-with HIP events on the worker streams) and the CPU oracle's rate on the host cores.
+The headline workload is the heavy 12-member ensemble (the largest of the workload configurations
+that one GPU holds); the other bf16 configurations are measured in the same run as sub-records.
+Prints one JSON line: images per second (whole K steps), median and relative standard deviation of
+the single steps, the rate with the images coming from pinned host memory, the roofline figures of
+the dominant kernel (durations from HIP events attached to the dispatches on the worker streams),
+per-kernel-class rates, and the CPU oracle's rate on the host cores.
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-os.environ.setdefault("GPU_MAX_HW_QUEUES", "8")   # one hardware queue per worker stream (before HIP starts)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised
-# in profiles/bench_resnet18x3_b32.md (scaled by the plain-copy calibration given there).  They
-# describe the kernel sources with the digest below; with any other sources the figure is withheld.
-TRAFFIC = {
-    "kernel": "conv3x3_halo_bf16<128,64,c64>",
-    "bytes_per_launch": 80.4e6,
-    "sources": ("conv_halo.hip", "conv_common.h", "kernels.h"),
-    "sha256": "4c78a285f36902f3fcec5f9b15c63a10e0b3cac99aba0bd07050e84f26cebdf5",
+WORKLOADS = {
+    2: "3 x ResNet-18-shaped ensemble",
+    3: "heterogeneous 4-member ensemble: ResNet-50 (224), Inception-v3-shaped (299, resized in the library), "
+       "EfficientNet-B0-shaped, DenseNet-121-shaped",
+    4: "heavy 12-member ensemble co-located on one GPU: ResNet-50/101/152, EfficientNet-B0/B2/B4-shaped, "
+       "DenseNet-121/169/201, 3 x Inception-v3-shaped",
+    5: "single ResNet-50 served by data-parallel instances",
 }
+CPU_SAMPLE = {2: 16, 3: 16, 4: 12, 5: 16}      # images the oracle is timed on (about 10-30 s of CPU work)
+
+# HBM bytes per launch of a kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
+# profiles/ (scaled by the plain-copy calibration given there).  An entry describes the kernel sources
+# with the digest recorded with it; with any other sources the figure is withheld (null).
+TRAFFIC = {}
 
 
 def sources_digest(names):
@@ -38,63 +47,63 @@ def sources_digest(names):
     return h.hexdigest()
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--images", type=int, default=1024)
-    ap.add_argument("--batch", type=int, default=32)
-    ap.add_argument("--instances", type=int, default=2, help="workers per member (rows of the allocation matrix)")
-    ap.add_argument("--cpu-sample", type=int, default=16, help="images the CPU oracle is timed on (0 = skip)")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run one plain 256 MiB device copy (reference for the HBM byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py measures one GPU: the path uses no second device (run with --gpus 1)")
+def is_conv(name):
+    return name.startswith(("conv", "bottleneck", "dense_layer", "stem"))
 
-    import numpy as np
+
+def measure(ens, cfg, n, steps, warmup, profile_steps, host_steps, matrix=None, segment=None):
+    """Loads configuration `cfg`, installs its kept allocation and times `steps` requests of n images."""
     import torch
-    import paper_2208_14049_amd as ens
     import synth
     from synth import nets as N, weights as W
-    assert torch.cuda.is_available(), "bench.py needs the GPU"
-    ens.lib()
-
-    nets = N.config_members(2)                                  # 3 x ResNet-18-shaped, bf16
-    blobs = [W.quantise_weights_bf16(n, W.make_blob(n, synth.BASE_SEED, i)) for i, n in enumerate(nets)]
+    nets = N.config_members(cfg)
+    blobs = [W.quantise_weights_bf16(net, W.make_blob(net, synth.BASE_SEED, i)) for i, net in enumerate(nets)]
+    with open(os.path.join(ROOT, "paper_2208_14049_amd", "allocations.json")) as f:
+        kept = json.load(f)[str(cfg)]
+    matrix = matrix or kept["matrix"]
+    segment = segment or kept["segment"]
     E = ens.Ensemble(nets, blobs)
-    alloc = [[args.batch] * len(nets) for _ in range(args.instances)]
-    E.ens_set_alloc(alloc)
-    n = args.images
+    E.ens_set_alloc(matrix, segment)
     g = torch.Generator(device="cuda").manual_seed(synth.BASE_SEED + 1000)
     images = torch.randn((n, 224, 224, 3), generator=g, device="cuda", dtype=torch.float32)
     out = torch.empty((n, E.classes), device="cuda", dtype=torch.float32)
     torch.cuda.synchronize()
-
-    if args.copy_calibration:
-        src = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
-        dst = torch.empty_like(src)
-        dst.copy_(src)                                          # reads 256 MiB, writes 256 MiB
-        torch.cuda.synchronize()
-        del src, dst
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         E.ens_predict(images, out)
     torch.cuda.synchronize()
+    per_step = []
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
+        t1 = time.perf_counter()
         E.ens_predict(images, out)                              # synchronous: returns when Y is complete
+        per_step.append(time.perf_counter() - t1)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-    value = n * args.steps / dt
+    rec = dict(workload=WORKLOADS[cfg], members=[net.name for net in nets], request_images=n, allocation=matrix,
+               segment_size=segment, allocation_source=kept["source"],
+               value=round(n * steps / dt, 1), ms_per_step=round(dt / steps * 1e3, 3),
+               median_ms_per_step=round(statistics.median(per_step) * 1e3, 3),
+               rsd_percent=round(100.0 * statistics.pstdev(per_step) / statistics.mean(per_step), 2) if steps > 1 else None)
 
-    # per-kernel durations: same launches, each bracketed by HIP events on its worker stream
+    # images in pinned host memory, probabilities returned to host memory (PCIe-inclusive; never `value`)
+    if host_steps > 0:
+        h_img = torch.empty(images.shape, dtype=torch.float32, pin_memory=True)
+        h_img.copy_(images)
+        h_out = torch.empty(out.shape, dtype=torch.float32, pin_memory=True)
+        E.ens_predict(h_img, h_out)
+        ts = []
+        for _ in range(host_steps):
+            t1 = time.perf_counter()
+            E.ens_predict(h_img, h_out)
+            ts.append(time.perf_counter() - t1)
+        rec["host_input_images_per_s"] = round(n / statistics.median(ts), 1)
+        del h_img, h_out
+
+    # per-kernel durations: the same launches, each with HIP events attached to its dispatch
     E.ens_set_profiling(1)
     prof = {}
-    psteps = max(1, min(3, args.steps))
     tp0 = time.perf_counter()
-    for _ in range(psteps):
+    for _ in range(profile_steps):
         E.ens_predict(images, out)
         for c in E.ens_profile():
             if not c["launches"]:
@@ -103,64 +112,118 @@ def main():
             for k in ("ms", "launches", "flop", "bytes"):
                 p[k] += c[k]
     E.ens_set_profiling(0)
-    profiled_ms_per_step = (time.perf_counter() - tp0) / psteps * 1e3
+    rec["profiled_ms_per_step"] = round((time.perf_counter() - tp0) / max(1, profile_steps) * 1e3, 3)
+    total_ms = sum(v["ms"] for v in prof.values()) or 1.0
+    conv_ms = sum(v["ms"] for k, v in prof.items() if is_conv(k)) or 1.0
+    conv_flop = sum(v["flop"] for k, v in prof.items() if is_conv(k))
+    rec["kernels"] = {
+        k: dict(ms_per_step=round(v["ms"] / profile_steps, 4), launches=v["launches"] // profile_steps,
+                share_of_kernel_time=round(v["ms"] / total_ms, 4),
+                tflops=round(v["flop"] / max(v["ms"], 1e-9) / 1e9, 2),
+                mfma_frac=round(v["flop"] / max(v["ms"], 1e-9) / 1e9 / PEAK_BF16_TFLOPS, 4) if is_conv(k) else None,
+                gbs=round(v["bytes"] / max(v["ms"], 1e-9) / 1e6, 1),
+                hbm_frac=round(v["bytes"] / max(v["ms"], 1e-9) / 1e6 / PEAK_HBM_GBS, 4))
+        for k, v in sorted(prof.items(), key=lambda kv: -kv[1]["ms"])}
+    # all convolution launches together, on the sum of their own durations, and on the step's wall time
+    rec["conv_mfma_frac_of_kernel_time"] = round(conv_flop / (conv_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)
+    rec["conv_mfma_frac_of_step"] = round(conv_flop / profile_steps / (dt / steps) / 1e12 / PEAK_BF16_TFLOPS, 4)
     dom_name, dom = max(prof.items(), key=lambda kv: kv[1]["ms"])
-    achieved = dom["flop"] / (dom["ms"] * 1e-3) / 1e12 if dom["ms"] > 0 else 0.0
+    if is_conv(dom_name):
+        achieved = dom["flop"] / (dom["ms"] * 1e-3) / 1e12
+        roof = dict(bound="mfma", kernel=dom_name, achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=round(achieved / PEAK_BF16_TFLOPS, 4))
+    else:
+        achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
+        roof = dict(bound="hbm", kernel=dom_name, achieved=round(achieved, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                    frac=round(achieved / PEAK_HBM_GBS, 4))
     traffic = None
-    if dom_name == TRAFFIC["kernel"] and sources_digest(TRAFFIC["sources"]) == TRAFFIC["sha256"]:
-        traffic = TRAFFIC["bytes_per_launch"]
-    # The worker rows run on separate streams: with more than one row two launches share the GPU
-    # and each takes longer than it would alone.  The same kernel timed with one row (its launches
-    # alone on the GPU) is reported next to it.
-    one_row = None
-    if args.instances > 1:
-        E.ens_set_alloc([[args.batch] * len(nets)])
-        E.ens_predict(images, out)
-        t1 = time.perf_counter()
-        E.ens_predict(images, out)
-        dt1 = time.perf_counter() - t1
-        E.ens_set_profiling(1)
-        E.ens_predict(images, out)
-        for c in E.ens_profile():
-            if c["name"] == dom_name and c["ms"] > 0:
-                a1 = c["flop"] / (c["ms"] * 1e-3) / 1e12
-                one_row = dict(achieved=round(a1, 2), frac=round(a1 / PEAK_BF16_TFLOPS, 4),
-                               avg_launch_us=round(c["ms"] * 1e3 / max(1, c["launches"]), 2),
-                               images_per_s=round(n / dt1, 1))
-        E.ens_set_profiling(0)
-    roofline = dict(bound="mfma", kernel=dom_name, achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS,
-                    unit="TFLOP/s", frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=traffic,
-                    flop_per_launch=round(dom["flop"] / max(1, dom["launches"]), 0),
-                    bytes_per_launch=round(dom["bytes"] / max(1, dom["launches"]), 0),
-                    avg_launch_us=round(dom["ms"] * 1e3 / max(1, dom["launches"]), 2), one_row=one_row,
-                    launches_per_step=dom["launches"] // psteps, profiled_ms_per_step=round(profiled_ms_per_step, 3),
-                    kernels={k: dict(ms_per_step=round(v["ms"] / psteps, 4), launches=v["launches"] // psteps,
-                                     tflops=round(v["flop"] / max(v["ms"], 1e-9) / 1e9, 2),
-                                     gbs=round(v["bytes"] / max(v["ms"], 1e-9) / 1e6, 1)) for k, v in prof.items()})
+    t = TRAFFIC.get((cfg, dom_name))
+    if t and sources_digest(t["sources"]) == t["sha256"]:
+        traffic = t["bytes_per_launch"]
+    roof.update(traffic=traffic, flop_per_launch=round(dom["flop"] / max(1, dom["launches"]), 0),
+                bytes_per_launch=round(dom["bytes"] / max(1, dom["launches"]), 0),
+                avg_launch_us=round(dom["ms"] * 1e3 / max(1, dom["launches"]), 2),
+                launches_per_step=dom["launches"] // profile_steps,
+                share_of_kernel_time=round(dom["ms"] / total_ms, 4))
+    rec["roofline"] = roof
+    E.close()
+    del images, out
+    torch.cuda.empty_cache()
+    return rec, nets, blobs
 
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--images", type=int, default=1024)
+    ap.add_argument("--config", type=int, default=4, choices=sorted(WORKLOADS), help="headline workload configuration")
+    ap.add_argument("--others", default="2,3,5", help="configurations measured as sub-records ('' = none)")
+    ap.add_argument("--cpu-sample", type=int, default=-1, help="images the CPU oracle is timed on (0 = skip, -1 = the configuration's default)")
+    ap.add_argument("--host-steps", type=int, default=3, help="extra steps with the images in pinned host memory (0 = skip)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference for the HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: the path uses no second device (run with --gpus 1)")
+
+    import torch
+    import paper_2208_14049_amd as ens
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    ens.lib()
+    if args.copy_calibration:
+        src = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                                          # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
+
+    psteps = max(1, min(3, args.steps))
+    main_rec, nets, blobs = measure(ens, args.config, args.images, args.steps, args.warmup, psteps, args.host_steps)
     cpu = None
-    if args.cpu_sample > 0:
+    ns = CPU_SAMPLE[args.config] if args.cpu_sample < 0 else args.cpu_sample
+    if ns > 0:
         import oracle
-        ns = args.cpu_sample
-        x = images[:ns].cpu().numpy()
-        oracle.forward_logits(nets[0], blobs[0], x[:1])          # loads the oracle library
+        import synth
+        from synth import weights as W
+        x = W.make_images(synth.BASE_SEED + 1000, ns, 224, 224)
+        oracle.forward_logits(nets[0], blobs[0], oracle.resize_bilinear(x[:1], nets[0].in_h, nets[0].in_w))   # loads the oracle library
         t0 = time.perf_counter()
         oracle.ensemble_predict(nets, blobs, x, real="f32")
         cdt = time.perf_counter() - t0
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
         cpu = dict(value=round(ns / cdt, 3), unit="images/s", cores=cores, kind="oracle",
-                   sample="%d of the %d request images through all %d members" % (ns, n, len(nets)))
-    E.close()
+                   sample="%d images of the request's distribution through all %d members" % (ns, len(nets)))
+    del nets, blobs
+    others = {}
+    for c in [int(v) for v in args.others.split(",") if v.strip()]:
+        if c == args.config:
+            continue
+        rec, _, _ = measure(ens, c, args.images, max(3, args.steps // 2), 1, 2, 2 if args.host_steps else 0)
+        others[str(c)] = rec
 
-    print(json.dumps({
-        "metric": "ensemble images/sec on 1 MI355X", "value": round(value, 1), "unit": "images/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+    roofline = main_rec.pop("roofline")
+    line = {
+        "metric": "ensemble images/sec on 1 MI355X", "value": main_rec.pop("value"), "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_rec.pop("ms_per_step"),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "3 x ResNet-18-shaped ensemble, 1000 classes, 224x224x3 N(0,1) images, "
-                               "batch %d per member, mean of softmax" % args.batch,
-                   "request_images": n, "allocation": alloc, "input": "fp32 NHWC resident in HBM"},
+        "config": {"workload": "config %d: %s; bf16, 1000 classes, 224x224x3 N(0,1) images, mean of softmax"
+                               % (args.config, main_rec.pop("workload")),
+                   "request_images": main_rec.pop("request_images"), "allocation": main_rec.pop("allocation"),
+                   "segment_size": main_rec.pop("segment_size"), "allocation_source": main_rec.pop("allocation_source"),
+                   "members": main_rec.pop("members"), "input": "fp32 NHWC resident in HBM",
+                   "gpu_max_hw_queues": os.environ.get("GPU_MAX_HW_QUEUES", "unset (HIP default: 4)")},
+        "median_ms_per_step": main_rec.pop("median_ms_per_step"), "rsd_percent": main_rec.pop("rsd_percent"),
+        "host_input_images_per_s": main_rec.pop("host_input_images_per_s", None),
         "roofline": roofline, "cpu_baseline": cpu,
-    }))
+        "conv_mfma_frac_of_kernel_time": main_rec.pop("conv_mfma_frac_of_kernel_time"),
+        "conv_mfma_frac_of_step": main_rec.pop("conv_mfma_frac_of_step"),
+        "profiled_ms_per_step": main_rec.pop("profiled_ms_per_step"),
+        "kernels": main_rec.pop("kernels"),
+        "other_configs": others,
+    }
+    print(json.dumps(line))
 
 
 if __name__ == "__main__":

@@ -7,12 +7,7 @@ It fails loudly when the library has not been built: there is no CPU fallback.
 import ctypes
 import os
 
-# Co-located workers run on their own HIP streams; the runtime maps streams onto hardware queues
-# and its default of 4 queues makes worker streams share one.  Takes effect when set before the
-# first HIP call of the process.
-os.environ.setdefault("GPU_MAX_HW_QUEUES", "8")
-
-import numpy as np  # noqa: E402
+import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libens_mi355x.so")
