@@ -423,6 +423,8 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
                 (i > 1 && m.ops[i - 2].fuse_chain) || m.ops[i + 1].fuse_chain)
                 continue;
             m.ops[i].fuse_dense = true;
+            // the one kernel writes the second output while it still reads the first input
+            m.tensors[q.dst].def = std::min(m.tensors[q.dst].def, i);
             pack_operand_order(m.ops[i]);
             pack_operand_order(m.ops[i + 1]);
         }

@@ -207,6 +207,10 @@ def test_conv_layer_bf16(ens, case, nb):
     src = net.ops[-3]["src"]
     if src != 0:
         x_in = E.ens_debug_tensor(0, src, net.tensors[src], nb)
+        # that tensor itself (the 1x1 lift of the image to cin channels) against the oracle's from the image
+        x_ref = oracle_tensor(net, blobs[0], imgs, src)
+        x_scale = np.sqrt(np.mean(x_ref ** 2))
+        assert x_scale > 0.1 and (np.abs(x_in - x_ref) <= 2.0 ** -7 * np.abs(x_ref) + x_scale * 2.0 ** -5 + 1e-6).all()
         sub = N.Net("sub", h, w, 8, dtype="bf16", in_c=cin)
         sub.ops, sub.params, sub.blob_size = [dict(net.ops[-3])], net.params, net.blob_size
         sub.tensors = [net.tensors[src], net.tensors[t]]

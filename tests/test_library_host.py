@@ -246,6 +246,22 @@ def test_dense_block_layers_in_descriptions():
     assert fused - plain == up(2 * 128 * 128) + up(2 * 9 * 128 * 32), fused - plain
 
 
+def test_dense_layer_output_does_not_share_memory_with_its_input():
+    """A pre-activated 1x1 (to 128 channels) followed by a 3x3 (to 32) may run as one kernel that writes the
+    3x3's output while other workgroups still read the 1x1's input: when the output is a tensor of its own it
+    must not be placed over that input, although the input's last reader is the first of the two operations."""
+    n = N.Net("dl", 16, 16, 8, dtype="bf16")
+    a = n.conv(0, 64, 3)
+    u = n.conv(a, 128, 1, pre=True)
+    c = n.conv(u, 32, 3, bn=False, act=None, bias=False)
+    n.fc(n.gap(c), 8)
+    batch = 4
+    _, arena = ens.ens_spec_bytes(n, batch)
+    px = batch * 16 * 16 * 2
+    workspace = 16 << 20                                         # split-K workspace appended to a bf16 worker's arena
+    assert arena - workspace >= px * (64 + 128 + 32)             # input, middle and output alive together
+
+
 def test_bottleneck_chains_in_descriptions():
     """The plan keeps a second copy, in matrix-core operand order (rows padded to 32, columns to 64), of
     the weights of layers that kernels fetch straight from memory: every 1x1 stride-1 convolution
