@@ -270,7 +270,6 @@ constexpr int DENSE_LDS_LIMIT = 160 * 1024;
 constexpr int DENSE_MIN_TILES = 1;   // measured on a DenseNet-121-shaped member: the one kernel is faster at every batch size, 1 to 128
 
 struct DensePlan { int bp, rows; size_t bytes; int tiles; };
-constexpr int DENSE_CUS = 256;
 
 static bool dense_plan(const ConvArgs& a1, const ConvArgs& a2, int nb, int G, DensePlan* pl) {
     if (a1.kh != 1 || a1.kw != 1 || a1.sh != 1 || a1.sw != 1 || a1.pt != 0 || a1.pl != 0 || a1.Ho != a1.H || a1.Wo != a1.W) return false;
@@ -292,8 +291,8 @@ static bool dense_plan(const ConvArgs& a1, const ConvArgs& a2, int nb, int G, De
     // and the window of the smaller tile fits the next smaller number of rows
     const int reach = 2 * (a1.W + 1) + 2;
     pl->bp = 128;
-    if (G * ((PP + 127) / 128) < DENSE_CUS && 64 + reach <= 128) pl->bp = 64;
-    if (G * ((PP + 63) / 64) < DENSE_CUS && 32 + reach <= 64) pl->bp = 32;
+    if (G * ((PP + 127) / 128) < cu_budget() && 64 + reach <= 128) pl->bp = 64;
+    if (G * ((PP + 63) / 64) < cu_budget() && 32 + reach <= 64) pl->bp = 32;
     const int need = pl->bp + reach;
     pl->rows = pl->bp == 32 ? 64 : pl->bp == 64 ? 128 : need <= 192 ? 192 : 256;
     if (need > pl->rows) return false;

@@ -247,7 +247,6 @@ static const HaloVariant HALO_VARIANTS[] = {
 constexpr int N_HALO_VARIANTS = sizeof(HALO_VARIANTS) / sizeof(HALO_VARIANTS[0]);
 constexpr int LDS_LIMIT = 160 * 1024;
 
-constexpr int HALO_CUS = 256;
 
 // Splits of the channel blocks for launches with fewer output tiles than compute units: as many
 // as give about two workgroups per compute unit, each with at least two channel blocks, within
@@ -258,8 +257,8 @@ static int halo_splits(const ConvArgs& a, const HaloVariant& v, int nb, int G) {
     const long long PP = (long long)nb * (a.H + 1) * (a.W + 1), P = (long long)nb * a.H * a.W;
     const long long tiles = G * ((PP + v.bp - 1) / v.bp) * ((a.cout + v.bc - 1) / v.bc);
     const int ncb = a.cin / v.cb;
-    if (tiles >= HALO_CUS || ncb < 4) return 1;
-    long long s = (2 * HALO_CUS + tiles - 1) / tiles;
+    if (tiles >= cu_budget() || ncb < 4) return 1;
+    long long s = (2 * cu_budget() + tiles - 1) / tiles;
     s = s < ncb / 2 ? s : ncb / 2;
     if (s > 8) s = 8;
     while (s > 1 && s * P * a.cout > a.ws_floats) s--;
@@ -304,8 +303,8 @@ int conv_halo_pick(const ConvArgs& a, int nb, int G) {
     if (a.cin % 64 == 0) {
         const long long PP = (long long)nb * (a.H + 1) * (a.W + 1);
         const long long tiles = G * ((PP + 127) / 128) * ((a.cout + 63) / 64);
-        choice = a.cin > 64 && tiles > 2 * HALO_CUS ? 6 : 0;
-        if (a.cout <= 32 && tiles > 2 * HALO_CUS) choice = a.cin > 64 ? 12 : 13;   // narrow outputs (dense-block growth layers)
+        choice = a.cin > 64 && tiles > 2 * cu_budget() ? 6 : 0;
+        if (a.cout <= 32 && tiles > 2 * cu_budget()) choice = a.cin > 64 ? 12 : 13;   // narrow outputs (dense-block growth layers)
     } else if (a.cin >= 96) {
         choice = 4;                                              // multiples of 32 only: 32-channel blocks
     }

@@ -417,7 +417,6 @@ static const Variant VARIANTS[] = {
     {128, 64, 64, "conv_igemm_bf16<128,64,k64>"},    // grids that fill the chip, deep K
     {128, 64, 32, "conv_igemm_bf16<128,64,k32>"},    // grids that fill the chip, shallow K
 };
-constexpr int CUS = 256;
 
 // A gang of G members multiplies the grid by G.  When 128x64 tiles still give two workgroups per
 // compute unit they are taken (a third less L2-to-LDS traffic per flop than 64x64); otherwise
@@ -425,7 +424,7 @@ constexpr int CUS = 256;
 static int pick_variant(const ConvArgs& a, long long P, long long K, int G) {
     if (a.cout <= 32) return 0;
     const long long t12864 = G * ((P + 127) / 128) * ((a.cout + 63) / 64);
-    if (t12864 >= 2 * CUS) return K <= 640 ? 4 : 3;
+    if (t12864 >= 2 * cu_budget()) return K <= 640 ? 4 : 3;
     return K <= 256 ? 2 : 1;
 }
 
@@ -436,8 +435,8 @@ static int pick_splits(const ConvArgs& a, long long P, long long K, int variant,
     const Variant& v = VARIANTS[variant];
     const long long tiles = G * ((P + v.bp - 1) / v.bp) * ((a.cout + v.bc - 1) / v.bc);
     const long long nk = (K + v.bk - 1) / v.bk;
-    if (tiles >= 2 * CUS || nk < 8) return 1;
-    long long s = (3 * CUS + tiles - 1) / tiles;
+    if (tiles >= 2 * cu_budget() || nk < 8) return 1;
+    long long s = (3 * cu_budget() + tiles - 1) / tiles;
     s = s < nk / 4 ? s : nk / 4;
     if (s > 16) s = 16;
     while (s > 1 && s * P * a.cout > a.ws_floats) s--;

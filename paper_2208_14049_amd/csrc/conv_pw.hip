@@ -223,7 +223,7 @@ static hipError_t launch_pw_variant(const ConvArgs& a, const ConvArgs* argv, int
 // 128: with 196 tiles or fewer the 128 x 64 tile is faster or equal, with 392 or more the larger one)
 static int pw_wpx(const ConvArgs& a, int nb, int G) {
     const long long tiles = (((long long)nb * a.H * a.W + PW_BP - 1) / PW_BP) * ((a.cout + 127) / 128) * G;
-    int wpx = a.cout <= 64 || tiles < 256 ? 2 : 1;
+    int wpx = a.cout <= 64 || tiles < cu_budget() ? 2 : 1;
     return wpx;
 }
 

@@ -150,12 +150,13 @@ static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G
             FcArgs& a = L.fc;
             a.x = (const float*)(w.arena + w.layout.offset[o.src]);
             a.w = P + pl.w;
+            a.wpk = pl.w_packed != SIZE_MAX ? P + pl.w_packed : nullptr;
             a.bias = (const float*)(P + pl.b);
             a.y = h->d_logits[w.member];                         // rows of the whole request
             a.nb = w.batch; a.cin = o.cin; a.cout = o.cout; a.ldy = o.cout;
             L.flop = 2.0 * nb * o.cin * o.cout;
             L.bytes = (double)o.cin * o.cout * es + nb * (o.cin + o.cout) * 4.0;
-            L.klass = prof_class(h, "fc_kernel");
+            L.klass = prof_class(h, m.bf16 && fc_mfma_applicable(a) ? "fc_mfma_bf16" : "fc_kernel");
             break;
         }
         case ENS_OP_SE: {
@@ -394,6 +395,12 @@ static int64_t alloc_bytes(const ens_handle* h, const ens_alloc& a) {
     return total;
 }
 
+// The worker streams of an allocation run at once: each launch counts on its share of the chip.
+static int stream_share(const ens_handle* h) {
+    const int streams = (int)std::max<size_t>(1, h->gangs.size());
+    return std::max(32, 256 / streams);
+}
+
 static int install_alloc(ens_handle* h, const ens_alloc& a, int segment_size) {
     const int M = (int)h->members.size();
     if (a.rows <= 0 || a.rows > ENS_MAX_SLOTS || a.cols != M) return ENS_E_INVALID;
@@ -462,6 +469,7 @@ static int install_alloc(ens_handle* h, const ens_alloc& a, int segment_size) {
         const int rc0 = ensure_buffers(h, 1);
         if (rc0 != ENS_OK) { destroy_workers(h); return rc0; }
     }
+    cu_budget() = stream_share(h);
     for (Gang& g : h->gangs) {
         hipError_t e = hipStreamCreateWithFlags(&g.stream, hipStreamNonBlocking);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&g.done, hipEventDisableTiming);
@@ -616,6 +624,7 @@ static int grow(float** p, size_t* cap, size_t want_floats) {
 // nothing on the way may allocate or free device memory.
 static int run_device(ens_handle* h, const float* d_images, int64_t n, float* d_probs, uint64_t mask, bool may_alloc = true) {
     if (n == 0) return ENS_OK;
+    cu_budget() = stream_share(h);
     int rc = may_alloc ? ensure_buffers(h, n) : ENS_OK;
     if (rc != ENS_OK) return rc;
     if ((size_t)n > h->d_logits_rows) return ENS_E_INVALID;

@@ -68,6 +68,7 @@ struct GapArgs {               // global average pool to fp32 [nb][c]
 struct FcArgs {                // logits[n][cout] = pooled[n][cin] . W[cin][cout] + bias
     const float* x;
     const void* w;             // [cin][cout] in the member's dtype
+    const void* wpk;           // bf16 members: the transposed weights [cout][cin] in matrix-core operand order, or null
     const float* bias;
     float* y;                  // logits of the whole request, row stride ldy
     int nb, cin, cout;
@@ -107,6 +108,9 @@ hipError_t launch_dwconv(const PoolArgs& a, const PoolArgs* argv, int G, int nb,
 hipError_t launch_pool(const PoolArgs& a, const PoolArgs* argv, int G, int nb, bool is_max, bool bf16, hipStream_t s);
 hipError_t launch_gap(const GapArgs& a, const GapArgs* argv, int G, int nb, bool bf16, hipStream_t s);
 hipError_t launch_fc(const FcArgs& a, const FcArgs* argv, int G, int nb, long long first, bool bf16, hipStream_t s);
+// the FC head on the matrix cores (bf16 members with a packed weight copy); launch_fc takes it when it applies
+bool fc_mfma_applicable(const FcArgs& a);
+hipError_t launch_fc_mfma(const FcArgs& a, const FcArgs* argv, int G, int nb, long long first, hipStream_t s);
 hipError_t launch_se(const SeArgs& a, const SeArgs* argv, int G, int nb, bool bf16, hipStream_t s);
 hipError_t launch_stage(const StageArgs& a, const StageArgs* argv, int G, int nb, long long first, bool bf16, hipStream_t s);
 // Combination rule; logits: n_members pointers (device array).
@@ -130,6 +134,12 @@ struct LaunchEvents {
     hipEvent_t start = nullptr, stop = nullptr;
 };
 LaunchEvents& next_launch_events();                  // per thread
+
+// Compute units a launch may count on: all 256 when its stream has the GPU to itself, a share of them
+// when several worker streams run at once.  The launchers' tile and split choices weigh idle compute
+// units against efficiency per workgroup by this number; the engine sets it (per thread) to the chip's
+// units divided by the number of streams of the installed allocation.
+int& cu_budget();
 
 }  // namespace ens
 

@@ -47,6 +47,11 @@ __device__ __forceinline__ uint4 pack8(const float* f) {
     return make_uint4(u[0], u[1], u[2], u[3]);
 }
 
+int& cu_budget() {
+    static thread_local int units = 256;
+    return units;
+}
+
 LaunchEvents& next_launch_events() {
     static thread_local LaunchEvents ev;
     return ev;
@@ -672,6 +677,7 @@ __global__ __launch_bounds__(FC_WAVES * 64) void fc_kernel(const FcArgs* __restr
 
 hipError_t launch_fc(const FcArgs& a, const FcArgs* argv, int G, int nb, long long first, bool bf16, hipStream_t s) {
     if (nb <= 0 || a.cin <= 0 || a.cout <= 0 || !a.bias || !a.y || G <= 0 || !argv) return hipErrorInvalidValue;
+    if (bf16 && fc_mfma_applicable(a)) return launch_fc_mfma(a, argv, G, nb, first, s);
     const dim3 g((a.cout + 63) / 64, (nb + FC_IMGS - 1) / FC_IMGS, G), b(FC_WAVES * 64);
     if (bf16) ENS_LAUNCH(fc_kernel<true>, g, b, 0, s, argv, nb, first);
     else ENS_LAUNCH(fc_kernel<false>, g, b, 0, s, argv, nb, first);

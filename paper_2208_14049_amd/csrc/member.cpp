@@ -310,6 +310,24 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
                 std::vector<float> bias(params + o.off_b, params + o.off_b + o.cout);
                 pl.w = bw.put(wf, m.bf16);
                 pl.b = bw.put_f32(bias);
+                if (m.bf16 && o.cin % 8 == 0) {
+                    // A second copy, transposed to [cout][cin] and in matrix-core operand order (see
+                    // pack_operand_order below: blocks of 32 rows, steps of 16 columns, a lane's 8 values in a
+                    // row), for the FC kernel that runs on the matrix cores.
+                    const int rows = o.cout, K = o.cin;
+                    const int rows_p = (rows + 31) / 32 * 32, K_p = (K + 63) / 64 * 64, NS = K_p / 16;
+                    std::vector<float> wt((size_t)rows_p * K_p, 0.f);
+                    for (int rb = 0; rb < rows_p / 32; rb++)
+                        for (int st = 0; st < NS; st++)
+                            for (int lane = 0; lane < 64; lane++) {
+                                const int r = lane & 31, hh = lane >> 5;
+                                const int row = 32 * rb + ((r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1)), col = 16 * st + 8 * hh;
+                                if (row >= rows) continue;
+                                for (int e = 0; e < 8 && col + e < K; e++)
+                                    wt[(((size_t)rb * NS + st) * 64 + lane) * 8 + e] = wf[(size_t)(col + e) * o.cout + row];
+                            }
+                    pl.w_packed = bw.put(wt, true);
+                }
                 break;
             }
             case ENS_OP_SE: {

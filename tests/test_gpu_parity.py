@@ -485,6 +485,48 @@ def test_squeeze_excite_shapes(ens, dtype, h, c, r, nb):
     assert np.abs(got - ref).max() <= tol * (scale + np.abs(ref).max()) * (4 if bf else 1), (np.abs(got - ref).max(), scale)
 
 
+@pytest.mark.parametrize("F,classes,nb,G", [(2048, 1000, 128, 1), (1280, 1000, 37, 1), (1408, 1000, 64, 1), (512, 200, 96, 2), (72, 24, 5, 1)],
+                         ids=["2048-1000_n128", "1280-1000_n37", "1408-1000_n64", "512-200_n96_gang2", "72-24_n5"])
+def test_fc_head_on_matrix_cores(ens, F, classes, nb, G):
+    """The FC head of a bf16 member (fp32 pooled features split into two bf16 parts, bf16 weights, matrix
+    cores): the pooled features the GPU computed are read back and fed to the oracle's FC, so that only
+    this layer is compared.  Shapes: four image blocks and a ragged one, a K range that is no multiple of
+    64 (1408 = 88 steps of 16), a last class block with 8 of 32 classes (200, 1000), two members in one
+    launch, a head smaller than one block.  The error left is the 2^-17 of each feature that two bf16
+    parts do not hold and the order of the fp32 sums."""
+    nets = []
+    for g in range(G):
+        n = N.Net("fc%d" % g, 4, 4, classes, dtype="bf16")
+        t = n.conv(0, F, 1)
+        n.fc(n.gap(t), classes)
+        nets.append(n)
+    blobs = [W.quantise_weights_bf16(n, W.make_blob(n, 81, i)) for i, n in enumerate(nets)]
+    imgs = W.round_bf16(W.make_images(82, nb, 4, 4))
+    E = ens.Ensemble(nets, blobs)
+    E.set_base_size(4, 4)
+    E.ens_debug_keep_tensors()
+    E.ens_set_alloc([[nb] * G])
+    E.ens_set_profiling(1)
+    E.ens_predict(imgs)
+    ran = {k["name"]: k["launches"] for k in E.ens_profile() if k["launches"]}
+    assert ran.get("fc_mfma_bf16") == 1 and "fc_kernel" not in ran, ran
+    for g in range(G):
+        net = nets[g]
+        pooled = net.ops[-1]["src"]
+        x = E.ens_debug_tensor(g, pooled, net.tensors[pooled], nb)          # nb x 1 x 1 x F fp32, as the FC kernel read it
+        z = E.ens_member_logits(g, nb)
+        sub = N.Net("sub", 1, 1, classes, dtype="bf16", in_c=F)
+        sub.ops, sub.params, sub.blob_size = [dict(net.ops[-1])], net.params, net.blob_size
+        sub.tensors = [net.tensors[pooled], net.tensors[net.out_tensor]]
+        sub.ops[0].update(src=0, dst=1)
+        sub.out_tensor = 1
+        ref = oracle.forward_logits(sub, blobs[g], x, real="f64")
+        assert np.abs(x).max() > 0.1 and ref.std() > 0.05
+        bound = 1e-4 * (np.abs(ref) + ref.std())
+        assert (np.abs(z - ref) <= bound).all(), (g, float((np.abs(z - ref) / bound).max()))
+    E.close()
+
+
 def test_resize_staging(ens):
     """A member at 45 x 45 fed from 32 x 32 requests: bilinear resize inside the library."""
     for dtype in ("fp32", "bf16"):
