@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libens_mi355x.so")
-SOURCES = ["conv_mfma.hip", "conv_halo.hip", "conv_taps.hip", "conv_wreg.hip", "conv_bneck.hip", "conv_pw.hip", "conv_dense.hip", "conv_regstage.hip", "layers.hip", "fc_mfma.hip", "static_scratch.hip", "member.cpp", "planner.cpp", "seedgen.cpp", "engine.cpp"]
+SOURCES = ["conv_mfma.hip", "conv_halo.hip", "conv_taps.hip", "conv_stempool.hip", "conv_wreg.hip", "conv_bneck.hip", "conv_pw.hip", "conv_dense.hip", "conv_regstage.hip", "layers.hip", "fc_mfma.hip", "static_scratch.hip", "member.cpp", "planner.cpp", "seedgen.cpp", "engine.cpp"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]

@@ -228,6 +228,12 @@ bool conv_taps_applicable(const ConvArgs& a, int nb);
 const char* conv_taps_name(const ConvArgs& a);
 hipError_t launch_conv_taps(const ConvArgs& a, const ConvArgs* argv, int G, int nb, hipStream_t s);
 
+// The input stem and the 3x3 / stride-2 max-pool behind it as one kernel; defined in conv_stempool.hip.
+// `pool` carries the pooled output (y, Ho, Wo); argv: G blocks of the convolution, then G of the pool.
+bool conv_stempool_applicable(const ConvArgs& a, const ConvArgs& pool, int nb, int G);
+const char* conv_stempool_name();
+hipError_t launch_conv_stempool(const ConvArgs& a, const ConvArgs& pool, const ConvArgs* argv, int G, int nb, hipStream_t s);
+
 // Register-staged variant (pre-activated inputs); defined in conv_regstage.hip.
 hipError_t launch_conv_regstage(const ConvArgs& a, const ConvArgs* argv, int G, int nb, int P, hipStream_t s);
 const char* conv_regstage_name(const ConvArgs& a, int P);

@@ -35,6 +35,9 @@ const char* conv_bneck_name(const ConvArgs& a1);
 hipError_t launch_conv_bneck(const ConvArgs& a1, const ConvArgs& a2, const ConvArgs& a3, const ConvArgs* argv, int G, int nb,
                              hipStream_t s);
 bool conv_dense_applicable(const ConvArgs& a1, const ConvArgs& a2, int nb, int G);
+bool conv_stempool_applicable(const ConvArgs& a, const ConvArgs& pool, int nb, int G);
+const char* conv_stempool_name();
+hipError_t launch_conv_stempool(const ConvArgs& a, const ConvArgs& pool, const ConvArgs* argv, int G, int nb, hipStream_t s);
 const char* conv_dense_name();
 hipError_t launch_conv_dense(const ConvArgs& a1, const ConvArgs& a2, const ConvArgs* argv, int G, int nb, hipStream_t s);
 
@@ -212,6 +215,26 @@ static int build_launches(ens_handle* h, Gang& g, bool may_alloc = true) {
             chain[i + 1] = 2;
         }
     }
+    // The stem and the max-pool behind it as one kernel: chain[] 4 marks the stem, 2 the pool it runs
+    auto pool_as_conv = [&](const Worker& w, const OpPlan& pl) {   // the pooled output in the convolution's argument form
+        const Member& mw = h->members[w.member];
+        ConvArgs p;
+        memset(&p, 0, sizeof(p));
+        p.y = view_of(w, leader, mw, pl.op.dst, pl.op.dst_c0);
+        p.Ho = mw.tensors[pl.op.dst].h;
+        p.Wo = mw.tensors[pl.op.dst].w;
+        p.nb = w.batch;
+        return p;
+    };
+    for (size_t i = 0; i + 1 < m.ops.size(); i++) {
+        if (!m.ops[i].fuse_pool || h->keep_tensors || chain[i] || chain[i + 1]) continue;
+        Launch a;
+        if (fill_args(h, leader, leader, G, m.ops[i], a) != ENS_OK) continue;
+        if (conv_stempool_applicable(a.conv, pool_as_conv(leader, m.ops[i + 1]), leader.batch, G)) {
+            chain[i] = 4;
+            chain[i + 1] = 2;
+        }
+    }
     // Which pairs of convolutions run as one launch: planned as such, and both on the generic kernel
     // for this batch size (its workgroups read every field of their own argument block).
     std::vector<char> fused(m.ops.size(), 0);                    // 1: takes the next operation along, 2: taken along
@@ -230,7 +253,7 @@ static int build_launches(ens_handle* h, Gang& g, bool may_alloc = true) {
     std::vector<size_t> first_blk(m.ops.size() + 1, 0);          // argument blocks: G * sub per operation
     for (size_t i = 0; i < m.ops.size(); i++)
         first_blk[i + 1] = first_blk[i] + (fused[i] == 2 || chain[i] == 2 ? 0
-                                           : (size_t)G * (chain[i] == 1 ? 3 : chain[i] == 3 || fused[i] == 1 ? 2 : (m.ops[i].sub > 1 ? m.ops[i].sub : 1)));
+                                           : (size_t)G * (chain[i] == 1 ? 3 : chain[i] == 3 || chain[i] == 4 || fused[i] == 1 ? 2 : (m.ops[i].sub > 1 ? m.ops[i].sub : 1)));
     const size_t n_blk = first_blk[m.ops.size()];
     std::vector<char> host((n_blk + (size_t)G) * slot, 0);
     if (!may_alloc && (!g.d_args || g.d_args_bytes < host.size())) return ENS_E_INVALID;
@@ -241,6 +264,29 @@ static int build_launches(ens_handle* h, Gang& g, bool may_alloc = true) {
         Launch L;
         if (fused[i] == 2 || chain[i] == 2) {                    // its argument blocks are in an earlier launch
             L.kind = L_SKIP;
+            g.launches.push_back(L);
+            continue;
+        }
+        if (chain[i] == 4) {                                     // stem and pool: G blocks of the convolution, then G of the pooled output
+            for (int k = G - 1; k >= 0; k--) {
+                const Worker& wk = h->workers[g.workers[k]];
+                const Member& mk = h->members[wk.member];
+                const ConvArgs p = pool_as_conv(wk, mk.ops[i + 1]);
+                const int rc = fill_args(h, wk, leader, G, mk.ops[i], L);
+                if (rc != ENS_OK) return rc;
+                L.conv.ws = nullptr;
+                L.conv.ws_floats = 0;
+                if (k == 0) L.conv2 = p;
+                memcpy(host.data() + (first_blk[i] + (size_t)k) * slot, &L.conv, sizeof(ConvArgs));
+                memcpy(host.data() + (first_blk[i] + (size_t)G + k) * slot, &p, sizeof(ConvArgs));
+            }
+            // algorithmic bytes: the image once, the pooled map once, the filter
+            L.bytes = (double)leader.batch * ((double)L.conv.H * L.conv.W * L.conv.cin + (double)L.conv2.Ho * L.conv2.Wo * L.conv.cout) * 2.0 +
+                      2.0 * L.conv.kh * L.conv.kw * L.conv.cin * L.conv.cout;
+            L.kind = L_STEMPOOL;
+            L.sub = 2;
+            L.klass = prof_class(h, conv_stempool_name());
+            L.d_argv = g.d_args + first_blk[i] * slot;
             g.launches.push_back(L);
             continue;
         }
@@ -349,7 +395,8 @@ static int build_launches(ens_handle* h, Gang& g, bool may_alloc = true) {
         switch (L.kind) {
             case L_CONV:
             case L_BNECK:
-            case L_DENSE: sz = sizeof(ConvArgs); break;
+            case L_DENSE:
+            case L_STEMPOOL: sz = sizeof(ConvArgs); break;
             case L_DWCONV:
             case L_POOL: sz = sizeof(PoolArgs); break;
             case L_GAP: sz = sizeof(GapArgs); break;
@@ -512,6 +559,7 @@ static hipError_t issue(const Launch& L, bool bf16, int G, int nb, long long fir
         case L_SE: return launch_se(L.se, (const SeArgs*)L.d_argv, G, nb, bf16, s);
         case L_BNECK: return launch_conv_bneck(L.conv, L.conv2, L.conv3, (const ConvArgs*)L.d_argv, G, nb, s);
         case L_DENSE: return launch_conv_dense(L.conv, L.conv2, (const ConvArgs*)L.d_argv, G, nb, s);
+        case L_STEMPOOL: return launch_conv_stempool(L.conv, L.conv2, (const ConvArgs*)L.d_argv, G, nb, s);
         case L_SKIP: return hipSuccess;
     }
     return hipErrorInvalidValue;

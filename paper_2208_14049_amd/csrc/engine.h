@@ -45,6 +45,10 @@ struct OpPlan {
     // This pre-activated 1x1 convolution (to 128 channels) and the 3x3 after it (to 32 channels) are a layer
     // of a dense block whose middle tensor nobody else touches: one kernel can run both.
     bool fuse_dense;
+    // This convolution is the input stem (rewritten to stride 1 over the space-to-depth image, ReLU) and the
+    // next operation is a 3x3 / stride-2 / padding-1 max-pool that alone reads its output: one kernel can
+    // run both without writing the stem's output.
+    bool fuse_pool;
 };
 
 struct Member {
@@ -77,7 +81,7 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out);
 // keep_all gives every tensor its own region (debug read-back of intermediate tensors).
 ArenaLayout plan_arena(const Member& m, int batch, bool keep_all = false);
 
-enum LaunchKind { L_CONV, L_DWCONV, L_POOL, L_GAP, L_FC, L_SE, L_BNECK, L_DENSE, L_SKIP };   // L_SKIP: ran with an earlier launch
+enum LaunchKind { L_CONV, L_DWCONV, L_POOL, L_GAP, L_FC, L_SE, L_BNECK, L_DENSE, L_STEMPOOL, L_SKIP };   // L_SKIP: ran with an earlier launch
 
 // One operation of a gang: host copy of the first member's arguments (validation, grid sizing)
 // and the device array holding the arguments of every member of the gang.
@@ -87,7 +91,8 @@ struct Launch {
     int klass = 0;                 // profile class
     double flop = 0, bytes = 0;    // algorithmic work of one member's full-batch launch
     ConvArgs conv;
-    ConvArgs conv2, conv3;         // L_BNECK: the second and third convolution of the chain; L_DENSE: conv2 is the 3x3
+    ConvArgs conv2, conv3;         // L_BNECK: the second and third convolution of the chain; L_DENSE: conv2 is the 3x3;
+                                   // L_STEMPOOL: conv2 describes the pooled output
     PoolArgs pool;
     GapArgs gap;
     FcArgs fc;

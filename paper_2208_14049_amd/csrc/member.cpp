@@ -131,6 +131,7 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         pl.fuse_next = false;
         pl.fuse_chain = false;
         pl.fuse_dense = false;
+        pl.fuse_pool = false;
         TensorInfo& ts = m.tensors[o.src];
         TensorInfo& td = m.tensors[o.dst];
         if (o.cin <= 0 || o.cout <= 0 || o.src_c0 < 0 || o.dst_c0 < 0) return ENS_E_INVALID;
@@ -445,6 +446,24 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
             m.tensors[q.dst].def = std::min(m.tensors[q.dst].def, i);
             pack_operand_order(m.ops[i]);
             pack_operand_order(m.ops[i + 1]);
+        }
+    }
+    // The rewritten stem followed by a 3x3 / stride-2 / padding-1 max-pool that alone reads its output
+    if (stem_op >= 0 && stem_op + 1 < spec.n_ops) {
+        const ens_op &c = spec.ops[stem_op], &q = spec.ops[stem_op + 1];
+        int readers = 0;
+        for (int i = 0; i < spec.n_ops; i++) {
+            const ens_op& o = spec.ops[i];
+            readers += o.src == c.dst;
+            readers += o.kind == ENS_OP_CONV && o.res == c.dst;
+        }
+        if (q.kind == ENS_OP_MAXPOOL && q.src == c.dst && q.src_c0 == c.dst_c0 && q.cin == c.cout && readers == 1 &&
+            q.kh == 3 && q.kw == 3 && q.sh == 2 && q.sw == 2 && q.pt == 1 && q.pl == 1 && c.act == ENS_ACT_RELU && c.res < 0 &&
+            m.tensors[c.dst].c == c.cout && q.dst != c.dst && q.dst != 0 && m.ops[stem_op].op.kh == 4 && m.ops[stem_op].op.kw == 4 &&
+            !m.ops[stem_op].fuse_next && m.tensors[q.dst].h == (m.tensors[c.dst].h - 1) / 2 + 1 &&
+            m.tensors[q.dst].w == (m.tensors[c.dst].w - 1) / 2 + 1) {
+            m.ops[stem_op].fuse_pool = true;
+            m.tensors[q.dst].def = std::min(m.tensors[q.dst].def, stem_op);
         }
     }
     if (stem_op >= 0) {                                          // tensor 0 as the staging kernel writes it

@@ -303,6 +303,41 @@ def test_pointwise_layers_of_a_gang(ens):
             assert err.mean() <= 2.0 ** -6 * scale, (g, t, err.mean(), scale)
 
 
+@pytest.mark.parametrize("h,w,cout,G,nb", [(64, 64, 64, 1, 5), (70, 54, 64, 1, 7), (96, 96, 64, 2, 40), (60, 60, 96, 1, 9), (224, 224, 64, 1, 3)],
+                         ids=["64x64", "70x54_odd_maps", "96x96_gang2_many_bands", "60x60_96_channels", "224x224"])
+def test_stem_and_max_pool_in_one_kernel(ens, h, w, cout, G, nb):
+    """The 7x7 / stride-2 stem with ReLU and the 3x3 / stride-2 / padding-1 max-pool behind it run as one
+    kernel that keeps the stem's output in LDS.  The pooled map is read back and compared with the oracle
+    element by element, for each member of the gang; the profile says that the fused kernel ran and that
+    no separate pooling kernel did.  Shapes: odd stem output sizes (35 x 27: the last pooled row and column
+    reach past the map), more bands than workgroups, a second, half-empty channel tile, the full 224 x 224."""
+    nets = []
+    for g in range(G):
+        n = N.Net("sp%d" % g, h, w, 8, dtype="bf16")
+        x = n.conv(0, cout, 7, stride=2)
+        pooled = n.maxpool(x, 3, 2, 1)
+        n.fc(n.gap(pooled), 8)
+        nets.append(n)
+    blobs = [W.quantise_weights_bf16(n, W.make_blob(n, 91, i)) for i, n in enumerate(nets)]
+    imgs = W.round_bf16(W.make_images(92, nb, h, w))
+    E = ens.Ensemble(nets, blobs)
+    E.set_base_size(h, w)
+    E.ens_set_alloc([[nb] * G])
+    E.ens_set_profiling(1)
+    E.ens_predict(imgs)
+    ran = {k["name"]: k["launches"] for k in E.ens_profile() if k["launches"]}
+    got = [E.ens_debug_tensor(g, pooled, nets[g].tensors[pooled], nb) for g in range(G)]   # alive until the global pooling
+    E.close()
+    assert ran.get("stem_pool_bf16<4x4>") == 1 and "window_kernel<maxpool>" not in ran, ran
+    for g in range(G):
+        ref = oracle_tensor(nets[g], blobs[g], imgs, pooled)
+        scale = np.sqrt(np.mean(ref ** 2)) + 1e-6
+        err = np.abs(got[g] - ref)
+        bound = 2.0 ** -7 * np.abs(ref) + scale * 2.0 ** -5 + 1e-6     # one bf16 ulp + accumulation order, as for a single convolution
+        assert (err <= bound).all(), (g, float(err.max()), float(scale), float((err / bound).max()))
+        assert err.mean() <= 2.0 ** -8 * scale
+
+
 # (C, H, W, cin, cout, residual, activation of the last convolution, members in the gang, images, batch)
 BOTTLENECKS = [
     (64, 24, 24, 256, 256, "input", "relu", 1, 56, 64),        # identity block, short last batch
