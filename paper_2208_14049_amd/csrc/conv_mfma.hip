@@ -485,6 +485,7 @@ hipError_t launch_conv_bf16(const ConvArgs& a, const ConvArgs* argv, int G, int 
     const long long K64 = (long long)a.kh * a.kw * a.cin;
     if (P64 <= 0 || P64 >= (1LL << 31) || K64 >= (1LL << 31)) return hipErrorInvalidValue;
     const int P = (int)P64;
+    if (a.gate && (a.pre_scale || !conv_pw_applicable(a, nb, G))) return hipErrorInvalidValue;   // only the 1x1 kernel applies a gate
     if (a.pre_scale && !pre_in_dma_kernel(a)) return launch_conv_regstage(a, argv, G, nb, P, s);
     if (conv_pw_applicable(a, nb, G)) return launch_conv_pw(a, argv, G, nb, s);
     if (conv_taps_applicable(a, nb)) return launch_conv_taps(a, argv, G, nb, s);

@@ -25,9 +25,13 @@ namespace ens {
 
 constexpr int PW_BP = 128, PW_NXB = 3, PW_XS = PW_BP * 128;
 
-template <int WPX>
+// GATE: the input is multiplied by a gate per (image, input channel) on its way from LDS to the matrix cores
+// (the rescaling of a squeeze-excite block folded into the projection that follows it): product in fp32,
+// rounded to bf16 as the separate rescaling kernel would have stored it.  The gates of the images a tile
+// touches wait in LDS behind the ring, gimg images of nk * 64 floats.
+template <int WPX, bool GATE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void conv1x1_direct_bf16(const ConvArgs* __restrict__ argv,
-                                                                                                     const int nb_) {
+                                                                                                     const int nb_, const int gimg) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const ConvArgs a = argv[blockIdx.z];
     static_assert(WPX == 1 || WPX == 2, "one or two wavefronts along the pixels");
@@ -99,6 +103,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         sbl[t] = ok ? a.bias[c0 + t] : 0.f;
         sbl[BC + t] = ok ? a.scale[c0 + t] : 1.f;
     }
+    float* const gl = sbl + 2 * 128;                 // GATE: [image of the tile][nk * 64] gates, zeros past the last channel
+    int grow[TP];                                    // GATE: this lane's first gate of pixel row j, less the chunk's offset
+    if constexpr (GATE) {
+        const int HW = a.H * a.W, cinp = nk * 64;
+        const int n_first = p0 / HW, n_last = min(p0 + BP - 1, P - 1) / HW;
+        for (int i = t; i < gimg * cinp; i += 256) {
+            const int img = i / cinp, c = i - img * cinp;
+            gl[i] = (c < a.cin && n_first + img <= n_last) ? a.gate[(long long)(n_first + img) * a.gate_stride + c] : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < TP; j++) grow[j] = (min(p0 + wp0 + 32 * j + lrow, P - 1) / HW - n_first) * cinp + 8 * lhalf;
+    }
 
     // ---- input chunks: thread t fills chunk slot t % 8 of rows t / 8 + 32 s with the swizzled chunk
     const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc((void*)a.x.p, 0, (int)(npix * (unsigned)a.x.stride * 2u), 0x00020000);
@@ -164,6 +180,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             }
 #pragma unroll
             for (int j = 0; j < TP; j++) bn_tie(xf[b][j]);
+            if constexpr (GATE) {
+#pragma unroll
+                for (int j = 0; j < TP; j++) {
+                    const float* gp = gl + grow[j] + kc * 64 + ks * 16;
+                    const f32x4 g0 = *(const f32x4*)gp, g1 = *(const f32x4*)(gp + 4);
+                    u32x4 u = __builtin_bit_cast(u32x4, xf[b][j]);
+#pragma unroll
+                    for (int q = 0; q < 4; q++) {
+                        const float lo = __uint_as_float(u[q] << 16), hi = __uint_as_float(u[q] & 0xFFFF0000u);
+                        const float gq0 = q < 2 ? g0[2 * q] : g1[2 * q - 4], gq1 = q < 2 ? g0[2 * q + 1] : g1[2 * q - 3];
+                        u[q] = pack_bf16x2(lo * gq0, hi * gq1);
+                    }
+                    xf[b][j] = __builtin_bit_cast(bf16x8, u);
+                }
+            }
 #pragma unroll
             for (int j = 0; j < TP; j++) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc_[ks], xf[b][j], acc[j], 0, 0, 0);
         });
@@ -203,18 +234,34 @@ static bool pw_shape_ok(const ConvArgs& a, int nb) {
     return true;
 }
 
+// GATE: images a tile of PW_BP pixels can touch, and the bytes of their gates in LDS
+static int pw_gate_images(const ConvArgs& a) { return (PW_BP - 1) / (a.H * a.W) + 2; }
+static size_t pw_gate_bytes(const ConvArgs& a) { return a.gate ? (size_t)pw_gate_images(a) * ((a.cin + 63) / 64 * 64) * sizeof(float) : 0; }
+constexpr size_t PW_LDS_BASE = (size_t)PW_NXB * PW_XS + 2 * 128 * sizeof(float);
+
 bool conv_pw_applicable(const ConvArgs& a, int nb, int G) {
+    // (small maps with thousands of channels leave room for one workgroup per compute unit only: still better than a pass more)
+    if (a.gate && (a.gate_stride < a.cin || PW_LDS_BASE + pw_gate_bytes(a) > 160 * 1024)) return false;
     return pw_shape_ok(a, nb);
 }
 
 
 
-template <int WPX>
+template <int WPX, bool GATE>
 static hipError_t launch_pw_variant(const ConvArgs& a, const ConvArgs* argv, int G, int nb, hipStream_t s) {
     constexpr int BC = 32 * (4 / WPX);
     const long long P = (long long)nb * a.H * a.W;
     const dim3 grid((unsigned)(((P + PW_BP - 1) / PW_BP) * ((a.cout + BC - 1) / BC)), 1, G);
-    ENS_LAUNCH((conv1x1_direct_bf16<WPX>), grid, dim3(256), (size_t)PW_NXB * PW_XS + 2 * 128 * sizeof(float), s, argv, nb);
+    const size_t bytes = PW_LDS_BASE + pw_gate_bytes(a);
+    if (bytes > 64 * 1024) {                                     // LDS above 64 KB has to be asked for once
+        static bool raised = false;
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute((const void*)&conv1x1_direct_bf16<WPX, GATE>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
+    ENS_LAUNCH((conv1x1_direct_bf16<WPX, GATE>), grid, dim3(256), bytes, s, argv, nb, GATE ? pw_gate_images(a) : 0);
     return hipGetLastError();
 }
 
@@ -227,11 +274,18 @@ static int pw_wpx(const ConvArgs& a, int nb, int G) {
     return wpx;
 }
 
-const char* conv_pw_name(const ConvArgs& a, int G) { return pw_wpx(a, a.nb, G) == 2 ? "conv1x1_direct_bf16<128x64>" : "conv1x1_direct_bf16<128x128>"; }
+const char* conv_pw_name(const ConvArgs& a, int G) {
+    if (a.gate) return pw_wpx(a, a.nb, G) == 2 ? "conv1x1_direct_bf16<128x64,gate>" : "conv1x1_direct_bf16<128x128,gate>";
+    return pw_wpx(a, a.nb, G) == 2 ? "conv1x1_direct_bf16<128x64>" : "conv1x1_direct_bf16<128x128>";
+}
 
 hipError_t launch_conv_pw(const ConvArgs& a, const ConvArgs* argv, int G, int nb, hipStream_t s) {
     if (!pw_shape_ok(a, nb)) return hipErrorInvalidValue;
-    return pw_wpx(a, nb, G) == 2 ? launch_pw_variant<2>(a, argv, G, nb, s) : launch_pw_variant<1>(a, argv, G, nb, s);
+    if (a.gate) {
+        if (!conv_pw_applicable(a, nb, G)) return hipErrorInvalidValue;
+        return pw_wpx(a, nb, G) == 2 ? launch_pw_variant<2, true>(a, argv, G, nb, s) : launch_pw_variant<1, true>(a, argv, G, nb, s);
+    }
+    return pw_wpx(a, nb, G) == 2 ? launch_pw_variant<2, false>(a, argv, G, nb, s) : launch_pw_variant<1, false>(a, argv, G, nb, s);
 }
 
 }  // namespace ens

@@ -35,6 +35,7 @@ const char* conv_bneck_name(const ConvArgs& a1);
 hipError_t launch_conv_bneck(const ConvArgs& a1, const ConvArgs& a2, const ConvArgs& a3, const ConvArgs* argv, int G, int nb,
                              hipStream_t s);
 bool conv_dense_applicable(const ConvArgs& a1, const ConvArgs& a2, int nb, int G);
+bool conv_pw_applicable(const ConvArgs& a, int nb, int G);
 bool conv_stempool_applicable(const ConvArgs& a, const ConvArgs& pool, int nb, int G);
 const char* conv_stempool_name();
 hipError_t launch_conv_stempool(const ConvArgs& a, const ConvArgs& pool, const ConvArgs* argv, int G, int nb, hipStream_t s);
@@ -91,6 +92,7 @@ static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G
             a.pre_scale = pl.pre_scale != SIZE_MAX ? (const float*)(P + pl.pre_scale) : nullptr;
             a.pre_shift = pl.pre_shift != SIZE_MAX ? (const float*)(P + pl.pre_shift) : nullptr;
             a.ws = nullptr; a.ws_floats = 0;
+            a.gate = nullptr; a.gate_stride = 0;
             a.zeros = P + m.zeros_off;
             a.wpk = pl.w_packed != SIZE_MAX ? P + pl.w_packed : nullptr;
             if (w.layout.scratch_offset != SIZE_MAX) {
@@ -171,6 +173,7 @@ static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G
             a.w2 = (const float*)(P + pl.w2); a.b2 = (const float*)(P + pl.b2);
             a.scratch = (float*)(w.arena + w.layout.offset[pl.scratch]);
             a.nb = w.batch; a.HW = ts.h * ts.w; a.c = o.cin; a.r = o.r;
+            a.gate_only = 0;
             L.flop = 4.0 * nb * o.cin * o.r;
             L.bytes = nb * 3.0 * ts.h * ts.w * o.cin * es;
             L.klass = prof_class(h, "se_kernels");
@@ -248,6 +251,25 @@ static int build_launches(ens_handle* h, Gang& g, bool may_alloc = true) {
             strncmp(conv_bf16_variant_name(b.conv, 2 * G), generic, strlen(generic)) == 0) {
             fused[i] = 1;
             fused[i + 1] = 2;
+        }
+    }
+    // Squeeze-excite blocks that stop at the gates, which the 1x1 convolution behind them applies to its
+    // input: gated[] 1 marks the block, 2 the convolution.  gate_args turns the convolution's arguments round.
+    std::vector<char> gated(m.ops.size(), 0);
+    auto gate_args = [&](const Worker& w, const OpPlan& se, ConvArgs& c) {
+        const Member& mw = h->members[w.member];
+        c.x = view_of(w, leader, mw, se.op.src, se.op.src_c0);
+        c.gate = (const float*)(w.arena + w.layout.offset[se.scratch]) + se_gate_offset(se.op.cin, se.op.r);
+        c.gate_stride = se_scratch_floats(se.op.cin, se.op.r);
+    };
+    for (size_t i = 0; i + 1 < m.ops.size(); i++) {
+        if (!m.ops[i].fuse_gate || h->keep_tensors || chain[i] || chain[i + 1] || fused[i] || fused[i + 1]) continue;
+        Launch c;
+        if (fill_args(h, leader, leader, G, m.ops[i + 1], c) != ENS_OK) continue;
+        gate_args(leader, m.ops[i], c.conv);
+        if (c.conv.wpk && conv_pw_applicable(c.conv, leader.batch, G)) {
+            gated[i] = 1;
+            gated[i + 1] = 2;
         }
     }
     std::vector<size_t> first_blk(m.ops.size() + 1, 0);          // argument blocks: G * sub per operation
@@ -362,6 +384,13 @@ static int build_launches(ens_handle* h, Gang& g, bool may_alloc = true) {
                 const OpPlan& pl = fused[i] == 1 && (sub == 1) != second_leads ? mk.ops[i + 1] : mk.ops[i];
                 const int rc = fill_args(h, h->workers[g.workers[k]], leader, G, pl, L, fused[i] == 1 ? 0 : sub);
                 if (rc != ENS_OK) return rc;
+                if (gated[i] == 1) {                             // the block stops at the gates: one pass over its input
+                    L.se.gate_only = 1;
+                    L.bytes /= 3.0;
+                } else if (gated[i] == 2) {
+                    gate_args(h->workers[g.workers[k]], mk.ops[i - 1], L.conv);
+                    L.klass = prof_class(h, conv_bf16_variant_name(L.conv, G));
+                }
                 if (fused[i] == 1) {                             // no split of the depth: the two would share one workspace
                     L.conv.wpk = nullptr;                        // the generic kernel runs both
                     L.conv.ws = nullptr;

@@ -49,6 +49,10 @@ struct OpPlan {
     // next operation is a 3x3 / stride-2 / padding-1 max-pool that alone reads its output: one kernel can
     // run both without writing the stem's output.
     bool fuse_pool;
+    // This squeeze-excite block is followed by a 1x1 convolution that alone reads its output: the block can
+    // stop at the gates and the convolution multiply its input by them, so that the rescaled tensor is
+    // never written.
+    bool fuse_gate;
 };
 
 struct Member {

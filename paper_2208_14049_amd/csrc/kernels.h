@@ -41,6 +41,10 @@ struct ConvArgs {
     long long ws_floats;
     const void* zeros;         // at least 16 bytes of zeros in device memory (padding source of the register-staged kernel)
     const void* wpk;           // the weights in matrix-core operand order (fused bottleneck kernel), or null
+    // Squeeze-excite gate folded into a 1x1 convolution: input value (image n, channel ci) is multiplied by
+    // gate[n * gate_stride + ci] (and rounded to bf16) on its way to the matrix cores; null: no gate
+    const float* gate;
+    long long gate_stride;
     double inv_hw, inv_w;      // 1 / (Ho * Wo) and 1 / Wo, for the pixel index decomposition
     int nb, H, W, cin, Ho, Wo, cout;
     int kh, kw, sh, sw, pt, pl;
@@ -83,8 +87,10 @@ struct SeArgs {
     const float* w1; const float* b1; const float* w2; const float* b2;   // fp32
     float* scratch;            // per image SE_MAX_SPLITS * c partial sums, r hidden values, c gates (floats)
     int nb, HW, c, r;
+    int gate_only;             // non-zero: the gates go to `scratch` and y is not written (the consumer applies them)
 };
 __host__ __device__ inline int se_scratch_floats(int c, int r) { return (SE_MAX_SPLITS + 1) * c + r; }
+__host__ __device__ inline int se_gate_offset(int c, int r) { return SE_MAX_SPLITS * c + r; }   // of an image's gates in its scratch
 
 struct StageArgs {             // request images -> a worker's input tensor (convert, pad, resize)
     const float* src;          // request images, n x sh x sw x 3 fp32

@@ -833,6 +833,20 @@ __global__ __launch_bounds__(SE_GATE_THREADS) void se_gate_scale_kernel(const Se
     }
 }
 
+// The gates alone, one workgroup per image, into the image's scratch: for a squeeze-excite whose consumer
+// (a 1x1 convolution) multiplies its input by them, so that the rescaled tensor is never written.
+__global__ __launch_bounds__(SE_GATE_THREADS) void se_gate_only_kernel(const SeArgs* __restrict__ argv, const int nb_, const int splits) {
+    const SeArgs a = argv[blockIdx.z];
+    __shared__ float mean[SE_GATE_MAXC];
+    __shared__ __attribute__((aligned(16))) float gate[SE_GATE_MAXC];
+    __shared__ float red[SE_GATE_THREADS];
+    __shared__ float z[256];
+    const int n = blockIdx.y;
+    se_gate(a, n, splits, mean, red, z, gate);
+    float* out = a.scratch + (long long)n * se_scratch_floats(a.c, a.r) + se_gate_offset(a.c, a.r);
+    for (int c = threadIdx.x; c < a.c; c += SE_GATE_THREADS) out[c] = gate[c];
+}
+
 hipError_t launch_se(const SeArgs& a, const SeArgs* argv, int G, int nb, bool bf16, hipStream_t s) {
     if (nb <= 0 || a.c <= 0 || a.r <= 0 || a.HW <= 0 || !a.scratch || G <= 0 || !argv) return hipErrorInvalidValue;
     if (a.c > SE_GATE_MAXC || a.r > 256) return hipErrorInvalidValue;   // what the gate kernel holds in LDS
@@ -841,6 +855,10 @@ hipError_t launch_se(const SeArgs& a, const SeArgs* argv, int G, int nb, bool bf
     const int splits = se_splits(a.HW, nb * G);
     if (bf16) ENS_LAUNCH_FIRST(se_sum_kernel<true>, dim3(splits, nb, G), dim3(256), 0, s, argv, nb);
     else ENS_LAUNCH_FIRST(se_sum_kernel<false>, dim3(splits, nb, G), dim3(256), 0, s, argv, nb);
+    if (a.gate_only) {
+        ENS_LAUNCH_LAST(se_gate_only_kernel, dim3(1, nb, G), dim3(SE_GATE_THREADS), 0, s, argv, nb, splits);
+        return hipGetLastError();
+    }
     // shares of an image in the second kernel: about SE_SCALE_BYTES of the tensor each
     long long shares = ((long long)a.HW * a.c * (bf16 ? 2 : 4) + SE_SCALE_BYTES - 1) / SE_SCALE_BYTES;
     // and no more workgroups than the chip holds at once (two of 1024 threads per compute unit): every

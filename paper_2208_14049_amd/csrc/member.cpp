@@ -132,6 +132,7 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         pl.fuse_chain = false;
         pl.fuse_dense = false;
         pl.fuse_pool = false;
+        pl.fuse_gate = false;
         TensorInfo& ts = m.tensors[o.src];
         TensorInfo& td = m.tensors[o.dst];
         if (o.cin <= 0 || o.cout <= 0 || o.src_c0 < 0 || o.dst_c0 < 0) return ENS_E_INVALID;
@@ -446,6 +447,28 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
             m.tensors[q.dst].def = std::min(m.tensors[q.dst].def, i);
             pack_operand_order(m.ops[i]);
             pack_operand_order(m.ops[i + 1]);
+        }
+    }
+    // Squeeze-excite followed by a 1x1 convolution (stride 1, no pre-activation, not grouped) that alone reads its output
+    if (m.bf16) {
+        for (int i = 0; i + 1 < spec.n_ops; i++) {
+            const ens_op &e = spec.ops[i], &c = spec.ops[i + 1];
+            if (e.kind != ENS_OP_SE || c.kind != ENS_OP_CONV) continue;
+            if (c.kh != 1 || c.kw != 1 || c.sh != 1 || c.sw != 1 || c.pt != 0 || c.pl != 0 || c.r > 1 || c.pre) continue;
+            if (c.src != e.dst || c.src_c0 != e.dst_c0 || c.cin != e.cin || e.dst == e.src || c.dst == e.src || c.dst == e.dst) continue;
+            if (m.ops[i + 1].w_packed == SIZE_MAX || m.ops[i + 1].fuse_next || m.ops[i + 1].fuse_chain || m.ops[i + 1].fuse_dense) continue;
+            if (i > 0 && m.ops[i - 1].fuse_next) continue;
+            int readers = 0;
+            for (int k = 0; k < spec.n_ops; k++) {
+                const ens_op& o = spec.ops[k];
+                readers += o.src == e.dst;
+                readers += o.kind == ENS_OP_CONV && o.res == e.dst;
+            }
+            if (readers != 1 || m.tensors[e.dst].c != e.cin || m.tensors[e.src].c < e.src_c0 + e.cin) continue;
+            m.ops[i].fuse_gate = true;
+            // the convolution then reads the block's input and its scratch (the gates)
+            m.tensors[e.src].last = std::max(m.tensors[e.src].last, i + 1);
+            m.tensors[m.ops[i].scratch].last = std::max(m.tensors[m.ops[i].scratch].last, i + 1);
         }
     }
     // The rewritten stem followed by a 3x3 / stride-2 / padding-1 max-pool that alone reads its output

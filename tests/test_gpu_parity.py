@@ -562,6 +562,51 @@ def test_fc_head_on_matrix_cores(ens, F, classes, nb, G):
     E.close()
 
 
+@pytest.mark.parametrize("h,c,r,cout,res,G,nb", [(28, 144, 6, 24, False, 1, 5), (7, 1152, 48, 192, False, 1, 37), (14, 480, 20, 80, True, 2, 9),
+                                                  (56, 96, 4, 24, False, 1, 3), (5, 2688, 112, 448, False, 1, 6)],
+                         ids=["28x28x144-24", "7x7x1152-192_n37", "14x14x480-80_res_gang2", "56x56x96-24", "5x5x2688-448"])
+def test_squeeze_excite_gate_in_the_projection(ens, h, c, r, cout, res, G, nb):
+    """A squeeze-excite block followed by a 1x1 projection (the tail of an inverted-residual block): the
+    block stops at its gates and the projection multiplies its input by them, so the rescaled tensor is
+    never written.  The projection's output is compared with the oracle element by element and, bit for
+    bit, with the same network run layer by layer (every tensor kept: no fusion); the profile says which
+    kernels ran.  Shapes: tiles inside one image (56x56, 28x28), tiles over three to six images (7x7,
+    5x5), input channels that are no multiple of 64 (144, 480), a residual, two members in one launch."""
+    nets = []
+    for g in range(G):
+        n = N.Net("mb%d" % g, h, h, 8, dtype="bf16")
+        x = n.conv(0, cout, 3, act=None) if res else 0
+        t = n.conv(x, c, 1, act="silu")
+        u = n.se(t, r)
+        y = n.conv(u, cout, 1, act=None, res=x if res else None)
+        n.fc(n.gap(y), 8)
+        nets.append(n)
+    blobs = [W.quantise_weights_bf16(n, W.make_blob(n, 101, i)) for i, n in enumerate(nets)]
+    imgs = W.round_bf16(W.make_images(102, nb, h, h))
+    outs = []
+    for keep in (False, True):
+        E = ens.Ensemble(nets, blobs)
+        E.set_base_size(h, h)
+        if keep:
+            E.ens_debug_keep_tensors()
+        E.ens_set_alloc([[nb] * G])
+        E.ens_set_profiling(1)
+        E.ens_predict(imgs)
+        ran = {k["name"]: k["launches"] for k in E.ens_profile() if k["launches"]}
+        gate_ran = sum(v for k, v in ran.items() if k.endswith(",gate>"))
+        assert gate_ran == (0 if keep else 1), ran
+        outs.append([E.ens_debug_tensor(g, y, nets[g].tensors[y], nb) for g in range(G)])   # alive until the global pooling
+        E.close()
+    for g in range(G):
+        assert np.array_equal(outs[0][g], outs[1][g])              # same products, same roundings, same sums
+        ref = oracle_tensor(nets[g], blobs[g], imgs, y)
+        scale = np.sqrt(np.mean(ref ** 2)) + 1e-6
+        err = np.abs(outs[0][g] - ref)
+        # three bf16 layers in a row (expansion, rescaling, projection)
+        assert err.max() <= 0.05 * scale + 2.0 ** -6 * np.abs(ref).max(), (g, err.max(), scale)
+        assert err.mean() <= 2.0 ** -6 * scale, (g, err.mean(), scale)
+
+
 def test_resize_staging(ens):
     """A member at 45 x 45 fed from 32 x 32 requests: bilinear resize inside the library."""
     for dtype in ("fp32", "bf16"):
