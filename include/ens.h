@@ -239,6 +239,10 @@ int ens_spec_bytes(const ens_member_spec* spec, int32_t batch, int64_t* weight_b
  * algorithmic flop and the algorithmic bytes (each input, weight and output read or written
  * once) of those launches.  ens_last_ms is the wall time of the last ens_predict. */
 int ens_set_profiling(ens_handle* h, int32_t on);
+/* Measurement aid: with one_stream on, every worker issues its kernels on one stream, so that each kernel
+ * has the GPU to itself and ens_profile_get reports durations that no co-running kernel stretches.  Same
+ * results, no overlap; not for serving. */
+int ens_debug_one_stream(ens_handle* h, int32_t on);
 int ens_profile_get(const ens_handle* h, int32_t idx, char* name, int32_t name_len, double* ms,
                     int64_t* launches, double* flop, double* bytes);
 double ens_last_ms(const ens_handle* h);

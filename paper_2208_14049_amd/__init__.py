@@ -74,7 +74,7 @@ BENCH_SINGLE_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.c_int32, ctypes.c_int
 EXPORTS = ("ens_load", "ens_free", "ens_set_io", "ens_plan", "ens_set_alloc", "ens_bench", "ens_predict",
            "ens_predict_static", "ens_static_scratch_bytes",
            "ens_member_logits", "ens_debug_tensor", "ens_debug_keep_tensors", "ens_classes", "ens_n_members", "ens_member_bytes",
-           "ens_spec_bytes", "ens_set_profiling", "ens_profile_get", "ens_last_ms", "ens_set_combination", "ens_debug_fake_predictor",
+           "ens_spec_bytes", "ens_set_profiling", "ens_debug_one_stream", "ens_profile_get", "ens_last_ms", "ens_set_combination", "ens_debug_fake_predictor",
            "ens_planner_fit_mem", "ens_planner_wfd", "ens_planner_neighbors", "ens_planner_greedy",
            "ens_planner_bbs", "ens_partition", "ens_hand_out", "ens_strerror", "ens_version")
 
@@ -111,6 +111,7 @@ def lib():
         L.ens_member_bytes.argtypes = [vp, i32, i32, P(i64), P(i64)]
         L.ens_spec_bytes.argtypes = [P(EnsMemberSpec), i32, P(i64), P(i64)]
         L.ens_set_profiling.argtypes = [vp, i32]
+        L.ens_debug_one_stream.argtypes = [vp, i32]
         L.ens_set_combination.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_float)]
         L.ens_debug_fake_predictor.argtypes = [vp, i32]
         L.ens_profile_get.argtypes = [vp, i32, ctypes.c_char_p, i32, P(dbl), P(i64), P(dbl), P(dbl)]
@@ -330,6 +331,9 @@ class Ensemble:
 
     def ens_set_profiling(self, on):
         _check(lib().ens_set_profiling(self._h, int(on)), "ens_set_profiling")
+
+    def ens_debug_one_stream(self, on):
+        _check(lib().ens_debug_one_stream(self._h, int(on)), "ens_debug_one_stream")
 
     def ens_profile(self):
         """[{name, ms, launches, flop, bytes}] of the last profiled call."""

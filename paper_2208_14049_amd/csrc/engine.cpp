@@ -597,6 +597,7 @@ static hipError_t issue(const Launch& L, bool bf16, int G, int nb, long long fir
 // One batch of one gang: stage the images into the leader's arena, run every member, write the
 // logits rows of the batch.
 static int forward_batch(ens_handle* h, Gang& g, int64_t first, int nb) {
+    const hipStream_t st = h->one_stream ? h->main_stream : g.stream;
     const Worker& leader = h->workers[g.workers[0]];
     const Member& m = h->members[leader.member];
     const int G = (int)g.workers.size();
@@ -614,16 +615,16 @@ static int forward_batch(ens_handle* h, Gang& g, int64_t first, int nb) {
     if (h->fake_predictor) {                                     // zeros for the rows of this batch, nothing else
         for (int wi : g.workers) {
             const Worker& w = h->workers[wi];
-            HIP_TRY(launch_fill_zero(h->d_logits[w.member] + first * h->classes, (int64_t)nb * h->classes, g.stream));
+            HIP_TRY(launch_fill_zero(h->d_logits[w.member] + first * h->classes, (int64_t)nb * h->classes, st));
             h->workers[wi].last_nb = nb;
         }
         return ENS_OK;
     }
     const double stage_bytes = (double)leader.batch * (h->base_h * h->base_w * 12.0 + (double)m.tensors[0].h * m.tensors[0].w * g.stage.dc * (m.bf16 ? 2 : 4));
-    HIP_TRY(timed(h->stage_klass, 0.0, stage_bytes, [&] { return launch_stage(g.stage, g.d_stage, 1, nb, first, m.bf16, g.stream); }));
+    HIP_TRY(timed(h->stage_klass, 0.0, stage_bytes, [&] { return launch_stage(g.stage, g.d_stage, 1, nb, first, m.bf16, st); }));
     for (const Launch& L : g.launches) {
         if (L.kind == L_SKIP) continue;
-        HIP_TRY(timed(L.klass, L.flop * G, L.bytes * G, [&] { return issue(L, m.bf16, G, nb, first, g.stream); }));
+        HIP_TRY(timed(L.klass, L.flop * G, L.bytes * G, [&] { return issue(L, m.bf16, G, nb, first, st); }));
     }
     for (int wi : g.workers) h->workers[wi].last_nb = nb;
     return ENS_OK;
@@ -1209,6 +1210,13 @@ int ens_set_combination(ens_handle* h, int32_t rule, const float* weights) {
         HIP_TRY(hipMemcpy(h->d_weights, weights, h->members.size() * sizeof(float), hipMemcpyHostToDevice));
     }
     h->combine_rule = rule;
+    return ENS_OK;
+}
+
+int ens_debug_one_stream(ens_handle* h, int32_t on) {
+    if (!h) return ENS_E_INVALID;
+    (void)hipDeviceSynchronize();
+    h->one_stream = on != 0;
     return ENS_OK;
 }
 

@@ -176,6 +176,7 @@ struct ens_handle {
     bool profiling = false;
     bool keep_tensors = false;                   // debug: no reuse of arena regions
     bool fake_predictor = false;                 // overhead experiment: forward passes replaced by zeros
+    bool one_stream = false;                     // measurement: every worker issues on the main stream, one kernel at a time
     std::vector<ens::ProfClass> prof;
     std::vector<ens::ProfRec> prof_recs;
     std::vector<hipEvent_t> event_pool;
