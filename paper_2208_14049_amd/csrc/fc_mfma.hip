@@ -33,30 +33,44 @@ __global__ __launch_bounds__(256) void fc_mfma_bf16(const FcArgs* __restrict__ a
     const unsigned wv = (unsigned)(blockIdx.x * NS * 1024 + lane * 16);
     const int n = n0 + lrow;
     const bool row_ok = n < nb_;
-    const float* __restrict__ xrow = a.x + (size_t)(row_ok ? n : 0) * K + 8 * lhalf;
+    // features through a buffer descriptor: rows past the batch and steps past K read zeros, so the loop has no branch
+    // and the loads of several steps can be in flight together
+    constexpr unsigned OOBV = 0x80000000u;
+    const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, (int)((unsigned)nb_ * (unsigned)K * 4u), 0x00020000);
+    const unsigned xv = row_ok ? (unsigned)((n * K + 8 * lhalf) * 4) : OOBV;
 
     f32x16 acc;
     bn_zero(acc);
-    for (int s = s_begin; s < s_end; s++) {
-        const bf16x8 wf = bn_wload(wres, wv, s * 1024);
-        f32x4 x0 = f32x4{0.f, 0.f, 0.f, 0.f}, x1 = x0;
-        if (row_ok && 16 * s + 8 * lhalf + 8 <= K) {             // K is a multiple of 8: a lane's 8 features exist or do not
-            x0 = *ENS_GLOBAL(f32x4, xrow + 16 * s);
-            x1 = *ENS_GLOBAL(f32x4, xrow + 16 * s + 4);
-        }
-        const float xv[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
+    auto step = [&](const bf16x8& wf, const f32x4& x0, const f32x4& x1) {
+        const float xs[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
         uint32_t hi[4], lo[4];
 #pragma unroll
         for (int q = 0; q < 4; q++) {
-            hi[q] = pack_bf16x2(xv[2 * q], xv[2 * q + 1]);
-            const float r0 = xv[2 * q] - bf16_to_f32((uint16_t)(hi[q] & 0xFFFF));
-            const float r1 = xv[2 * q + 1] - bf16_to_f32((uint16_t)(hi[q] >> 16));
+            hi[q] = pack_bf16x2(xs[2 * q], xs[2 * q + 1]);
+            const float r0 = xs[2 * q] - bf16_to_f32((uint16_t)(hi[q] & 0xFFFF));
+            const float r1 = xs[2 * q + 1] - bf16_to_f32((uint16_t)(hi[q] >> 16));
             lo[q] = pack_bf16x2(r0, r1);
         }
         const bf16x8 xh = __builtin_bit_cast(bf16x8, u32x4{hi[0], hi[1], hi[2], hi[3]});
         const bf16x8 xl = __builtin_bit_cast(bf16x8, u32x4{lo[0], lo[1], lo[2], lo[3]});
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xh, acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xl, acc, 0, 0, 0);
+    };
+    constexpr int U = 8;                             // steps whose loads are issued together
+    for (int s0 = s_begin; s0 < s_end; s0 += U) {
+        bf16x8 wf[U];
+        f32x4 x0[U], x1[U];
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const int s = s0 + u;
+            // a lane's 8 features of a step exist or do not (K is a multiple of 8); steps past this wave's share read nothing
+            const bool live = s < s_end && 16 * s + 8 * lhalf + 8 <= K;
+            wf[u] = bn_wload(wres, s < s_end ? wv : OOBV, s * 1024);
+            x0[u] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(xres, live ? xv : OOBV, s * 64, 0));
+            x1[u] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(xres, live ? xv : OOBV, s * 64 + 16, 0));
+        }
+#pragma unroll
+        for (int u = 0; u < U; u++) step(wf[u], x0[u], x1[u]);
     }
     if (wave > 0) {
 #pragma unroll
