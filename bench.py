@@ -51,6 +51,11 @@ def is_conv(name):
     return name.startswith(("conv", "bottleneck", "dense_layer", "stem"))
 
 
+def progress(msg):
+    """One line on stderr per finished phase (stdout carries the JSON line only)."""
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
 def measure(ens, cfg, n, steps, warmup, profile_steps, host_steps, matrix=None, segment=None):
     """Loads configuration `cfg`, installs its kept allocation and times `steps` requests of n images."""
     import torch
@@ -71,6 +76,7 @@ def measure(ens, cfg, n, steps, warmup, profile_steps, host_steps, matrix=None, 
     for _ in range(warmup):
         E.ens_predict(images, out)
     torch.cuda.synchronize()
+    progress("config %d: %d members loaded, %d warm-up steps done" % (cfg, len(nets), warmup))
     per_step = []
     t0 = time.perf_counter()
     for _ in range(steps):
@@ -79,6 +85,7 @@ def measure(ens, cfg, n, steps, warmup, profile_steps, host_steps, matrix=None, 
         per_step.append(time.perf_counter() - t1)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    progress("config %d: %d timed steps, %.1f images/s" % (cfg, steps, n * steps / dt))
     rec = dict(workload=WORKLOADS[cfg], members=[net.name for net in nets], request_images=n, allocation=matrix,
                segment_size=segment, allocation_source=kept["source"],
                value=round(n * steps / dt, 1), ms_per_step=round(dt / steps * 1e3, 3),
@@ -103,8 +110,9 @@ def measure(ens, cfg, n, steps, warmup, profile_steps, host_steps, matrix=None, 
     E.ens_set_profiling(1)
     prof = {}
     tp0 = time.perf_counter()
-    for _ in range(profile_steps):
+    for i in range(profile_steps):
         E.ens_predict(images, out)
+        progress("config %d: profiled step %d of %d" % (cfg, i + 1, profile_steps))
         for c in E.ens_profile():
             if not c["launches"]:
                 continue                             # a class some other batch size or pairing would use
@@ -215,6 +223,7 @@ def main():
         t0 = time.perf_counter()
         oracle.ensemble_predict(nets, blobs, x, real="f32")
         cdt = time.perf_counter() - t0
+        progress("CPU oracle: %d images in %.1f s" % (ns, cdt))
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
         cpu = dict(value=round(ns / cdt, 3), unit="images/s", cores=cores, kind="oracle",
                    sample="%d images of the request's distribution through all %d members" % (ns, len(nets)))

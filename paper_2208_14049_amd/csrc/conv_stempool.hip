@@ -13,8 +13,8 @@
 // sub-tile the workgroup takes the 3x3 maxima from there.  Zeros stand in for the pool's padding:
 // after a ReLU no value is below zero and every window holds at least one pixel.
 //
-// LDS rows of the tile are 128 bytes (64 channels); the 16-byte chunks of row q are swizzled by
-// q mod 8 so that a wavefront's stores (one row per lane) and the pool's loads spread over the banks.
+// LDS rows of the tile are 128 bytes (64 channels, half of the 64 banks); the 16-byte chunks of row q are
+// swizzled by (q / 2) mod 8 to spread a wavefront's stores (one row per lane) and the pool's loads over the banks.
 #include "conv_common.h"
 
 #include <type_traits>
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(256) void stem_pool_bf16(const ConvArgs* __restrict
                         o[e] = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2, pack_bf16x2(v0, v1)), z));
                     }
                     const u32x4 val = pout >= 0 ? u32x4{o[0], o[1], o[2], o[3]} : u32x4{0u, 0u, 0u, 0u};
-                    *(u32x4*)(row + ((((4 * i + 2 * k + lhalf) ^ (q0 & 7))) << 4)) = val;
+                    *(u32x4*)(row + ((((4 * i + 2 * k + lhalf) ^ ((q0 >> 1) & 7))) << 4)) = val;
                 }
         };
         for (int sub = 0; sub < nsub; sub++) run_sub(sub);
@@ -237,13 +237,17 @@ __global__ __launch_bounds__(256) void stem_pool_bf16(const ConvArgs* __restrict
             mx[j] = s16x8{0, 0, 0, 0, 0, 0, 0, 0};
             if (!task_ok[j]) continue;
             const int g = (t + 256 * j) & 7;
+            // neighbouring groups of 8 lanes read columns two apart: rows of the same bank half.  Every other
+            // group takes the three columns of its window in rotated order, so that the two never meet.
+            const int rot = ((t + 256 * j) >> 3) & 1;
 #pragma unroll
             for (int dr = 0; dr < 3; dr++)
 #pragma unroll
-                for (int dc = 0; dc < 3; dc++) {
+                for (int d3 = 0; d3 < 3; d3++) {
+                    const int dc = d3 + rot >= 3 ? d3 + rot - 3 : d3 + rot;
                     if (dc == 0 && task_left[j]) continue;       // left of the image: padding
                     const int q = task_q[j] + dr * W1 + dc;
-                    const s16x8 v = *(const s16x8*)(ctile + q * 128 + ((g ^ (q & 7)) << 4));
+                    const s16x8 v = *(const s16x8*)(ctile + q * 128 + ((g ^ ((q >> 1) & 7)) << 4));
                     mx[j] = __builtin_elementwise_max(mx[j], v); // non-negative bf16 values order like 16-bit integers
                 }
         }
