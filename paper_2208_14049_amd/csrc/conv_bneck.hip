@@ -90,17 +90,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     };
     load_w(w0, 0);
     if (nk1 > 1) load_w(w1, 1);
+    // biases and scales are asked for at once and stored behind the first input chunks' loads (a loop of load
+    // and store here would cost a round trip to memory per turn before the first input is asked for)
+    static_assert(C <= 256, "one thread per middle channel");
+    constexpr int NB3 = 2048 / 256;                              // the launcher admits up to 2048 output channels
+    const bool mid_ok = t < C;
+    const float b1_r = mid_ok ? ENS_GLOBAL(float, a1.bias)[t] : 0.f, s1_r = mid_ok ? ENS_GLOBAL(float, a1.scale)[t] : 0.f;
+    const float b2_r = mid_ok ? ENS_GLOBAL(float, a2.bias)[t] : 0.f, s2_r = mid_ok ? ENS_GLOBAL(float, a2.scale)[t] : 0.f;
+    float b3_r[NB3], s3_r[NB3];
+#pragma unroll
+    for (int j = 0; j < NB3; j++) {
+        const int i = t + 256 * j;
+        b3_r[j] = i < cout3 ? ENS_GLOBAL(float, a3.bias)[i] : 0.f;
+        s3_r[j] = i < cout3 ? ENS_GLOBAL(float, a3.scale)[i] : 0.f;
+    }
     raster_table(tbl, R, pp0 - (W1 + 1), PP, H1, W1, a1.H, a1.W);
-    for (int i = t; i < C; i += 256) {
-        b1l[i] = a1.bias[i];
-        b2l[i] = a2.bias[i];
-        b1l[SBS + i] = a1.scale[i];
-        b2l[SBS + i] = a2.scale[i];
-    }
-    for (int i = t; i < cout3; i += 256) {
-        b3l[i] = a3.bias[i];
-        b3l[SBS + i] = a3.scale[i];
-    }
     __syncthreads();
 
     // ---- load side.  Offsets past the end of a buffer give zeros in LDS (loads) or are dropped
@@ -154,6 +158,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             for (int j = 0; j < TP1; j++) bn_zero(acc[i][j]);
         issue_x(0, 0);
         if (nk1 > 1) issue_x(1, 1);
+        // the tables' first readers come behind the barriers of the chunk loop
+        if (mid_ok) {
+            b1l[t] = b1_r;
+            b2l[t] = b2_r;
+            b1l[SBS + t] = s1_r;
+            b2l[SBS + t] = s2_r;
+        }
+#pragma unroll
+        for (int j = 0; j < NB3; j++) {
+            const int i = t + 256 * j;
+            if (i < cout3) {
+                b3l[i] = b3_r[j];
+                b3l[SBS + i] = s3_r[j];
+            }
+        }
         // One chunk: `wc` holds its weights, `wl` receives those of chunk kc + 2, BUF is its place in the
         // ring.  The three roles rotate with period three, so the loop below is written out three chunks
         // at a time: a rotation through register copies would have to wait for the loads just issued.

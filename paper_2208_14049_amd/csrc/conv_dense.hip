@@ -9,8 +9,8 @@
 // raster (one extra column per row, one extra row per image, treated as zeros); a workgroup of
 // four wavefronts owns 128 consecutive positions.  Phase 1 computes the first layer on the R
 // positions the 3x3 taps of the tile reach, input in chunks of 32 channels through a three-deep
-// ring of asynchronous global-to-LDS loads with counted waits; the pre-activation is applied to
-// the pixel fragments between LDS and the matrix cores (its scale and shift wait in LDS); the
+// ring of asynchronous global-to-LDS loads with counted waits; the pre-activation is applied in
+// place to each chunk once it has landed (its scale and shift wait in LDS); the
 // result goes to LDS as bf16 in the window layout of the 3x3 kernels, zeros where the raster holds
 // no pixel.  Phase 2 is the nine taps, each wavefront 32 positions x 32 channels, stored from the
 // accumulators.  On small maps a workgroup owns 64 or 32 positions instead (phase 2 then occupies two
@@ -25,7 +25,7 @@ namespace ens {
 
 constexpr int DN_C = 128, DN_CO = 32, DN_MAXCIN = 2048;
 template <int R>
-constexpr int dn_big() { return 3 * R * 64 > 2 * R * 128 ? 3 * R * 64 : 2 * R * 128; }
+constexpr int dn_big() { return 4 * R * 64 > 2 * R * 128 ? 4 * R * 64 : 2 * R * 128; }   // ring of four input chunks, then the middle tensor
 
 template <int OFFSET>
 __device__ __forceinline__ f32x4 dn_lds_read_f4(uint32_t addr) {
@@ -34,6 +34,8 @@ __device__ __forceinline__ f32x4 dn_lds_read_f4(uint32_t addr) {
     return v;
 }
 __device__ __forceinline__ void dn_tie(f32x4& v) { asm volatile("" : "+v"(v)); }
+// written as an instruction so that the compiler does not order it against the asynchronous loads in flight
+__device__ __forceinline__ void dn_lds_write(uint32_t addr, const u32x4& v) { asm volatile("ds_write_b128 %0, %1" ::"v"(addr), "v"(v) : "memory"); }
 
 // argv: the argument blocks of the two convolutions, gridDim.z of each (one per member of the gang)
 template <int BP, int R>
@@ -84,19 +86,44 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     };
     load_w(w0, 0);
     if (nk1 > 1) load_w(w1, 1);
+    // Everything the tables need from memory is asked for at once (a round trip to memory is about 2000
+    // clocks: one per 256 input channels, as a loop of load and store, was a quarter of the kernel at 1888 channels);
+    // the window table is worked out while the answers travel.
+    constexpr int NPRE = DN_MAXCIN / 256;
+    float ps_r[NPRE], ph_r[NPRE];
+#pragma unroll
+    for (int j = 0; j < NPRE; j++) {
+        const int i = t + 256 * j;
+        ps_r[j] = i < cin1 ? ENS_GLOBAL(float, a1.pre_scale)[i] : 0.f;
+        ph_r[j] = i < cin1 ? ENS_GLOBAL(float, a1.pre_shift)[i] : 0.f;
+    }
+    const float bias_r = t < C ? ENS_GLOBAL(float, a1.bias)[t] : (t < C + DN_CO ? ENS_GLOBAL(float, a2.bias)[t - C] : 0.f);
+    const float scale_r = t < C ? ENS_GLOBAL(float, a1.scale)[t] : (t < C + DN_CO ? ENS_GLOBAL(float, a2.scale)[t - C] : 0.f);
+    // The 3x3 filter (72 KB, the same for every workgroup) is touched once, a line per lane, so that phase 2, which
+    // streams it a few steps ahead of its use, finds it in the L2 instead of waiting for memory step after step.
+    float touch = 0.f;
+    if (wave == 3) {
+        constexpr int W2B = 9 * C * DN_CO * 2;
+#pragma unroll
+        for (int i = 0; i < (W2B + 8191) / 8192; i++) {
+            const int off = i * 8192 + lane * 128;
+            if (off < W2B) touch += ENS_GLOBAL(float, a2.wpk)[off / 4];
+        }
+    }
     raster_table(tbl, R, pp0 - (W1 + 1), PP, H1, W1, a1.H, a1.W);
-    for (int i = t; i < C; i += 256) {
-        b1l[i] = a1.bias[i];
-        b1l[SBS + i] = a1.scale[i];
+    if (t < C + DN_CO) {                             // b1l[0..C), b2l[0..CO) lie in a row, and so do the scales SBS further on
+        b1l[t] = bias_r;
+        b1l[SBS + t] = scale_r;
     }
-    if (t < DN_CO) {
-        b2l[t] = a2.bias[t];
-        b2l[SBS + t] = a2.scale[t];
+#pragma unroll
+    for (int j = 0; j < NPRE; j++) {
+        const int i = t + 256 * j;
+        if (i < cin1) {
+            psl[i] = ps_r[j];
+            phl[i] = ph_r[j];
+        }
     }
-    for (int i = t; i < cin1; i += 256) {
-        psl[i] = a1.pre_scale[i];
-        phl[i] = a1.pre_shift[i];
-    }
+    asm volatile("" ::"v"(touch));                   // the touches only have to have been issued
     __syncthreads();
 
     // ---- load side.  Offsets past the end of a buffer give zeros in LDS (loads) or are dropped
@@ -114,7 +141,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         xvo[s] = p >= 0 ? (unsigned)(p * a1.x.stride * 2) + (unsigned)(a1.x.c0 * 2 + c4 * 16) : OOBV;
     }
     unsigned char* const mine = lds + wave * 1024;               // this wave's quarter of a 4 KB load
-    auto issue_x = [&](int buf, int kc) {
+    auto issue_x = [&](int buf, int kc) {                        // buf: place in the ring
 #pragma unroll
         for (int s = 0; s < XO; s++)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(xres, (lds_ptr_t)(mine + buf * XS + s * 4096), LDS_LOAD_BYTES, xvo[s], kc * 64, 0, 0);
@@ -125,13 +152,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const unsigned wv2 = (unsigned)(lane * 16);
     bf16x8 wq2[PW];
 
-    // ---- phase 1: the middle tensor over the window.  Chunk kc + 2 of the input and the weights of chunk
-    //      kc + 2 are asked for while chunk kc is used.  Loads complete in the order they were issued, so
-    //      the wait before a chunk is used counts what was issued after it and may still be on its way.
+    // ---- phase 1: the middle tensor over the window.  The input chunks come through a ring of four LDS
+    //      buffers: while the matrix cores work on chunk kc (already pre-activated), the same wavefront turns
+    //      its own pieces of chunk kc + 1 into relu(x * scale + shift) in place, and chunks kc + 2 and kc + 3
+    //      are on their way; the weights of chunk kc + 2 are asked for while chunk kc is used.  Loads complete
+    //      in the order they were issued, so a wait counts what was issued after the load it needs.
     {
         const int xr = row0 + lrow;
         const uint32_t psl0 = (uint32_t)(uintptr_t)(lds_ptr_t)psl;
         const uint32_t xs1 = lds0 + (uint32_t)(xr * 64 + ((lhalf ^ ((xr >> 2) & 3)) << 4));
+        const uint32_t own0 = lds0 + (uint32_t)(wave * 1024 + lane * 16);   // where this thread's piece of a 4 KB load lands
         f32x16 acc[TC1][TP1];
 #pragma unroll
         for (int i = 0; i < TC1; i++)
@@ -139,70 +169,125 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             for (int j = 0; j < TP1; j++) bn_zero(acc[i][j]);
         issue_x(0, 0);
         if (nk1 > 1) issue_x(1, 1);
-        // One chunk: `wc` holds its weights, `wl` receives those of chunk kc + 2, BUF is its place in the
-        // ring.  The three roles rotate with period three, so the loop below is written out three chunks
-        // at a time: a rotation through register copies would have to wait for the loads just issued.
-        auto chunk = [&](auto buf_c, bf16x8 (&wc)[2][TC1], bf16x8 (&wl)[2][TC1], const int kc) {
-            constexpr int buf = decltype(buf_c)::value;
-            if (kc == 0) {
-                if (nk1 > 1) bn_wait_vm<XO>(); else bn_wait_vm<0>();
-            } else {
-                if (kc + 1 < nk1) bn_wait_vm<WO + XO>(); else bn_wait_vm<0>();
+        if (nk1 > 2) issue_x(2, 2);
+        // a * XO + b * WO loads may still be in flight (fewer than allowed is always safe)
+        auto wait_vm = [&](int a, int b) {
+            if (a == 2 && b == 2) bn_wait_vm<2 * XO + 2 * WO>();
+            else if (a == 2 && b == 1) bn_wait_vm<2 * XO + WO>();
+            else if (a == 1 && b == 2) bn_wait_vm<XO + 2 * WO>();
+            else if (a == 2 && b == 0) bn_wait_vm<2 * XO>();
+            else if (a == 1 && b == 0) bn_wait_vm<XO>();
+            else if (a == 0 && b == 1) bn_wait_vm<WO>();
+            else bn_wait_vm<0>();
+        };
+        // The pre-activation, in place: every thread converts the 16-byte pieces its own loads brought in (the
+        // same 8 channels of XO rows).  Applied to the fragments on their way to the matrix cores instead, each
+        // value would be converted by both wavefronts that share its rows.
+        bf16x8 xv[XO];
+        f32x4 ps0, ps1, ph0, ph1;
+        auto pre_read = [&](int kc) {
+            const uint32_t pa = psl0 + (uint32_t)((kc * 32 + 8 * c4) * 4), ha = pa + (uint32_t)(cin1 * 4);
+            ps0 = dn_lds_read_f4<0>(pa); ps1 = dn_lds_read_f4<16>(pa);
+            ph0 = dn_lds_read_f4<0>(ha); ph1 = dn_lds_read_f4<16>(ha);
+            const uint32_t own = own0 + (uint32_t)((kc & 3) * XS);
+            bn_unroll<XO>([&](auto sc) { xv[decltype(sc)::value] = bn_lds_read<decltype(sc)::value * 4096>(own); });
+        };
+        auto pre_tie = [&]() {
+            dn_tie(ps0); dn_tie(ps1); dn_tie(ph0); dn_tie(ph1);
+#pragma unroll
+            for (int x = 0; x < XO; x++) bn_tie(xv[x]);
+        };
+        auto pre_math = [&]() {
+            const float sc[8] = {ps0[0], ps0[1], ps0[2], ps0[3], ps1[0], ps1[1], ps1[2], ps1[3]};
+            const float sh[8] = {ph0[0], ph0[1], ph0[2], ph0[3], ph1[0], ph1[1], ph1[2], ph1[3]};
+#pragma unroll
+            for (int x = 0; x < XO; x++) {
+                u32x4 u = __builtin_bit_cast(u32x4, xv[x]);
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const float lo = __uint_as_float(u[q] << 16), hi = __uint_as_float(u[q] & 0xFFFF0000u);
+                    typedef short s16x2 __attribute__((ext_vector_type(2)));
+                    const s16x2 z = {0, 0};                      // relu on the rounded pair: a negative bf16 is a negative 16-bit integer
+                    u[q] = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(
+                        __builtin_bit_cast(s16x2, pack_bf16x2(fmaf(lo, sc[2 * q], sh[2 * q]), fmaf(hi, sc[2 * q + 1], sh[2 * q + 1]))), z));
+                }
+                xv[x] = __builtin_bit_cast(bf16x8, u);
             }
-            __builtin_amdgcn_s_barrier();
-            if (kc + 2 < nk1) {
-                load_w(wl, kc + 2);
-                issue_x((buf + 2) % 3, kc + 2);
-            }
-            // scale and shift of this lane's 8 channels in each of the chunk's two steps
-            // (read with the fragments, behind the barrier: read any earlier they would only occupy registers)
-            f32x4 ps[2][2], ph[2][2];
-            const uint32_t pa = psl0 + (uint32_t)((kc * 32 + 8 * lhalf) * 4), ha = pa + (uint32_t)(cin1 * 4);
-            ps[0][0] = dn_lds_read_f4<0>(pa); ps[0][1] = dn_lds_read_f4<16>(pa);
-            ps[1][0] = dn_lds_read_f4<64>(pa); ps[1][1] = dn_lds_read_f4<80>(pa);
-            ph[0][0] = dn_lds_read_f4<0>(ha); ph[0][1] = dn_lds_read_f4<16>(ha);
-            ph[1][0] = dn_lds_read_f4<64>(ha); ph[1][1] = dn_lds_read_f4<80>(ha);
-            const uint32_t xs = xs1 + (uint32_t)(buf * XS);
+        };
+        auto pre_write = [&](int kc) {
+            const uint32_t own = own0 + (uint32_t)((kc & 3) * XS);
+#pragma unroll
+            for (int x = 0; x < XO; x++) dn_lds_write(own + (uint32_t)(x * 4096), __builtin_bit_cast(u32x4, xv[x]));
+        };
+        // chunk 0 is converted before the loop
+        wait_vm((nk1 > 1) + (nk1 > 2), 0);
+        pre_read(0);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        pre_tie();
+        pre_math();
+        pre_write(0);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        // One chunk: `wc` holds its weights, `wl` receives those of chunk kc + 2.  The roles of the three weight
+        // sets rotate with period three, so the loop below is written out three chunks at a time: a rotation
+        // through register copies would have to wait for the loads just issued.
+        // `steady`: chunk kc + 3 exists, so every load is issued and the wait is one constant (with
+        // conditional loads in the loop the compiler's own waits for the weight registers assume the path
+        // on which nothing was issued, and wait for everything).
+        auto chunk = [&](auto mode_c, bf16x8 (&wc)[2][TC1], bf16x8 (&wl)[2][TC1], const int kc) {
+            constexpr bool steady = decltype(mode_c)::value > 0, first = decltype(mode_c)::value == 2;
+            // behind the barrier: chunk kc is converted, nobody reads chunk kc - 1 any more
+            if (steady || kc + 3 < nk1) issue_x((kc + 3) & 3, kc + 3);
+            if (steady || kc + 2 < nk1) load_w(wl, kc + 2);
+            const uint32_t xs = xs1 + (uint32_t)((kc & 3) * XS);
             bf16x8 xf[2][TP1];
             bn_unroll<TP1>([&](auto j) { xf[0][decltype(j)::value] = bn_lds_read<decltype(j)::value * 2048>(xs); });
             bn_unroll<TP1>([&](auto j) { xf[1][decltype(j)::value] = bn_lds_read<decltype(j)::value * 2048>(xs ^ 32u); });
+            // the loads of chunk kc + 1 have landed: issued after them are the loads of chunks kc + 2 and kc + 3
+            // and the weights of chunks kc + 1 (from chunk 1 on: the first two sets are asked for up front) and kc + 2
+            if (first) bn_wait_vm<2 * XO + WO>();
+            else if (steady) bn_wait_vm<2 * XO + 2 * WO>();
+            else wait_vm((kc + 2 < nk1) + (kc + 3 < nk1), (kc + 2 < nk1) + (kc >= 1 && kc + 1 < nk1));
+            const int kn = steady || kc + 1 < nk1 ? kc + 1 : kc; // after the last chunk: converted again, not written
+            pre_read(kn);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
             for (int ks = 0; ks < 2; ks++)
 #pragma unroll
-                for (int q = 0; q < 2; q++) {
-                    dn_tie(ps[ks][q]);
-                    dn_tie(ph[ks][q]);
-                }
+                for (int j = 0; j < TP1; j++) bn_tie(xf[ks][j]);
+            pre_tie();
+            // matrix-core work on chunk kc and vector work on chunk kc + 1, independent of each other
 #pragma unroll
-            for (int ks = 0; ks < 2; ks++) {
-#pragma unroll
-                for (int j = 0; j < TP1; j++) {
-                    bn_tie(xf[ks][j]);
-                    u32x4 u = __builtin_bit_cast(u32x4, xf[ks][j]);
-#pragma unroll
-                    for (int q = 0; q < 4; q++) {
-                        const float lo = __uint_as_float(u[q] << 16), hi = __uint_as_float(u[q] & 0xFFFF0000u);
-                        const float sl = ps[ks][q >> 1][(2 * q) & 3], sh = ps[ks][q >> 1][(2 * q + 1) & 3];
-                        const float hl = ph[ks][q >> 1][(2 * q) & 3], hh = ph[ks][q >> 1][(2 * q + 1) & 3];
-                        u[q] = pack_bf16x2(fmaxf(fmaf(lo, sl, hl), 0.f), fmaxf(fmaf(hi, sh, hh), 0.f));
-                    }
-                    xf[ks][j] = __builtin_bit_cast(bf16x8, u);
-                }
+            for (int ks = 0; ks < 2; ks++)
 #pragma unroll
                 for (int i = 0; i < TC1; i++)
 #pragma unroll
                     for (int j = 0; j < TP1; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[ks][i], xf[ks][j], acc[i][j], 0, 0, 0);
-            }
+            pre_math();
+            if (steady || kc + 1 < nk1) pre_write(kn);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
         };
+        constexpr std::integral_constant<int, 0> near_the_end{};
+        constexpr std::integral_constant<int, 1> all_there{};
+        constexpr std::integral_constant<int, 2> all_there_first{};  // chunk 0: the weights of chunk 1 were asked for up front
         int kc = 0;
-        for (; kc + 2 < nk1; kc += 3) {
-            chunk(std::integral_constant<int, 0>{}, w0, w2, kc);
-            chunk(std::integral_constant<int, 1>{}, w1, w0, kc + 1);
-            chunk(std::integral_constant<int, 2>{}, w2, w1, kc + 2);
+        if (nk1 > 5) {                                           // chunks 0 to 2 of a long input: the same code as the loop's
+            chunk(all_there_first, w0, w2, 0);
+            chunk(all_there, w1, w0, 1);
+            chunk(all_there, w2, w1, 2);
+            kc = 3;
         }
-        if (kc < nk1) chunk(std::integral_constant<int, 0>{}, w0, w2, kc);
-        if (kc + 1 < nk1) chunk(std::integral_constant<int, 1>{}, w1, w0, kc + 1);
+        for (; kc + 5 < nk1; kc += 3) {
+            chunk(all_there, w0, w2, kc);
+            chunk(all_there, w1, w0, kc + 1);
+            chunk(all_there, w2, w1, kc + 2);
+        }
+        for (; kc < nk1; kc += 3) {
+            chunk(near_the_end, w0, w2, kc);
+            if (kc + 1 < nk1) chunk(near_the_end, w1, w0, kc + 1);
+            if (kc + 2 < nk1) chunk(near_the_end, w2, w1, kc + 2);
+        }
         if (wave < BP / 32) {                                    // the wavefronts that take part in phase 2
 #pragma unroll
             for (int s = 0; s < PW; s++) wq2[s] = bn_wload(w2res, wv2, s * 1024);

@@ -96,22 +96,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
     for (int j = 0; j < TP; j++) bn_zero(acc[j]);
     // bias and scale of the tile's BC channels wait in LDS behind the ring (zeros and ones past the last
-    // channel); the first barrier of the chunk loop comes between this write and the epilogue's reads
+    // channel).  They are asked for here and stored once the first input chunks are on their way: a store
+    // right here would hold those back by a round trip to memory.
     float* const sbl = (float*)(lds + PW_NXB * XS);
-    if (t < BC) {
-        const bool ok = c0 + t < a.cout;
-        sbl[t] = ok ? a.bias[c0 + t] : 0.f;
-        sbl[BC + t] = ok ? a.scale[c0 + t] : 1.f;
-    }
+    const bool sb_ok = t < BC && c0 + t < a.cout;
+    const float bias_r = sb_ok ? ENS_GLOBAL(float, a.bias)[c0 + t] : 0.f;
+    const float scale_r = sb_ok ? ENS_GLOBAL(float, a.scale)[c0 + t] : 1.f;
     float* const gl = sbl + 2 * 128;                 // GATE: [image of the tile][nk * 64] gates, zeros past the last channel
     int grow[TP];                                    // GATE: this lane's first gate of pixel row j, less the chunk's offset
+    const int HW = a.H * a.W, cinp = nk * 64;
+    const int n_first = p0 / HW, n_last = min(p0 + BP - 1, P - 1) / HW;
     if constexpr (GATE) {
-        const int HW = a.H * a.W, cinp = nk * 64;
-        const int n_first = p0 / HW, n_last = min(p0 + BP - 1, P - 1) / HW;
-        for (int i = t; i < gimg * cinp; i += 256) {
-            const int img = i / cinp, c = i - img * cinp;
-            gl[i] = (c < a.cin && n_first + img <= n_last) ? a.gate[(long long)(n_first + img) * a.gate_stride + c] : 0.f;
-        }
 #pragma unroll
         for (int j = 0; j < TP; j++) grow[j] = (min(p0 + wp0 + 32 * j + lrow, P - 1) / HW - n_first) * cinp + 8 * lhalf;
     }
@@ -138,6 +133,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     };
     issue_x(0, 0);
     if (nk > 1) issue_x(1, 1);
+    // the first barrier of the chunk loop comes between these writes and their readers
+    if (t < BC) {
+        sbl[t] = bias_r;
+        sbl[BC + t] = scale_r;
+    }
+    if constexpr (GATE) {
+        // the gates of the tile's images, sixteen loads in flight per thread (one at a time, the table of a
+        // 2688-channel layer over four images was forty round trips to memory)
+        const int n_g = gimg * cinp;
+        for (int i0 = t; i0 < n_g; i0 += 256 * 16) {
+            float g[16];
+#pragma unroll
+            for (int u = 0; u < 16; u++) {
+                const int i = i0 + 256 * u;
+                const int img = i / cinp, c = i - img * cinp;
+                g[u] = (i < n_g && c < a.cin && n_first + img <= n_last) ? ENS_GLOBAL(float, a.gate)[(long long)(n_first + img) * a.gate_stride + c] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 16; u++)
+                if (i0 + 256 * u < n_g) gl[i0 + 256 * u] = g[u];
+        }
+    }
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
     const int xr = wp0 + lrow;
