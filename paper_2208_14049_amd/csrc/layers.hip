@@ -762,11 +762,18 @@ constexpr int SE_SCALE_BYTES = 32768;   // about what a workgroup of the last ke
 // small FC layers (SiLU, sigmoid) with all threads on the first one.
 __device__ __forceinline__ void se_gate(const SeArgs& a, const int n, const int splits, float* mean, float* red, float* z, float* gate) {
     const int t = threadIdx.x;
+    // Every loop below asks for a batch of values before it uses the first: a round trip to memory is about
+    // 2000 clocks, and taken one load at a time the sums, the two weight matrices and the biases were some
+    // thirty of them in a row (18 us per launch for a few ten thousand multiply-adds).
     const float* part = a.scratch + (long long)n * se_scratch_floats(a.c, a.r);   // partial sums of the image
     const float inv = 1.f / (float)a.HW;
     for (int c = t; c < a.c; c += SE_GATE_THREADS) {
+        float v[SE_MAX_SPLITS];
+#pragma unroll
+        for (int k = 0; k < SE_MAX_SPLITS; k++) v[k] = k < splits ? part[(long long)k * a.c + c] : 0.f;
         float m = 0.f;
-        for (int k = 0; k < splits; k++) m += part[(long long)k * a.c + c];   // fixed order
+#pragma unroll
+        for (int k = 0; k < SE_MAX_SPLITS; k++) m += v[k];       // fixed order; the terms past the last split are zeros
         mean[c] = m * inv;
     }
     __syncthreads();
@@ -778,8 +785,20 @@ __device__ __forceinline__ void se_gate(const SeArgs& a, const int n, const int 
         const int r = r0 + t % rp, slice = t / rp;
         float acc = 0.f;
         if (r < a.r) {
-#pragma unroll 8
-            for (int c = slice; c < a.c; c += slices) acc = fmaf(mean[c], a.w1[(long long)c * a.r + r], acc);
+            constexpr int U = 16;
+            for (int c0 = slice; c0 < a.c; c0 += slices * U) {
+                float w[U];
+#pragma unroll
+                for (int u = 0; u < U; u++) {
+                    const int c = c0 + u * slices;
+                    w[u] = c < a.c ? a.w1[(long long)c * a.r + r] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < U; u++) {
+                    const int c = c0 + u * slices;
+                    acc = fmaf(c < a.c ? mean[c] : 0.f, w[u], acc);
+                }
+            }
         }
         red[t] = acc;
         __syncthreads();
@@ -792,8 +811,14 @@ __device__ __forceinline__ void se_gate(const SeArgs& a, const int n, const int 
     }
     for (int c = t; c < a.c; c += SE_GATE_THREADS) {
         float acc = a.b2[c];
-#pragma unroll 8
-        for (int r = 0; r < a.r; r++) acc = fmaf(z[r], a.w2[(long long)r * a.c + c], acc);
+        constexpr int U = 16;
+        for (int r0 = 0; r0 < a.r; r0 += U) {
+            float w[U];
+#pragma unroll
+            for (int u = 0; u < U; u++) w[u] = r0 + u < a.r ? a.w2[(long long)(r0 + u) * a.c + c] : 0.f;
+#pragma unroll
+            for (int u = 0; u < U; u++) acc = fmaf(r0 + u < a.r ? z[r0 + u] : 0.f, w[u], acc);
+        }
         gate[c] = 1.f / (1.f + __expf(-acc));
     }
     __syncthreads();
