@@ -14,11 +14,14 @@ __device__ __forceinline__ uint16_t f2bf(float f) {
     u += 0x7FFFu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
 }
+// fp32 members: the exponential at full precision (the fast one is for results that are rounded to bf16)
 __device__ __forceinline__ float act_f(float v, int act) {
     if (act == ACT_RELU) return fmaxf(v, 0.f);
-    if (act == ACT_SILU) return v / (1.f + __expf(-v));
+    if (act == ACT_SILU) return v / (1.f + expf(-v));
     return v;
 }
+template <bool FAST>
+__device__ __forceinline__ float exp_neg(float v) { return FAST ? __expf(-v) : expf(-v); }
 __device__ __forceinline__ void unpack8(const uint4 v, float* f) {
     const uint32_t u[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -264,7 +267,7 @@ __global__ void window_kernel(const PoolArgs* __restrict__ argv, const int nb_) 
         for (int e = 0; e < V; e++) acc[e] = fmaf(acc[e], a.scale[c + e], a.bias[c + e]);
         if (a.act == ACT_SILU) {
 #pragma unroll
-            for (int e = 0; e < V; e++) acc[e] = acc[e] / (1.f + __expf(-acc[e]));
+            for (int e = 0; e < V; e++) acc[e] = acc[e] / (1.f + exp_neg<BF16>(acc[e]));
         } else {
             const bool relu = a.act == ACT_RELU;
 #pragma unroll
@@ -760,6 +763,7 @@ constexpr int SE_SCALE_BYTES = 32768;   // about what a workgroup of the last ke
 
 // The gate of image n into LDS (`gate`): the partial sums added in a fixed order, then the two
 // small FC layers (SiLU, sigmoid) with all threads on the first one.
+template <bool FAST>
 __device__ __forceinline__ void se_gate(const SeArgs& a, const int n, const int splits, float* mean, float* red, float* z, float* gate) {
     const int t = threadIdx.x;
     // Every loop below asks for a batch of values before it uses the first: a round trip to memory is about
@@ -805,7 +809,7 @@ __device__ __forceinline__ void se_gate(const SeArgs& a, const int n, const int 
         if (t < rp && r < a.r) {
             float sum = a.b1[r];
             for (int k = 0; k < slices; k++) sum += red[k * rp + t];
-            z[r] = sum / (1.f + __expf(-sum));
+            z[r] = sum / (1.f + exp_neg<FAST>(sum));
         }
         __syncthreads();
     }
@@ -819,7 +823,7 @@ __device__ __forceinline__ void se_gate(const SeArgs& a, const int n, const int 
 #pragma unroll
             for (int u = 0; u < U; u++) acc = fmaf(r0 + u < a.r ? z[r0 + u] : 0.f, w[u], acc);
         }
-        gate[c] = 1.f / (1.f + __expf(-acc));
+        gate[c] = 1.f / (1.f + exp_neg<FAST>(acc));
     }
     __syncthreads();
 }
@@ -835,7 +839,7 @@ __global__ __launch_bounds__(SE_GATE_THREADS) void se_gate_scale_kernel(const Se
     __shared__ float red[SE_GATE_THREADS];
     __shared__ float z[256];
     const int n = blockIdx.y;
-    se_gate(a, n, splits, mean, red, z, gate);
+    se_gate<BF16>(a, n, splits, mean, red, z, gate);
     constexpr int V = BF16 ? 8 : 1;
     const int cv = a.c / V;
     const int per = (a.HW + (int)gridDim.x - 1) / (int)gridDim.x;
@@ -867,7 +871,7 @@ __global__ __launch_bounds__(SE_GATE_THREADS) void se_gate_only_kernel(const SeA
     __shared__ float red[SE_GATE_THREADS];
     __shared__ float z[256];
     const int n = blockIdx.y;
-    se_gate(a, n, splits, mean, red, z, gate);
+    se_gate<true>(a, n, splits, mean, red, z, gate);        // bf16 members only
     float* out = a.scratch + (long long)n * se_scratch_floats(a.c, a.r) + se_gate_offset(a.c, a.r);
     for (int c = threadIdx.x; c < a.c; c += SE_GATE_THREADS) out[c] = gate[c];
 }
