@@ -35,7 +35,12 @@ CPU_SAMPLE = {2: 16, 3: 16, 4: 12, 5: 16}      # images the oracle is timed on (
 # HBM bytes per launch of a kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (scaled by the plain-copy calibration given there).  An entry describes the kernel sources
 # with the digest recorded with it; with any other sources the figure is withheld (null).
-TRAFFIC = {}
+TRAFFIC = {
+    (4, "conv1x1_direct_bf16<128x128>"): dict(
+        bytes_per_launch=98.6e6,                 # 55.4 MB read + 43.2 MB written (profiles/bench_config4_12members_b128.md)
+        sources=["conv_pw.hip", "conv_direct.h", "conv_common.h", "kernels.h"],
+        sha256="267cd64839435198368dcc6ed859897cfcd86bb0a5b1b95699af6f388a1a4d6b"),
+}
 
 
 def sources_digest(names):
