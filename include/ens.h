@@ -126,8 +126,10 @@ typedef struct {
 typedef struct ens_handle ens_handle;
 
 /* ---- life cycle ----------------------------------------------------------------------------
- * ens_load: section "Inference frameworks" ("load" puts a trained DNN on a device).  Folds the
- * batch-norms into the weights, converts to the member's dtype and uploads them.  Parameters
+ * ens_load: section "Inference frameworks" ("load" puts a trained DNN on a device).  Turns every
+ * batch-norm into a scale and a bias per output channel (fp32 members: the scale goes into the
+ * weights; bf16 members keep the weights as given and apply the fp32 scale to the sum), converts
+ * to the member's dtype and uploads.  Parameters
  * come from spec.params, or are drawn from `seed` (member index, parameter index) with the
  * library's counter-based generator when spec.params is NULL.  On ENS_E_NOMEM nothing stays
  * allocated.  *out is the new handle.
@@ -173,7 +175,9 @@ int ens_bench(ens_handle* h, const ens_alloc* a, int32_t segment_size, int64_t n
  *   images   : n x base_h x base_w x 3 fp32 (host or device, see ens_set_io)
  *   probs_out: n x classes fp32, written completely before the call returns
  * Needs an installed allocation (ens_plan or ens_set_alloc); without one, every member gets one
- * worker of batch size 8.
+ * worker of batch size 8.  A call with a larger n than any before it (or with another device
+ * image pointer) allocates device memory and rewrites argument blocks before it starts;
+ * ens_predict_static below never allocates.
  */
 int ens_predict(ens_handle* h, const float* images, int64_t n, float* probs_out);
 
