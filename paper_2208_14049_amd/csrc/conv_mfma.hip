@@ -46,6 +46,12 @@ __device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr) {
     return v;
 }
 
+// Bytes of the ring of a tile shape: NS stages of (BP + BC) rows, or the first chunk of the staged output tile if larger.
+template <int BP, int BC, int NS, int BKT>
+constexpr int igemm_ring_bytes() {
+    return NS * (BP + BC) * BKT * 2 > 32 * (BC + 4) * 4 ? NS * (BP + BC) * BKT * 2 : 32 * (BC + 4) * 4;
+}
+
 template <int BP, int BC, int WP, int WC, int NS, int BKT, bool PRE = false>
 __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restrict__ argv, const int nb_) {
     ConvArgs a = argv[blockIdx.z];
@@ -66,12 +72,12 @@ __global__ __launch_bounds__(256) void conv_igemm_bf16(const ConvArgs* __restric
     static_assert(NS >= 2 && (NS - 2) * NLOAD <= 63, "outstanding loads must fit the wait counter");
 
     constexpr int OROW = BC + 4;                     // floats per pixel row of the staged output tile
-    constexpr int RING = NS * STAGE > 32 * OROW * 4 ? NS * STAGE : 32 * OROW * 4;
+    constexpr int RING = igemm_ring_bytes<BP, BC, NS, BKT>();
     // the output tile is staged through the ring in chunks of HROWS pixel rows
     constexpr int HFIT = RING / (OROW * 4) / 32 * 32;
     constexpr int HROWS = HFIT >= BP ? BP : (HFIT >= BP / 2 ? BP / 2 : (HFIT >= BP / 4 ? BP / 4 : 32));
     static_assert(HROWS >= 32 && BP % HROWS == 0 && HROWS * OROW * 4 <= RING, "output staging chunk");
-    __shared__ __attribute__((aligned(1024))) unsigned char ring[RING];
+    extern __shared__ __attribute__((aligned(1024))) unsigned char ring[];   // RING bytes, given at the launch
     // PRE (1x1 layers with a pre-activation): relu(x * scale + shift) per input channel is applied to
     // the pixel fragments on their way from LDS to the matrix cores; scale and shift of all K
     // channels wait in LDS (zero past K, so the zero-filled K tail stays zero).
@@ -416,6 +422,7 @@ static const Variant VARIANTS[] = {
     {64, 64, 32, "conv_igemm_bf16<64,64,k32>"},      // small grids, shallow K
     {128, 64, 64, "conv_igemm_bf16<128,64,k64>"},    // grids that fill the chip, deep K
     {128, 64, 32, "conv_igemm_bf16<128,64,k32>"},    // grids that fill the chip, shallow K
+    {128, 128, 64, "conv_igemm_bf16<128,128,k64>"},  // many pixels, wide outputs, deep K: a third less load traffic per flop
 };
 
 // A gang of G members multiplies the grid by G.  When 128x64 tiles still give two workgroups per
@@ -424,6 +431,8 @@ static const Variant VARIANTS[] = {
 static int pick_variant(const ConvArgs& a, long long P, long long K, int G) {
     if (a.cout <= 32) return 0;
     const long long t12864 = G * ((P + 127) / 128) * ((a.cout + 63) / 64);
+    const long long t128128 = G * ((P + 127) / 128) * ((a.cout + 127) / 128);
+    if (a.cout % 128 == 0 && K > 640 && t128128 >= 3 * cu_budget()) return 5;   // no channel tile half empty
     if (t12864 >= 2 * cu_budget()) return K <= 640 ? 4 : 3;
     return K <= 256 ? 2 : 1;
 }
@@ -463,12 +472,28 @@ const char* conv_bf16_variant_name(const ConvArgs& a, int G) {
 template <int BP, int BC, int WP, int WC, int NS, int BKT = 64>
 static hipError_t launch_variant(const ConvArgs& a, const ConvArgs* argv, int G, int nb, int P, int splits, hipStream_t s) {
     const dim3 grid(((P + BP - 1) / BP) * ((a.cout + BC - 1) / BC), splits, G);
+    constexpr int ring = igemm_ring_bytes<BP, BC, NS, BKT>();
+    // LDS above 64 KB (the ring plus the kernel's own tables) has to be asked for once per kernel
+    auto raise = [&](const void* kernel, bool& raised) -> hipError_t {
+        if (raised) return hipSuccess;
+        hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, ring);
+        raised = e == hipSuccess;
+        return e;
+    };
     if (a.pre_scale) {                                           // pre-activated 1x1: no K split (the launcher asks for none)
-        ENS_LAUNCH((conv_igemm_bf16<BP, BC, WP, WC, NS, BKT, true>), grid, dim3(256), 0, s, argv, nb);
+        if constexpr (ring + 2 * (PRE_MAXK + 64) * 4 > 64 * 1024) {
+            static bool raised = false;
+            if (hipError_t e = raise((const void*)&conv_igemm_bf16<BP, BC, WP, WC, NS, BKT, true>, raised); e != hipSuccess) return e;
+        }
+        ENS_LAUNCH((conv_igemm_bf16<BP, BC, WP, WC, NS, BKT, true>), grid, dim3(256), ring, s, argv, nb);
         return hipGetLastError();
     }
-    if (splits > 1) ENS_LAUNCH_FIRST((conv_igemm_bf16<BP, BC, WP, WC, NS, BKT>), grid, dim3(256), 0, s, argv, nb);
-    else ENS_LAUNCH((conv_igemm_bf16<BP, BC, WP, WC, NS, BKT>), grid, dim3(256), 0, s, argv, nb);
+    if constexpr (ring + 64 > 64 * 1024) {
+        static bool raised = false;
+        if (hipError_t e = raise((const void*)&conv_igemm_bf16<BP, BC, WP, WC, NS, BKT>, raised); e != hipSuccess) return e;
+    }
+    if (splits > 1) ENS_LAUNCH_FIRST((conv_igemm_bf16<BP, BC, WP, WC, NS, BKT>), grid, dim3(256), ring, s, argv, nb);
+    else ENS_LAUNCH((conv_igemm_bf16<BP, BC, WP, WC, NS, BKT>), grid, dim3(256), ring, s, argv, nb);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && splits > 1) e = launch_conv_splitk_epilogue(a, argv, G, nb, P, splits, s);
     return e;
@@ -500,6 +525,8 @@ hipError_t launch_conv_bf16(const ConvArgs& a, const ConvArgs* argv, int G, int 
         case 2: return launch_variant<64, 64, 2, 2, 2, 32>(a, argv, G, nb, P, splits, s);
         case 3: return launch_variant<128, 64, 2, 2, 2, 64>(a, argv, G, nb, P, splits, s);
         case 4: return launch_variant<128, 64, 2, 2, 2, 32>(a, argv, G, nb, P, splits, s);
+        case 5: return a.pre_scale ? launch_variant<128, 64, 2, 2, 2, 64>(a, argv, G, nb, P, splits, s)
+                                   : launch_variant<128, 128, 2, 2, 2, 64>(a, argv, G, nb, P, splits, s);
         default: return launch_variant<64, 64, 2, 2, 2, 64>(a, argv, G, nb, P, splits, s);
     }
 }
