@@ -1,4 +1,4 @@
-// 1x1, stride-1 convolution on the CDNA4 matrix cores with the weights taken straight from memory
+// 1x1 convolution (stride 1, or a stride without padding: the shortcuts of residual stages) on the CDNA4 matrix cores with the weights taken straight from memory
 // in matrix-core operand order (conv_direct.h): the 1x1 layers of residual bottlenecks that do not
 // run inside the fused bottleneck kernel, the expansion and projection layers of inverted-residual
 // blocks, the pointwise halves of separable convolutions.  Channel counts are multiples of 8; the
@@ -37,7 +37,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     static_assert(WPX == 1 || WPX == 2, "one or two wavefronts along the pixels");
     constexpr int BP = PW_BP, WCG = 4 / WPX, TP = BP / (32 * WPX), BC = 32 * WCG, XS = PW_XS;
     constexpr int XO = BP / 32, WO = 4;              // loads per thread and chunk: input rows, weight fragments
-    const int P = nb_ * a.H * a.W;
+    const int P = nb_ * a.Ho * a.Wo;                 // output pixels (the input's too, unless the layer has a stride)
     const int t = threadIdx.x, lane = t & 63, lrow = lane & 31, lhalf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int n_ptiles = (P + BP - 1) / BP, n_ctiles = (a.cout + BC - 1) / BC;
@@ -112,13 +112,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
 
     // ---- input chunks: thread t fills chunk slot t % 8 of rows t / 8 + 32 s with the swizzled chunk
-    const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc((void*)a.x.p, 0, (int)(npix * (unsigned)a.x.stride * 2u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)a.x.p, 0, (int)((unsigned)nb_ * (unsigned)(a.H * a.W) * (unsigned)a.x.stride * 2u), 0x00020000);
     const int r8 = t >> 3, c8 = (t & 7) ^ ((r8 >> 1) & 7);
+    const bool strided = a.sh != 1 || a.sw != 1;
     unsigned xvo[XO];
 #pragma unroll
     for (int s = 0; s < XO; s++) {
         const int p = p0 + r8 + 32 * s;
-        xvo[s] = p < P ? (unsigned)(p * a.x.stride * 2) + (unsigned)(a.x.c0 * 2 + c8 * 16) : OOBV;
+        int pin = p;                                 // the input pixel of output pixel p
+        if (strided && p < P) {
+            // p -> (image, row, column) with one double multiply per division and a correction step
+            int n = (int)((double)p * a.inv_hw);
+            int rem = p - n * (a.Ho * a.Wo);
+            if (rem < 0) { n--; rem += a.Ho * a.Wo; } else if (rem >= a.Ho * a.Wo) { n++; rem -= a.Ho * a.Wo; }
+            int ho = (int)((double)rem * a.inv_w);
+            int wo = rem - ho * a.Wo;
+            if (wo < 0) { ho--; wo += a.Wo; } else if (wo >= a.Wo) { ho++; wo -= a.Wo; }
+            pin = (n * a.H + ho * a.sh) * a.W + wo * a.sw;
+        }
+        xvo[s] = p < P ? (unsigned)(pin * a.x.stride * 2) + (unsigned)(a.x.c0 * 2 + c8 * 16) : OOBV;
     }
     // in the last chunk of a layer whose input channels are not a multiple of 64 this thread's 8 channels
     // may lie past the last one: zeros then (what follows them in memory belongs to the next pixel)
@@ -239,11 +252,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
 // ---- host side -----------------------------------------------------------------------------
 static bool pw_shape_ok(const ConvArgs& a, int nb) {
-    if (a.kh != 1 || a.kw != 1 || a.sh != 1 || a.sw != 1 || a.pt != 0 || a.pl != 0 || a.Ho != a.H || a.Wo != a.W) return false;
+    if (a.kh != 1 || a.kw != 1 || a.pt != 0 || a.pl != 0 || a.sh < 1 || a.sw < 1) return false;
+    if (a.Ho != (a.H - 1) / a.sh + 1 || a.Wo != (a.W - 1) / a.sw + 1) return false;
+    if ((a.sh != 1 || a.sw != 1) && a.gate) return false;       // the gates are looked up by the input's image, which a tile finds from its output pixels
     if (a.pre_scale || !a.wpk || a.cin % 8 || a.cout % 8) return false;
     // 32-bit byte offsets with 2^31 standing for 'outside'
-    const long long P = (long long)nb * a.H * a.W;
-    if (P * a.x.stride * 2 >= 0x7FFFFF00LL || P * a.y.stride * 2 >= 0x7FFFFF00LL) return false;
+    const long long P = (long long)nb * a.Ho * a.Wo, Pin = (long long)nb * a.H * a.W;
+    if (Pin * a.x.stride * 2 >= 0x7FFFFF00LL || P * a.y.stride * 2 >= 0x7FFFFF00LL) return false;
     if (a.res.p && P * a.res.stride * 2 >= 0x7FFFFF00LL) return false;
     if ((long long)(a.cout + 31) * (a.cin + 63) * 2 >= 0x7FFFFF00LL) return false;
     if (a.x.stride % 8 || a.x.c0 % 8 || a.y.stride % 8 || a.y.c0 % 8) return false;
@@ -267,7 +282,7 @@ bool conv_pw_applicable(const ConvArgs& a, int nb, int G) {
 template <int WPX, bool GATE>
 static hipError_t launch_pw_variant(const ConvArgs& a, const ConvArgs* argv, int G, int nb, hipStream_t s) {
     constexpr int BC = 32 * (4 / WPX);
-    const long long P = (long long)nb * a.H * a.W;
+    const long long P = (long long)nb * a.Ho * a.Wo;
     const dim3 grid((unsigned)(((P + PW_BP - 1) / PW_BP) * ((a.cout + BC - 1) / BC)), 1, G);
     const size_t bytes = PW_LDS_BASE + pw_gate_bytes(a);
     if (bytes > 64 * 1024) {                                     // LDS above 64 KB has to be asked for once
@@ -286,7 +301,7 @@ static hipError_t launch_pw_variant(const ConvArgs& a, const ConvArgs* argv, int
 // number fewer than the compute units (measured over the 1x1 layers of a ResNet-50 at batches of 16 to
 // 128: with 196 tiles or fewer the 128 x 64 tile is faster or equal, with 392 or more the larger one)
 static int pw_wpx(const ConvArgs& a, int nb, int G) {
-    const long long tiles = (((long long)nb * a.H * a.W + PW_BP - 1) / PW_BP) * ((a.cout + 127) / 128) * G;
+    const long long tiles = (((long long)nb * a.Ho * a.Wo + PW_BP - 1) / PW_BP) * ((a.cout + 127) / 128) * G;
     int wpx = a.cout <= 64 || tiles < cu_budget() ? 2 : 1;
     return wpx;
 }

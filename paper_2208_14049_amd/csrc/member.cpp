@@ -383,11 +383,11 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
                 }
         pl.w_packed = off;
     };
-    // 1x1 stride-1 layers without pre-activation: the kernel of conv_pw.hip
+    // 1x1 layers without padding or pre-activation (stride 1, or the strided shortcuts of residual stages): the kernel of conv_pw.hip
     if (m.bf16) {
         for (int i = 0; i < spec.n_ops; i++) {
             const ens_op& o = spec.ops[i];
-            if (o.kind == ENS_OP_CONV && o.kh == 1 && o.kw == 1 && o.sh == 1 && o.sw == 1 && o.pt == 0 && o.pl == 0 && o.r <= 1 &&
+            if (o.kind == ENS_OP_CONV && o.kh == 1 && o.kw == 1 && o.sh >= 1 && o.sw >= 1 && o.pt == 0 && o.pl == 0 && o.r <= 1 &&
                 !o.pre && o.cin % 8 == 0 && o.cout % 8 == 0 && m.ops[i].cin_s == o.cin)
                 pack_operand_order(m.ops[i]);
         }

@@ -186,6 +186,8 @@ CONV_LAYERS = [
     (10, 10, 64, 32, 1, 1, "same", {"act": None}),             # ... one chunk, one block of channels
     (14, 14, 80, 80, 1, 1, "same", {"res": True, "act": None}),    # ... channels in 8s: half-empty last chunk and last block, residual
     (19, 19, 728, 728, 1, 1, "same", {}),                      # ... the pointwise half of a 728-channel separable layer
+    (15, 15, 64, 128, 1, 2, "same", {"act": None}),            # ... a strided shortcut on an odd map: every other pixel of every other row
+    (28, 28, 512, 1024, 1, 2, "same", {"act": None}),          # ... eight input chunks, 128-wide channel tiles
 ]
 
 
@@ -197,6 +199,7 @@ MANY_TILES = [
     ((96, 96, 3, 64, 7, 2, "same", {}), 64),                    # stem: 601 tiles of 256 positions for 512 workgroups
     ((56, 56, 64, 160, 1, 1, "same", {}), 6),                   # 1x1 from operand-ordered weights, 128x128 tiles, 32 channels in the last
     ((28, 28, 128, 128, 1, 1, "same", {"res": True}), 48),      # ... with the residual
+    ((56, 56, 256, 512, 1, 2, "same", {"act": None}), 6),       # ... strided: tiles that span rows and images of the output
 ]
 
 

@@ -149,6 +149,8 @@ def test_memory_model_from_description():
     # bf16 weights; the FC head once more, transposed, in matrix-core operand order (1000 rows padded to 1024);
     # fp32 bias and scale per output channel; alignment; the stem's filter padded to 16 channels per tap
     fc_copy = 2 * 1024 * 512
+    # and the three strided 1x1 shortcuts once more in operand order (rows in 32s, input channels in 64s)
+    fc_copy += 2 * (128 * 64 + 256 * 128 + 512 * 256)
     assert 2 * n_w + fc_copy <= w <= 2 * n_w + fc_copy + 2 * 4 * 20000 + 256 * 4 * len(net.ops) + 2 * 8 * 64 * 49
     # the arena is at least the two largest tensors alive together (stem output and its input, which
     # a bf16 member stores space-to-depth: 112 x 112 pixels of 16 channels)
@@ -196,9 +198,9 @@ def test_grouped_convolutions_in_descriptions():
     n_w = sum(p["size"] for p in net.params if p["role"] == "conv_w")
     dense_blocks = sum(9 * op["cout"] * 32 for op in net.ops if op["kind"] == N.CONV and op["r"] > 1)
     grouped = sum(9 * op["cout"] * op["cin"] // op["r"] for op in net.ops if op["kind"] == N.CONV and op["r"] > 1)
-    # plus the second, operand-ordered copy of the 1x1 stride-1 layers that a kernel fetches straight from memory
+    # plus the second, operand-ordered copy of the 1x1 layers (padding 0) that a kernel fetches straight from memory
     copies = sum(-(-op["cin"] // 64) * 64 * -(-op["cout"] // 32) * 32 for op in net.ops
-                 if op["kind"] == N.CONV and op["kh"] == 1 and op["kw"] == 1 and op["sh"] == 1 and op["r"] <= 1)
+                 if op["kind"] == N.CONV and op["kh"] == 1 and op["kw"] == 1 and op["r"] <= 1)
     assert copies > 0
     copies += 1024 * 2048                                        # the FC head once more, transposed, 1000 rows padded to 1024
     expected = 2 * (n_w - grouped + dense_blocks + copies)
@@ -268,8 +270,8 @@ def test_dense_layer_output_does_not_share_memory_with_its_input():
 
 def test_bottleneck_chains_in_descriptions():
     """The plan keeps a second copy, in matrix-core operand order (rows padded to 32, columns to 64), of
-    the weights of layers that kernels fetch straight from memory: every 1x1 stride-1 convolution
-    without pre-activation, and the 3x3 layer of a residual bottleneck that one kernel can run (1x1, 3x3
+    the weights of layers that kernels fetch straight from memory: every 1x1 convolution without padding
+    or pre-activation, and the 3x3 layer of a residual bottleneck that one kernel can run (1x1, 3x3
     stride 1, 1x1, with 64 or 128 channels in between and nobody else touching the two middle
     tensors).  The parameter block grows by exactly those copies: the same layers with a stride on the
     3x3, another width in the middle, a second reader of a middle tensor or fp32 parameters get no
@@ -293,11 +295,15 @@ def test_bottleneck_chains_in_descriptions():
         fused, _ = ens.ens_spec_bytes(block(c, cin, cout), 8)
         plain, _ = ens.ens_spec_bytes(block(c, cin, cout, stride=2), 8)
         assert fused - plain == up(2 * 9 * c * c), (c, cin, cout, fused - plain)
-    # the 1x1 layers alone: a stride-1 layer gets the padded copy (256 -> 64 as it is; 40 -> 24 as 64 -> 32), a stride-2 layer none
+    # the 1x1 layers alone: a layer without padding gets the padded copy (256 -> 64 as it is; 40 -> 24 as 64 -> 32) at
+    # stride 1 and at stride 2 (the shortcuts of residual stages), a pre-activated one none
     for cin, cout in ((256, 64), (40, 24)):
         n1 = N.Net("p", 16, 16, 10, dtype="bf16"); n1.fc(n1.gap(n1.conv(n1.conv(0, cin, 3), cout, 1)), 10)
         n2 = N.Net("p", 16, 16, 10, dtype="bf16"); n2.fc(n2.gap(n2.conv(n2.conv(0, cin, 3), cout, 1, stride=2)), 10)
-        assert ens.ens_spec_bytes(n1, 8)[0] - ens.ens_spec_bytes(n2, 8)[0] == pointwise(cin, cout)
+        n3 = N.Net("p", 16, 16, 10, dtype="bf16"); n3.fc(n3.gap(n3.conv(n3.conv(0, cin, 3), cout, 1, pre=True)), 10)
+        assert ens.ens_spec_bytes(n1, 8)[0] == ens.ens_spec_bytes(n2, 8)[0]
+        # (the pre-activation brings its own scale and shift per input channel)
+        assert 0 <= ens.ens_spec_bytes(n3, 8)[0] + pointwise(cin, cout) - ens.ens_spec_bytes(n1, 8)[0] <= 2 * up(4 * cin) + 512
     plain, _ = ens.ens_spec_bytes(block(96, 256, 256, stride=2), 8)
     assert ens.ens_spec_bytes(block(96, 256, 256), 8)[0] == plain            # 96 channels in the middle
     w_tap, _ = ens.ens_spec_bytes(block(64, 256, 256, tap_t1=True), 8)
