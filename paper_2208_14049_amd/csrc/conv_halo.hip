@@ -304,6 +304,8 @@ int conv_halo_pick(const ConvArgs& a, int nb, int G) {
         const long long PP = (long long)nb * (a.H + 1) * (a.W + 1);
         const long long tiles = G * ((PP + 127) / 128) * ((a.cout + 63) / 64);
         choice = a.cin > 64 && tiles > 2 * cu_budget() ? 6 : 0;
+        // many tiles and whole 128-channel tiles: the wider tile reads two fragments per matrix-core instruction instead of three
+        if (a.cin > 64 && a.cout % 128 == 0 && tiles / 2 >= 3 * cu_budget()) choice = 8;
         if (a.cout <= 32 && tiles > 2 * cu_budget()) choice = a.cin > 64 ? 12 : 13;   // narrow outputs (dense-block growth layers)
     } else if (a.cin >= 96) {
         choice = 4;                                              // multiples of 32 only: 32-channel blocks

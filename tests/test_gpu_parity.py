@@ -200,6 +200,7 @@ MANY_TILES = [
     ((56, 56, 64, 160, 1, 1, "same", {}), 6),                   # 1x1 from operand-ordered weights, 128x128 tiles, 32 channels in the last
     ((28, 28, 128, 128, 1, 1, "same", {"res": True}), 48),      # ... with the residual
     ((56, 56, 256, 512, 1, 2, "same", {"act": None}), 6),       # ... strided: tiles that span rows and images of the output
+    ((28, 28, 128, 256, 3, 1, "same", {}), 64),                 # window-in-LDS 3x3 kernel with 128 x 128 tiles: 842 of them
 ]
 
 
