@@ -131,6 +131,7 @@ static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G
             a.scale = o.kind == ENS_OP_DWCONV ? (const float*)(P + pl.scale) : nullptr;
             a.nb = w.batch; a.H = ts.h; a.W = ts.w; a.c = o.cin; a.Ho = td.h; a.Wo = td.w;
             a.kh = o.kh; a.kw = o.kw; a.sh = o.sh; a.sw = o.sw; a.pt = o.pt; a.pl = o.pl; a.act = o.act;
+            a.sums = nullptr; a.sums_stride = 0;
             L.flop = o.kind == ENS_OP_DWCONV ? 2.0 * nb * td.h * td.w * o.cin * o.kh * o.kw : 0.0;
             L.bytes = nb * ((double)ts.h * ts.w + (double)td.h * td.w) * o.cin * es;
             L.klass = prof_class(h, o.kind == ENS_OP_DWCONV ? "window_kernel<dwconv>"
@@ -174,6 +175,7 @@ static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G
             a.scratch = (float*)(w.arena + w.layout.offset[pl.scratch]);
             a.nb = w.batch; a.HW = ts.h * ts.w; a.c = o.cin; a.r = o.r;
             a.gate_only = 0;
+            a.cap = pl.se_cap; a.have_sums = 0;
             L.flop = 4.0 * nb * o.cin * o.r;
             L.bytes = nb * 3.0 * ts.h * ts.w * o.cin * es;
             L.klass = prof_class(h, "se_kernels");
@@ -259,8 +261,8 @@ static int build_launches(ens_handle* h, Gang& g, bool may_alloc = true) {
     auto gate_args = [&](const Worker& w, const OpPlan& se, ConvArgs& c) {
         const Member& mw = h->members[w.member];
         c.x = view_of(w, leader, mw, se.op.src, se.op.src_c0);
-        c.gate = (const float*)(w.arena + w.layout.offset[se.scratch]) + se_gate_offset(se.op.cin, se.op.r);
-        c.gate_stride = se_scratch_floats(se.op.cin, se.op.r);
+        c.gate = (const float*)(w.arena + w.layout.offset[se.scratch]) + se_gate_offset(se.op.cin, se.op.r, se.se_cap);
+        c.gate_stride = se_scratch_floats(se.op.cin, se.op.r, se.se_cap);
     };
     for (size_t i = 0; i + 1 < m.ops.size(); i++) {
         if (!m.ops[i].fuse_gate || h->keep_tensors || chain[i] || chain[i + 1] || fused[i] || fused[i + 1]) continue;
@@ -270,6 +272,18 @@ static int build_launches(ens_handle* h, Gang& g, bool may_alloc = true) {
         if (c.conv.wpk && conv_pw_applicable(c.conv, leader.batch, G)) {
             gated[i] = 1;
             gated[i + 1] = 2;
+        }
+    }
+    // Depthwise convolutions whose kernel leaves the channel sums for the squeeze-excite block behind them:
+    // summed[] 1 marks the convolution, 2 the block.
+    std::vector<char> summed(m.ops.size(), 0);
+    for (size_t i = 0; i + 1 < m.ops.size(); i++) {
+        if (!m.ops[i].fuse_sums || h->keep_tensors || m.ops[i + 1].op.kind != ENS_OP_SE) continue;
+        Launch d;
+        if (fill_args(h, leader, leader, G, m.ops[i], d) != ENS_OK) continue;
+        if (dwconv_sums_applicable(d.pool, m.bf16) && dwconv_sums_blocks(d.pool.Ho, d.pool.Wo, d.pool.c) <= m.ops[i + 1].se_cap) {
+            summed[i] = 1;
+            summed[i + 1] = 2;
         }
     }
     std::vector<size_t> first_blk(m.ops.size() + 1, 0);          // argument blocks: G * sub per operation
@@ -384,9 +398,21 @@ static int build_launches(ens_handle* h, Gang& g, bool may_alloc = true) {
                 const OpPlan& pl = fused[i] == 1 && (sub == 1) != second_leads ? mk.ops[i + 1] : mk.ops[i];
                 const int rc = fill_args(h, h->workers[g.workers[k]], leader, G, pl, L, fused[i] == 1 ? 0 : sub);
                 if (rc != ENS_OK) return rc;
+                const double se_pass = L.bytes / 3.0;            // squeeze-excite: the tensor is read twice and written once
+                if (summed[i] == 1) {                            // the sums go to the scratch of the block behind
+                    const Worker& wk = h->workers[g.workers[k]];
+                    const OpPlan& se = mk.ops[i + 1];
+                    L.pool.sums = (float*)(wk.arena + wk.layout.offset[se.scratch]);
+                    L.pool.sums_stride = se_scratch_floats(se.op.cin, se.op.r, se.se_cap);
+                    L.klass = prof_class(h, "window_kernel<dwconv,sums>");
+                } else if (summed[i] == 2) {                     // one pass over the input less
+                    L.se.have_sums = dwconv_sums_blocks(mk.tensors[pl.op.src].h, mk.tensors[pl.op.src].w, pl.op.cin);
+                    L.bytes -= se_pass;
+                }
                 if (gated[i] == 1) {                             // the block stops at the gates: one pass over its input
                     L.se.gate_only = 1;
-                    L.bytes /= 3.0;
+                    L.bytes -= 2.0 * se_pass;
+                    if (summed[i] == 2) L.bytes = (double)L.se.nb * L.se.have_sums * L.se.c * sizeof(float);   // only the rows of sums
                 } else if (gated[i] == 2) {
                     gate_args(h->workers[g.workers[k]], mk.ops[i - 1], L.conv);
                     L.klass = prof_class(h, conv_bf16_variant_name(L.conv, G));

@@ -53,6 +53,11 @@ struct OpPlan {
     // stop at the gates and the convolution multiply its input by them, so that the rescaled tensor is
     // never written.
     bool fuse_gate;
+    // This depthwise convolution is followed by a squeeze-excite block over its output: its kernel can leave
+    // the channel sums the block starts from (one row per workgroup, in the block's scratch, which then lives
+    // from this operation on and holds se_cap rows), and the block does not read the tensor for them.
+    bool fuse_sums;
+    int se_cap;      // squeeze-excite: rows of partial sums its scratch holds per image
 };
 
 struct Member {

@@ -59,6 +59,10 @@ struct PoolArgs {              // max / average pooling, depthwise convolution
     int nb, H, W, c, Ho, Wo;
     int kh, kw, sh, sw, pt, pl;
     int act;
+    // depthwise in front of a squeeze-excite block: each workgroup also leaves the channel sums of its outputs in the
+    // block's scratch (per image `sums_stride` floats apart, one row of c floats per workgroup of the image), or null
+    float* sums;
+    int sums_stride;
 };
 
 struct GapArgs {               // global average pool to fp32 [nb][c]
@@ -85,12 +89,18 @@ constexpr int SE_MAX_SPLITS = 16;
 struct SeArgs {
     View x, y;
     const float* w1; const float* b1; const float* w2; const float* b2;   // fp32
-    float* scratch;            // per image SE_MAX_SPLITS * c partial sums, r hidden values, c gates (floats)
+    float* scratch;            // per image `cap` rows of c partial sums, r hidden values, c gates (floats)
     int nb, HW, c, r;
     int gate_only;             // non-zero: the gates go to `scratch` and y is not written (the consumer applies them)
+    int cap;                   // rows of partial sums the scratch holds per image (SE_MAX_SPLITS, or more when the kernel
+                               // that writes x leaves one row per workgroup)
+    int have_sums;             // > 0: the kernel that wrote x has left this many rows of partial sums in `scratch`
 };
-__host__ __device__ inline int se_scratch_floats(int c, int r) { return (SE_MAX_SPLITS + 1) * c + r; }
-__host__ __device__ inline int se_gate_offset(int c, int r) { return SE_MAX_SPLITS * c + r; }   // of an image's gates in its scratch
+// (the hidden values take a multiple of four floats: with c a multiple of four, every row stays 16-byte aligned)
+__host__ __device__ inline int se_scratch_floats(int c, int r, int cap) { return (cap + 1) * c + (r + 3) / 4 * 4; }
+__host__ __device__ inline int se_gate_offset(int c, int r, int cap) { return cap * c + (r + 3) / 4 * 4; }   // of an image's gates in its scratch
+// Workgroups (of 256 lanes, one lane per 4 output columns x 8 channels) the summing depthwise kernel gives an image
+__host__ __device__ inline int dwconv_sums_blocks(int Ho, int Wo, int c) { return (Ho * ((Wo + 3) / 4) * (c / 8) + 255) / 256; }
 
 struct StageArgs {             // request images -> a worker's input tensor (convert, pad, resize)
     const float* src;          // request images, n x sh x sw x 3 fp32
@@ -111,6 +121,7 @@ struct StageArgs {             // request images -> a worker's input tensor (con
 hipError_t launch_conv_bf16(const ConvArgs& a, const ConvArgs* argv, int G, int nb, hipStream_t s);
 hipError_t launch_conv_f32(const ConvArgs& a, const ConvArgs* argv, int G, int nb, hipStream_t s);
 hipError_t launch_dwconv(const PoolArgs& a, const PoolArgs* argv, int G, int nb, bool bf16, hipStream_t s);
+bool dwconv_sums_applicable(const PoolArgs& a, bool bf16);     // can the depthwise kernel also leave the channel sums of its output?
 hipError_t launch_pool(const PoolArgs& a, const PoolArgs* argv, int G, int nb, bool is_max, bool bf16, hipStream_t s);
 hipError_t launch_gap(const GapArgs& a, const GapArgs* argv, int G, int nb, bool bf16, hipStream_t s);
 hipError_t launch_fc(const FcArgs& a, const FcArgs* argv, int G, int nb, long long first, bool bf16, hipStream_t s);

@@ -457,6 +457,106 @@ __global__ __launch_bounds__(256) void dwconv_row_bf16_kernel(const PoolArgs* __
     }
 }
 
+// The depthwise convolution in front of a squeeze-excite block: dwconv_row_bf16_kernel, and each workgroup also
+// leaves the channel sums of its outputs (of the rounded values, as the block's own summing kernel would read them)
+// as one row of the block's scratch, so that the block does not read the tensor for them.  The workgroups of an
+// image do not reach into the next one (`blocks` of them per image, the last one partly idle); a lane adds up
+// its own outputs, the lanes of a workgroup that hold the same 8 channels are added through LDS in lane order,
+// and every workgroup writes all c sums of its row (zeros for channels it holds no lane of): the order of every
+// sum is fixed.
+template <int K, int S, int NW>
+__global__ __launch_bounds__(256) void dwconv_row_sum_bf16_kernel(const PoolArgs* __restrict__ argv, const int nb_, const int blocks) {
+    const PoolArgs a = argv[blockIdx.z];
+    constexpr int NCOL = (NW - 1) * S + K;
+    __shared__ float red[256 * 8];
+    const int t = threadIdx.x;
+    const unsigned cv = (unsigned)(a.c / 8);
+    const unsigned wgroups = (unsigned)(a.Wo + NW - 1) / NW;     // lanes' runs of NW columns per output row
+    const unsigned wg = xcd_block();                             // workgroups regrouped per XCD, an image's side by side
+    const unsigned nu = wg / (unsigned)blocks, blk = wg - nu * (unsigned)blocks;
+    const unsigned items = (unsigned)a.Ho * wgroups * cv;        // (run of columns, 8 channels) pairs of one image
+    const unsigned idx = blk * 256u + (unsigned)t;
+    float sum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (idx < items) {
+        const unsigned gu = idx / cv;
+        const int c = (int)(idx - gu * cv) * 8;
+        const int ho = (int)(gu / wgroups);
+        const int wo0 = (int)(gu - (unsigned)ho * wgroups) * NW;
+        const uint16_t* __restrict__ x = (const uint16_t*)a.x.p + (long long)nu * a.H * a.W * a.x.stride + a.x.c0 + c;
+        const uint16_t* __restrict__ w = (const uint16_t*)a.w + c;
+        float acc[NW][8];
+#pragma unroll
+        for (int o = 0; o < NW; o++)
+#pragma unroll
+            for (int e = 0; e < 8; e++) acc[o][e] = 0.f;
+        const int wi0 = wo0 * S - a.pl;
+#pragma unroll 1
+        for (int kh = 0; kh < K; kh++) {
+            const int hi = ho * S - a.pt + kh;
+            const bool hok = (unsigned)hi < (unsigned)a.H;
+            const int hic = min(max(hi, 0), a.H - 1);
+            uint4 xv[NCOL], wv[K];
+#pragma unroll
+            for (int j = 0; j < NCOL; j++) {
+                const int wic = min(max(wi0 + j, 0), a.W - 1);
+                xv[j] = *(const uint4*)(x + (long long)(hic * a.W + wic) * a.x.stride);
+            }
+#pragma unroll
+            for (int kw = 0; kw < K; kw++) wv[kw] = *(const uint4*)(w + (kh * K + kw) * a.c);
+            float wf[K][8];
+#pragma unroll
+            for (int kw = 0; kw < K; kw++) unpack8(wv[kw], wf[kw]);
+#pragma unroll
+            for (int j = 0; j < NCOL; j++) {
+                const bool ok = hok && (unsigned)(wi0 + j) < (unsigned)a.W;
+                if (!ok) xv[j] = make_uint4(0u, 0u, 0u, 0u);
+                float xf[8];
+                unpack8(xv[j], xf);
+#pragma unroll
+                for (int o = 0; o < NW; o++) {
+                    const int kw = j - o * S;                    // input column j is tap kw of output o
+                    if (kw >= 0 && kw < K) {
+#pragma unroll
+                        for (int e = 0; e < 8; e++) acc[o][e] = fmaf(xf[e], wf[kw][e], acc[o][e]);
+                    }
+                }
+            }
+        }
+        uint16_t* __restrict__ y = (uint16_t*)a.y.p + (((long long)nu * a.Ho + ho) * a.Wo + wo0) * a.y.stride + a.y.c0 + c;
+#pragma unroll
+        for (int o = 0; o < NW; o++) {
+            if (wo0 + o >= a.Wo) break;
+            scale_bias8(acc[o], a.scale + c, a.bias + c);
+            if (a.act == ACT_SILU) {
+#pragma unroll
+                for (int e = 0; e < 8; e++) acc[o][e] = acc[o][e] / (1.f + __expf(-acc[o][e]));
+            } else if (a.act == ACT_RELU) {
+#pragma unroll
+                for (int e = 0; e < 8; e++) acc[o][e] = fmaxf(acc[o][e], 0.f);
+            }
+            const uint4 packed = pack8(acc[o]);
+            *(uint4*)(y + (long long)o * a.y.stride) = packed;
+            float r[8];
+            unpack8(packed, r);
+#pragma unroll
+            for (int e = 0; e < 8; e++) sum[e] += r[e];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; e++) red[t * 8 + e] = sum[e];
+    __syncthreads();
+    float* out = a.sums + (long long)nu * a.sums_stride + (long long)blk * a.c;
+    const unsigned shift = (blk * 256u) % cv;                    // lane t holds channel group (shift + t) mod cv
+    for (unsigned g = (unsigned)t; g < cv; g += 256u) {
+        float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (unsigned l = (g + cv - shift) % cv; l < 256u; l += cv)
+#pragma unroll
+            for (int e = 0; e < 8; e++) v[e] += red[l * 8 + e];
+        *(float4*)(out + g * 8) = make_float4(v[0], v[1], v[2], v[3]);
+        *(float4*)(out + g * 8 + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    }
+}
+
 // Average pooling over the in-bounds part of a K x K window, bf16, one lane per (pixel, 8
 // channels): loads from clamped positions, taps outside the image zeroed by a select and left out
 // of the divisor.
@@ -511,6 +611,11 @@ static hipError_t check_window(const PoolArgs& a, bool bf16) {
     return hipSuccess;
 }
 
+bool dwconv_sums_applicable(const PoolArgs& a, bool bf16) {
+    const int st = a.sh == a.sw ? a.sh : 0;
+    return bf16 && a.kh == a.kw && (a.kh == 3 || a.kh == 5) && (st == 1 || st == 2) && a.c % 8 == 0;
+}
+
 hipError_t launch_dwconv(const PoolArgs& a, const PoolArgs* argv, int G, int nb, bool bf16, hipStream_t s) {
     if (check_window(a, bf16) != hipSuccess || !a.w || !a.bias || !a.scale || nb <= 0 || G <= 0 || !argv) return hipErrorInvalidValue;
     const long long total = (long long)nb * a.Ho * a.Wo * (a.c / (bf16 ? 8 : 1));
@@ -518,6 +623,18 @@ hipError_t launch_dwconv(const PoolArgs& a, const PoolArgs* argv, int G, int nb,
     const dim3 g(blocks_for(total, 256), 1, G);
     // 3x3 and 5x5 at strides 1 and 2: four output columns per lane (eight were measured too: no faster)
     const int st = a.sh == a.sw ? a.sh : 0;
+    if (a.sums) {                                                // and a row of channel sums per workgroup
+        if (!dwconv_sums_applicable(a, bf16) || a.sums_stride <= 0 || ((uintptr_t)a.sums & 15) || a.sums_stride % 4) return hipErrorInvalidValue;
+        constexpr int NW = 4;
+        const int blocks = dwconv_sums_blocks(a.Ho, a.Wo, a.c);
+        if ((long long)blocks * nb >= (1LL << 31) / 256) return hipErrorInvalidValue;
+        const dim3 gs((unsigned)(blocks * nb), 1, (unsigned)G);
+        if (a.kh == 3 && st == 1) ENS_LAUNCH((dwconv_row_sum_bf16_kernel<3, 1, NW>), gs, dim3(256), 0, s, argv, nb, blocks);
+        else if (a.kh == 3) ENS_LAUNCH((dwconv_row_sum_bf16_kernel<3, 2, NW>), gs, dim3(256), 0, s, argv, nb, blocks);
+        else if (st == 1) ENS_LAUNCH((dwconv_row_sum_bf16_kernel<5, 1, NW>), gs, dim3(256), 0, s, argv, nb, blocks);
+        else ENS_LAUNCH((dwconv_row_sum_bf16_kernel<5, 2, NW>), gs, dim3(256), 0, s, argv, nb, blocks);
+        return hipGetLastError();
+    }
     if (bf16 && a.kh == a.kw && (a.kh == 3 || a.kh == 5) && (st == 1 || st == 2)) {
         constexpr int NW = 4;
         const dim3 gw(blocks_for((long long)nb * a.Ho * ((a.Wo + NW - 1) / NW) * (a.c / 8), 256), 1, G);
@@ -716,7 +833,7 @@ __global__ __launch_bounds__(256) void se_sum_kernel(const SeArgs* __restrict__ 
     const int cols = min(cv, 256);                    // groups handled side by side
     const int rows = 256 / cols;                      // pixel phases
     const int col = threadIdx.x % cols, row = threadIdx.x / cols;
-    float* out = a.scratch + (long long)n * se_scratch_floats(a.c, a.r) + (long long)split * a.c;
+    float* out = a.scratch + (long long)n * se_scratch_floats(a.c, a.r, a.cap) + (long long)split * a.c;
     for (int g0 = 0; g0 < cv; g0 += cols) {
         const int g = g0 + col;
         float acc[V];
@@ -769,15 +886,17 @@ __device__ __forceinline__ void se_gate(const SeArgs& a, const int n, const int 
     // Every loop below asks for a batch of values before it uses the first: a round trip to memory is about
     // 2000 clocks, and taken one load at a time the sums, the two weight matrices and the biases were some
     // thirty of them in a row (18 us per launch for a few ten thousand multiply-adds).
-    const float* part = a.scratch + (long long)n * se_scratch_floats(a.c, a.r);   // partial sums of the image
+    const float* part = a.scratch + (long long)n * se_scratch_floats(a.c, a.r, a.cap);   // partial sums of the image
     const float inv = 1.f / (float)a.HW;
     for (int c = t; c < a.c; c += SE_GATE_THREADS) {
-        float v[SE_MAX_SPLITS];
-#pragma unroll
-        for (int k = 0; k < SE_MAX_SPLITS; k++) v[k] = k < splits ? part[(long long)k * a.c + c] : 0.f;
         float m = 0.f;
+        for (int k0 = 0; k0 < splits; k0 += SE_MAX_SPLITS) {     // sixteen rows at a time; the summing depthwise kernel leaves more than that
+            float v[SE_MAX_SPLITS];
 #pragma unroll
-        for (int k = 0; k < SE_MAX_SPLITS; k++) m += v[k];       // fixed order; the terms past the last split are zeros
+            for (int k = 0; k < SE_MAX_SPLITS; k++) v[k] = k0 + k < splits ? part[(long long)(k0 + k) * a.c + c] : 0.f;
+#pragma unroll
+            for (int k = 0; k < SE_MAX_SPLITS; k++) m += v[k];   // fixed order; the terms past the last row are zeros
+        }
         mean[c] = m * inv;
     }
     __syncthreads();
@@ -872,7 +991,7 @@ __global__ __launch_bounds__(SE_GATE_THREADS) void se_gate_only_kernel(const SeA
     __shared__ float z[256];
     const int n = blockIdx.y;
     se_gate<true>(a, n, splits, mean, red, z, gate);        // bf16 members only
-    float* out = a.scratch + (long long)n * se_scratch_floats(a.c, a.r) + se_gate_offset(a.c, a.r);
+    float* out = a.scratch + (long long)n * se_scratch_floats(a.c, a.r, a.cap) + se_gate_offset(a.c, a.r, a.cap);
     for (int c = threadIdx.x; c < a.c; c += SE_GATE_THREADS) out[c] = gate[c];
 }
 
@@ -881,11 +1000,14 @@ hipError_t launch_se(const SeArgs& a, const SeArgs* argv, int G, int nb, bool bf
     if (a.c > SE_GATE_MAXC || a.r > 256) return hipErrorInvalidValue;   // what the gate kernel holds in LDS
     if (bf16 && (a.c % 8 || a.x.stride % 8 || a.x.c0 % 8 || a.y.stride % 8 || a.y.c0 % 8)) return hipErrorInvalidValue;
     if ((long long)nb * a.HW >= (1LL << 31) / 8) return hipErrorInvalidValue;
-    const int splits = se_splits(a.HW, nb * G);
-    if (bf16) ENS_LAUNCH_FIRST(se_sum_kernel<true>, dim3(splits, nb, G), dim3(256), 0, s, argv, nb);
+    if (a.cap < SE_MAX_SPLITS || a.have_sums > a.cap || (a.have_sums && !bf16)) return hipErrorInvalidValue;
+    const int splits = a.have_sums > 0 ? a.have_sums : se_splits(a.HW, nb * G);
+    if (a.have_sums > 0) {}                                      // the kernel that wrote x has left the rows of partial sums
+    else if (bf16) ENS_LAUNCH_FIRST(se_sum_kernel<true>, dim3(splits, nb, G), dim3(256), 0, s, argv, nb);
     else ENS_LAUNCH_FIRST(se_sum_kernel<false>, dim3(splits, nb, G), dim3(256), 0, s, argv, nb);
     if (a.gate_only) {
-        ENS_LAUNCH_LAST(se_gate_only_kernel, dim3(1, nb, G), dim3(SE_GATE_THREADS), 0, s, argv, nb, splits);
+        if (a.have_sums > 0) ENS_LAUNCH(se_gate_only_kernel, dim3(1, nb, G), dim3(SE_GATE_THREADS), 0, s, argv, nb, splits);
+        else ENS_LAUNCH_LAST(se_gate_only_kernel, dim3(1, nb, G), dim3(SE_GATE_THREADS), 0, s, argv, nb, splits);
         return hipGetLastError();
     }
     // shares of an image in the second kernel: about SE_SCALE_BYTES of the tensor each
@@ -896,7 +1018,8 @@ hipError_t launch_se(const SeArgs& a, const SeArgs* argv, int G, int nb, bool bf
     if (shares > room) shares = room;
     if (shares > a.HW) shares = a.HW;
     if (shares < 1) shares = 1;
-    if (bf16) ENS_LAUNCH_LAST(se_gate_scale_kernel<true>, dim3((unsigned)shares, nb, G), dim3(SE_GATE_THREADS), 0, s, argv, nb, splits);
+    if (a.have_sums > 0) ENS_LAUNCH(se_gate_scale_kernel<true>, dim3((unsigned)shares, nb, G), dim3(SE_GATE_THREADS), 0, s, argv, nb, splits);
+    else if (bf16) ENS_LAUNCH_LAST(se_gate_scale_kernel<true>, dim3((unsigned)shares, nb, G), dim3(SE_GATE_THREADS), 0, s, argv, nb, splits);
     else ENS_LAUNCH_LAST(se_gate_scale_kernel<false>, dim3((unsigned)shares, nb, G), dim3(SE_GATE_THREADS), 0, s, argv, nb, splits);
     return hipGetLastError();
 }

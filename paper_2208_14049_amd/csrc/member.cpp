@@ -133,6 +133,8 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         pl.fuse_dense = false;
         pl.fuse_pool = false;
         pl.fuse_gate = false;
+        pl.fuse_sums = false;
+        pl.se_cap = SE_MAX_SPLITS;
         TensorInfo& ts = m.tensors[o.src];
         TensorInfo& td = m.tensors[o.dst];
         if (o.cin <= 0 || o.cout <= 0 || o.src_c0 < 0 || o.dst_c0 < 0) return ENS_E_INVALID;
@@ -345,8 +347,18 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
                 pl.w2 = bw.put_f32(std::vector<float>(params + o.off_w2, params + o.off_w2 + n1));
                 pl.b2 = bw.put_f32(std::vector<float>(params + o.off_b2, params + o.off_b2 + o.cin));
                 TensorInfo sc;                                   // per-image scratch: partial sums, hidden, gates
-                sc.h = 1; sc.w = 1; sc.c = sc.cs = se_scratch_floats(o.cin, o.r);
-                sc.f32 = true; sc.def = i; sc.last = i; sc.external = false;
+                sc.def = i;
+                if (m.bf16 && i > 0) {                           // behind a depthwise convolution whose kernel can leave the sums
+                    const ens_op& d = spec.ops[i - 1];
+                    if (d.kind == ENS_OP_DWCONV && d.dst == o.src && d.dst_c0 == o.src_c0 && d.cin == o.cin && d.kh == d.kw &&
+                        (d.kh == 3 || d.kh == 5) && d.sh == d.sw && (d.sh == 1 || d.sh == 2) && o.cin % 8 == 0) {
+                        m.ops[i - 1].fuse_sums = true;
+                        pl.se_cap = std::max((int)SE_MAX_SPLITS, dwconv_sums_blocks(ts.h, ts.w, o.cin));
+                        sc.def = i - 1;
+                    }
+                }
+                sc.h = 1; sc.w = 1; sc.c = sc.cs = se_scratch_floats(o.cin, o.r, pl.se_cap);
+                sc.f32 = true; sc.last = i; sc.external = false;
                 pl.scratch = (int)m.tensors.size();
                 m.tensors.push_back(sc);
                 break;

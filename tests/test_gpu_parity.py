@@ -609,6 +609,56 @@ def test_squeeze_excite_gate_in_the_projection(ens, h, c, r, cout, res, G, nb):
         assert_after_bf16_layers(outs[0][g], ref, (g,))
 
 
+@pytest.mark.parametrize("h,c,k,s,r,nb,G,proj", [(28, 144, 3, 1, 6, 5, 1, 0), (57, 96, 3, 2, 4, 3, 1, 24), (14, 480, 5, 1, 20, 9, 2, 80),
+                                                  (5, 2688, 5, 1, 112, 6, 1, 0), (112, 32, 3, 1, 8, 2, 1, 16), (3, 8, 3, 2, 2, 4, 1, 0),
+                                                  (17, 672, 5, 2, 28, 37, 1, 112)],
+                         ids=["28x28x144_k3", "57x57x96_k3s2_proj", "14x14x480_k5_gang2_proj", "5x5x2688_k5", "112x112x32_k3_proj",
+                              "3x3x8_k3s2", "17x17x672_k5s2_n37_proj"])
+def test_depthwise_leaves_the_channel_sums(ens, h, c, k, s, r, nb, G, proj):
+    """A depthwise convolution followed by a squeeze-excite block (the middle of an inverted-residual block):
+    the depthwise kernel leaves the channel sums of its output, one row per workgroup, and the block starts
+    from them instead of reading the tensor.  What the block (or the 1x1 projection behind it that applies
+    its gates) writes is compared with the oracle element by element and with the same network run layer by
+    layer, where the block takes its own sums (in another order: equal up to the rounding of the gates);
+    the profile says which kernels ran.  Shapes: 14 and 49 workgroups per image (more rows than the block's
+    own kernel writes), a ragged last run of columns (29 wide), a last workgroup that is partly idle, more
+    channel groups than a workgroup has lanes (2688 channels), an image smaller than one workgroup (3x3x8),
+    two members in one launch, stride 2, 37 images."""
+    nets = []
+    for g in range(G):
+        n = N.Net("dwse%d" % g, h, h, 8, dtype="bf16")
+        t = n.conv(0, c, 1, act="silu")
+        d = n.dwconv(t, k, s)
+        u = n.se(d, r)
+        y = n.conv(u, proj, 1, act=None) if proj else u
+        n.fc(n.gap(y), 8)
+        nets.append(n)
+    blobs = [W.quantise_weights_bf16(n, W.make_blob(n, 111, i)) for i, n in enumerate(nets)]
+    imgs = W.round_bf16(W.make_images(112, nb, h, h))
+    outs = []
+    for keep in (False, True):
+        E = ens.Ensemble(nets, blobs)
+        E.set_base_size(h, h)
+        if keep:
+            E.ens_debug_keep_tensors()
+        E.ens_set_alloc([[nb] * G])
+        E.ens_set_profiling(1)
+        E.ens_predict(imgs)
+        ran = {kk["name"]: kk["launches"] for kk in E.ens_profile() if kk["launches"]}
+        assert ran.get("window_kernel<dwconv,sums>", 0) == (0 if keep else 1), ran
+        assert ran.get("window_kernel<dwconv>", 0) == (1 if keep else 0), ran
+        outs.append([E.ens_debug_tensor(g, y, nets[g].tensors[y], nb) for g in range(G)])   # alive until the global pooling
+        E.close()
+    for g in range(G):
+        ref = oracle_tensor(nets[g], blobs[g], imgs, y)
+        # three or four bf16 layers in a row (expansion, depthwise, rescaling, projection)
+        assert_after_bf16_layers(outs[0][g], ref, (g, "sums from the depthwise kernel"))
+        assert_after_bf16_layers(outs[1][g], ref, (g, "layer by layer"))
+        # the two runs differ by the order of the fp32 sums behind the gates only: a bf16 step here and there
+        d = np.abs(outs[0][g] - outs[1][g])
+        assert d.max() <= 2.0 ** -7 * np.abs(outs[1][g]).max() and (d > 0).mean() < 0.02, (g, float(d.max()), float((d > 0).mean()))
+
+
 def test_resize_staging(ens):
     """A member at 45 x 45 fed from 32 x 32 requests: bilinear resize inside the library."""
     for dtype in ("fp32", "bf16"):

@@ -252,6 +252,30 @@ def test_dense_block_layers_in_descriptions():
     assert fused - plain == up(2 * 128 * 128) + up(2 * 9 * 128 * 32), fused - plain
 
 
+def test_squeeze_excite_scratch_behind_a_depthwise_layer():
+    """A squeeze-excite block behind a 3x3 or 5x5 depthwise layer (bf16) gets the channel sums from that layer's
+    kernel, one row per workgroup of an image: its scratch holds as many rows as that kernel has workgroups per
+    image (never fewer than the block's own kernel writes) and is live from the depthwise layer on.  A 7x7
+    depthwise layer, which that kernel does not run, leaves the block's scratch as it is.  (That the rows are
+    enough is checked where the kernel runs: the engine takes the summing kernel only when they are.)"""
+    def net(h, c, k):
+        n = N.Net("dwse", h, h, 8, dtype="bf16")
+        t = n.conv(0, c, 1, act="silu")
+        u = n.se(n.dwconv(t, k, 1), 4)
+        n.fc(n.gap(u), 8)
+        return n
+
+    batch = 8
+    for h, c in ((112, 32), (56, 144), (14, 480)):
+        rows = max(16, -(-(h * -(-h // 4) * (c // 8)) // 256))   # 256 lanes of 4 columns x 8 channels
+        for k in (3, 5):
+            _, fused = ens.ens_spec_bytes(net(h, c, k), batch)
+            _, plain = ens.ens_spec_bytes(net(h, c, 7), batch)
+            # the arena grows by the extra rows at most (by less where the scratch fits a gap that the packing leaves)
+            assert 0 <= fused - plain <= batch * (rows - 16) * c * 4 + 256, (h, c, k, fused - plain, rows)
+    assert rows == 16 and fused == plain                         # 14x14x480: 14 workgroups, the scratch stays at 16 rows
+
+
 def test_dense_layer_output_does_not_share_memory_with_its_input():
     """A pre-activated 1x1 (to 128 channels) followed by a 3x3 (to 32) may run as one kernel that writes the
     3x3's output while other workgroups still read the 1x1's input: when the output is a tensor of its own it
