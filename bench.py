@@ -39,7 +39,7 @@ TRAFFIC = {
     (4, "conv1x1_direct_bf16<128x128>"): dict(
         bytes_per_launch=99.4e6,                 # read + written (profiles/bench_config4_12members_b128.md)
         sources=["conv_pw.hip", "conv_direct.h", "conv_common.h", "kernels.h"],
-        sha256="f6661e87c7937833dd39877300e6d36cdba10cc6468c13a4eace6066ce584f0c"),
+        sha256="e28cc256625f173a20194ac6af7396d0351ea5a164a77acabcf41d53b8ed05e7"),
 }
 
 
