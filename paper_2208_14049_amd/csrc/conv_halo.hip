@@ -1,20 +1,23 @@
-// 3x3, stride 1, padding 1 convolution on the CDNA4 matrix cores with the input window held in
-// LDS: every input pixel a workgroup needs is fetched once per channel block and serves all nine
-// filter taps, where the generic implicit-GEMM kernel fetches it once per tap.
+// Stride-1 convolutions with "same" padding and a KH x KW filter (3x3, and the 1x7 / 7x1 / 1x3 / 3x1 filters of
+// factorised inception modules) on the CDNA4 matrix cores with the input window held in LDS: every input
+// pixel a workgroup needs is fetched once per channel block and serves all KH * KW filter taps, where the
+// generic implicit-GEMM kernel fetches it once per tap.
 //
-// Pixels are numbered in a padded raster: image n, row hi, column wi sits at position
-//   pp = (n * (H + 1) + hi) * (W + 1) + wi
-// with one extra column per row and one extra row per image that hold no pixel.  In that raster
-// the tap (dh, dw) of ANY output position is the position dh * (W + 1) + dw further on, and the
-// neighbours that fall outside an image land on the extra column / row: they are loaded as zeros
+// Pixels are numbered in a padded raster: with gh = (KH - 1) / 2 and gw = (KW - 1) / 2, image n, row hi,
+// column wi sits at position
+//   pp = (n * (H + gh) + hi) * (W + gw) + wi
+// with gw extra columns per row and gh extra rows per image that hold no pixel.  In that raster
+// the tap (dh, dw) of ANY output position is the position dh * (W + gw) + dw further on, and the
+// neighbours that fall outside an image land on the extra columns / rows (to the left of a row on those of
+// the row before, above an image on those of the image before): they are loaded as zeros
 // (a buffer load past the end of its buffer writes zeros), so the filter taps need no masks and
 // the fragment addresses of a tap differ from the centre's by one constant.  The price is
-// matrix-core work on the padding positions themselves, (H+1)(W+1)/(HW) - 1 of the total.
+// matrix-core work on the padding positions themselves, (H+gh)(W+gw)/(HW) - 1 of the total.
 //
 // A workgroup of 4 wavefronts owns BP consecutive padded positions x BC output channels.  Its
-// "halo" is the run of BP + 2(W+1) + 2 positions those outputs read, CB channels wide, one LDS
+// "halo" is the run of BP + (KH-1)(W+gw) + KW-1 positions those outputs read, CB channels wide, one LDS
 // row of 2*CB bytes per position with the 16-byte chunks swizzled as in the generic kernel.  The
-// loop runs over channel blocks and, inside, the nine taps; each step takes a BC x CB tile of
+// loop runs over channel blocks and, inside, the taps; each step takes a BC x CB tile of
 // the weights through a two-stage ring.  While block cb is being used the halo of block cb+1
 // arrives in the second halo buffer, a slice of it with every tap.  All loads are asynchronous
 // global-to-LDS loads; the weight loads' per-thread offsets are loop invariant (the moving part
@@ -33,9 +36,9 @@ __device__ __forceinline__ bf16x8 halo_lds_read(uint32_t addr) {
     return v;
 }
 
-template <int BP, int BC, int WP, int WC, int CB, int NHL>
-__global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restrict__ argv, const int nb_,
-                                                         const int hrows, const int nbuf) {
+template <int KH, int KW, int BP, int BC, int WP, int WC, int CB, int NHL>
+__global__ __launch_bounds__(256) void conv_halo_bf16(const ConvArgs* __restrict__ argv, const int nb_,
+                                                      const int hrows, const int nbuf) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const ConvArgs a = argv[blockIdx.z];
     static_assert(WP * WC == 4, "four wavefronts per workgroup");
@@ -58,7 +61,9 @@ __global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restr
     constexpr int HROWS = HFIT >= BP ? BP : (HFIT >= BP / 2 ? BP / 2 : (HFIT >= BP / 4 ? BP / 4 : 32));
     static_assert(HROWS >= 32 && BP % HROWS == 0 && HROWS * OROW * 4 <= MINLDS, "output staging chunk");
 
-    const int W1 = a.W + 1, img = (a.H + 1) * W1;
+    constexpr int NT = KH * KW, GH = (KH - 1) / 2, GW = (KW - 1) / 2;   // taps; gap rows per image and gap columns per row
+    const int W1 = a.W + GW, H1 = a.H + GH, img = H1 * W1;
+    const int origin = GH * W1 + GW;                 // from a tile's first halo row to its first output
     const int PP = nb_ * img;                        // padded positions of the batch
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -80,7 +85,7 @@ __global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restr
     int* const tbl = (int*)(halo + nbuf * hbytes);   // halo row -> pixel index (n*H + hi)*W + wi, -1: padding
 
     // ---- which pixel each halo row is; row 0 is the top-left tap of the tile's first output
-    raster_table(tbl, hrows, pp0 - (W1 + 1), PP, a.H + 1, W1, a.H, a.W);
+    raster_table(tbl, hrows, pp0 - origin, PP, H1, W1, a.H, a.W);
     __syncthreads();
 
     // ---- load side.  Offsets past the end of a buffer give zeros in LDS; 2^31 is past the end of
@@ -89,7 +94,7 @@ __global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restr
     const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
         (void*)a.x.p, 0, (int)((unsigned)nb_ * (unsigned)(a.H * a.W) * (unsigned)a.x.stride * 2u), 0x00020000);
     const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)a.w, 0, (int)((unsigned)a.cout * (unsigned)(9 * a.cin) * 2u), 0x00020000);
+        (void*)a.w, 0, (int)((unsigned)a.cout * (unsigned)(NT * a.cin) * 2u), 0x00020000);
     const int r0 = t / CH;
     const int cchunk = (t % CH) ^ (CH == 8 ? (r0 >> 1) & 7 : (r0 >> 2) & 3);
     const unsigned xlane = (unsigned)(a.x.c0 * 2 + cchunk * 16);
@@ -104,7 +109,7 @@ __global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restr
 #pragma unroll
     for (int i = 0; i < NCL; i++) {
         const int r = c0 + r0 + RS * i;
-        wvo[i] = r < a.cout ? (unsigned)r * (unsigned)(9 * a.cin) * 2u + (unsigned)cchunk * 16u : OOBV;
+        wvo[i] = r < a.cout ? (unsigned)r * (unsigned)(NT * a.cin) * 2u + (unsigned)cchunk * 16u : OOBV;
     }
     auto issue_weights = [&](int stage, int cb, int tap) {
         const int so = (tap * a.cin + cb * CB) * 2;
@@ -131,7 +136,7 @@ __global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restr
 
     // ---- what the epilogue needs from memory is asked for now and is there long before it is used
     const bool split = gridDim.y > 1;
-    const int* own = tbl + W1 + 1;                               // the centre tap's halo rows: this tile's outputs
+    const int* own = tbl + origin;                               // the centre tap's halo rows: this tile's outputs
     TilePrefetch<BP, BC> pf;
     pf.load(a, own, c0, split);
 
@@ -165,7 +170,7 @@ __global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restr
         const uint32_t hbuf = halo0 + (uint32_t)(hb * hbytes);
         const bool more = cb + 1 < ncb;
 #pragma unroll
-        for (int tap = 0; tap < 9; tap++) {
+        for (int tap = 0; tap < NT; tap++) {
             // this step's weights (and, at tap 0, the block's halo) have landed; the barrier extends
             // that to the other waves' loads and says that nobody still reads what is refilled next
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -175,7 +180,7 @@ __global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restr
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 __builtin_amdgcn_s_barrier();
             }
-            if (tap < 8) issue_weights(stage ^ 1, cb, tap + 1);
+            if (tap < NT - 1) issue_weights(stage ^ 1, cb, tap + 1);
             else if (more) issue_weights(stage ^ 1, cb + 1, 0);
             if (more && !single) {
 #pragma unroll
@@ -183,7 +188,7 @@ __global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restr
                     if (tap * NHL + j < nsl) issue_halo(hb ^ 1, tap * NHL + j, cb + 1);
             }
             // tap (dh, dw): dh rows of the padded raster down, dw positions to the right
-            const uint32_t q = lq + (uint32_t)((tap / 3) * W1 + tap % 3);
+            const uint32_t q = lq + (uint32_t)((tap / KW) * W1 + tap % KW);
             const uint32_t key = CH == 8 ? (q >> 1) & 7 : (q >> 2) & 3;
             const uint32_t xs = hbuf + q * ROWB + ((((uint32_t)lhalf) ^ key) << 4);
             const uint32_t ws = wrow_addr + (uint32_t)stage * WSTAGE;
@@ -227,23 +232,42 @@ __global__ __launch_bounds__(256) void conv3x3_halo_bf16(const ConvArgs* __restr
 
 // ---- host side -----------------------------------------------------------------------------
 // name: the kernel instance (the one- and two-buffer forms of a tile are the same instance)
-struct HaloVariant { int bp, bc, cb, nhl; bool single; const char* name; };
+struct HaloVariant { int kh, kw, bp, bc, cb, nhl; bool single; const char* name; };
 static const HaloVariant HALO_VARIANTS[] = {
-    {128, 64, 64, 1, false, "conv3x3_halo_bf16<128,64,c64>"},
-    {256, 64, 64, 2, false, "conv3x3_halo_bf16<256,64,c64>"},
-    {128, 128, 64, 1, false, "conv3x3_halo_bf16<128,128,c64>"},
-    {256, 64, 32, 1, false, "conv3x3_halo_bf16<256,64,c32>"},
-    {128, 64, 32, 1, false, "conv3x3_halo_bf16<128,64,c32>"},
-    {128, 128, 32, 1, false, "conv3x3_halo_bf16<128,128,c32>"},
-    {128, 64, 64, 1, true, "conv3x3_halo_bf16<128,64,c64>"},
-    {256, 64, 64, 2, true, "conv3x3_halo_bf16<256,64,c64>"},
-    {128, 128, 64, 1, true, "conv3x3_halo_bf16<128,128,c64>"},
-    {128, 64, 32, 1, true, "conv3x3_halo_bf16<128,64,c32>"},
-    {256, 64, 32, 1, true, "conv3x3_halo_bf16<256,64,c32>"},
-    {128, 128, 32, 1, true, "conv3x3_halo_bf16<128,128,c32>"},
-    {256, 32, 64, 2, true, "conv3x3_halo_bf16<256,32,c64>"},
-    {256, 32, 64, 2, false, "conv3x3_halo_bf16<256,32,c64>"},
+    {3, 3, 128, 64, 64, 1, false, "conv3x3_halo_bf16<128,64,c64>"},
+    {3, 3, 256, 64, 64, 2, false, "conv3x3_halo_bf16<256,64,c64>"},
+    {3, 3, 128, 128, 64, 1, false, "conv3x3_halo_bf16<128,128,c64>"},
+    {3, 3, 256, 64, 32, 1, false, "conv3x3_halo_bf16<256,64,c32>"},
+    {3, 3, 128, 64, 32, 1, false, "conv3x3_halo_bf16<128,64,c32>"},
+    {3, 3, 128, 128, 32, 1, false, "conv3x3_halo_bf16<128,128,c32>"},
+    {3, 3, 128, 64, 64, 1, true, "conv3x3_halo_bf16<128,64,c64>"},
+    {3, 3, 256, 64, 64, 2, true, "conv3x3_halo_bf16<256,64,c64>"},
+    {3, 3, 128, 128, 64, 1, true, "conv3x3_halo_bf16<128,128,c64>"},
+    {3, 3, 128, 64, 32, 1, true, "conv3x3_halo_bf16<128,64,c32>"},
+    {3, 3, 256, 64, 32, 1, true, "conv3x3_halo_bf16<256,64,c32>"},
+    {3, 3, 128, 128, 32, 1, true, "conv3x3_halo_bf16<128,128,c32>"},
+    {3, 3, 256, 32, 64, 2, true, "conv3x3_halo_bf16<256,32,c64>"},
+    {3, 3, 256, 32, 64, 2, false, "conv3x3_halo_bf16<256,32,c64>"},
+    // the one-dimensional filters, four entries each from HALO_LINE on: 64-channel blocks with two halo buffers
+    // and with one, 32-channel blocks with two and with one (the two forms are one kernel instance)
+    {1, 7, 128, 64, 64, 1, false, "conv1x7_halo_bf16<128,64,c64>"},
+    {1, 7, 128, 64, 64, 1, true, "conv1x7_halo_bf16<128,64,c64>"},
+    {1, 7, 128, 64, 32, 1, false, "conv1x7_halo_bf16<128,64,c32>"},
+    {1, 7, 128, 64, 32, 1, true, "conv1x7_halo_bf16<128,64,c32>"},
+    {7, 1, 128, 64, 64, 2, false, "conv7x1_halo_bf16<128,64,c64>"},
+    {7, 1, 128, 64, 64, 2, true, "conv7x1_halo_bf16<128,64,c64>"},
+    {7, 1, 128, 64, 32, 1, false, "conv7x1_halo_bf16<128,64,c32>"},
+    {7, 1, 128, 64, 32, 1, true, "conv7x1_halo_bf16<128,64,c32>"},
+    {1, 3, 128, 64, 64, 2, false, "conv1x3_halo_bf16<128,64,c64>"},
+    {1, 3, 128, 64, 64, 2, true, "conv1x3_halo_bf16<128,64,c64>"},
+    {1, 3, 128, 64, 32, 1, false, "conv1x3_halo_bf16<128,64,c32>"},
+    {1, 3, 128, 64, 32, 1, true, "conv1x3_halo_bf16<128,64,c32>"},
+    {3, 1, 128, 64, 64, 2, false, "conv3x1_halo_bf16<128,64,c64>"},
+    {3, 1, 128, 64, 64, 2, true, "conv3x1_halo_bf16<128,64,c64>"},
+    {3, 1, 128, 64, 32, 1, false, "conv3x1_halo_bf16<128,64,c32>"},
+    {3, 1, 128, 64, 32, 1, true, "conv3x1_halo_bf16<128,64,c32>"},
 };
+constexpr int HALO_LINE = 14;                        // first entry of the one-dimensional filters
 constexpr int N_HALO_VARIANTS = sizeof(HALO_VARIANTS) / sizeof(HALO_VARIANTS[0]);
 constexpr int LDS_LIMIT = 160 * 1024;
 
@@ -252,9 +276,13 @@ constexpr int LDS_LIMIT = 160 * 1024;
 // as give about two workgroups per compute unit, each with at least two channel blocks, within
 // the workspace (one P x cout fp32 slice per split).  With one tile per compute unit or more the
 // extra pass over fp32 partial sums costs more than the idle units (measured).
+static long long halo_positions(const ConvArgs& a, int nb) {   // of the padded raster
+    return (long long)nb * (a.H + (a.kh - 1) / 2) * (a.W + (a.kw - 1) / 2);
+}
+
 static int halo_splits(const ConvArgs& a, const HaloVariant& v, int nb, int G) {
     if (!a.ws) return 1;
-    const long long PP = (long long)nb * (a.H + 1) * (a.W + 1), P = (long long)nb * a.H * a.W;
+    const long long PP = halo_positions(a, nb), P = (long long)nb * a.H * a.W;
     const long long tiles = G * ((PP + v.bp - 1) / v.bp) * ((a.cout + v.bc - 1) / v.bc);
     const int ncb = a.cin / v.cb;
     if (tiles >= cu_budget() || ncb < 4) return 1;
@@ -269,25 +297,27 @@ static int halo_splits(const ConvArgs& a, const HaloVariant& v, int nb, int G) {
 
 // Rows and bytes of LDS variant v needs for this layer; false when it does not fit.
 static bool halo_layout(const ConvArgs& a, const HaloVariant& v, int splits, int* hrows, int* nbuf, size_t* bytes) {
-    if (a.cin % v.cb) return false;
+    if (a.cin % v.cb || a.kh != v.kh || a.kw != v.kw) return false;
     const int rs = 256 / (v.cb / 8);
-    const int need = v.bp + 2 * (a.W + 1) + 2;
+    const int need = v.bp + (a.kh - 1) * (a.W + (a.kw - 1) / 2) + a.kw - 1;
     const int rows = (need + rs - 1) / rs * rs;
     const int ncb = a.cin / v.cb, per = (ncb + splits - 1) / splits;
     *hrows = rows;
     *nbuf = per > 1 && !v.single ? 2 : 1;
     // the blocks after the first arrive nhl load slots per tap
-    if (*nbuf == 2 && rows / rs > 9 * v.nhl) return false;
+    if (*nbuf == 2 && rows / rs > a.kh * a.kw * v.nhl) return false;
     *bytes = (size_t)2 * v.bc * v.cb * 2 + (size_t)*nbuf * rows * v.cb * 2 + (size_t)rows * 4;
     return *bytes <= (size_t)LDS_LIMIT;
 }
 
 static bool halo_shape_ok(const ConvArgs& a, int nb) {
-    if (a.kh != 3 || a.kw != 3 || a.sh != 1 || a.sw != 1 || a.pt != 1 || a.pl != 1) return false;
+    const bool square = a.kh == 3 && a.kw == 3;
+    const bool line = (a.kh == 1 && (a.kw == 7 || a.kw == 3)) || (a.kw == 1 && (a.kh == 7 || a.kh == 3));
+    if ((!square && !line) || a.sh != 1 || a.sw != 1 || a.pt != (a.kh - 1) / 2 || a.pl != (a.kw - 1) / 2) return false;
     if (a.Ho != a.H || a.Wo != a.W || a.pre_scale || a.cin % 32 || a.cout % 8) return false;
     // 32-bit byte offsets with 2^31 standing for 'outside'; float index arithmetic is exact below 2^24
-    if ((long long)nb * a.H * a.W * a.x.stride * 2 >= 0x7FFFFF00LL || (long long)a.cout * 9 * a.cin * 2 >= 0x7FFFFF00LL) return false;
-    if ((long long)nb * (a.H + 1) * (a.W + 1) >= (1LL << 24)) return false;
+    if ((long long)nb * a.H * a.W * a.x.stride * 2 >= 0x7FFFFF00LL || (long long)a.cout * a.kh * a.kw * a.cin * 2 >= 0x7FFFFF00LL) return false;
+    if (halo_positions(a, nb) >= (1LL << 24)) return false;
     return true;
 }
 
@@ -300,9 +330,21 @@ static bool halo_shape_ok(const ConvArgs& a, int nb) {
 int conv_halo_pick(const ConvArgs& a, int nb, int G) {
     if (!halo_shape_ok(a, nb)) return -1;
     int choice = -1;
+    const long long PP = halo_positions(a, nb);
+    const long long tiles = G * ((PP + 127) / 128) * ((a.cout + 63) / 64);
+    if (a.kh != 3 || a.kw != 3) {
+        // a one-dimensional filter: its four entries; one halo buffer under the same rule as below, and where two do not fit
+        const int base = HALO_LINE + 4 * (a.kh == 1 ? (a.kw == 7 ? 0 : 2) : (a.kh == 7 ? 1 : 3)) + (a.cin % 64 == 0 ? 0 : 2);
+        const bool one = a.cin > 64 && tiles > 2 * cu_budget();
+        for (int k = one ? 1 : 0; k < 2; k++) {
+            int hrows, nbuf;
+            size_t bytes;
+            const HaloVariant& v = HALO_VARIANTS[base + k];
+            if (halo_layout(a, v, halo_splits(a, v, nb, G), &hrows, &nbuf, &bytes)) return base + k;
+        }
+        return -1;
+    }
     if (a.cin % 64 == 0) {
-        const long long PP = (long long)nb * (a.H + 1) * (a.W + 1);
-        const long long tiles = G * ((PP + 127) / 128) * ((a.cout + 63) / 64);
         choice = a.cin > 64 && tiles > 2 * cu_budget() ? 6 : 0;
         // many tiles and whole 128-channel tiles: the wider tile reads two fragments per matrix-core instruction instead of three
         if (a.cin > 64 && a.cout % 128 == 0 && tiles / 2 >= 3 * cu_budget()) choice = 8;
@@ -319,20 +361,20 @@ int conv_halo_pick(const ConvArgs& a, int nb, int G) {
 
 const char* conv_halo_name(int variant) { return HALO_VARIANTS[variant].name; }
 
-template <int BP, int BC, int WP, int WC, int CB, int NHL>
+template <int KH, int KW, int BP, int BC, int WP, int WC, int CB, int NHL>
 static hipError_t launch_halo_variant(const ConvArgs& a, const ConvArgs* argv, int G, int nb, int splits, int hrows,
                                       int nbuf, size_t bytes, hipStream_t s) {
     static bool raised = false;                                  // LDS above 64 KB has to be asked for once
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)&conv3x3_halo_bf16<BP, BC, WP, WC, CB, NHL>,
+        hipError_t e = hipFuncSetAttribute((const void*)&conv_halo_bf16<KH, KW, BP, BC, WP, WC, CB, NHL>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    const long long PP = (long long)nb * (a.H + 1) * (a.W + 1);
+    const long long PP = halo_positions(a, nb);
     const dim3 grid((unsigned)(((PP + BP - 1) / BP) * ((a.cout + BC - 1) / BC)), splits, G);
-    if (splits > 1) ENS_LAUNCH_FIRST((conv3x3_halo_bf16<BP, BC, WP, WC, CB, NHL>), grid, dim3(256), bytes, s, argv, nb, hrows, nbuf);
-    else ENS_LAUNCH((conv3x3_halo_bf16<BP, BC, WP, WC, CB, NHL>), grid, dim3(256), bytes, s, argv, nb, hrows, nbuf);
+    if (splits > 1) ENS_LAUNCH_FIRST((conv_halo_bf16<KH, KW, BP, BC, WP, WC, CB, NHL>), grid, dim3(256), bytes, s, argv, nb, hrows, nbuf);
+    else ENS_LAUNCH((conv_halo_bf16<KH, KW, BP, BC, WP, WC, CB, NHL>), grid, dim3(256), bytes, s, argv, nb, hrows, nbuf);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && splits > 1) e = launch_conv_splitk_epilogue(a, argv, G, nb, nb * a.H * a.W, splits, s);
     return e;
@@ -347,19 +389,37 @@ hipError_t launch_conv_halo(const ConvArgs& a, const ConvArgs* argv, int G, int 
     int splits = halo_splits(a, HALO_VARIANTS[variant], nb, G);
     if (!halo_layout(a, HALO_VARIANTS[variant], splits, &hrows, &nbuf, &bytes)) return hipErrorInvalidValue;
     switch (variant) {
-        case 0: return launch_halo_variant<128, 64, 2, 2, 64, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
-        case 1: return launch_halo_variant<256, 64, 4, 1, 64, 2>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
-        case 2: return launch_halo_variant<128, 128, 2, 2, 64, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
-        case 3: return launch_halo_variant<256, 64, 4, 1, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
-        case 4: return launch_halo_variant<128, 64, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
-        case 5: return launch_halo_variant<128, 128, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
-        case 6: return launch_halo_variant<128, 64, 2, 2, 64, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
-        case 7: return launch_halo_variant<256, 64, 4, 1, 64, 2>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
-        case 8: return launch_halo_variant<128, 128, 2, 2, 64, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
-        case 9: return launch_halo_variant<128, 64, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
-        case 10: return launch_halo_variant<256, 64, 4, 1, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
-        case 11: return launch_halo_variant<128, 128, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
-        default: return launch_halo_variant<256, 32, 4, 1, 64, 2>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 0: return launch_halo_variant<3, 3, 128, 64, 2, 2, 64, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 1: return launch_halo_variant<3, 3, 256, 64, 4, 1, 64, 2>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 2: return launch_halo_variant<3, 3, 128, 128, 2, 2, 64, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 3: return launch_halo_variant<3, 3, 256, 64, 4, 1, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 4: return launch_halo_variant<3, 3, 128, 64, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 5: return launch_halo_variant<3, 3, 128, 128, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 6: return launch_halo_variant<3, 3, 128, 64, 2, 2, 64, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 7: return launch_halo_variant<3, 3, 256, 64, 4, 1, 64, 2>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 8: return launch_halo_variant<3, 3, 128, 128, 2, 2, 64, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 9: return launch_halo_variant<3, 3, 128, 64, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 10: return launch_halo_variant<3, 3, 256, 64, 4, 1, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 11: return launch_halo_variant<3, 3, 128, 128, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case 12:
+        case 13: return launch_halo_variant<3, 3, 256, 32, 4, 1, 64, 2>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case HALO_LINE + 0:
+        case HALO_LINE + 1: return launch_halo_variant<1, 7, 128, 64, 2, 2, 64, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case HALO_LINE + 2:
+        case HALO_LINE + 3: return launch_halo_variant<1, 7, 128, 64, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case HALO_LINE + 4:
+        case HALO_LINE + 5: return launch_halo_variant<7, 1, 128, 64, 2, 2, 64, 2>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case HALO_LINE + 6:
+        case HALO_LINE + 7: return launch_halo_variant<7, 1, 128, 64, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case HALO_LINE + 8:
+        case HALO_LINE + 9: return launch_halo_variant<1, 3, 128, 64, 2, 2, 64, 2>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case HALO_LINE + 10:
+        case HALO_LINE + 11: return launch_halo_variant<1, 3, 128, 64, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case HALO_LINE + 12:
+        case HALO_LINE + 13: return launch_halo_variant<3, 1, 128, 64, 2, 2, 64, 2>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        case HALO_LINE + 14:
+        case HALO_LINE + 15: return launch_halo_variant<3, 1, 128, 64, 2, 2, 32, 1>(a, argv, G, nb, splits, hrows, nbuf, bytes, s);
+        default: return hipErrorInvalidValue;
     }
 }
 

@@ -170,12 +170,18 @@ CONV_LAYERS = [
     (56, 56, 64, 256, 1, 1, "same", {}),
     (28, 28, 128, 128, 3, 2, "same", {}),
     (14, 14, 256, 512, 1, 2, "same", {"act": None}),
-    (17, 17, 128, 192, (1, 7), 1, "same", {}),
-    (17, 17, 128, 160, (7, 1), 1, "same", {}),
+    (17, 17, 128, 192, (1, 7), 1, "same", {"ran": "conv1x7_halo_bf16<128,64,c64>"}),   # window-in-LDS kernel, filters along one axis
+    (17, 17, 128, 160, (7, 1), 1, "same", {"ran": "conv7x1_halo_bf16<128,64,c64>"}),
+    (17, 17, 160, 192, (7, 1), 1, "same", {"ran": "conv7x1_halo_bf16<128,64,c32>"}),   # ... 32-channel blocks
+    (17, 17, 160, 160, (1, 7), 1, "same", {"ran": "conv1x7_halo_bf16<128,64,c32>"}),
+    (9, 30, 64, 72, (1, 7), 1, "same", {"ran": "conv1x7_halo_bf16<128,64,c64>", "act": None}),   # ... one channel block, wide rows
+    (30, 9, 96, 64, (7, 1), 1, "same", {"ran": "conv7x1_halo_bf16<128,64,c32>", "res": False}),
     (35, 35, 48, 64, 5, 1, "same", {}),
     (35, 35, 96, 96, 3, 2, "valid", {}),
-    (8, 8, 384, 384, (1, 3), 1, "same", {}),
-    (8, 8, 448, 384, (3, 1), 1, "same", {}),
+    (8, 8, 384, 384, (1, 3), 1, "same", {"ran": "conv1x3_halo_bf16<128,64,c64>"}),
+    (8, 8, 448, 384, (3, 1), 1, "same", {"ran": "conv3x1_halo_bf16<128,64,c64>"}),
+    (11, 13, 96, 40, (3, 1), 1, "same", {"ran": "conv3x1_halo_bf16<128,64,c32>"}),
+    (11, 13, 224, 136, (1, 3), 1, "same", {"ran": "conv1x3_halo_bf16<128,64,c32>"}),
     (28, 28, 40, 240, 1, 1, "same", {"act": "silu"}),
     (28, 28, 192, 32, 3, 1, "same", {"bn": False, "act": None, "bias": False}),
     (28, 28, 160, 128, 1, 1, "same", {"pre": True}),
@@ -201,6 +207,9 @@ MANY_TILES = [
     ((28, 28, 128, 128, 1, 1, "same", {"res": True}), 48),      # ... with the residual
     ((56, 56, 256, 512, 1, 2, "same", {"act": None}), 6),       # ... strided: tiles that span rows and images of the output
     ((28, 28, 128, 256, 3, 1, "same", {}), 64),                 # window-in-LDS 3x3 kernel with 128 x 128 tiles: 842 of them
+    ((17, 17, 192, 192, (1, 7), 1, "same", {"ran": "conv1x7_halo_bf16<128,64,c64>"}), 96),   # ... 1x7 and 7x1: 765 tiles, one halo buffer
+    ((17, 17, 192, 192, (7, 1), 1, "same", {"ran": "conv7x1_halo_bf16<128,64,c64>"}), 96),
+    ((8, 8, 384, 384, (3, 1), 1, "same", {"ran": "conv3x1_halo_bf16<128,64,c64>"}), 160),    # ... 3x1: 540 tiles
 ]
 
 
@@ -210,6 +219,7 @@ def test_conv_layer_bf16(ens, case, nb):
     h, w, cin, cout, k, stride, pad, extra = case
     extra = dict(extra)
     with_res = extra.pop("res", False)
+    ran = extra.pop("ran", None)                                # the kernel class that has to run the layer
     net, t = layer_net(h, w, cin, lambda n, s: n.conv(s, cout, k, stride=stride, pad=pad,
                                                       res=s if with_res else None, **extra), "bf16")
     blobs, imgs = prepared([net], 11, nb, h, bf16=True)
@@ -218,7 +228,11 @@ def test_conv_layer_bf16(ens, case, nb):
     E.set_base_size(h, w)
     E.ens_debug_keep_tensors()
     E.ens_set_alloc([[max(4, nb)]])
+    E.ens_set_profiling(1 if ran else 0)
     E.ens_predict(imgs)
+    if ran:
+        classes = [kk["name"] for kk in E.ens_profile() if kk["launches"]]
+        assert ran in classes, classes
     got = E.ens_debug_tensor(0, t, net.tensors[t], nb)
     # feed the oracle the bf16 tensor the GPU layer actually read, so only this layer is compared
     src = net.ops[-3]["src"]
