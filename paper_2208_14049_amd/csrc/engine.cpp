@@ -130,7 +130,8 @@ static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G
             a.bias = o.kind == ENS_OP_DWCONV ? (const float*)(P + pl.b) : nullptr;
             a.scale = o.kind == ENS_OP_DWCONV ? (const float*)(P + pl.scale) : nullptr;
             a.nb = w.batch; a.H = ts.h; a.W = ts.w; a.c = o.cin; a.Ho = td.h; a.Wo = td.w;
-            a.kh = o.kh; a.kw = o.kw; a.sh = o.sh; a.sw = o.sw; a.pt = o.pt; a.pl = o.pl; a.act = o.act;
+            a.kh = o.kh; a.kw = o.kw; a.sh = o.sh; a.sw = o.sw; a.pt = o.pt; a.pl = o.pl;
+            a.act = o.kind == ENS_OP_DWCONV ? o.act : ACT_NONE;  // a pool has none of its own
             a.sums = nullptr; a.sums_stride = 0;
             L.flop = o.kind == ENS_OP_DWCONV ? 2.0 * nb * td.h * td.w * o.cin * o.kh * o.kw : 0.0;
             L.bytes = nb * ((double)ts.h * ts.w + (double)td.h * td.w) * o.cin * es;
@@ -286,6 +287,14 @@ static int build_launches(ens_handle* h, Gang& g, bool may_alloc = true) {
             summed[i + 1] = 2;
         }
     }
+    // Average pools that change places with the 1x1 convolution behind them: swapped[] 1 marks the pool's place
+    // (the convolution runs there), 2 the convolution's (the pool runs there, on the convolution's channels).
+    std::vector<char> swapped(m.ops.size(), 0);
+    for (size_t i = 0; i + 1 < m.ops.size(); i++) {
+        if (!m.ops[i].swap_pool || h->keep_tensors || chain[i] || chain[i + 1] || fused[i] || fused[i + 1] || gated[i + 1]) continue;
+        swapped[i] = 1;
+        swapped[i + 1] = 2;
+    }
     std::vector<size_t> first_blk(m.ops.size() + 1, 0);          // argument blocks: G * sub per operation
     for (size_t i = 0; i < m.ops.size(); i++)
         first_blk[i + 1] = first_blk[i] + (fused[i] == 2 || chain[i] == 2 ? 0
@@ -395,9 +404,35 @@ static int build_launches(ens_handle* h, Gang& g, bool may_alloc = true) {
         for (int sub = nsub - 1; sub >= 0; sub--)
             for (int k = G - 1; k >= 0; k--) {                   // (k, sub) == (0, 0) last: L keeps the leader's first block
                 const Member& mk = h->members[h->workers[g.workers[k]].member];
-                const OpPlan& pl = fused[i] == 1 && (sub == 1) != second_leads ? mk.ops[i + 1] : mk.ops[i];
+                const OpPlan& pl = swapped[i] == 1 ? mk.ops[i + 1] : swapped[i] == 2 ? mk.ops[i - 1]
+                                   : fused[i] == 1 && (sub == 1) != second_leads ? mk.ops[i + 1] : mk.ops[i];
                 const int rc = fill_args(h, h->workers[g.workers[k]], leader, G, pl, L, fused[i] == 1 ? 0 : sub);
                 if (rc != ENS_OK) return rc;
+                if (swapped[i]) {
+                    // the convolution first: from the pool's input into the pool's output memory, as many channels wide
+                    // as the convolution has, batch-norm but no activation; then the pool over that, with the activation
+                    const Worker& wk = h->workers[g.workers[k]];
+                    const OpPlan& q = swapped[i] == 1 ? mk.ops[i] : mk.ops[i - 1];
+                    const OpPlan& c = swapped[i] == 1 ? mk.ops[i + 1] : mk.ops[i];
+                    View mid;
+                    mid.p = wk.arena + wk.layout.offset[q.op.dst];
+                    mid.stride = c.op.cout;
+                    mid.c0 = 0;
+                    const double px = (double)wk.batch * mk.tensors[q.op.dst].h * mk.tensors[q.op.dst].w;
+                    if (swapped[i] == 1) {
+                        L.conv.x = view_of(wk, leader, mk, q.op.src, q.op.src_c0);
+                        L.conv.y = mid;
+                        L.conv.act = ACT_NONE;
+                        L.klass = prof_class(h, conv_bf16_variant_name(L.conv, G));
+                    } else {
+                        L.pool.x = mid;
+                        L.pool.y = view_of(wk, leader, mk, c.op.dst, c.op.dst_c0);
+                        L.pool.c = c.op.cout;
+                        L.pool.act = c.op.act;
+                        L.bytes = px * c.op.cout * 2.0 * 2.0;
+                        L.klass = prof_class(h, "window_kernel<avgpool,act>");
+                    }
+                }
                 const double se_pass = L.bytes / 3.0;            // squeeze-excite: the tensor is read twice and written once
                 if (summed[i] == 1) {                            // the sums go to the scratch of the block behind
                     const Worker& wk = h->workers[g.workers[k]];

@@ -57,6 +57,12 @@ struct OpPlan {
     // the channel sums the block starts from (one row per workgroup, in the block's scratch, which then lives
     // from this operation on and holds se_cap rows), and the block does not read the tensor for them.
     bool fuse_sums;
+    // This 3x3 / stride-1 / padding-1 average pool is followed by a plain 1x1 convolution that alone reads its output
+    // and has no more output channels than the pool has channels (the pool branch of an inception module): the
+    // two are linear and commute, so the convolution (with its batch-norm, which an average whose weights add up
+    // to one also commutes with) can run first, into the pool's output memory, and the pool then averages the
+    // narrower tensor and applies the activation.
+    bool swap_pool;
     int se_cap;      // squeeze-excite: rows of partial sums its scratch holds per image
 };
 

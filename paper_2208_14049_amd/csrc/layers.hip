@@ -602,6 +602,14 @@ __global__ void avgpool_bf16_kernel(const PoolArgs* __restrict__ argv, const int
     const float inv = cnt ? 1.f / (float)cnt : 0.f;
 #pragma unroll
     for (int e = 0; e < 8; e++) acc[e] *= inv;
+    // the activation of a 1x1 convolution that changed places with this pool
+    if (a.act == ACT_RELU) {
+#pragma unroll
+        for (int e = 0; e < 8; e++) acc[e] = fmaxf(acc[e], 0.f);
+    } else if (a.act == ACT_SILU) {
+#pragma unroll
+        for (int e = 0; e < 8; e++) acc[e] = acc[e] / (1.f + __expf(-acc[e]));
+    }
     *(uint4*)((uint16_t*)a.y.p + (long long)pu * a.y.stride + a.y.c0 + c) = pack8(acc);
 }
 
@@ -656,6 +664,8 @@ hipError_t launch_pool(const PoolArgs& a, const PoolArgs* argv, int G, int nb, b
     const long long total = (long long)nb * a.Ho * a.Wo * (a.c / (bf16 ? 8 : 1));
     if (total >= (1LL << 31) - 256) return hipErrorInvalidValue;   // 32-bit work item index in the kernel
     const dim3 g(blocks_for(total, 256), 1, G), b(256);
+    // only the two bf16 average-pool kernels apply an activation
+    if (a.act != ACT_NONE && (is_max || !bf16 || a.kh != a.kw || (a.kh != 3 && a.kh != 2))) return hipErrorInvalidValue;
     if (is_max) {
         // every window must overlap the image for the clamped fast path (true for the padded layers of real networks)
         const bool overlap = a.pt < a.kh && a.pl < a.kw && (a.Ho - 1) * a.sh - a.pt < a.H && (a.Wo - 1) * a.sw - a.pl < a.W;

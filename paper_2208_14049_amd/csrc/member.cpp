@@ -134,6 +134,7 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         pl.fuse_pool = false;
         pl.fuse_gate = false;
         pl.fuse_sums = false;
+        pl.swap_pool = false;
         pl.se_cap = SE_MAX_SPLITS;
         TensorInfo& ts = m.tensors[o.src];
         TensorInfo& td = m.tensors[o.dst];
@@ -481,6 +482,27 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
             // the convolution then reads the block's input and its scratch (the gates)
             m.tensors[e.src].last = std::max(m.tensors[e.src].last, i + 1);
             m.tensors[m.ops[i].scratch].last = std::max(m.tensors[m.ops[i].scratch].last, i + 1);
+        }
+    }
+    // A 3x3 / stride-1 / padding-1 average pool followed by a plain 1x1 convolution that alone reads its output
+    if (m.bf16) {
+        for (int i = 0; i + 1 < spec.n_ops; i++) {
+            const ens_op &q = spec.ops[i], &c = spec.ops[i + 1];
+            if (q.kind != ENS_OP_AVGPOOL || c.kind != ENS_OP_CONV) continue;
+            if (q.kh != 3 || q.kw != 3 || q.sh != 1 || q.sw != 1 || q.pt != 1 || q.pl != 1) continue;
+            if (c.kh != 1 || c.kw != 1 || c.sh != 1 || c.sw != 1 || c.pt != 0 || c.pl != 0 || c.r > 1 || c.pre || c.res >= 0) continue;
+            if (c.src != q.dst || q.dst_c0 != 0 || c.src_c0 != 0 || c.cin != q.cin || m.tensors[q.dst].c != q.cin) continue;
+            if (q.dst == q.src || c.dst == q.dst || c.cout > q.cin || c.cout % 8) continue;
+            if (m.ops[i + 1].fuse_next || m.ops[i + 1].fuse_chain || m.ops[i + 1].fuse_dense || m.ops[i + 1].fuse_pool) continue;
+            if (i > 0 && m.ops[i - 1].fuse_next) continue;
+            int readers = 0;
+            for (int k = 0; k < spec.n_ops; k++) {
+                const ens_op& o = spec.ops[k];
+                readers += o.src == q.dst;
+                readers += o.kind == ENS_OP_CONV && o.res == q.dst;
+            }
+            if (readers != 1) continue;
+            m.ops[i].swap_pool = true;
         }
     }
     // The rewritten stem followed by a 3x3 / stride-2 / padding-1 max-pool that alone reads its output

@@ -673,6 +673,50 @@ def test_depthwise_leaves_the_channel_sums(ens, h, c, k, s, r, nb, G, proj):
         assert d.max() <= 2.0 ** -7 * np.abs(outs[1][g]).max() and (d > 0).mean() < 0.02, (g, float(d.max()), float((d > 0).mean()))
 
 
+@pytest.mark.parametrize("h,w,cin,cout,act,G,nb", [(35, 35, 192, 32, "relu", 1, 3), (17, 17, 768, 192, "relu", 1, 5), (8, 8, 1280, 192, "relu", 2, 9),
+                                                    (9, 13, 64, 64, "silu", 1, 4), (12, 7, 96, 8, None, 1, 2)],
+                         ids=["35x35x192-32", "17x17x768-192", "8x8x1280-192_gang2", "9x13x64-64_silu", "12x7x96-8_linear"])
+def test_average_pool_changes_places_with_the_projection(ens, h, w, cin, cout, act, G, nb):
+    """The pool branch of an inception module: a 3x3 / stride-1 average pool (over the in-bounds part of its window)
+    and a 1x1 convolution with batch-norm and activation.  Both are linear up to the activation and the weights of
+    an average add up to one, so the library runs convolution and batch-norm first (into the pool's output memory,
+    cout channels wide) and the pool, which then applies the activation, on that narrower tensor.  The module's
+    output slice is compared with the oracle (which pools first, as the network says) element by element and with
+    the library run layer by layer; the profile says which kernels ran."""
+    nets = []
+    for g in range(G):
+        n = N.Net("pb%d" % g, h, w, 8, dtype="bf16")
+        x = n.conv(0, cin, 1, act="relu")
+        o = n.tensor(h, w, 16 + cout)
+        n.conv(x, 16, 1, dst=(o, 0))
+        u = n.avgpool(x, 3, 1, 1)
+        n.conv(u, cout, 1, act=act, dst=(o, 16))
+        n.fc(n.gap(o), 8)
+        nets.append(n)
+    blobs = [W.quantise_weights_bf16(n, W.make_blob(n, 121, i)) for i, n in enumerate(nets)]
+    imgs = W.round_bf16(W.make_images(122, nb, h, w))
+    outs = []
+    for keep in (False, True):
+        E = ens.Ensemble(nets, blobs)
+        E.set_base_size(h, w)
+        if keep:
+            E.ens_debug_keep_tensors()
+        E.ens_set_alloc([[nb] * G])
+        E.ens_set_profiling(1)
+        E.ens_predict(imgs)
+        ran = {kk["name"]: kk["launches"] for kk in E.ens_profile() if kk["launches"]}
+        assert ran.get("window_kernel<avgpool,act>", 0) == (0 if keep else 1), ran
+        assert ran.get("window_kernel<avgpool>", 0) == (1 if keep else 0), ran
+        outs.append([E.ens_debug_tensor(g, o, nets[g].tensors[o], nb) for g in range(G)])
+        E.close()
+    for g in range(G):
+        ref = oracle_tensor(nets[g], blobs[g], imgs, o)
+        assert np.abs(ref[..., 16:]).max() > 0.1
+        assert_after_bf16_layers(outs[0][g], ref, (g, "convolution first"))
+        assert_after_bf16_layers(outs[1][g], ref, (g, "layer by layer"))
+        assert np.array_equal(outs[0][g][..., :16], outs[1][g][..., :16])      # the other branch is the same launch either way
+
+
 def test_resize_staging(ens):
     """A member at 45 x 45 fed from 32 x 32 requests: bilinear resize inside the library."""
     for dtype in ("fp32", "bf16"):
