@@ -133,6 +133,7 @@ static int fill_args(ens_handle* h, const Worker& w, const Worker& leader, int G
             a.kh = o.kh; a.kw = o.kw; a.sh = o.sh; a.sw = o.sw; a.pt = o.pt; a.pl = o.pl;
             a.act = o.kind == ENS_OP_DWCONV ? o.act : ACT_NONE;  // a pool has none of its own
             a.sums = nullptr; a.sums_stride = 0;
+            a.pre_scale = a.pre_shift = nullptr;
             L.flop = o.kind == ENS_OP_DWCONV ? 2.0 * nb * td.h * td.w * o.cin * o.kh * o.kw : 0.0;
             L.bytes = nb * ((double)ts.h * ts.w + (double)td.h * td.w) * o.cin * es;
             L.klass = prof_class(h, o.kind == ENS_OP_DWCONV ? "window_kernel<dwconv>"
@@ -295,6 +296,15 @@ static int build_launches(ens_handle* h, Gang& g, bool may_alloc = true) {
         swapped[i] = 1;
         swapped[i + 1] = 2;
     }
+    // ... and pre-activated 1x1 convolutions that let the 2x2 average pool behind them go first: 3 marks the
+    // convolution's place (the pool runs there, on the convolution's input), 4 the pool's (the convolution, on the pooled map)
+    for (size_t i = 0; i + 1 < m.ops.size(); i++) {
+        if (!m.ops[i].swap_conv || h->keep_tensors || chain[i] || chain[i + 1] || fused[i] || fused[i + 1] || gated[i] || swapped[i] ||
+            swapped[i + 1])
+            continue;
+        swapped[i] = 3;
+        swapped[i + 1] = 4;
+    }
     std::vector<size_t> first_blk(m.ops.size() + 1, 0);          // argument blocks: G * sub per operation
     for (size_t i = 0; i < m.ops.size(); i++)
         first_blk[i + 1] = first_blk[i] + (fused[i] == 2 || chain[i] == 2 ? 0
@@ -404,11 +414,42 @@ static int build_launches(ens_handle* h, Gang& g, bool may_alloc = true) {
         for (int sub = nsub - 1; sub >= 0; sub--)
             for (int k = G - 1; k >= 0; k--) {                   // (k, sub) == (0, 0) last: L keeps the leader's first block
                 const Member& mk = h->members[h->workers[g.workers[k]].member];
-                const OpPlan& pl = swapped[i] == 1 ? mk.ops[i + 1] : swapped[i] == 2 ? mk.ops[i - 1]
+                const OpPlan& pl = swapped[i] == 1 || swapped[i] == 3 ? mk.ops[i + 1] : swapped[i] == 2 || swapped[i] == 4 ? mk.ops[i - 1]
                                    : fused[i] == 1 && (sub == 1) != second_leads ? mk.ops[i + 1] : mk.ops[i];
                 const int rc = fill_args(h, h->workers[g.workers[k]], leader, G, pl, L, fused[i] == 1 ? 0 : sub);
                 if (rc != ENS_OK) return rc;
-                if (swapped[i]) {
+                if (swapped[i] >= 3) {
+                    // the pool first: pre-activation and average of the convolution's input into the convolution's output
+                    // memory, as many channels wide as that input; then the convolution over the pooled map, nothing in front
+                    const Worker& wk = h->workers[g.workers[k]];
+                    const OpPlan& c = swapped[i] == 3 ? mk.ops[i] : mk.ops[i - 1];
+                    const OpPlan& q = swapped[i] == 3 ? mk.ops[i + 1] : mk.ops[i];
+                    const TensorInfo &tx = mk.tensors[c.op.src], &tq = mk.tensors[q.op.dst];
+                    View mid;
+                    mid.p = wk.arena + wk.layout.offset[c.op.dst];
+                    mid.stride = c.op.cin;
+                    mid.c0 = 0;
+                    const char* P = mk.dev_params;
+                    if (swapped[i] == 3) {
+                        L.pool.x = view_of(wk, leader, mk, c.op.src, c.op.src_c0);
+                        L.pool.y = mid;
+                        L.pool.c = c.op.cin;
+                        L.pool.H = tx.h; L.pool.W = tx.w;
+                        L.pool.pre_scale = (const float*)(P + c.pre_scale);
+                        L.pool.pre_shift = (const float*)(P + c.pre_shift);
+                        L.bytes = (double)wk.batch * ((double)tx.h * tx.w + (double)tq.h * tq.w) * c.op.cin * 2.0;
+                        L.klass = prof_class(h, "window_kernel<avgpool,pre>");
+                    } else {
+                        L.conv.x = mid;
+                        L.conv.y = view_of(wk, leader, mk, q.op.dst, q.op.dst_c0);
+                        L.conv.pre_scale = L.conv.pre_shift = nullptr;
+                        L.conv.H = L.conv.Ho = tq.h; L.conv.W = L.conv.Wo = tq.w;
+                        L.conv.inv_hw = 1.0 / ((double)tq.h * tq.w); L.conv.inv_w = 1.0 / (double)tq.w;
+                        L.flop = 2.0 * wk.batch * tq.h * tq.w * (double)c.op.cout * c.op.cin;
+                        L.bytes = (double)wk.batch * tq.h * tq.w * (c.op.cin + c.op.cout) * 2.0 + (double)c.op.cin * c.op.cout * 2.0;
+                        L.klass = prof_class(h, conv_bf16_variant_name(L.conv, G));
+                    }
+                } else if (swapped[i]) {
                     // the convolution first: from the pool's input into the pool's output memory, as many channels wide
                     // as the convolution has, batch-norm but no activation; then the pool over that, with the activation
                     const Worker& wk = h->workers[g.workers[k]];

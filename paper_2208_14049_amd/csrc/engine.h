@@ -63,6 +63,10 @@ struct OpPlan {
     // to one also commutes with) can run first, into the pool's output memory, and the pool then averages the
     // narrower tensor and applies the activation.
     bool swap_pool;
+    // This pre-activated 1x1 convolution without an activation of its own is followed by a 2x2 / stride-2 average
+    // pool that alone reads its output (the transition between two dense blocks): pre-activation and pool can run
+    // first, into the convolution's output memory, and the convolution on a quarter of the pixels.
+    bool swap_conv;
     int se_cap;      // squeeze-excite: rows of partial sums its scratch holds per image
 };
 

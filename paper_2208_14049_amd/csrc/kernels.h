@@ -63,6 +63,10 @@ struct PoolArgs {              // max / average pooling, depthwise convolution
     // block's scratch (per image `sums_stride` floats apart, one row of c floats per workgroup of the image), or null
     float* sums;
     int sums_stride;
+    // average pool that runs in front of the pre-activated 1x1 convolution it stood behind: relu(x * pre_scale[c] +
+    // pre_shift[c]) (fp32, per channel) is what it averages; null: the values as they are
+    const float* pre_scale;
+    const float* pre_shift;
 };
 
 struct GapArgs {               // global average pool to fp32 [nb][c]

@@ -588,6 +588,15 @@ __global__ void avgpool_bf16_kernel(const PoolArgs* __restrict__ argv, const int
             xv[kh * K + kw] = *(const uint4*)(x + (long long)(hic * a.W + wic) * a.x.stride);
         }
     }
+    // the pre-activation of a 1x1 convolution that lets this pool go first: relu(x * scale + shift) is averaged
+    const bool pre = a.pre_scale != nullptr;
+    float ps[8], pf[8];
+    if (pre) {
+        *(float4*)ps = *(const float4*)(a.pre_scale + c);
+        *(float4*)(ps + 4) = *(const float4*)(a.pre_scale + c + 4);
+        *(float4*)pf = *(const float4*)(a.pre_shift + c);
+        *(float4*)(pf + 4) = *(const float4*)(a.pre_shift + c + 4);
+    }
 #pragma unroll
     for (int kh = 0; kh < K; kh++)
 #pragma unroll
@@ -595,6 +604,10 @@ __global__ void avgpool_bf16_kernel(const PoolArgs* __restrict__ argv, const int
             const bool ok = (unsigned)(ho * a.sh - a.pt + kh) < (unsigned)a.H && (unsigned)(wo * a.sw - a.pl + kw) < (unsigned)a.W;
             float f[8];
             unpack8(xv[kh * K + kw], f);
+            if (pre) {
+#pragma unroll
+                for (int e = 0; e < 8; e++) f[e] = fmaxf(fmaf(f[e], ps[e], pf[e]), 0.f);
+            }
             cnt += ok ? 1 : 0;
 #pragma unroll
             for (int e = 0; e < 8; e++) acc[e] += ok ? f[e] : 0.f;
@@ -664,8 +677,9 @@ hipError_t launch_pool(const PoolArgs& a, const PoolArgs* argv, int G, int nb, b
     const long long total = (long long)nb * a.Ho * a.Wo * (a.c / (bf16 ? 8 : 1));
     if (total >= (1LL << 31) - 256) return hipErrorInvalidValue;   // 32-bit work item index in the kernel
     const dim3 g(blocks_for(total, 256), 1, G), b(256);
-    // only the two bf16 average-pool kernels apply an activation
-    if (a.act != ACT_NONE && (is_max || !bf16 || a.kh != a.kw || (a.kh != 3 && a.kh != 2))) return hipErrorInvalidValue;
+    // only the two bf16 average-pool kernels apply an activation or a pre-activation
+    if ((a.act != ACT_NONE || a.pre_scale) && (is_max || !bf16 || a.kh != a.kw || (a.kh != 3 && a.kh != 2))) return hipErrorInvalidValue;
+    if ((a.pre_scale == nullptr) != (a.pre_shift == nullptr) || ((uintptr_t)a.pre_scale & 15) || ((uintptr_t)a.pre_shift & 15)) return hipErrorInvalidValue;
     if (is_max) {
         // every window must overlap the image for the clamped fast path (true for the padded layers of real networks)
         const bool overlap = a.pt < a.kh && a.pl < a.kw && (a.Ho - 1) * a.sh - a.pt < a.H && (a.Wo - 1) * a.sw - a.pl < a.W;

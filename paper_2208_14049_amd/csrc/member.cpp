@@ -135,6 +135,7 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
         pl.fuse_gate = false;
         pl.fuse_sums = false;
         pl.swap_pool = false;
+        pl.swap_conv = false;
         pl.se_cap = SE_MAX_SPLITS;
         TensorInfo& ts = m.tensors[o.src];
         TensorInfo& td = m.tensors[o.dst];
@@ -503,6 +504,32 @@ int build_member(const ens_member_spec& spec, const float* params, Member* out) 
             }
             if (readers != 1) continue;
             m.ops[i].swap_pool = true;
+        }
+    }
+    // A pre-activated 1x1 convolution with no activation, followed by a 2x2 / stride-2 average pool that alone reads its output
+    if (m.bf16) {
+        for (int i = 0; i + 1 < spec.n_ops; i++) {
+            const ens_op &c = spec.ops[i], &q = spec.ops[i + 1];
+            if (c.kind != ENS_OP_CONV || q.kind != ENS_OP_AVGPOOL) continue;
+            if (q.kh != 2 || q.kw != 2 || q.sh != 2 || q.sw != 2 || q.pt != 0 || q.pl != 0) continue;
+            if (c.kh != 1 || c.kw != 1 || c.sh != 1 || c.sw != 1 || c.pt != 0 || c.pl != 0 || c.r > 1 || !c.pre || c.res >= 0 ||
+                c.act != ENS_ACT_NONE)
+                continue;
+            if (q.src != c.dst || c.dst_c0 != 0 || q.src_c0 != 0 || q.cin != c.cout || m.tensors[c.dst].c != c.cout) continue;
+            if (c.dst == c.src || q.dst == c.dst || c.cin % 8 || c.cout % 8 || m.ops[i].cin_s != c.cin) continue;
+            if (m.ops[i].fuse_next || m.ops[i].fuse_chain || m.ops[i].fuse_dense || m.ops[i].fuse_pool) continue;
+            if (i > 0 && (m.ops[i - 1].fuse_next || m.ops[i - 1].fuse_dense)) continue;
+            const TensorInfo &tu = m.tensors[c.dst], &tq = m.tensors[q.dst];
+            if ((long long)tq.h * tq.w * c.cin > (long long)tu.h * tu.w * c.cout) continue;   // the pooled input fits the middle tensor
+            int readers = 0;
+            for (int k = 0; k < spec.n_ops; k++) {
+                const ens_op& o = spec.ops[k];
+                readers += o.src == c.dst;
+                readers += o.kind == ENS_OP_CONV && o.res == c.dst;
+            }
+            if (readers != 1) continue;
+            m.ops[i].swap_conv = true;
+            pack_operand_order(m.ops[i]);                        // behind the pool it is a plain 1x1 layer: the kernel of conv_pw.hip
         }
     }
     // The rewritten stem followed by a 3x3 / stride-2 / padding-1 max-pool that alone reads its output

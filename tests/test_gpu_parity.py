@@ -717,6 +717,50 @@ def test_average_pool_changes_places_with_the_projection(ens, h, w, cin, cout, a
         assert np.array_equal(outs[0][g][..., :16], outs[1][g][..., :16])      # the other branch is the same launch either way
 
 
+@pytest.mark.parametrize("h,w,cin,cout,bn,G,nb", [(56, 56, 256, 128, False, 1, 3), (15, 15, 64, 32, False, 1, 5), (14, 14, 1024, 512, False, 2, 7),
+                                                   (9, 12, 1792, 896, False, 1, 4), (28, 28, 96, 64, True, 1, 2)],
+                         ids=["56x56x256-128", "15x15x64-32_odd", "14x14x1024-512_gang2", "9x12x1792-896", "28x28x96-64_affine"])
+def test_transition_pools_before_its_convolution(ens, h, w, cin, cout, bn, G, nb):
+    """The transition between two dense blocks: a pre-activated 1x1 convolution with no activation behind it and a
+    2x2 / stride-2 average pool.  The convolution is linear (with a batch-norm of its own: affine, which an average
+    commutes with as well), so the library averages the pre-activated input first, into the convolution's output
+    memory, and runs the convolution on a quarter of the pixels.  The pooled output is compared with the oracle
+    (which convolves first, as the network says) element by element and with the library run layer by layer; the
+    profile says which kernels ran.  An odd map (15x15: the pool drops the last row and column either way), two
+    members in one launch, a convolution with batch-norm."""
+    nets = []
+    for g in range(G):
+        n = N.Net("tr%d" % g, h, w, 8, dtype="bf16")
+        x = n.conv(0, cin, 1, act=None)
+        u = n.conv(x, cout, 1, pre=True, bn=bn, act=None, bias=False)
+        nxt = n.tensor(h // 2, w // 2, cout + 32)
+        n.avgpool(u, 2, 2, dst=(nxt, 0))
+        n.conv(nxt, 32, 3, src_slice=(0, cout), dst=(nxt, cout))
+        n.fc(n.gap(nxt), 8)
+        nets.append(n)
+    blobs = [W.quantise_weights_bf16(n, W.make_blob(n, 131, i)) for i, n in enumerate(nets)]
+    imgs = W.round_bf16(W.make_images(132, nb, h, w))
+    outs = []
+    for keep in (False, True):
+        E = ens.Ensemble(nets, blobs)
+        E.set_base_size(h, w)
+        if keep:
+            E.ens_debug_keep_tensors()
+        E.ens_set_alloc([[nb] * G])
+        E.ens_set_profiling(1)
+        E.ens_predict(imgs)
+        ran = {kk["name"]: kk["launches"] for kk in E.ens_profile() if kk["launches"]}
+        assert ran.get("window_kernel<avgpool,pre>", 0) == (0 if keep else 1), ran
+        assert ran.get("window_kernel<avgpool>", 0) == (1 if keep else 0), ran
+        outs.append([E.ens_debug_tensor(g, nxt, nets[g].tensors[nxt], nb)[..., :cout] for g in range(G)])
+        E.close()
+    for g in range(G):
+        ref = oracle_tensor(nets[g], blobs[g], imgs, nxt)[..., :cout]
+        assert np.abs(ref).max() > 0.1
+        assert_after_bf16_layers(outs[0][g], ref, (g, "pool first"))
+        assert_after_bf16_layers(outs[1][g], ref, (g, "layer by layer"))
+
+
 def test_resize_staging(ens):
     """A member at 45 x 45 fed from 32 x 32 requests: bilinear resize inside the library."""
     for dtype in ("fp32", "bf16"):
