@@ -252,6 +252,32 @@ def test_dense_block_layers_in_descriptions():
     assert fused - plain == up(2 * 128 * 128) + up(2 * 9 * 128 * 32), fused - plain
 
 
+def test_transition_convolution_gets_an_operand_ordered_copy():
+    """The pre-activated 1x1 convolution of a transition (no activation, its output read by a 2x2 / stride-2 average
+    pool alone) can run behind that pool as a plain 1x1 layer: the plan gives it the second, operand-ordered copy of
+    its weights that the weights-from-memory kernel reads (input channels padded to 64, output channels to 32).
+    With a max-pool behind it, an activation of its own, or a second reader of its output it gets none."""
+    def net(pool, act=None, tap=False):
+        n = N.Net("tr", 16, 16, 8, dtype="bf16")
+        x = n.conv(0, 96, 3)
+        u = n.conv(x, 40, 1, pre=True, bn=False, act=act, bias=False)
+        t = n.avgpool(u, 2, 2) if pool == "avg" else n.maxpool(u, 2, 2)
+        t2 = n.conv(u, 8, 3, stride=2) if tap else None            # a second reader of the convolution's output
+        v = n.conv(t, 8, 3, res=t2)
+        n.fc(n.gap(v), 8)
+        return n
+
+    up = lambda b: (b + 255) // 256 * 256
+    swapped, _ = ens.ens_spec_bytes(net("avg"), 8)
+    plain, _ = ens.ens_spec_bytes(net("max"), 8)
+    assert swapped - plain == up(2 * 128 * 64), swapped - plain     # 96 -> 128 input channels, 40 -> 64 output channels
+    with_act, _ = ens.ens_spec_bytes(net("avg", act="relu"), 8)
+    assert with_act == plain
+    a, _ = ens.ens_spec_bytes(net("avg", tap=True), 8)
+    b, _ = ens.ens_spec_bytes(net("max", tap=True), 8)
+    assert a == b
+
+
 def test_squeeze_excite_scratch_behind_a_depthwise_layer():
     """A squeeze-excite block behind a 3x3 or 5x5 depthwise layer (bf16) gets the channel sums from that layer's
     kernel, one row per workgroup of an image: its scratch holds as many rows as that kernel has workgroups per
