@@ -25,7 +25,8 @@ namespace ens {
 
 constexpr int PW_BP = 128, PW_NXB = 3, PW_XS = PW_BP * 128;
 
-// GATE: the input is multiplied by a gate per (image, input channel) on its way from LDS to the matrix cores
+// GATE: the input is multiplied by a gate per (image, input channel) in LDS, each chunk in place by the threads
+// that brought it in, before the matrix cores read it
 // (the rescaling of a squeeze-excite block folded into the projection that follows it): product in fp32,
 // rounded to bf16 as the separate rescaling kernel would have stored it.  The gates of the images a tile
 // touches wait in LDS behind the ring, gimg images of nk * 64 floats.
@@ -103,19 +104,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const float bias_r = sb_ok ? ENS_GLOBAL(float, a.bias)[c0 + t] : 0.f;
     const float scale_r = sb_ok ? ENS_GLOBAL(float, a.scale)[c0 + t] : 1.f;
     float* const gl = sbl + 2 * 128;                 // GATE: [image of the tile][nk * 64] gates, zeros past the last channel
-    int grow[TP];                                    // GATE: this lane's first gate of pixel row j, less the chunk's offset
+    int gpiece[BP / 32];                             // GATE: first gate of the 16 bytes this thread brings in of input row r8 + 32 s, less the chunk's offset
     const int HW = a.H * a.W, cinp = nk * 64;
     const int n_first = p0 / HW, n_last = min(p0 + BP - 1, P - 1) / HW;
-    if constexpr (GATE) {
-#pragma unroll
-        for (int j = 0; j < TP; j++) grow[j] = (min(p0 + wp0 + 32 * j + lrow, P - 1) / HW - n_first) * cinp + 8 * lhalf;
-    }
 
     // ---- input chunks: thread t fills chunk slot t % 8 of rows t / 8 + 32 s with the swizzled chunk
     const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
         (void*)a.x.p, 0, (int)((unsigned)nb_ * (unsigned)(a.H * a.W) * (unsigned)a.x.stride * 2u), 0x00020000);
     const int r8 = t >> 3, c8 = (t & 7) ^ ((r8 >> 1) & 7);
     const bool strided = a.sh != 1 || a.sw != 1;
+    if constexpr (GATE) {
+#pragma unroll
+        for (int s = 0; s < XO; s++) gpiece[s] = (min(p0 + r8 + 32 * s, P - 1) / HW - n_first) * cinp + 8 * c8;
+    }
     unsigned xvo[XO];
 #pragma unroll
     for (int s = 0; s < XO; s++) {
@@ -167,6 +168,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             for (int u = 0; u < 16; u++)
                 if (i0 + 256 * u < n_g) gl[i0 + 256 * u] = g[u];
         }
+        __syncthreads();                                         // the first chunk is gated before the loop's first barrier
     }
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
@@ -184,6 +186,33 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             if (nk > 1) bn_wait_vm<XO>(); else bn_wait_vm<0>();
         } else {
             if (kc + 1 < nk) bn_wait_vm<WO + XO>(); else bn_wait_vm<0>();
+        }
+        if constexpr (GATE) {
+            // every thread multiplies the 16-byte pieces it brought in itself by their gates, in place and once per value
+            // (done per fragment, each wavefront along the output channels did it again: twenty vector instructions for
+            // every matrix-core instruction); the barrier below hands the gated chunk to the readers
+            unsigned char* const my = mine + buf * XS + lane * 16;
+            u32x4 xp[XO];
+            f32x4 g0[XO], g1[XO];
+#pragma unroll
+            for (int s2 = 0; s2 < XO; s2++) {
+                xp[s2] = *(const u32x4*)(my + s2 * 4096);
+                const float* gp = gl + gpiece[s2] + kc * 64;
+                g0[s2] = *(const f32x4*)gp;
+                g1[s2] = *(const f32x4*)(gp + 4);
+            }
+#pragma unroll
+            for (int s2 = 0; s2 < XO; s2++) {
+                u32x4 u = xp[s2];
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const float lo = __uint_as_float(u[q] << 16), hi = __uint_as_float(u[q] & 0xFFFF0000u);
+                    const float gq0 = q < 2 ? g0[s2][2 * q] : g1[s2][2 * q - 4], gq1 = q < 2 ? g0[s2][2 * q + 1] : g1[s2][2 * q - 3];
+                    u[q] = pack_bf16x2(lo * gq0, hi * gq1);
+                }
+                *(u32x4*)(my + s2 * 4096) = u;
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
         __builtin_amdgcn_s_barrier();
         if (kc + 2 < nk) {
@@ -210,21 +239,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             }
 #pragma unroll
             for (int j = 0; j < TP; j++) bn_tie(xf[b][j]);
-            if constexpr (GATE) {
-#pragma unroll
-                for (int j = 0; j < TP; j++) {
-                    const float* gp = gl + grow[j] + kc * 64 + ks * 16;
-                    const f32x4 g0 = *(const f32x4*)gp, g1 = *(const f32x4*)(gp + 4);
-                    u32x4 u = __builtin_bit_cast(u32x4, xf[b][j]);
-#pragma unroll
-                    for (int q = 0; q < 4; q++) {
-                        const float lo = __uint_as_float(u[q] << 16), hi = __uint_as_float(u[q] & 0xFFFF0000u);
-                        const float gq0 = q < 2 ? g0[2 * q] : g1[2 * q - 4], gq1 = q < 2 ? g0[2 * q + 1] : g1[2 * q - 3];
-                        u[q] = pack_bf16x2(lo * gq0, hi * gq1);
-                    }
-                    xf[b][j] = __builtin_bit_cast(bf16x8, u);
-                }
-            }
 #pragma unroll
             for (int j = 0; j < TP; j++) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc_[ks], xf[b][j], acc[j], 0, 0, 0);
         });
