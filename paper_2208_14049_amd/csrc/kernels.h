@@ -42,7 +42,7 @@ struct ConvArgs {
     const void* zeros;         // at least 16 bytes of zeros in device memory (padding source of the register-staged kernel)
     const void* wpk;           // the weights in matrix-core operand order (fused bottleneck kernel), or null
     // Squeeze-excite gate folded into a 1x1 convolution: input value (image n, channel ci) is multiplied by
-    // gate[n * gate_stride + ci] (and rounded to bf16) on its way to the matrix cores; null: no gate
+    // gate[n * gate_stride + ci] (and rounded to bf16) before the matrix cores read it; null: no gate
     const float* gate;
     long long gate_stride;
     double inv_hw, inv_w;      // 1 / (Ho * Wo) and 1 / Wo, for the pixel index decomposition
