@@ -39,7 +39,7 @@ TRAFFIC = {
     (4, "conv1x1_direct_bf16<128x128>"): dict(
         bytes_per_launch=97.2e6,                 # read + written (profiles/bench_config4_12members_b128.md)
         sources=["conv_pw.hip", "conv_direct.h", "conv_common.h", "kernels.h"],
-        sha256="0c46ef8dad8b622cedf1db2a82581bf4b1a29a3bea171841981bc807270082e1"),
+        sha256="5119a20acf9c0b64cb2ad90a1e8a33ccbd2747c48b7645bd7fba83864d033d63"),
 }
 
 
